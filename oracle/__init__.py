@@ -1,0 +1,185 @@
+"""Python face of the CPU oracle (plain C in this directory, built with gcc).
+
+TEST INFRASTRUCTURE.  Only tests, ``__graft_entry__.smoke()`` and the bench's
+``cpu_baseline`` leg may import this package.  It shares no code with the HIP
+library, never imports it, and is never a fallback for it.
+
+Functions mirror the dispatcher's problem statement (OrchMLLM Sec. 5.1:
+inputs are the instance count and the list of sequence lengths, the output is
+the list of new batches) and the attention definition; all arrays are numpy,
+host memory.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRCS = [os.path.join(_HERE, "dispatch_oracle.c"), os.path.join(_HERE, "attention_oracle.c")]
+_LIB_PATH = os.path.join(_HERE, "liborch_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (fp64 arithmetic kept strict: no fast-math)."""
+    stale = force or not os.path.exists(_LIB_PATH) or any(
+        os.path.getmtime(s) > os.path.getmtime(_LIB_PATH) for s in _SRCS)
+    if stale:
+        tmp = _LIB_PATH + ".tmp%d" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp",
+                               "-ffp-contract=off", "-o", tmp] + _SRCS + ["-lm"])
+        os.replace(tmp, _LIB_PATH)
+    return _LIB_PATH
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        for name in ("orc_cost", "orc_sort_desc", "orc_greedy", "orc_balance", "orc_pack",
+                     "orc_row_map", "orc_attn_fwd", "orc_attn_rows"):
+            getattr(_lib, name).restype = C.c_int
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+class OracleError(RuntimeError):
+    def __init__(self, code):
+        super().__init__("oracle status %d" % code)
+        self.code = code
+
+
+def _check(rc):
+    if rc != 0:
+        raise OracleError(rc)
+
+
+def _i32(x):
+    return np.ascontiguousarray(x, dtype=np.int32)
+
+
+def cost(lengths, a: int, b: int) -> np.ndarray:
+    L = _i32(lengths)
+    out = np.empty(len(L), dtype=np.uint64)
+    _check(lib().orc_cost(_p(L), C.c_int32(len(L)), C.c_uint64(a), C.c_uint64(b), _p(out)))
+    return out
+
+
+def sort_desc(cost_arr) -> np.ndarray:
+    c = np.ascontiguousarray(cost_arr, dtype=np.uint64)
+    out = np.empty(len(c), dtype=np.int32)
+    _check(lib().orc_sort_desc(_p(c), C.c_int32(len(c)), _p(out)))
+    return out
+
+
+@dataclass
+class Assignment:
+    inst: np.ndarray        # int32[n]
+    order: np.ndarray       # int32[n]
+    seq_off: np.ndarray     # int32[D+1]
+    tok_off: np.ndarray     # int64[D+1]
+    cu_seqlens: np.ndarray  # int32[n+D]
+    loads: np.ndarray       # uint64[D]
+
+    def cu_of(self, i: int) -> np.ndarray:
+        lo = int(self.seq_off[i]) + i
+        return self.cu_seqlens[lo: lo + int(self.seq_off[i + 1] - self.seq_off[i]) + 1]
+
+    def seqs_of(self, i: int) -> np.ndarray:
+        return self.order[int(self.seq_off[i]): int(self.seq_off[i + 1])]
+
+
+def balance(lengths, D: int, a: int, b: int) -> Assignment:
+    L = _i32(lengths)
+    n = len(L)
+    if D < 1:
+        raise OracleError(-1)
+    out = Assignment(np.empty(n, np.int32), np.empty(n, np.int32), np.empty(D + 1, np.int32),
+                     np.empty(D + 1, np.int64), np.empty(n + D, np.int32), np.empty(D, np.uint64))
+    _check(lib().orc_balance(_p(L), C.c_int32(n), C.c_int32(D), C.c_uint64(a), C.c_uint64(b),
+                             _p(out.inst), _p(out.order), _p(out.seq_off), _p(out.tok_off),
+                             _p(out.cu_seqlens), _p(out.loads)))
+    return out
+
+
+def pack(tokens: np.ndarray, lengths, asg: Assignment, inst_begin: int = 0, inst_end: int | None = None):
+    """tokens: 2-D array [T, H] of any 2-byte dtype; returns the packed rows of
+    instances [inst_begin, inst_end)."""
+    L = _i32(lengths)
+    D = len(asg.loads)
+    if inst_end is None:
+        inst_end = D
+    tokens = np.ascontiguousarray(tokens)
+    rows = int(asg.tok_off[inst_end] - asg.tok_off[inst_begin])
+    out = np.empty((rows, tokens.shape[1]), dtype=tokens.dtype)
+    rb = tokens.shape[1] * tokens.dtype.itemsize
+    _check(lib().orc_pack(_p(tokens), _p(out), _p(L), C.c_int32(len(L)), C.c_int32(D), C.c_int64(rb),
+                          _p(asg.order), _p(asg.seq_off), _p(asg.tok_off), _p(asg.cu_seqlens),
+                          C.c_int32(inst_begin), C.c_int32(inst_end)))
+    return out
+
+
+def row_map(lengths, asg: Assignment) -> np.ndarray:
+    L = _i32(lengths)
+    D = len(asg.loads)
+    out = np.empty(int(asg.tok_off[D]), dtype=np.int64)
+    _check(lib().orc_row_map(_p(L), C.c_int32(len(L)), C.c_int32(D), _p(asg.order), _p(asg.seq_off),
+                             _p(asg.tok_off), _p(asg.cu_seqlens), _p(out)))
+    return out
+
+
+def _u16(x):
+    x = np.ascontiguousarray(x)
+    assert x.dtype.itemsize == 2
+    return x.view(np.uint16)
+
+
+def attn_fwd(q, k, v, cu_seqlens, causal: bool, scale: float = 0.0, nthreads: int = 1,
+             want_lse: bool = False):
+    """q [T,Hq,d], k,v [T,Hkv,d] as bf16 bit patterns (any 2-byte dtype).
+    Returns fp64 out [T,Hq,d] (and lse [Hq,T]); also the thread count used."""
+    q, k, v = _u16(q), _u16(k), _u16(v)
+    cu = _i32(cu_seqlens)
+    T, Hq, d = q.shape
+    Hkv = k.shape[1]
+    out = np.zeros((T, Hq, d), dtype=np.float64)
+    lse = np.zeros((Hq, T), dtype=np.float64) if want_lse else None
+    used = C.c_int(0)
+    _check(lib().orc_attn_fwd(_p(q), _p(k), _p(v), _p(out), _p(lse), _p(cu), C.c_int32(len(cu) - 1),
+                              C.c_int32(Hq), C.c_int32(Hkv), C.c_int32(d), C.c_double(scale),
+                              C.c_int(1 if causal else 0), C.c_int(nthreads), C.byref(used)))
+    attn_fwd.last_threads = used.value
+    return (out, lse) if want_lse else out
+
+
+def attn_rows(q, k, v, cu_seqlens, causal: bool, seq, head, abs_row, scale: float = 0.0,
+              nthreads: int = 1, want_lse: bool = False):
+    """Selected output rows only: out fp64 [M, d] for (seq[m], head[m], abs_row[m])."""
+    q, k, v = _u16(q), _u16(k), _u16(v)
+    cu = _i32(cu_seqlens)
+    seq, head, abs_row = _i32(seq), _i32(head), _i32(abs_row)
+    _, Hq, d = q.shape
+    Hkv = k.shape[1]
+    M = len(seq)
+    out = np.zeros((M, d), dtype=np.float64)
+    lse = np.zeros(M, dtype=np.float64) if want_lse else None
+    _check(lib().orc_attn_rows(_p(q), _p(k), _p(v), _p(cu), C.c_int32(len(cu) - 1), C.c_int32(Hq),
+                               C.c_int32(Hkv), C.c_int32(d), C.c_double(scale),
+                               C.c_int(1 if causal else 0), _p(seq), _p(head), _p(abs_row),
+                               C.c_int32(M), _p(out), _p(lse), C.c_int(nthreads)))
+    return (out, lse) if want_lse else out
+
+
+def load_ratio(lengths, inst, D: int, a: int, b: int) -> float:
+    """max_i load / mean_i load of an arbitrary assignment, with Eq. 2's cost."""
+    c = cost(lengths, a, b).astype(np.float64)
+    loads = np.zeros(D)
+    np.add.at(loads, np.asarray(inst), c)
+    return float(loads.max() / loads.mean()) if loads.mean() > 0 else 1.0

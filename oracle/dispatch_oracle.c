@@ -1,0 +1,190 @@
+/* CPU oracle for the Batch Post-Balancing dispatch step.  TEST INFRASTRUCTURE:
+ * only tests, the smoke check and the bench's cpu_baseline leg may call it; it
+ * shares no code with the HIP library and is never a fallback for it.
+ *
+ * What it computes, in the paper's order (OrchMLLM, Sec. 5.1):
+ *   - per-sequence cost from the no-padding branch of Eq. 2: a batch's cost
+ *     alpha*sum(l) + beta*sum(l^2) is additive over sequences, so sequence s
+ *     carries c_s = a*l_s^2 + b*l_s with a = beta, b = alpha (exact, u64);
+ *   - Algorithm 1 ("Post-Balancing without paddings") with that cost as the
+ *     key: sort descending, then give every sequence in turn to the batch whose
+ *     summed key is smallest (longest-processing-time-first greedy).  With
+ *     a = 0, b = 1 this is Algorithm 1 literally;
+ *   - the packed, padding-free layout each instance then batches along the
+ *     sequence dimension (Sec. 7, input preprocessing) and the row movement the
+ *     All-to-All Batch Communicator performs (Sec. 5.2.1), on one device.
+ *
+ * Readings where the paper is silent: equal keys keep ascending index order
+ * (stable sort); among equally loaded batches the lowest-numbered one is the
+ * "top"; the batch created i-th is instance i; sequences stay in push order
+ * inside a batch; zero-length sequences are kept as empty segments.
+ *
+ * Every function takes HOST pointers.  Return value 0 = ok, -1 = bad argument,
+ * -5 = bad data (negative length or arithmetic overflow).
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* Eq. 2, no-padding branch, per sequence. */
+int orc_cost(const int32_t *lengths, int32_t n, uint64_t a, uint64_t b, uint64_t *cost)
+{
+    if (n < 0 || (n > 0 && (!lengths || !cost))) return -1;
+    unsigned __int128 total = 0;
+    for (int32_t s = 0; s < n; ++s) {
+        if (lengths[s] < 0) return -5;
+        unsigned __int128 l = (unsigned __int128)(uint32_t)lengths[s];
+        unsigned __int128 c = (unsigned __int128)a * l * l + (unsigned __int128)b * l;
+        total += c;
+        if (total >> 63) return -5;
+        cost[s] = (uint64_t)c;
+    }
+    return 0;
+}
+
+/* Algorithm 1, line 1: indices in descending key order; equal keys keep
+ * ascending index order.  Bottom-up merge sort, stable. */
+int orc_sort_desc(const uint64_t *cost, int32_t n, int32_t *sorted)
+{
+    if (n < 0 || (n > 0 && (!cost || !sorted))) return -1;
+    int32_t *a = sorted, *b = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n > 0 ? n : 1));
+    if (!b) return -1;
+    for (int32_t i = 0; i < n; ++i) a[i] = i;
+    for (int64_t w = 1; w < n; w *= 2) {
+        for (int64_t lo = 0; lo < n; lo += 2 * w) {
+            int64_t mid = lo + w < n ? lo + w : n, hi = lo + 2 * w < n ? lo + 2 * w : n;
+            int64_t i = lo, j = mid, k = lo;
+            while (i < mid && j < hi) {
+                /* take from the right run only when its key is strictly larger */
+                if (cost[a[j]] > cost[a[i]]) b[k++] = a[j++];
+                else b[k++] = a[i++];
+            }
+            while (i < mid) b[k++] = a[i++];
+            while (j < hi) b[k++] = a[j++];
+        }
+        int32_t *t = a; a = b; b = t;
+    }
+    if (a != sorted) { memcpy(sorted, a, sizeof(int32_t) * (size_t)n); b = a; }
+    free(b);
+    return 0;
+}
+
+/* Algorithm 1, lines 2-7.  The priority queue's top() is found by a plain scan:
+ * first strictly smaller load wins, so ties go to the lowest instance.
+ * rank[s] = how many sequences the batch held before s was pushed. */
+int orc_greedy(const uint64_t *cost, const int32_t *sorted, int32_t n, int32_t D,
+               int32_t *inst, int32_t *rank, uint64_t *loads, int32_t *counts)
+{
+    if (n < 0 || D < 1) return -1;
+    for (int32_t i = 0; i < D; ++i) { loads[i] = 0; counts[i] = 0; }
+    for (int32_t t = 0; t < n; ++t) {
+        int32_t s = sorted[t], best = 0;
+        for (int32_t i = 1; i < D; ++i)
+            if (loads[i] < loads[best]) best = i;
+        inst[s] = best;
+        rank[s] = counts[best]++;
+        loads[best] += cost[s];
+    }
+    return 0;
+}
+
+/* The whole dispatch: cost -> sort -> greedy -> layout.
+ *   inst[n]        instance of sequence s
+ *   order[n]       sequence ids, instance-major, push order inside an instance
+ *   seq_off[D+1]   order[seq_off[i] .. seq_off[i+1]) is instance i
+ *   tok_off[D+1]   first packed row of instance i (i64)
+ *   cu_seqlens[n+D] instance i's slice starts at seq_off[i]+i, has cnt_i+1
+ *                  entries, starts at 0 (rows local to the instance)
+ *   loads[D]       summed cost per instance
+ */
+int orc_balance(const int32_t *lengths, int32_t n, int32_t D, uint64_t a, uint64_t b,
+                int32_t *inst, int32_t *order, int32_t *seq_off, int64_t *tok_off,
+                int32_t *cu_seqlens, uint64_t *loads)
+{
+    if (n < 0 || D < 1) return -1;
+    size_t nn = (size_t)(n > 0 ? n : 1);
+    uint64_t *cost = (uint64_t *)malloc(nn * sizeof(uint64_t));
+    int32_t *sorted = (int32_t *)malloc(nn * sizeof(int32_t));
+    int32_t *rank = (int32_t *)malloc(nn * sizeof(int32_t));
+    int32_t *counts = (int32_t *)malloc((size_t)D * sizeof(int32_t));
+    int rc = -1;
+    if (!cost || !sorted || !rank || !counts) goto done;
+    if ((rc = orc_cost(lengths, n, a, b, cost)) != 0) goto done;
+    if ((rc = orc_sort_desc(cost, n, sorted)) != 0) goto done;
+    if ((rc = orc_greedy(cost, sorted, n, D, inst, rank, loads, counts)) != 0) goto done;
+
+    seq_off[0] = 0;
+    for (int32_t i = 0; i < D; ++i) seq_off[i + 1] = seq_off[i] + counts[i];
+    for (int32_t s = 0; s < n; ++s) order[seq_off[inst[s]] + rank[s]] = s;
+    tok_off[0] = 0;
+    for (int32_t i = 0; i < D; ++i) {
+        int32_t *cu = cu_seqlens + seq_off[i] + i;
+        int64_t run = 0;
+        cu[0] = 0;
+        for (int32_t j = 0; j < counts[i]; ++j) {
+            run += lengths[order[seq_off[i] + j]];
+            if (run > INT32_MAX) { rc = -5; goto done; }
+            cu[j + 1] = (int32_t)run;
+        }
+        tok_off[i + 1] = tok_off[i] + run;
+    }
+    rc = 0;
+done:
+    free(cost); free(sorted); free(rank); free(counts);
+    return rc;
+}
+
+/* Row movement of the rearrangement: sequence s occupies source rows
+ * [src_cu[s], src_cu[s]+l_s) (sequences concatenated in original order) and
+ * lands at instance-major position tok_off[i] + cu_i[j].  One memcpy per
+ * sequence.  Only instances [inst_begin, inst_end) are produced, at rows
+ * relative to tok_off[inst_begin].  row_bytes = bytes per token row. */
+int orc_pack(const void *tokens, void *packed, const int32_t *lengths, int32_t n, int32_t D,
+             int64_t row_bytes, const int32_t *order, const int32_t *seq_off,
+             const int64_t *tok_off, const int32_t *cu_seqlens,
+             int32_t inst_begin, int32_t inst_end)
+{
+    if (n < 0 || D < 1 || inst_begin < 0 || inst_end > D || inst_begin > inst_end || row_bytes < 1)
+        return -1;
+    int64_t *src_cu = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n + 1));
+    if (!src_cu) return -1;
+    src_cu[0] = 0;
+    for (int32_t s = 0; s < n; ++s) src_cu[s + 1] = src_cu[s] + lengths[s];
+    const char *src = (const char *)tokens;
+    char *dst = (char *)packed;
+    for (int32_t i = inst_begin; i < inst_end; ++i) {
+        const int32_t *cu = cu_seqlens + seq_off[i] + i;
+        for (int32_t j = 0; j < seq_off[i + 1] - seq_off[i]; ++j) {
+            int32_t s = order[seq_off[i] + j];
+            int64_t drow = tok_off[i] - tok_off[inst_begin] + cu[j];
+            memcpy(dst + drow * row_bytes, src + src_cu[s] * row_bytes,
+                   (size_t)lengths[s] * (size_t)row_bytes);
+        }
+    }
+    free(src_cu);
+    return 0;
+}
+
+/* Same movement as an index map: src_row_of_dst[r] = source row that lands in
+ * global packed row r (all instances), for checking device output in chunks
+ * without holding both buffers on the host. */
+int orc_row_map(const int32_t *lengths, int32_t n, int32_t D, const int32_t *order,
+                const int32_t *seq_off, const int64_t *tok_off, const int32_t *cu_seqlens,
+                int64_t *src_row_of_dst)
+{
+    if (n < 0 || D < 1) return -1;
+    int64_t *src_cu = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n + 1));
+    if (!src_cu) return -1;
+    src_cu[0] = 0;
+    for (int32_t s = 0; s < n; ++s) src_cu[s + 1] = src_cu[s] + lengths[s];
+    for (int32_t i = 0; i < D; ++i) {
+        const int32_t *cu = cu_seqlens + seq_off[i] + i;
+        for (int32_t j = 0; j < seq_off[i + 1] - seq_off[i]; ++j) {
+            int32_t s = order[seq_off[i] + j];
+            for (int32_t r = 0; r < lengths[s]; ++r)
+                src_row_of_dst[tok_off[i] + cu[j] + r] = src_cu[s] + r;
+        }
+    }
+    free(src_cu);
+    return 0;
+}
