@@ -1,0 +1,262 @@
+#!/usr/bin/env python3
+"""Benchmark of the dispatcher hot path on one MI355X.
+
+One step = one pass of the whole hot path over one seeded synthetic batch:
+  orch_balance (all D instances)  ->  orch_pack (every token row of the batch)
+  ->  orch_varlen_attn_fwd on the most loaded instance's packed share.
+Inputs are resident in HBM before the timed region.  Default workload: C4 (LLM
+phase with modality-composition incoherence), the configuration the targets are
+stated on.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0       # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
+
+
+def attn_flops(cu, Hq, d, causal):
+    """4*d FLOP per visible (query, key) pair per q-head; masked pairs are not counted."""
+    import numpy as np
+
+    L = np.diff(np.asarray(cu, dtype=np.int64))
+    pairs = (L * (L + 1) // 2).sum() if causal else (L * L).sum()
+    return float(4 * d * Hq) * float(pairs)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=4, help="workload C1..C5 (C5 packs one instance's share)")
+    ap.add_argument("--seed", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the attention oracle sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the dispatcher for all D instances plus one "
+              "instance's attention); --gpus %d is not supported." % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2503_23830_amd as orch
+    import workloads as wl
+
+    if not os.path.exists(orch.library_path()):
+        import __graft_entry__ as ge
+        ge.build()
+    orch.load_library()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w = wl.WORKLOADS[args.config]
+    base_seed = wl.BASE_SEED if args.seed is None else args.seed
+    L = wl.draw_lengths(w, base_seed)
+    n, D, H = w.n, w.D, w.H
+
+    # ---------------- setup (untimed): inputs resident in HBM -----------------
+    Ld = torch.from_numpy(L).to(dev)
+    asg = orch.Assignment.empty(n, D, dev)
+    ws_bal = torch.empty(orch.balance_workspace(n, D), dtype=torch.uint8, device=dev)
+    ws_pack = torch.empty(orch.pack_workspace(n, D), dtype=torch.uint8, device=dev)
+    orch.balance(Ld, D, w.a, w.b, out=asg, ws=ws_bal)
+    torch.cuda.synchronize()
+    assert int(asg.dev_status.item()) == 0
+    loads = asg.loads.cpu().numpy().view(np.uint64).astype(np.float64)
+    seq_off = asg.seq_off.cpu().numpy()
+    tok_off = asg.tok_off.cpu().numpy()
+    cu_all = asg.cu_seqlens.cpu().numpy()
+    i_star = int(np.argmax(loads))  # the straggler instance sets the step time
+    cu_lo = int(seq_off[i_star]) + i_star
+    batch_i = int(seq_off[i_star + 1] - seq_off[i_star])
+    cu_i = np.ascontiguousarray(cu_all[cu_lo: cu_lo + batch_i + 1])
+    T_i = int(cu_i[-1])
+
+    # pack scope: the whole batch when it fits, else (C5) the straggler's share from a compacted source
+    T_all = int(L.sum(dtype=np.int64))
+    free, _ = torch.cuda.mem_get_info()
+    attn_bytes = T_i * (2 * w.Hq + 2 * w.Hkv) * w.d * 2
+    whole = 2 * T_all * H * 2 + attn_bytes + (6 << 30) < free
+    if whole:
+        L_pack, inst_lo, inst_hi, pack_scope = L, 0, D, "all %d instances" % D
+    else:
+        keep = asg.inst.cpu().numpy()[:n] == i_star
+        L_pack = np.where(keep, L, 0).astype(np.int32)
+        inst_lo, inst_hi, pack_scope = i_star, i_star + 1, "instance %d of %d (compacted source)" % (i_star, D)
+    Lp_d = torch.from_numpy(L_pack).to(dev)
+    T_pack = int(L_pack.sum(dtype=np.int64))
+    tokens = wl.token_tag_torch(0, T_pack, H, dev)
+    packed = torch.empty((T_pack, H), dtype=torch.int16, device=dev)
+    if not whole:  # balance must see the lengths the source buffer holds
+        asg_pack = orch.Assignment.empty(n, D, dev)
+    else:
+        asg_pack = asg
+
+    q = wl.normal_bf16_torch((T_i, w.Hq, w.d), base_seed, 1, dev)
+    k = wl.normal_bf16_torch((T_i, w.Hkv, w.d), base_seed, 2, dev)
+    v = wl.normal_bf16_torch((T_i, w.Hkv, w.d), base_seed, 3, dev)
+    out = torch.empty_like(q)
+    ws_attn = torch.empty(orch.varlen_attn_workspace(batch_i), dtype=torch.uint8, device=dev)
+    cu_view = asg.cu_seqlens[cu_lo: cu_lo + batch_i + 1]  # device slice written by balance each step
+
+    def step(ev=None):
+        if ev: ev[0].record()
+        orch.balance(Ld, D, w.a, w.b, out=asg, ws=ws_bal)
+        if not whole:
+            orch.balance(Lp_d, D, w.a, w.b, out=asg_pack, ws=ws_bal)
+        if ev: ev[1].record()
+        orch.pack(tokens, Lp_d, asg_pack, inst_lo if whole else 0, inst_hi if whole else D, out=packed, ws=ws_pack)
+        if ev: ev[2].record()
+        orch.varlen_attn_fwd(q, k, v, cu_view, w.causal, out=out, ws=ws_attn)
+        if ev: ev[3].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(events[s])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_step = (t1 - t0) * 1e3 / args.steps
+    bal_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
+    pack_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
+    attn_ms = float(np.mean([e[2].elapsed_time(e[3]) for e in events]))
+
+    flops = attn_flops(cu_i, w.Hq, w.d, w.causal)
+    attn_tflops = flops / (attn_ms * 1e-3) / 1e12
+    pack_bytes = 2.0 * T_pack * H * 2
+    pack_gbps = pack_bytes / (pack_ms * 1e-3) / 1e9
+
+    # ---------------- verify after the timed loop (sampled) -------------------
+    import oracle
+
+    t_or = time.perf_counter()
+    ref = oracle.balance(L, D, w.a, w.b)
+    cpu_dispatch_ms = (time.perf_counter() - t_or) * 1e3
+    ok = int(asg.dev_status.item()) == 0
+    ok &= np.array_equal(asg.inst.cpu().numpy()[:n], ref.inst)
+    ok &= np.array_equal(asg.cu_seqlens.cpu().numpy()[: n + D], ref.cu_seqlens)
+    ok &= np.array_equal(asg.tok_off.cpu().numpy(), ref.tok_off)
+    ref_pack = ref if whole else oracle.balance(L_pack, D, w.a, w.b)
+    rmap = oracle.row_map(L_pack, ref_pack)
+    bits = lambda t: t.cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+    for r0 in [0, max(0, T_pack - 128)] + [int(x) for x in wl.uniform01(5, 1, 14) * max(1, T_pack - 128)]:
+        ok &= np.array_equal(bits(packed[r0: r0 + 128]), wl.token_tag_np(rmap[r0: r0 + 128], H))
+    before = oracle.load_ratio(L, (np.arange(n, dtype=np.int64) * D) // n, D, w.a, w.b)
+    after = float(loads.max() / loads.mean())
+
+    cores = min(16, os.cpu_count() or 1)
+    qh, kh, vh = bits(q), bits(k), bits(v)
+    lens_i = np.diff(cu_i)
+    nz = np.nonzero(lens_i)[0]
+
+    def draw_rows(M, seed):
+        u = wl.uniform01(seed, 3, 3 * M).reshape(3, M)
+        t = nz[(u[0] * len(nz)).astype(np.int64)]
+        return (t.astype(np.int32), (u[1] * w.Hq).astype(np.int32),
+                (cu_i[t] + (u[2] * lens_i[t]).astype(np.int64)).astype(np.int32))
+
+    def rows_flops(t, row):
+        vis = (row - cu_i[t] + 1) if w.causal else lens_i[t]
+        return float(4 * w.d) * float(np.sum(vis, dtype=np.int64))
+
+    # parity sample (always): 512 rows against the fp64 oracle
+    st, sh, sr = draw_rows(512, 17)
+    want = oracle.attn_rows(qh, kh, vh, cu_i, w.causal, st, sh, sr, nthreads=cores)
+    got = out[torch.from_numpy(sr.astype(np.int64)).to(dev), torch.from_numpy(sh.astype(np.int64)).to(dev)]
+    err = np.abs(got.float().cpu().numpy().astype(np.float64) - want)
+    ok &= bool(err.max() <= 2e-2 and err.mean() <= 2e-3)
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        tt = time.perf_counter()
+        oracle.attn_rows(qh, kh, vh, cu_i, w.causal, st, sh, sr, nthreads=cores)
+        t_probe = time.perf_counter() - tt
+        M = int(min(400000, max(512, 512 * args.cpu_seconds / max(t_probe, 1e-4))))
+        bt, bh, br = draw_rows(M, 23)
+        tt = time.perf_counter()
+        oracle.attn_rows(qh, kh, vh, cu_i, w.causal, bt, bh, br, nthreads=cores)
+        t_attn = time.perf_counter() - tt
+        cpu_tflops = rows_flops(bt, br) / t_attn / 1e12
+        # pack oracle: memcpy per sequence on a host slice of about 2 GB
+        take = max(1, min(T_pack, (2 << 30) // (H * 2)))
+        nseq = int(np.searchsorted(np.cumsum(L_pack, dtype=np.int64), take, side="right"))
+        nseq = max(1, nseq)
+        Ls = L_pack[:nseq].copy()
+        Dh = min(D, max(1, nseq))
+        ra = oracle.balance(Ls, Dh, w.a, w.b)
+        host_tok = wl.token_tag_np(np.arange(min(int(Ls.sum()), 1024)), H)
+        host_tok = np.resize(host_tok, (int(Ls.sum()), H))
+        tt = time.perf_counter()
+        oracle.pack(host_tok, Ls, ra)
+        t_pack = time.perf_counter() - tt
+        cpu_baseline = {
+            "value": cpu_tflops, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": "naive fp64 attention oracle on %d seeded (sequence, head, row) samples of the same "
+                      "instance (%.2f GFLOP counted, %.1f s); extrapolated whole-instance time %.0f s"
+                      % (M, rows_flops(bt, br) / 1e9, t_attn, flops / (cpu_tflops * 1e12)),
+            "pack_GBps": 2.0 * host_tok.nbytes / t_pack / 1e9,
+            "pack_sample": "memcpy-per-sequence oracle, 1 core, first %d sequences (%.2f GB of rows)" % (nseq, host_tok.nbytes / 1e9),
+            "dispatch_ms": cpu_dispatch_ms,
+            "dispatch_sample": "whole config, 1 core (cost, stable merge sort, linear-scan greedy, layout)",
+        }
+
+    # ---------------- roofline of the dominant kernel -------------------------
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    dominant = "attn" if attn_ms >= pack_ms else "pack"
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("C%d" % w.cid, {}).get(dominant)
+        except Exception:
+            traffic = None
+    if dominant == "attn":
+        roofline = {"kernel": "attn_fwd_kernel<%d,%s> (%s)" % (w.d, "causal" if w.causal else "full", orch.attn_variant()),
+                    "bound": "mfma", "achieved": attn_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic,
+                    "launch_ms": attn_ms, "flop_per_launch": flops}
+    else:
+        roofline = {"kernel": "pack_copy_kernel", "bound": "hbm", "achieved": pack_gbps, "peak": HBM_PEAK_GBPS,
+                    "unit": "GB/s", "frac": pack_gbps / HBM_PEAK_GBPS, "traffic": traffic,
+                    "launch_ms": pack_ms, "bytes_per_launch": pack_bytes}
+
+    result = {
+        "metric": "varlen attn TFLOP/s + pack GB/s (% peak); max/mean instance load, 1 GPU",
+        "value": attn_tflops, "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "n": n, "D": D, "cost": [w.a, w.b], "seed": base_seed,
+                   "pack_scope": pack_scope, "pack_rows": T_pack, "row_bf16": H,
+                   "attn_instance": i_star, "attn_tokens": T_i, "attn_sequences": batch_i,
+                   "heads": [w.Hq, w.Hkv], "head_dim": w.d, "causal": w.causal},
+        "attn": {"tflops": attn_tflops, "frac_mfma_peak": attn_tflops / MFMA_BF16_PEAK_TFLOPS, "ms": attn_ms,
+                 "variant": orch.attn_variant()},
+        "pack": {"GBps": pack_gbps, "frac_hbm_peak": pack_gbps / HBM_PEAK_GBPS, "ms": pack_ms, "bytes": pack_bytes},
+        "dispatch": {"ms": bal_ms, "calls_per_step": 1 if whole else 2},
+        "load_max_over_mean": {"before": before, "after": after},
+        "verified": bool(ok), "attn_err": {"max_abs": float(err.max()), "mean_abs": float(err.mean())},
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+    }
+    print(json.dumps(result), flush=True)
+    if not ok:
+        sys.exit(1)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,125 @@
+/* liborch: the data-parallel hot path behind OrchMLLM's Batch Post-Balancing
+ * Dispatcher, for one MI355X (gfx950).
+ *
+ *   orch_balance          Sec. 5.1: Eq. 2 (no-padding branch) as a per-sequence
+ *                         cost, Algorithm 1 (sort descending, give each
+ *                         sequence to the least-loaded new batch) and the
+ *                         padding-free batch layout of Sec. 7.
+ *   orch_pack             Sec. 5.2.1: the row movement of the All-to-All Batch
+ *                         Communicator, performed on one device.
+ *   orch_varlen_attn_fwd  the padding-free ("batched along the sequence
+ *                         length") attention each instance then runs; its
+ *                         quadratic term is beta*sum(l^2) in Eq. 2.
+ *
+ * Conventions
+ *   - Every pointer is a DEVICE pointer unless its name starts with host_.
+ *     The caller owns every buffer; the library allocates nothing and keeps no
+ *     state between calls besides a thread-local error string.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All
+ *     work is enqueued on it; no call synchronises with the host.
+ *   - Return value: ORCH_OK or a negative orch_status.  Errors the host can see
+ *     (bad sizes, null pointers, unsupported head_dim, small workspace) return
+ *     before anything is launched.  Errors only the device can see (a negative
+ *     length, cost overflow, a buffer too small for the rows an assignment
+ *     implies) store ORCH_EDATA into `dev_status[0]`; the other outputs are
+ *     then unspecified but no access leaves the caller's buffers.
+ *   - Inputs are never written.  Workspaces need 256-byte alignment.
+ */
+#ifndef ORCH_H
+#define ORCH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ORCH_OK = 0,
+    ORCH_EINVAL = -1,       /* bad argument */
+    ORCH_ENOSPC = -2,       /* workspace too small */
+    ORCH_EUNSUPPORTED = -3, /* head_dim / sizes outside what the kernels cover */
+    ORCH_EHIP = -4,         /* a HIP runtime call failed */
+    ORCH_EDATA = -5         /* data error found on the device (dev_status) */
+} orch_status;
+
+/* Per-sequence cost of a phase: cost(L) = a*L*L + b*L, exact in u64 (Eq. 2,
+ * no-padding branch, a = beta, b = alpha).  a = 0, b = 1 balances token counts
+ * (Algorithm 1 as printed).  Precondition: the sum of all costs is < 2^63. */
+typedef struct {
+    uint64_t a, b;
+} orch_phase;
+
+/* Outputs of orch_balance (device memory, caller-allocated). */
+typedef struct {
+    int32_t *inst;        /* [n]    instance that receives sequence s */
+    int32_t *order;       /* [n]    sequence ids, instance-major; inside an
+                                    instance in the order Algorithm 1 pushed them */
+    int32_t *seq_off;     /* [D+1]  order[seq_off[i] .. seq_off[i+1]) is instance i */
+    int64_t *tok_off;     /* [D+1]  first packed row of instance i */
+    int32_t *cu_seqlens;  /* [n+D]  instance i's cumulative lengths: cnt_i+1
+                                    entries starting at index seq_off[i]+i,
+                                    first entry 0, rows local to the instance */
+    uint64_t *loads;      /* [D]    summed cost per instance */
+    int32_t *dev_status;  /* [1]    ORCH_OK or ORCH_EDATA, written by the device */
+} orch_assignment;
+
+/* Bytes of workspace orch_balance needs for n sequences and D instances. */
+size_t orch_balance_workspace(int32_t n, int32_t D);
+
+/* Sec. 5.1, Algorithm 1 with Eq. 2's per-sequence cost as the key.
+ *   lengths[n]  int32, >= 0 (zero-length sequences are kept as empty segments)
+ *   1 <= D <= 4096, n >= 0
+ * Ties: equal costs keep ascending sequence index; among equally loaded
+ * instances the lowest index receives the sequence. */
+int orch_balance(const int32_t *lengths, int32_t n, int32_t D, orch_phase phase,
+                 orch_assignment out, void *ws, size_t ws_bytes, void *stream);
+
+/* Bytes of workspace orch_pack needs. */
+size_t orch_pack_workspace(int32_t n, int32_t D);
+
+/* Sec. 5.2.1 on one device: packed[tok_off[i]-tok_off[inst_begin] + cu_i[j] + r, :]
+ * = tokens[src_cu[s] + r, :] for s the j-th sequence of instance i, 0 <= r < L_s,
+ * inst_begin <= i < inst_end, where src_cu is the exclusive prefix sum of
+ * lengths in original order (the source buffer holds the sequences
+ * concatenated in original order).
+ *   tokens  [T, H] 16-bit words, row-major; T = sum of lengths
+ *   packed  [packed_rows, H]; packed_rows must cover the rows of the chosen
+ *           instances, else dev_status is set and nothing past it is written
+ *   a       the assignment orch_balance produced for these lengths
+ * Rows are copied bit for bit. */
+int orch_pack(const void *tokens, void *packed, const int32_t *lengths, int32_t n, int32_t D,
+              int64_t T, int32_t H, int64_t packed_rows, orch_assignment a, int32_t inst_begin,
+              int32_t inst_end, void *ws, size_t ws_bytes, void *stream);
+
+/* Bytes of workspace orch_varlen_attn_fwd needs. */
+size_t orch_varlen_attn_workspace(int32_t batch);
+
+/* Padding-free attention forward over `batch` sequences stored back to back.
+ * For sequence t (rows cu_seqlens[t] .. cu_seqlens[t+1]), q-head h, kv-head
+ * g = h / (Hq/Hkv), row i:  out[i,h,:] = softmax_j(scale * q[i,h,:].k[j,g,:]) v[j,g,:]
+ * over all rows j of the sequence, or j <= i when causal != 0.
+ *   q, out  [total_tokens, Hq, d] bf16      k, v  [total_tokens, Hkv, d] bf16
+ *   lse     [Hq, total_tokens] fp32 natural-log-sum-exp, or NULL
+ *   cu_seqlens [batch+1] int32, non-decreasing, cu_seqlens[batch] <= total_tokens
+ *   max_seqlen  an upper bound on any sequence length (<= total_tokens), or 0
+ *   d in {64, 128}; Hq % Hkv == 0; scale <= 0 means 1/sqrt(d)
+ * bf16 inputs, fp32 accumulation, bf16 output (round to nearest even).
+ * Empty sequences write nothing. */
+int orch_varlen_attn_fwd(const void *q, const void *k, const void *v, void *out, float *lse,
+                         const int32_t *cu_seqlens, int32_t batch, int32_t total_tokens,
+                         int32_t max_seqlen, int32_t Hq, int32_t Hkv, int32_t d, float scale,
+                         int32_t causal, void *ws, size_t ws_bytes, void *stream);
+
+/* Message for the last non-OK status returned on this thread; never NULL. */
+const char *orch_last_error(void);
+
+/* Name of the kernel variant the last orch_varlen_attn_fwd on this thread
+ * launched (for profiling logs); never NULL. */
+const char *orch_attn_variant(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ORCH_H */

@@ -153,7 +153,7 @@ def attn_fwd(q, k, v, cu_seqlens, causal: bool, scale: float = 0.0, nthreads: in
     lse = np.zeros((Hq, T), dtype=np.float64) if want_lse else None
     used = C.c_int(0)
     _check(lib().orc_attn_fwd(_p(q), _p(k), _p(v), _p(out), _p(lse), _p(cu), C.c_int32(len(cu) - 1),
-                              C.c_int32(Hq), C.c_int32(Hkv), C.c_int32(d), C.c_double(scale),
+                              C.c_int64(T), C.c_int32(Hq), C.c_int32(Hkv), C.c_int32(d), C.c_double(scale),
                               C.c_int(1 if causal else 0), C.c_int(nthreads), C.byref(used)))
     attn_fwd.last_threads = used.value
     return (out, lse) if want_lse else out

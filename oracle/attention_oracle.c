@@ -63,16 +63,18 @@ static void attn_row(const uint16_t *q, const uint16_t *k, const uint16_t *v, in
     if (lse) *lse = m + log(z);
 }
 
-/* Full forward.  out: fp64 [T,Hq,d]; lse: fp64 [Hq,T] or NULL.
+/* Full forward.  out: fp64 [T,Hq,d]; lse: fp64 [Hq,T] or NULL, where T =
+ * total_tokens >= cu[batch] is the row count of the buffers.
  * nthreads <= 0 means one thread.  Returns the thread count used via *used. */
 int orc_attn_fwd(const uint16_t *q, const uint16_t *k, const uint16_t *v, double *out, double *lse,
-                 const int32_t *cu, int32_t batch, int32_t Hq, int32_t Hkv, int32_t d, double scale,
-                 int causal, int nthreads, int *used)
+                 const int32_t *cu, int32_t batch, int64_t total_tokens, int32_t Hq, int32_t Hkv,
+                 int32_t d, double scale, int causal, int nthreads, int *used)
 {
     if (batch < 0 || Hq < 1 || Hkv < 1 || Hq % Hkv || d < 1 || !cu) return -1;
     for (int32_t t = 0; t < batch; ++t) if (cu[t + 1] < cu[t]) return -1;
     if (scale <= 0) scale = 1.0 / sqrt((double)d);
-    int64_t T = batch > 0 ? cu[batch] : 0;
+    int64_t T = total_tokens;
+    if (batch > 0 && cu[batch] > T) return -1;
     int32_t maxlen = 0;
     for (int32_t t = 0; t < batch; ++t) if (cu[t + 1] - cu[t] > maxlen) maxlen = cu[t + 1] - cu[t];
     if (nthreads < 1) nthreads = 1;

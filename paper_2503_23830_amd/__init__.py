@@ -1,0 +1,15 @@
+"""MI355X-native hot path behind OrchMLLM's Batch Post-Balancing Dispatcher:
+balance -> pack -> varlen attention, hand-written HIP behind a C ABI."""
+from .binding import (  # noqa: F401
+    Assignment,
+    OrchError,
+    attn_variant,
+    balance,
+    balance_workspace,
+    library_path,
+    load_library,
+    pack,
+    pack_workspace,
+    varlen_attn_fwd,
+    varlen_attn_workspace,
+)

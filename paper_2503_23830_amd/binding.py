@@ -1,0 +1,195 @@
+"""Thin ctypes binding over liborch.so: argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels.  torch supplies
+device memory (``torch.empty``), raw pointers (``data_ptr()``) and the current
+HIP stream; nothing here computes.  There is no CPU fallback: if the library is
+missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "liborch.so")
+_lib = None
+
+EXPORTS = ("orch_balance_workspace", "orch_balance", "orch_pack_workspace", "orch_pack",
+           "orch_varlen_attn_workspace", "orch_varlen_attn_fwd", "orch_last_error",
+           "orch_attn_variant")
+
+
+class OrchError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__("liborch status %d: %s" % (code, msg))
+        self.code = code
+
+
+class _Phase(C.Structure):
+    _fields_ = [("a", C.c_uint64), ("b", C.c_uint64)]
+
+
+class _Assignment(C.Structure):
+    _fields_ = [("inst", C.c_void_p), ("order", C.c_void_p), ("seq_off", C.c_void_p),
+                ("tok_off", C.c_void_p), ("cu_seqlens", C.c_void_p), ("loads", C.c_void_p),
+                ("dev_status", C.c_void_p)]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """dlopen liborch.so (built in-tree by build.py); raises if it is absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise OrchError(-4, "liborch.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+    lib = C.CDLL(_LIB_PATH)
+    lib.orch_balance_workspace.restype = C.c_size_t
+    lib.orch_balance_workspace.argtypes = [C.c_int32, C.c_int32]
+    lib.orch_pack_workspace.restype = C.c_size_t
+    lib.orch_pack_workspace.argtypes = [C.c_int32, C.c_int32]
+    lib.orch_varlen_attn_workspace.restype = C.c_size_t
+    lib.orch_varlen_attn_workspace.argtypes = [C.c_int32]
+    lib.orch_balance.restype = C.c_int
+    lib.orch_balance.argtypes = [C.c_void_p, C.c_int32, C.c_int32, _Phase, _Assignment, C.c_void_p,
+                                 C.c_size_t, C.c_void_p]
+    lib.orch_pack.restype = C.c_int
+    lib.orch_pack.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int64,
+                              C.c_int32, C.c_int64, _Assignment, C.c_int32, C.c_int32, C.c_void_p,
+                              C.c_size_t, C.c_void_p]
+    lib.orch_varlen_attn_fwd.restype = C.c_int
+    lib.orch_varlen_attn_fwd.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                         C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                         C.c_int32, C.c_int32, C.c_float, C.c_int32, C.c_void_p,
+                                         C.c_size_t, C.c_void_p]
+    lib.orch_last_error.restype = C.c_char_p
+    lib.orch_attn_variant.restype = C.c_char_p
+    _lib = lib
+    return lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise OrchError(rc, load_library().orch_last_error().decode())
+
+
+def _stream(device) -> int:
+    return torch.cuda.current_stream(device).cuda_stream
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _workspace(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+@dataclass
+class Assignment:
+    """Device tensors written by balance (see orch_assignment in include/orch.h)."""
+    inst: torch.Tensor
+    order: torch.Tensor
+    seq_off: torch.Tensor
+    tok_off: torch.Tensor
+    cu_seqlens: torch.Tensor
+    loads: torch.Tensor       # int64 storage holding u64 values
+    dev_status: torch.Tensor
+    n: int
+    D: int
+
+    def _c(self) -> _Assignment:
+        return _Assignment(self.inst.data_ptr(), self.order.data_ptr(), self.seq_off.data_ptr(),
+                           self.tok_off.data_ptr(), self.cu_seqlens.data_ptr(), self.loads.data_ptr(),
+                           self.dev_status.data_ptr())
+
+    @staticmethod
+    def empty(n: int, D: int, device) -> "Assignment":
+        e = lambda m, dt: torch.empty(max(m, 1), dtype=dt, device=device)
+        return Assignment(e(n, torch.int32), e(n, torch.int32), e(D + 1, torch.int32),
+                          e(D + 1, torch.int64), e(n + D, torch.int32), e(D, torch.int64),
+                          torch.zeros(1, dtype=torch.int32, device=device), n, D)
+
+
+def balance_workspace(n: int, D: int) -> int:
+    return load_library().orch_balance_workspace(n, D)
+
+
+def pack_workspace(n: int, D: int) -> int:
+    return load_library().orch_pack_workspace(n, D)
+
+
+def varlen_attn_workspace(batch: int) -> int:
+    return load_library().orch_varlen_attn_workspace(batch)
+
+
+def balance(lengths: torch.Tensor, D: int, a: int, b: int, out: Assignment | None = None,
+            ws: torch.Tensor | None = None) -> Assignment:
+    """orch_balance: lengths int32[n] on the GPU -> Assignment (Sec. 5.1, Alg. 1)."""
+    lib = load_library()
+    assert lengths.dtype == torch.int32 and lengths.is_cuda and lengths.is_contiguous()
+    n = lengths.numel()
+    dev = lengths.device
+    if out is None:
+        out = Assignment.empty(n, D, dev)
+    if ws is None:
+        ws = _workspace(lib.orch_balance_workspace(n, max(D, 1)), dev)
+    _check(lib.orch_balance(_ptr(lengths), n, D, _Phase(a, b), out._c(), _ptr(ws), ws.numel(),
+                            C.c_void_p(_stream(dev))))
+    return out
+
+
+def pack(tokens: torch.Tensor, lengths: torch.Tensor, asg: Assignment, inst_begin: int = 0,
+         inst_end: int | None = None, out: torch.Tensor | None = None, packed_rows: int | None = None,
+         ws: torch.Tensor | None = None) -> torch.Tensor:
+    """orch_pack: tokens [T,H] (any 2-byte dtype) -> packed rows of the chosen instances
+    (Sec. 5.2.1).  Without `out`, packed_rows rows are allocated (default T)."""
+    lib = load_library()
+    assert tokens.is_cuda and tokens.is_contiguous() and tokens.element_size() == 2 and tokens.dim() == 2
+    T, H = tokens.shape
+    dev = tokens.device
+    if inst_end is None:
+        inst_end = asg.D
+    if out is None:
+        out = torch.empty((T if packed_rows is None else packed_rows, H), dtype=tokens.dtype, device=dev)
+    assert out.is_contiguous() and out.dtype == tokens.dtype and out.shape[1] == H
+    if ws is None:
+        ws = _workspace(lib.orch_pack_workspace(asg.n, asg.D), dev)
+    _check(lib.orch_pack(_ptr(tokens), _ptr(out), _ptr(lengths), asg.n, asg.D, T, H, out.shape[0],
+                         asg._c(), inst_begin, inst_end, _ptr(ws), ws.numel(), C.c_void_p(_stream(dev))))
+    return out
+
+
+def varlen_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cu_seqlens: torch.Tensor,
+                    causal: bool, scale: float = 0.0, max_seqlen: int = 0, out: torch.Tensor | None = None,
+                    lse: torch.Tensor | None = None, ws: torch.Tensor | None = None) -> torch.Tensor:
+    """orch_varlen_attn_fwd: q [T,Hq,d], k,v [T,Hkv,d] bf16, cu_seqlens int32[batch+1]."""
+    lib = load_library()
+    for t in (q, k, v):
+        assert t.is_cuda and t.is_contiguous() and t.dtype == torch.bfloat16 and t.dim() == 3
+    assert cu_seqlens.dtype == torch.int32 and cu_seqlens.is_cuda and cu_seqlens.is_contiguous()
+    T, Hq, d = q.shape
+    Hkv = k.shape[1]
+    assert k.shape == v.shape == (T, Hkv, d)
+    dev = q.device
+    batch = cu_seqlens.numel() - 1
+    if out is None:
+        out = torch.empty_like(q)
+    if lse is not None:
+        assert lse.dtype == torch.float32 and lse.is_contiguous() and lse.numel() == Hq * T
+    if ws is None:
+        ws = _workspace(lib.orch_varlen_attn_workspace(batch), dev)
+    _check(lib.orch_varlen_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(cu_seqlens),
+                                    batch, T, max_seqlen, Hq, Hkv, d, float(scale), 1 if causal else 0,
+                                    _ptr(ws), ws.numel(), C.c_void_p(_stream(dev))))
+    return out
+
+
+def attn_variant() -> str:
+    return load_library().orch_attn_variant().decode()

@@ -1,0 +1,94 @@
+// The C ABI of liborch: argument validation, then the launchers.
+#include <string.h>
+
+#include "common.h"
+
+namespace orch {
+
+static thread_local char g_err[512] = "";
+static thread_local char g_variant[128] = "";
+
+void set_error(const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+}
+
+void set_attn_variant(const char *name)
+{
+    strncpy(g_variant, name, sizeof g_variant - 1);
+    g_variant[sizeof g_variant - 1] = 0;
+}
+
+static bool assignment_complete(const orch_assignment &a)
+{
+    return a.inst && a.order && a.seq_off && a.tok_off && a.cu_seqlens && a.loads && a.dev_status;
+}
+
+}  // namespace orch
+
+using namespace orch;
+
+extern "C" {
+
+const char *orch_last_error(void) { return g_err; }
+const char *orch_attn_variant(void) { return g_variant; }
+
+size_t orch_balance_workspace(int32_t n, int32_t D) { return balance_ws_bytes(n, D); }
+size_t orch_pack_workspace(int32_t n, int32_t D) { return pack_ws_bytes(n, D); }
+size_t orch_varlen_attn_workspace(int32_t batch) { return attn_ws_bytes(batch); }
+
+int orch_balance(const int32_t *lengths, int32_t n, int32_t D, orch_phase phase, orch_assignment out,
+                 void *ws, size_t ws_bytes, void *stream)
+{
+    if (n < 0) ORCH_FAIL(ORCH_EINVAL, "orch_balance: n = %d < 0", n);
+    if (D < 1) ORCH_FAIL(ORCH_EINVAL, "orch_balance: D = %d < 1", D);
+    if (D > 4096) ORCH_FAIL(ORCH_EUNSUPPORTED, "orch_balance: D = %d > 4096", D);
+    if (n > 0 && !lengths) ORCH_FAIL(ORCH_EINVAL, "orch_balance: lengths is NULL");
+    if (!assignment_complete(out)) ORCH_FAIL(ORCH_EINVAL, "orch_balance: an output pointer is NULL");
+    if (!ws) ORCH_FAIL(ORCH_EINVAL, "orch_balance: workspace is NULL");
+    if ((uintptr_t)ws & 255) ORCH_FAIL(ORCH_EINVAL, "orch_balance: workspace not 256-byte aligned");
+    return launch_balance(lengths, n, D, phase, out, ws, ws_bytes, (hipStream_t)stream);
+}
+
+int orch_pack(const void *tokens, void *packed, const int32_t *lengths, int32_t n, int32_t D, int64_t T,
+              int32_t H, int64_t packed_rows, orch_assignment a, int32_t inst_begin, int32_t inst_end,
+              void *ws, size_t ws_bytes, void *stream)
+{
+    if (n < 0 || D < 1) ORCH_FAIL(ORCH_EINVAL, "orch_pack: n = %d, D = %d", n, D);
+    if (T < 0 || packed_rows < 0) ORCH_FAIL(ORCH_EINVAL, "orch_pack: T = %lld, packed_rows = %lld", (long long)T, (long long)packed_rows);
+    if (H < 1) ORCH_FAIL(ORCH_EINVAL, "orch_pack: H = %d < 1", H);
+    if (inst_begin < 0 || inst_end > D || inst_begin > inst_end)
+        ORCH_FAIL(ORCH_EINVAL, "orch_pack: instance range [%d, %d) outside [0, %d]", inst_begin, inst_end, D);
+    if (n > 0 && !lengths) ORCH_FAIL(ORCH_EINVAL, "orch_pack: lengths is NULL");
+    if ((T > 0 && !tokens) || (packed_rows > 0 && !packed)) ORCH_FAIL(ORCH_EINVAL, "orch_pack: a row buffer is NULL");
+    if (((uintptr_t)tokens | (uintptr_t)packed) & 1) ORCH_FAIL(ORCH_EINVAL, "orch_pack: row buffers must be 2-byte aligned");
+    if (!assignment_complete(a)) ORCH_FAIL(ORCH_EINVAL, "orch_pack: an assignment pointer is NULL");
+    if (!ws) ORCH_FAIL(ORCH_EINVAL, "orch_pack: workspace is NULL");
+    if ((uintptr_t)ws & 255) ORCH_FAIL(ORCH_EINVAL, "orch_pack: workspace not 256-byte aligned");
+    return launch_pack(tokens, packed, lengths, n, D, T, H, packed_rows, a, inst_begin, inst_end, ws,
+                       ws_bytes, (hipStream_t)stream);
+}
+
+int orch_varlen_attn_fwd(const void *q, const void *k, const void *v, void *out, float *lse,
+                         const int32_t *cu_seqlens, int32_t batch, int32_t total_tokens,
+                         int32_t max_seqlen, int32_t Hq, int32_t Hkv, int32_t d, float scale,
+                         int32_t causal, void *ws, size_t ws_bytes, void *stream)
+{
+    if (batch < 0 || total_tokens < 0) ORCH_FAIL(ORCH_EINVAL, "orch_varlen_attn_fwd: batch = %d, total_tokens = %d", batch, total_tokens);
+    if (max_seqlen < 0 || max_seqlen > total_tokens) ORCH_FAIL(ORCH_EINVAL, "orch_varlen_attn_fwd: max_seqlen = %d outside [0, %d]", max_seqlen, total_tokens);
+    if (Hq < 1 || Hkv < 1 || Hq % Hkv) ORCH_FAIL(ORCH_EINVAL, "orch_varlen_attn_fwd: Hq = %d, Hkv = %d", Hq, Hkv);
+    if (d != 64 && d != 128) ORCH_FAIL(ORCH_EUNSUPPORTED, "orch_varlen_attn_fwd: head_dim %d (64 and 128 are built)", d);
+    if (!cu_seqlens) ORCH_FAIL(ORCH_EINVAL, "orch_varlen_attn_fwd: cu_seqlens is NULL");
+    if (total_tokens > 0 && (!q || !k || !v || !out)) ORCH_FAIL(ORCH_EINVAL, "orch_varlen_attn_fwd: q, k, v or out is NULL");
+    if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) & 15)
+        ORCH_FAIL(ORCH_EINVAL, "orch_varlen_attn_fwd: q, k, v, out must be 16-byte aligned");
+    if (!ws) ORCH_FAIL(ORCH_EINVAL, "orch_varlen_attn_fwd: workspace is NULL");
+    if ((uintptr_t)ws & 255) ORCH_FAIL(ORCH_EINVAL, "orch_varlen_attn_fwd: workspace not 256-byte aligned");
+    return launch_attn(q, k, v, out, lse, cu_seqlens, batch, total_tokens, Hq, Hkv, d, scale, causal, ws,
+                       ws_bytes, (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,44 @@
+// Internal helpers shared by the HIP translation units of liborch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdarg.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "orch.h"
+
+namespace orch {
+
+// Thread-local message behind orch_last_error().
+void set_error(const char *fmt, ...);
+void set_attn_variant(const char *name);
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+#define ORCH_FAIL(code, ...)            \
+    do {                                \
+        ::orch::set_error(__VA_ARGS__); \
+        return (code);                  \
+    } while (0)
+
+#define ORCH_HIP_CHECK(expr)                                                        \
+    do {                                                                            \
+        hipError_t e_ = (expr);                                                     \
+        if (e_ != hipSuccess) ORCH_FAIL(ORCH_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+// Launchers implemented per translation unit (host side).
+int launch_balance(const int32_t *lengths, int32_t n, int32_t D, orch_phase phase,
+                   orch_assignment out, void *ws, size_t ws_bytes, hipStream_t stream);
+int launch_pack(const void *tokens, void *packed, const int32_t *lengths, int32_t n, int32_t D,
+                int64_t T, int32_t H, int64_t packed_rows, orch_assignment a, int32_t inst_begin,
+                int32_t inst_end, void *ws, size_t ws_bytes, hipStream_t stream);
+int launch_attn(const void *q, const void *k, const void *v, void *out, float *lse,
+                const int32_t *cu_seqlens, int32_t batch, int32_t total_tokens, int32_t Hq,
+                int32_t Hkv, int32_t d, float scale, int32_t causal, void *ws, size_t ws_bytes,
+                hipStream_t stream);
+size_t balance_ws_bytes(int32_t n, int32_t D);
+size_t pack_ws_bytes(int32_t n, int32_t D);
+size_t attn_ws_bytes(int32_t batch);
+
+}  // namespace orch
