@@ -41,6 +41,9 @@ def main():
     ap.add_argument("--config", type=int, default=4, help="workload C1..C5 (C5 packs one instance's share)")
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="after the timed loop run one plain 1 GiB device copy (a known-size kernel "
+                         "against which rocprofv3 byte counters are scaled)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the attention oracle sample")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -135,6 +138,13 @@ def main():
     bal_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
     pack_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
     attn_ms = float(np.mean([e[2].elapsed_time(e[3]) for e in events]))
+
+    if args.calib_copy:
+        ca = torch.zeros(1 << 29, dtype=torch.int16, device=dev)
+        cb = torch.empty_like(ca)
+        cb.copy_(ca)
+        torch.cuda.synchronize()
+        del ca, cb
 
     flops = attn_flops(cu_i, w.Hq, w.d, w.causal)
     attn_tflops = flops / (attn_ms * 1e-3) / 1e12

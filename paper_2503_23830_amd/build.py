@@ -8,10 +8,22 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB_PATH = os.path.join(PKG, "liborch.so")
+PROF_PATH = os.path.join(PKG, "orch_prof")
 SOURCES = ["api.hip", "balance.hip", "pack.hip", "attn.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]
+
+
+def _run(cmd):
+    """hipcc's host pass prints one harmless 'not a recognized feature' line per
+    -packed-fp32-ops mention; drop those, keep everything else."""
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    for line in r.stdout.splitlines():
+        if "packed-fp32-ops" not in line:
+            print(line, flush=True)
+    if r.returncode != 0:
+        raise subprocess.CalledProcessError(r.returncode, cmd)
 
 
 def build_library(verbose: bool = False) -> str:
@@ -22,8 +34,17 @@ def build_library(verbose: bool = False) -> str:
           [os.path.join(CSRC, s) for s in SOURCES]
     if verbose:
         print(" ".join(cmd), flush=True)
-    subprocess.check_call(cmd)
+    _run(cmd)
     os.replace(tmp, LIB_PATH)
+    # torch-free profiler driver, linked against the library it sits beside
+    prof = [hipcc, "--offload-arch=gfx950", "-O2", "-std=c++17", "-Wno-unused-command-line-argument",
+            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+            "-I", os.path.join(ROOT, "include"), "-o", PROF_PATH + ".tmp",
+            os.path.join(CSRC, "orch_prof.hip"), "-L", PKG, "-lorch", "-Wl,-rpath,$ORIGIN"]
+    if verbose:
+        print(" ".join(prof), flush=True)
+    _run(prof)
+    os.replace(PROF_PATH + ".tmp", PROF_PATH)
     return LIB_PATH
 
 

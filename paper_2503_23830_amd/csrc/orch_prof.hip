@@ -1,0 +1,189 @@
+// orch_prof: a torch-free driver of liborch for profiler runs (rocprofv3
+// --kernel-trace / --pmc).  It reads a binary int32 lengths file (written by
+// `python -m paper_2503_23830_amd.dump_lengths`), fills synthetic rows and
+// q/k/v on the device, runs balance -> pack -> varlen attention `steps` times
+// through the C ABI, and finishes with one plain copy kernel of known size
+// against which byte counters can be scaled.
+//
+//   orch_prof lengths.bin D a b H Hq Hkv d causal steps [pack_all]
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <stdlib.h>
+
+#include <algorithm>
+#include <vector>
+
+#include "orch.h"
+
+#define CK(x)                                                                              \
+    do {                                                                                   \
+        hipError_t e_ = (x);                                                               \
+        if (e_ != hipSuccess) { fprintf(stderr, "%s: %s\n", #x, hipGetErrorString(e_)); exit(1); } \
+    } while (0)
+#define OK(x)                                                                          \
+    do {                                                                               \
+        int r_ = (x);                                                                  \
+        if (r_ != 0) { fprintf(stderr, "%s -> %d: %s\n", #x, r_, orch_last_error()); exit(1); } \
+    } while (0)
+
+__device__ __forceinline__ uint64_t mix(uint64_t x)
+{
+    x += 0x9E3779B97F4A7C15ull;
+    x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
+    x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
+    return x ^ (x >> 31);
+}
+
+// opaque 16-bit words for the token rows
+__global__ void fill_words(uint16_t *p, size_t count, uint64_t seed)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x)
+        p[i] = (uint16_t)(mix(i ^ seed) >> 40);
+}
+
+// bf16 values with roughly unit variance (sum of four uniforms, centred)
+__global__ void fill_bf16(uint16_t *p, size_t count, uint64_t seed)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x) {
+        uint64_t h = mix(i ^ seed);
+        float s = 0.f;
+        for (int j = 0; j < 4; ++j) s += (float)((h >> (16 * j)) & 0xffff) * (1.0f / 65536.0f);
+        float z = (s - 2.0f) * 1.7320508f;
+        uint32_t u = __float_as_uint(z);
+        p[i] = (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+    }
+}
+
+// the known-size kernel: reads `count` 16-byte words and writes them once
+__global__ void calib_copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t count)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x)
+        dst[i] = src[i];
+}
+
+int main(int argc, char **argv)
+{
+    if (argc < 11) {
+        fprintf(stderr, "usage: %s lengths.bin D a b H Hq Hkv d causal steps [pack_all=1]\n", argv[0]);
+        return 2;
+    }
+    const char *path = argv[1];
+    const int D = atoi(argv[2]);
+    const uint64_t a = strtoull(argv[3], 0, 10), b = strtoull(argv[4], 0, 10);
+    const int H = atoi(argv[5]), Hq = atoi(argv[6]), Hkv = atoi(argv[7]), d = atoi(argv[8]);
+    const int causal = atoi(argv[9]), steps = atoi(argv[10]);
+    const int pack_all = argc > 11 ? atoi(argv[11]) : 1;
+
+    FILE *f = fopen(path, "rb");
+    if (!f) { perror(path); return 1; }
+    std::vector<int32_t> L;
+    int32_t x;
+    while (fread(&x, 4, 1, f) == 1) L.push_back(x);
+    fclose(f);
+    const int n = (int)L.size();
+    int64_t T = 0;
+    for (int32_t l : L) T += l;
+    printf("n=%d D=%d T=%lld H=%d heads=%d/%d d=%d causal=%d\n", n, D, (long long)T, H, Hq, Hkv, d, causal);
+
+    hipStream_t st;
+    CK(hipStreamCreate(&st));
+    int32_t *dL;
+    CK(hipMalloc(&dL, sizeof(int32_t) * std::max(n, 1)));
+    CK(hipMemcpy(dL, L.data(), sizeof(int32_t) * n, hipMemcpyHostToDevice));
+    orch_assignment as;
+    CK(hipMalloc(&as.inst, 4 * std::max(n, 1)));
+    CK(hipMalloc(&as.order, 4 * std::max(n, 1)));
+    CK(hipMalloc(&as.seq_off, 4 * (D + 1)));
+    CK(hipMalloc(&as.tok_off, 8 * (D + 1)));
+    CK(hipMalloc(&as.cu_seqlens, 4 * (n + D)));
+    CK(hipMalloc(&as.loads, 8 * D));
+    CK(hipMalloc(&as.dev_status, 4));
+    size_t wsb = orch_balance_workspace(n, D), wsp = orch_pack_workspace(n, D);
+    void *ws_b, *ws_p;
+    CK(hipMalloc(&ws_b, wsb));
+    CK(hipMalloc(&ws_p, wsp));
+    OK(orch_balance(dL, n, D, orch_phase{a, b}, as, ws_b, wsb, st));
+    CK(hipStreamSynchronize(st));
+
+    std::vector<uint64_t> loads(D);
+    std::vector<int32_t> seq_off(D + 1), cu(n + D);
+    std::vector<int64_t> tok_off(D + 1);
+    int32_t status;
+    CK(hipMemcpy(loads.data(), as.loads, 8 * D, hipMemcpyDeviceToHost));
+    CK(hipMemcpy(seq_off.data(), as.seq_off, 4 * (D + 1), hipMemcpyDeviceToHost));
+    CK(hipMemcpy(tok_off.data(), as.tok_off, 8 * (D + 1), hipMemcpyDeviceToHost));
+    CK(hipMemcpy(cu.data(), as.cu_seqlens, 4 * (n + D), hipMemcpyDeviceToHost));
+    CK(hipMemcpy(&status, as.dev_status, 4, hipMemcpyDeviceToHost));
+    if (status != 0) { fprintf(stderr, "dev_status %d\n", status); return 1; }
+    const int istar = (int)(std::max_element(loads.begin(), loads.end()) - loads.begin());
+    const int batch = seq_off[istar + 1] - seq_off[istar];
+    const int32_t *cu_dev = as.cu_seqlens + seq_off[istar] + istar;
+    const int32_t *cu_host = cu.data() + seq_off[istar] + istar;
+    const int Ti = cu_host[batch];
+    double pairs = 0;
+    for (int t = 0; t < batch; ++t) {
+        double l = cu_host[t + 1] - cu_host[t];
+        pairs += causal ? l * (l + 1) / 2 : l * l;
+    }
+    const double flops = 4.0 * d * Hq * pairs;
+
+    // pack buffers: everything, or only the straggler instance's range
+    const int ib = pack_all ? 0 : istar, ie = pack_all ? D : istar + 1;
+    const int64_t prow = tok_off[ie] - tok_off[ib];
+    uint16_t *tokens, *packed;
+    CK(hipMalloc(&tokens, (size_t)std::max<int64_t>(T, 1) * H * 2));
+    CK(hipMalloc(&packed, (size_t)std::max<int64_t>(prow, 1) * H * 2));
+    hipLaunchKernelGGL(fill_words, dim3(4096), dim3(256), 0, st, tokens, (size_t)T * H, 1234ull);
+
+    uint16_t *q, *k, *v, *o;
+    const size_t qn = (size_t)Ti * Hq * d, kn = (size_t)Ti * Hkv * d;
+    CK(hipMalloc(&q, std::max<size_t>(qn, 1) * 2));
+    CK(hipMalloc(&o, std::max<size_t>(qn, 1) * 2));
+    CK(hipMalloc(&k, std::max<size_t>(kn, 1) * 2));
+    CK(hipMalloc(&v, std::max<size_t>(kn, 1) * 2));
+    hipLaunchKernelGGL(fill_bf16, dim3(4096), dim3(256), 0, st, q, qn, 11ull);
+    hipLaunchKernelGGL(fill_bf16, dim3(4096), dim3(256), 0, st, k, kn, 22ull);
+    hipLaunchKernelGGL(fill_bf16, dim3(4096), dim3(256), 0, st, v, kn, 33ull);
+    size_t wsa = orch_varlen_attn_workspace(batch);
+    void *ws_a;
+    CK(hipMalloc(&ws_a, wsa));
+    CK(hipStreamSynchronize(st));
+
+    hipEvent_t e0, e1, e2, e3;
+    CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1)); CK(hipEventCreate(&e2)); CK(hipEventCreate(&e3));
+    double tb = 0, tp = 0, ta = 0;
+    for (int s = 0; s < steps + 1; ++s) {  // first pass is a warm-up
+        CK(hipEventRecord(e0, st));
+        OK(orch_balance(dL, n, D, orch_phase{a, b}, as, ws_b, wsb, st));
+        CK(hipEventRecord(e1, st));
+        OK(orch_pack(tokens, packed, dL, n, D, T, H, prow, as, ib, ie, ws_p, wsp, st));
+        CK(hipEventRecord(e2, st));
+        OK(orch_varlen_attn_fwd(q, k, v, o, nullptr, cu_dev, batch, Ti, 0, Hq, Hkv, d, 0.f, causal, ws_a, wsa, st));
+        CK(hipEventRecord(e3, st));
+        CK(hipStreamSynchronize(st));
+        float m;
+        if (s > 0) {
+            CK(hipEventElapsedTime(&m, e0, e1)); tb += m;
+            CK(hipEventElapsedTime(&m, e1, e2)); tp += m;
+            CK(hipEventElapsedTime(&m, e2, e3)); ta += m;
+        }
+    }
+    CK(hipMemcpy(&status, as.dev_status, 4, hipMemcpyDeviceToHost));
+    tb /= steps; tp /= steps; ta /= steps;
+    const double pbytes = 2.0 * (double)prow * H * 2;
+    printf("dev_status=%d instance=%d attn_tokens=%d\n", status, istar, Ti);
+    printf("balance %.3f ms | pack %.3f ms %.1f GB/s (%.3e B) | attn %.3f ms %.1f TFLOP/s (%.3e FLOP) [%s]\n", tb, tp,
+           pbytes / tp / 1e6, pbytes, ta, flops / ta / 1e9, flops, orch_attn_variant());
+
+    // calibration: 1 GiB read + 1 GiB written by a plain copy
+    const size_t cbytes = (size_t)1 << 30;
+    uint4 *ca, *cb;
+    CK(hipMalloc(&ca, cbytes));
+    CK(hipMalloc(&cb, cbytes));
+    CK(hipMemsetAsync(ca, 1, cbytes, st));
+    hipLaunchKernelGGL(calib_copy_kernel, dim3(8192), dim3(256), 0, st, ca, cb, cbytes / 16);
+    CK(hipStreamSynchronize(st));
+    printf("calib_copy_kernel: %zu bytes read, %zu bytes written\n", cbytes, cbytes);
+    return status == 0 ? 0 : 1;
+}
