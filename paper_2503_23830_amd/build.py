@@ -10,7 +10,7 @@ CSRC = os.path.join(PKG, "csrc")
 LIB_PATH = os.path.join(PKG, "liborch.so")
 PROF_PATH = os.path.join(PKG, "orch_prof")
 SOURCES = ["api.hip", "balance.hip", "pack.hip", "attn.hip"]
-FLAGS = os.environ.get("ORCH_EXTRA_FLAGS", "").split() + ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]
 

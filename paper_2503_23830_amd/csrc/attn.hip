@@ -14,8 +14,6 @@
 // rescaling O is a per-lane multiply.  The running maximum is only moved when a
 // row's maximum grows by more than 2^8 (exact: the stale reference cancels in
 // the final division), so O is rarely rescaled after the first tile.
-#include <stdlib.h>
-
 #include <type_traits>
 
 #include "common.h"
@@ -372,38 +370,108 @@ __global__ __launch_bounds__(kThreads, (MB * HD > 128 ? 1 : 2)) void attn_fwd_ke
 
 
 // ---------------------------------------------------------------------------
-// Ping-pong variant: 8 wavefronts (two per SIMD) own 256 query rows, 32 each.
-// The key sequence is walked in 32-key blocks b; a wavefront alternates
-//     M(b): S^T = K_b Q^T  and  O^T += V_{b-1}^T P_{b-1}^T   (16 MFMAs, LDS reads)
-//     V(b): online softmax of block b -> P_b                  (vector ALU),
-//           plus its share of the global -> LDS staging
+// Ping-pong variant: 8 wavefronts (two per SIMD) own 256 query rows, 32 each,
+// and share double-buffered K / V^T tiles of 64 keys.  The key sequence is walked
+// in 32-key blocks b; a wavefront alternates
+//     M(b): S = QK(b), O += PV(b-1)      16 MFMAs (HD = 128), plus its share of
+//                                        the global -> LDS staging
+//     V(b): online softmax of block b    vector ALU; first it requests the LDS
+//                                        fragments of M(b+1), which arrive meanwhile
 // with a workgroup barrier after every phase.  Wavefronts 4..7 run one phase
 // behind wavefronts 0..3, so on every SIMD one wavefront is in its MFMA phase
-// while the other is in its vector-ALU phase: the matrix cores and the vector
-// ALU work at the same time without relying on instruction scheduling.
+// while the other is in its vector-ALU phase: matrix cores and vector ALU work
+// at the same time without relying on instruction scheduling.  (Left to
+// themselves the two wavefronts of a SIMD stay in lockstep and the units take
+// turns.)
 //
-// K and V^T tiles (64 keys = two blocks) are double-buffered in LDS.  With
-// phases numbered t (group 0: M(b) at 2b; group 1: M(b) at 2b+1), tile i's K is
-// read during t in [4i, 4i+3] and its V during [4i+2, 4i+5]; every wavefront
-// stores its share of K_{i+1} in V(2i) and of V_{i+1} in V(2i+1), which for both
-// groups falls after the last read of the buffer being replaced and before the
-// first read of the new tile.
+// LDS hazards, with phases numbered t (group 0: M(b) at 2b, V(b) at 2b+1; group
+// 1 one later): K_{i+1} is stored in M(2i) (t = 4i, 4i+1) into the buffer of
+// K_{i-1}, whose last fragment read was requested in V(2i-2) (t <= 4i-2); its
+// first read is requested in V(2i+1) (t >= 4i+3).  V_{i+1} is stored in M(2i+1)
+// (t = 4i+2, 4i+3) over V_{i-1}, last requested in V(2i-1) (t <= 4i); first
+// requested in V(2i+2) (t >= 4i+5).
+//
+// The MFMA groups are inline asm: MFMAs go back to back, and the hazards the
+// compiler would pad for a builtin MFMA (vector-ALU write -> MFMA read, MFMA
+// write -> vector-ALU read) are padded by hand with s_nop.
 // ---------------------------------------------------------------------------
 constexpr int kPPThreads = 512;
-#ifndef ORCH_DBG_NOSHIFT
-#define ORCH_DBG_NOSHIFT 0
-#endif
-#ifndef ORCH_DBG_TIMING
-#define ORCH_DBG_TIMING 0
-#endif
 
-// Workgroup barrier that orders LDS traffic only: LDS writes of this wavefront
-// are complete before it, but global loads already in flight (the prefetch of a
-// later tile) are NOT waited for, unlike __syncthreads().
 __device__ __forceinline__ void lds_barrier()
 {
+    // LDS writes of this wavefront are complete before the barrier; global loads
+    // in flight (the prefetch of a later tile) are not waited for
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
+
+// four 16-byte LDS reads at addr + O0..O3
+template <int O0, int O1, int O2, int O3>
+__device__ __forceinline__ void lds_rd4(bf16x8 &f0, bf16x8 &f1, bf16x8 &f2, bf16x8 &f3, uint32_t addr)
+{
+    asm volatile(
+        "ds_read_b128 %0, %4 offset:%5\n\t"
+        "ds_read_b128 %1, %4 offset:%6\n\t"
+        "ds_read_b128 %2, %4 offset:%7\n\t"
+        "ds_read_b128 %3, %4 offset:%8\n\t"
+        : "=&v"(f0), "=&v"(f1), "=&v"(f2), "=&v"(f3)
+        : "v"(addr), "n"(O0), "n"(O1), "n"(O2), "n"(O3)
+        : "memory");
+}
+
+#define ORCH_MFMA "v_mfma_f32_32x32x16_bf16 "
+// S = (FIRST ? 0 : S) + sum_j f_j q_j ; with W >= 0 the j-th MFMA first waits
+// until at most W-j LDS reads are outstanding (reads return in order)
+template <bool FIRST, int W>
+__device__ __forceinline__ void mfma_qk4(f32x16 &S, const bf16x8 &f0, const bf16x8 &f1, const bf16x8 &f2,
+                                         const bf16x8 &f3, const bf16x8 &q0, const bf16x8 &q1,
+                                         const bf16x8 &q2, const bf16x8 &q3)
+{
+    if constexpr (FIRST) {
+        if constexpr (W >= 0)
+            asm volatile("s_waitcnt lgkmcnt(%9)\n\t" ORCH_MFMA "%0, %1, %5, 0\n\t"
+                         "s_waitcnt lgkmcnt(%10)\n\t" ORCH_MFMA "%0, %2, %6, %0\n\t"
+                         "s_waitcnt lgkmcnt(%11)\n\t" ORCH_MFMA "%0, %3, %7, %0\n\t"
+                         "s_waitcnt lgkmcnt(%12)\n\t" ORCH_MFMA "%0, %4, %8, %0\n\t"
+                         : "=&v"(S)
+                         : "v"(f0), "v"(f1), "v"(f2), "v"(f3), "v"(q0), "v"(q1), "v"(q2), "v"(q3),
+                           "n"(W), "n"(W - 1), "n"(W - 2), "n"(W - 3));
+        else
+            asm volatile(ORCH_MFMA "%0, %1, %5, 0\n\t" ORCH_MFMA "%0, %2, %6, %0\n\t"
+                         ORCH_MFMA "%0, %3, %7, %0\n\t" ORCH_MFMA "%0, %4, %8, %0\n\t"
+                         : "=&v"(S)
+                         : "v"(f0), "v"(f1), "v"(f2), "v"(f3), "v"(q0), "v"(q1), "v"(q2), "v"(q3));
+    } else {
+        if constexpr (W >= 0)
+            asm volatile("s_waitcnt lgkmcnt(%9)\n\t" ORCH_MFMA "%0, %1, %5, %0\n\t"
+                         "s_waitcnt lgkmcnt(%10)\n\t" ORCH_MFMA "%0, %2, %6, %0\n\t"
+                         "s_waitcnt lgkmcnt(%11)\n\t" ORCH_MFMA "%0, %3, %7, %0\n\t"
+                         "s_waitcnt lgkmcnt(%12)\n\t" ORCH_MFMA "%0, %4, %8, %0\n\t"
+                         : "+v"(S)
+                         : "v"(f0), "v"(f1), "v"(f2), "v"(f3), "v"(q0), "v"(q1), "v"(q2), "v"(q3),
+                           "n"(W), "n"(W - 1), "n"(W - 2), "n"(W - 3));
+        else
+            asm volatile(ORCH_MFMA "%0, %1, %5, %0\n\t" ORCH_MFMA "%0, %2, %6, %0\n\t"
+                         ORCH_MFMA "%0, %3, %7, %0\n\t" ORCH_MFMA "%0, %4, %8, %0\n\t"
+                         : "+v"(S)
+                         : "v"(f0), "v"(f1), "v"(f2), "v"(f3), "v"(q0), "v"(q1), "v"(q2), "v"(q3));
+    }
+}
+// oa += f0 p0 + f1 p1 ; ob += f2 p0 + f3 p1
+__device__ __forceinline__ void mfma_pv4(f32x16 &oa, f32x16 &ob, const bf16x8 &f0, const bf16x8 &f1,
+                                         const bf16x8 &f2, const bf16x8 &f3, const bf16x8 &p0,
+                                         const bf16x8 &p1)
+{
+    asm volatile(ORCH_MFMA "%0, %2, %6, %0\n\t" ORCH_MFMA "%1, %4, %6, %1\n\t"
+                 ORCH_MFMA "%0, %3, %7, %0\n\t" ORCH_MFMA "%1, %5, %7, %1\n\t"
+                 : "+v"(oa), "+v"(ob)
+                 : "v"(f0), "v"(f1), "v"(f2), "v"(f3), "v"(p0), "v"(p1));
+}
+#undef ORCH_MFMA
+// all LDS reads issued so far have landed; vector-ALU results written just before
+// (P, rescaled O) are safe to read from an MFMA
+__device__ __forceinline__ void mfma_group_begin() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_nop 7" ::: "memory"); }
+// MFMA results are safe to read from the vector ALU
+__device__ __forceinline__ void mfma_group_end() { asm volatile("s_nop 15\n\ts_nop 7" ::: "memory"); }
 
 template <int HD, bool CAUSAL>
 __global__ __launch_bounds__(kPPThreads) void attn_fwd_pp_kernel(
@@ -413,16 +481,19 @@ __global__ __launch_bounds__(kPPThreads) void attn_fwd_pp_kernel(
     int32_t total_tokens, int32_t Hq, int32_t Hkv, float scale, float scale_log2)
 {
     constexpr int BM = 256;
-    constexpr int KS = HD + 8;
-    constexpr int VS = BN + 8;
-    constexpr int NC = HD / 16;
-    constexpr int NDB = HD / 32;
+    constexpr int KS = HD + 8;    // K tile row stride (elements): 16-byte rows land on distinct banks
+    constexpr int VS = BN + 8;    // V^T tile row stride
+    constexpr int NC = HD / 16;   // 16-wide chunks of the head dimension
+    constexpr int NDB = HD / 32;  // 32-row blocks of O^T
     constexpr int KTILE = BN * KS, VTILE = HD * VS;
     __shared__ __attribute__((aligned(16))) uint16_t Ks[2 * KTILE];
     __shared__ __attribute__((aligned(16))) uint16_t Vt[2 * VTILE];
 
     const int total_tiles = hdr->total_tiles;
     const int group = Hq / Hkv;
+    // block -> (query tile u, head h).  With Hkv a multiple of 8 the kv-head is
+    // chosen by blockIdx % 8, i.e. by XCD, so the blocks that share a K/V stream
+    // share an L2.
     int u, h;
     {
         const int bid = blockIdx.x;
@@ -447,20 +518,20 @@ __global__ __launch_bounds__(kPPThreads) void attn_fwd_pp_kernel(
     const int row0 = cu[seq];
     const int L = cu[seq + 1] - row0;
     const int ntile_q = (L + BM - 1) / BM;
-    const int qt = ntile_q - 1 - (u - tile_off[seq]);
+    const int qt = ntile_q - 1 - (u - tile_off[seq]);  // heaviest (last) tile first
     const int q0 = qt * BM;
 
     const int tid = threadIdx.x, lane = tid & 63;
-    // wave-uniform values are kept in scalar registers so that per-wavefront
-    // decisions become scalar branches
+    // wave-uniform values live in scalar registers: per-wavefront decisions are scalar branches
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, g = lane >> 5;
-    const int grp = ORCH_DBG_NOSHIFT ? 0 : (wave >> 2);  // 0: leading group, 1: one phase behind
+    const int grp = wave >> 2;   // 0: leading group, 1: one phase behind
     // waves w and w+4 share a SIMD; row blocks w and 7-w even out the causal work per SIMD
     const int rblk = wave < 4 ? wave : 11 - wave;
     const int qrow0 = q0 + 32 * rblk;
     const int qm = qrow0 + l32;
 
+    // ---- Q fragments: B operand, column m = lane%32, k = 16c + 8g + [0..7]
     bf16x8 qf[NC];
     {
         const int qm_c = qm < L ? qm : L - 1;
@@ -474,15 +545,18 @@ __global__ __launch_bounds__(kPPThreads) void attn_fwd_pp_kernel(
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc_o[d][e] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
+    // a row's reference maximum moves only when it grows by more than 2^8
     const float lazy_thr = 8.0f / scale_log2;
 
     const int kend = CAUSAL ? min(L, q0 + BM) : L;
     const int ntile_k = (kend + BN - 1) / BN;               // tiles the workgroup stages
-    const int nblk = 2 * ntile_k;                           // 32-key blocks every wavefront steps through
     const int kend_w = CAUSAL ? min(L, qrow0 + 32) : L;
-    const int nblk_w = qrow0 < L ? (kend_w + 31) / 32 : 0;  // blocks this wavefront computes
+    const int nblk_w = qrow0 < L ? (kend_w + 31) / 32 : 0;  // 32-key blocks this wavefront computes
 
-    // ---- global -> register -> LDS staging (512 threads)
+    // ---- global -> register -> LDS staging (512 threads).  Addresses are a
+    // uniform tile base (scalar) plus a 32-bit per-thread offset; rows past the
+    // sequence end repeat row L-1 (they are masked later), tiles past the end
+    // repeat the last tile (the copy lands in a buffer nobody reads again).
     constexpr int KLOADS = BN * (HD / 8) / kPPThreads;      // 16-byte K loads per thread
     constexpr int KROWS_PER_PASS = kPPThreads / (HD / 8);
     constexpr int VBLOCKS = (BN / 4) * (HD / 4);            // 4(key) x 4(dim) blocks per tile
@@ -490,31 +564,35 @@ __global__ __launch_bounds__(kPPThreads) void attn_fwd_pp_kernel(
     u32x4 kreg[KLOADS];
     u32x2 vreg[4];
     const int k_col = (tid % (HD / 8)) * 8, k_row = tid / (HD / 8);
+    // V blocks: 8 adjacent lanes take 8 different key quads (their transposed
+    // 8-byte LDS writes fall on different banks), the next lane bits walk the head dimension
     const int v_dq = (tid >> 3) % (HD / 4);
     const int v_nq = ((tid & 7) + 8 * ((tid >> 3) / (HD / 4))) & 15;
-    const uint16_t *kbase = k + ((size_t)row0 * Hkv + g_kv) * HD + k_col;
-    const uint16_t *vbase = v + ((size_t)row0 * Hkv + g_kv) * HD + 4 * v_dq;
-    const size_t rstride = (size_t)Hkv * HD;
+    const uint32_t rstride_b = (uint32_t)Hkv * HD * 2;      // bytes between consecutive keys
+    const char *kseq = (const char *)(k + ((size_t)row0 * Hkv + g_kv) * HD);
+    const char *vseq = (const char *)(v + ((size_t)row0 * Hkv + g_kv) * HD);
+    // key n = 16t + 8u + 4g + w is stored at slot 16t + 8g + 4u + w, so the 8 keys
+    // a lane contracts in one MFMA are contiguous
     const int v_slot = 16 * (v_nq >> 2) + 8 * (v_nq & 1) + 4 * ((v_nq >> 1) & 1);
 
-    // tile indices past the end are clamped (the copy lands in a buffer nobody
-    // reads again); rows past the sequence end repeat row L-1 and are masked later
     auto load_k = [&](int t) {
         t = t < ntile_k ? t : ntile_k - 1;
+        const char *tb = kseq + (size_t)t * BN * rstride_b;
+        const int lrem = L - 1 - t * BN;
 #pragma unroll
         for (int p = 0; p < KLOADS; ++p) {
-            int n = t * BN + p * KROWS_PER_PASS + k_row;
-            n = n < L ? n : L - 1;
-            kreg[p] = *(const u32x4 *)(kbase + (size_t)n * rstride);
+            const int r = min(p * KROWS_PER_PASS + k_row, lrem);
+            kreg[p] = *(const u32x4 *)(tb + (__umul24((uint32_t)r, rstride_b) + 2u * (uint32_t)k_col));
         }
     };
     auto load_v = [&](int t) {
         t = t < ntile_k ? t : ntile_k - 1;
+        const char *tb = vseq + (size_t)t * BN * rstride_b;
+        const int lrem = L - 1 - t * BN;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            int n = t * BN + 4 * v_nq + j;
-            n = n < L ? n : L - 1;
-            vreg[j] = *(const u32x2 *)(vbase + (size_t)n * rstride);
+            const int r = min(4 * v_nq + j, lrem);
+            vreg[j] = *(const u32x2 *)(tb + (__umul24((uint32_t)r, rstride_b) + 8u * (uint32_t)v_dq));
         }
     };
     auto store_k = [&](int buf) {
@@ -538,200 +616,104 @@ __global__ __launch_bounds__(kPPThreads) void attn_fwd_pp_kernel(
         }
     };
 
-    f32x16 S;      // scores of the current block
+    f32x16 S;      // scores of the current block (S^T: lane = query, 16 keys)
     bf16x8 P[2];   // its probabilities: two 16-key chunks (B operand of P V)
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk) P[kk] = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
 
-    // M phase of block b.  All 16 LDS fragment reads are issued back to back
-    // (inline asm keeps them in this order and in flight together); each MFMA
-    // then waits only until ITS fragment has arrived (LDS returns in order, so
-    // "at most n reads outstanding" means the first 16-n are complete).
-    const uint32_t lds_k0 = (uint32_t)(uintptr_t)(&Ks[0]) + 2u * (uint32_t)(l32 * KS + 8 * g);
-    const uint32_t lds_v0 = (uint32_t)(uintptr_t)(&Vt[0]) + 2u * (uint32_t)(l32 * VS + 8 * g);
-    // The phase is branch-free: a wavefront that does not need block b (beyond its
-    // causal range) still runs the MFMAs -- it would otherwise idle at the barrier
-    // -- on valid staged data, with P = 0 so that O is unchanged.
-    // It is written as two asm blocks so that the order is exactly: all LDS reads,
-    // then per MFMA "wait until my fragment is in, multiply".  The compiler does
-    // not know these are MFMAs, so the hazards it would pad are padded by hand:
-    // s_nop before the second block (vector-ALU write of P / O -> MFMA read) and
-    // after it (MFMA write -> vector-ALU read).
-    auto phase_m = [&](int b) {
-        const int pb = b >= 1 ? b - 1 : 0;
-        const uint32_t ka = lds_k0 + 2u * (uint32_t)(((b >> 1) & 1) * KTILE + 32 * (b & 1) * KS);
-        const uint32_t va = lds_v0 + 2u * (uint32_t)(((pb >> 1) & 1) * VTILE + 32 * (pb & 1));
-        if constexpr (HD == 128) {
-            bf16x8 k0, k1, k2, k3, k4, k5, k6, k7, v0, v1, v2, v3, v4, v5, v6, v7;
-            asm volatile(
-                "ds_read_b128 %1, %17 offset:0\n\t"
-                "ds_read_b128 %2, %17 offset:32\n\t"
-                "ds_read_b128 %3, %17 offset:64\n\t"
-                "ds_read_b128 %4, %17 offset:96\n\t"
-                "ds_read_b128 %5, %17 offset:128\n\t"
-                "ds_read_b128 %6, %17 offset:160\n\t"
-                "ds_read_b128 %7, %17 offset:192\n\t"
-                "ds_read_b128 %8, %17 offset:224\n\t"
-                "ds_read_b128 %9, %18 offset:0\n\t"
-                "ds_read_b128 %10, %18 offset:32\n\t"
-                "ds_read_b128 %11, %18 offset:%27\n\t"
-                "ds_read_b128 %12, %18 offset:%28\n\t"
-                "ds_read_b128 %13, %18 offset:%29\n\t"
-                "ds_read_b128 %14, %18 offset:%30\n\t"
-                "ds_read_b128 %15, %18 offset:%31\n\t"
-                "ds_read_b128 %16, %18 offset:%32\n\t"
-                "s_waitcnt lgkmcnt(15)\n\t"
-                "v_mfma_f32_32x32x16_bf16 %0, %1, %19, 0\n\t"
-                "s_waitcnt lgkmcnt(14)\n\t"
-                "v_mfma_f32_32x32x16_bf16 %0, %2, %20, %0\n\t"
-                "s_waitcnt lgkmcnt(13)\n\t"
-                "v_mfma_f32_32x32x16_bf16 %0, %3, %21, %0\n\t"
-                "s_waitcnt lgkmcnt(12)\n\t"
-                "v_mfma_f32_32x32x16_bf16 %0, %4, %22, %0\n\t"
-                "s_waitcnt lgkmcnt(11)\n\t"
-                "v_mfma_f32_32x32x16_bf16 %0, %5, %23, %0\n\t"
-                "s_waitcnt lgkmcnt(10)\n\t"
-                "v_mfma_f32_32x32x16_bf16 %0, %6, %24, %0\n\t"
-                "s_waitcnt lgkmcnt(9)\n\t"
-                "v_mfma_f32_32x32x16_bf16 %0, %7, %25, %0\n\t"
-                "s_waitcnt lgkmcnt(8)\n\t"
-                "v_mfma_f32_32x32x16_bf16 %0, %8, %26, %0\n\t"
-                : "=&v"(S), "=&v"(k0), "=&v"(k1), "=&v"(k2), "=&v"(k3), "=&v"(k4), "=&v"(k5), "=&v"(k6),
-                  "=&v"(k7), "=&v"(v0), "=&v"(v1), "=&v"(v2), "=&v"(v3), "=&v"(v4), "=&v"(v5), "=&v"(v6),
-                  "=&v"(v7)
-                : "v"(ka), "v"(va), "v"(qf[0]), "v"(qf[1]), "v"(qf[2]), "v"(qf[3]), "v"(qf[4]), "v"(qf[5]),
-                  "v"(qf[6]), "v"(qf[7]), "n"(2 * 32 * VS), "n"(2 * 32 * VS + 32), "n"(4 * 32 * VS),
-                  "n"(4 * 32 * VS + 32), "n"(6 * 32 * VS), "n"(6 * 32 * VS + 32)
-                : "memory");
-            asm volatile(
-                "s_nop 7\n\t"
-                "s_waitcnt lgkmcnt(7)\n\t"
-                "v_mfma_f32_32x32x16_bf16 %0, %4, %12, %0\n\t"
-                "s_waitcnt lgkmcnt(6)\n\t"
-                "v_mfma_f32_32x32x16_bf16 %0, %5, %13, %0\n\t"
-                "s_waitcnt lgkmcnt(5)\n\t"
-                "v_mfma_f32_32x32x16_bf16 %1, %6, %12, %1\n\t"
-                "s_waitcnt lgkmcnt(4)\n\t"
-                "v_mfma_f32_32x32x16_bf16 %1, %7, %13, %1\n\t"
-                "s_waitcnt lgkmcnt(3)\n\t"
-                "v_mfma_f32_32x32x16_bf16 %2, %8, %12, %2\n\t"
-                "s_waitcnt lgkmcnt(2)\n\t"
-                "v_mfma_f32_32x32x16_bf16 %2, %9, %13, %2\n\t"
-                "s_waitcnt lgkmcnt(1)\n\t"
-                "v_mfma_f32_32x32x16_bf16 %3, %10, %12, %3\n\t"
-                "s_waitcnt lgkmcnt(0)\n\t"
-                "v_mfma_f32_32x32x16_bf16 %3, %11, %13, %3\n\t"
-                "s_nop 15\n\t"
-                : "+v"(acc_o[0]), "+v"(acc_o[1]), "+v"(acc_o[2]), "+v"(acc_o[3])
-                : "v"(v0), "v"(v1), "v"(v2), "v"(v3), "v"(v4), "v"(v5), "v"(v6), "v"(v7), "v"(P[0]), "v"(P[1])
-                : "memory");
-        } else {
-            bf16x8 k0, k1, k2, k3, v0, v1, v2, v3;
-            asm volatile(
-                "ds_read_b128 %1, %9 offset:0\n\t"
-                "ds_read_b128 %2, %9 offset:32\n\t"
-                "ds_read_b128 %3, %9 offset:64\n\t"
-                "ds_read_b128 %4, %9 offset:96\n\t"
-                "ds_read_b128 %5, %10 offset:0\n\t"
-                "ds_read_b128 %6, %10 offset:32\n\t"
-                "ds_read_b128 %7, %10 offset:%15\n\t"
-                "ds_read_b128 %8, %10 offset:%16\n\t"
-                "s_waitcnt lgkmcnt(7)\n\t"
-                "v_mfma_f32_32x32x16_bf16 %0, %1, %11, 0\n\t"
-                "s_waitcnt lgkmcnt(6)\n\t"
-                "v_mfma_f32_32x32x16_bf16 %0, %2, %12, %0\n\t"
-                "s_waitcnt lgkmcnt(5)\n\t"
-                "v_mfma_f32_32x32x16_bf16 %0, %3, %13, %0\n\t"
-                "s_waitcnt lgkmcnt(4)\n\t"
-                "v_mfma_f32_32x32x16_bf16 %0, %4, %14, %0\n\t"
-                : "=&v"(S), "=&v"(k0), "=&v"(k1), "=&v"(k2), "=&v"(k3), "=&v"(v0), "=&v"(v1), "=&v"(v2),
-                  "=&v"(v3)
-                : "v"(ka), "v"(va), "v"(qf[0]), "v"(qf[1]), "v"(qf[2]), "v"(qf[3]), "n"(2 * 32 * VS),
-                  "n"(2 * 32 * VS + 32)
-                : "memory");
-            asm volatile(
-                "s_nop 7\n\t"
-                "s_waitcnt lgkmcnt(3)\n\t"
-                "v_mfma_f32_32x32x16_bf16 %0, %2, %6, %0\n\t"
-                "s_waitcnt lgkmcnt(2)\n\t"
-                "v_mfma_f32_32x32x16_bf16 %0, %3, %7, %0\n\t"
-                "s_waitcnt lgkmcnt(1)\n\t"
-                "v_mfma_f32_32x32x16_bf16 %1, %4, %6, %1\n\t"
-                "s_waitcnt lgkmcnt(0)\n\t"
-                "v_mfma_f32_32x32x16_bf16 %1, %5, %7, %1\n\t"
-                "s_nop 15\n\t"
-                : "+v"(acc_o[0]), "+v"(acc_o[1])
-                : "v"(v0), "v"(v1), "v"(v2), "v"(v3), "v"(P[0]), "v"(P[1])
-                : "memory");
-        }
-    };
     // softmax of block b: S -> P, running statistics, rescale of O when the
-    // reference maximum moves
-    auto softmax = [&](bool masked, int b) {
-        if (masked) {
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int n = 32 * b + 8 * (e >> 2) + 4 * g + (e & 3);
-                const bool vis = n < L && (!CAUSAL || n <= qm);
-                if (!vis) S[e] = -INFINITY;
-            }
-        }
-        float tmax = S[0];
-#pragma unroll
-        for (int e = 1; e < 16; ++e) tmax = fmaxf(tmax, S[e]);
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-        const bool upd = tmax > m_run + lazy_thr;
-        const float m_new = upd ? tmax : m_run;
-        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-        if (__any(upd)) {
-            const float alpha = upd ? __builtin_amdgcn_exp2f((m_run - m_use) * scale_log2) : 1.0f;
-            l_run *= alpha;
-#pragma unroll
-            for (int d = 0; d < NDB; ++d)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) acc_o[d][e] *= alpha;
-        }
-        m_run = m_new;
-        const float mbias = m_use * scale_log2;
-        float psum = 0.f;
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            u32x4 pk;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float p0 = __builtin_amdgcn_exp2f(S[8 * kk + 2 * e] * scale_log2 - mbias);
-                const float p1 = __builtin_amdgcn_exp2f(S[8 * kk + 2 * e + 1] * scale_log2 - mbias);
-                psum += p0 + p1;
-                pk[e] = pack_bf16(p0, p1);
-            }
-            P[kk] = __builtin_bit_cast(bf16x8, pk);
-        }
-        l_run += psum;
-    };
-    auto softmax_or_skip = [&](int b) {
+    // reference maximum moves.  A block beyond the wavefront's causal range gets
+    // P = 0: its MFMAs still run (branch-free groups) and leave O unchanged.
+    auto softmax = [&](int b) {
         if (b < nblk_w) {
             const bool masked = (32 * b + 32 > L) || (CAUSAL && 32 * b + 31 > qrow0);
-            softmax(masked, b);
+            if (masked) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int n = 32 * b + 8 * (e >> 2) + 4 * g + (e & 3);
+                    const bool vis = n < L && (!CAUSAL || n <= qm);
+                    if (!vis) S[e] = -INFINITY;
+                }
+            }
+            float tmax = S[0];
+#pragma unroll
+            for (int e = 1; e < 16; ++e) tmax = fmaxf(tmax, S[e]);
+            {   // the other half of the row lives in lane ^ 32
+                const uint32_t tb = __float_as_uint(tmax);
+                const auto sw = __builtin_amdgcn_permlane32_swap(tb, tb, false, false);
+                tmax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+            }
+            const bool upd = tmax > m_run + lazy_thr;
+            const float m_new = upd ? tmax : m_run;
+            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+            if (__any(upd)) {
+                const float alpha = upd ? __builtin_amdgcn_exp2f((m_run - m_use) * scale_log2) : 1.0f;
+                l_run *= alpha;
+#pragma unroll
+                for (int d = 0; d < NDB; ++d)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) acc_o[d][e] *= alpha;
+            }
+            m_run = m_new;
+            const float mbias = m_use * scale_log2;
+            float psum = 0.f;
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk) {
+                u32x4 pk;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float p0 = __builtin_amdgcn_exp2f(S[8 * kk + 2 * e] * scale_log2 - mbias);
+                    const float p1 = __builtin_amdgcn_exp2f(S[8 * kk + 2 * e + 1] * scale_log2 - mbias);
+                    psum += p0 + p1;
+                    pk[e] = pack_bf16(p0, p1);
+                }
+                P[kk] = __builtin_bit_cast(bf16x8, pk);
+            }
+            l_run += psum;
         } else {
 #pragma unroll
             for (int kk = 0; kk < 2; ++kk) P[kk] = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
         }
     };
-    // V phases of the two blocks of tile i.  The staging is written without any
-    // parity test so that the prefetch registers have one definition per loop
-    // trip: K_{i+1} replaces K_{i-1} in the even phase, V_{i+1} replaces V_{i-1}
-    // in the odd one, and each new global load lands in the registers just stored.
-    auto phase_v_even = [&](int i) {
-        softmax_or_skip(2 * i);
-        store_k((i + 1) & 1);
-        asm volatile("" ::: "memory");
-        load_k(i + 2);
+
+    // per-lane LDS byte addresses of the fragments (block 0 of buffer 0)
+    const uint32_t lds_k0 = (uint32_t)(uintptr_t)(&Ks[0]) + 2u * (uint32_t)(l32 * KS + 8 * g);
+    const uint32_t lds_v0 = (uint32_t)(uintptr_t)(&Vt[0]) + 2u * (uint32_t)(l32 * VS + 8 * g);
+    constexpr int VD = 2 * 32 * VS;  // bytes between 32-row blocks of V^T
+    bf16x8 kf[NC], vf[2 * NDB];
+    auto read_k = [&](uint32_t a) {
+        lds_rd4<0, 32, 64, 96>(kf[0], kf[1], kf[2], kf[3], a);
+        if constexpr (NC == 8) lds_rd4<128, 160, 192, 224>(kf[4], kf[5], kf[6], kf[7], a);
     };
-    auto phase_v_odd = [&](int i) {
-        softmax_or_skip(2 * i + 1);
-        store_v((i + 1) & 1);
-        asm volatile("" ::: "memory");
-        if (v_active) load_v(i + 2);
+    auto read_v = [&](uint32_t a) {
+        lds_rd4<0, 32, VD, VD + 32>(vf[0], vf[1], vf[2], vf[3], a);
+        if constexpr (NDB == 4) lds_rd4<2 * VD, 2 * VD + 32, 3 * VD, 3 * VD + 32>(vf[4], vf[5], vf[6], vf[7], a);
+    };
+    auto do_pv = [&]() {
+        mfma_pv4(acc_o[0], acc_o[1], vf[0], vf[1], vf[2], vf[3], P[0], P[1]);
+        if constexpr (NDB == 4) mfma_pv4(acc_o[2], acc_o[3], vf[4], vf[5], vf[6], vf[7], P[0], P[1]);
+    };
+
+    // fragments of M(b): K block b and V block b-1 (block 0 for b = 0, where P = 0)
+    auto reads_for = [&](int b) {
+        const int pb = b >= 1 ? b - 1 : 0;
+        read_k(lds_k0 + 2u * (uint32_t)(((b >> 1) & 1) * KTILE + 32 * (b & 1) * KS));
+        read_v(lds_v0 + 2u * (uint32_t)(((pb >> 1) & 1) * VTILE + 32 * (pb & 1)));
+    };
+    // M phase: S = QK(b), O += PV(b-1) on the fragments requested one phase
+    // earlier; the wavefront's share of the global -> LDS staging sits between
+    // the two halves, where it issues while the matrix core is busy
+    auto phase_m = [&](auto &&stage) {
+        mfma_group_begin();
+        if constexpr (NC == 8) {
+            mfma_qk4<true, -1>(S, kf[0], kf[1], kf[2], kf[3], qf[0], qf[1], qf[2], qf[3]);
+            mfma_qk4<false, -1>(S, kf[4], kf[5], kf[6], kf[7], qf[4], qf[5], qf[6], qf[7]);
+        } else {
+            mfma_qk4<true, -1>(S, kf[0], kf[1], kf[2], kf[3], qf[0], qf[1], qf[2], qf[3]);
+        }
+        stage();
+        do_pv();
+        mfma_group_end();
     };
 
     // ---- prologue: tile 0 into LDS, tile 1 into the staging registers
@@ -739,44 +721,43 @@ __global__ __launch_bounds__(kPPThreads) void attn_fwd_pp_kernel(
     if (v_active) load_v(0);
     store_k(0);
     store_v(0);
+    asm volatile("" ::: "memory");
     load_k(1);
     if (v_active) load_v(1);
     lds_barrier();
     if (grp == 1) lds_barrier();   // the trailing group starts one phase late
+    reads_for(0);
 
-#if ORCH_DBG_TIMING
-    // debug build only: workgroup 0 of head 0 stamps the shader clock at every
-    // phase boundary into the lse buffer (viewed as uint64[8 waves][1024])
-    uint64_t *dbg = (uint64_t *)lse + (size_t)wave * 1024;
-    int dbg_n = 0;
-    const bool dbg_on = blockIdx.x == (unsigned)ORCH_DBG_TIMING - 1 && lane == 0 && lse != nullptr;
-#define ORCH_STAMP() do { if (dbg_on && dbg_n < 1024) dbg[dbg_n++] = __builtin_amdgcn_s_memtime(); } while (0)
-#else
-#define ORCH_STAMP() do { } while (0)
-#endif
     for (int i = 0; i < ntile_k; ++i) {
-        ORCH_STAMP();
-        phase_m(2 * i);
-        ORCH_STAMP();
+        phase_m([&]() {                  // M(2i); K_{i+1} replaces K_{i-1}
+            store_k((i + 1) & 1);
+            asm volatile("" ::: "memory");   // the prefetch reloads the registers just stored, in place
+            load_k(i + 2);
+        });
         lds_barrier();
-        ORCH_STAMP();
-        phase_v_even(i);
-        ORCH_STAMP();
+        reads_for(2 * i + 1);            // V(2i)
+        softmax(2 * i);
         lds_barrier();
-        ORCH_STAMP();
-        phase_m(2 * i + 1);
-        ORCH_STAMP();
+        phase_m([&]() {                  // M(2i+1); V_{i+1} replaces V_{i-1}
+            store_v((i + 1) & 1);
+            asm volatile("" ::: "memory");
+            if (v_active) load_v(i + 2);
+        });
         lds_barrier();
-        ORCH_STAMP();
-        phase_v_odd(i);
-        ORCH_STAMP();
+        reads_for(2 * i + 2);            // V(2i+1)
+        softmax(2 * i + 1);
         lds_barrier();
     }
-    ORCH_STAMP();
-    phase_m(nblk);                   // drain: P V of the last block
-    if (grp == 0) lds_barrier();   // every wavefront passes the same number of barriers
+    phase_m([]() {});                    // drain: O += PV(last block)
+    if (grp == 0) lds_barrier();         // every wavefront passes the same number of barriers
 
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    // ---- epilogue
+    float l_tot;
+    {
+        const uint32_t lb = __float_as_uint(l_run);
+        const auto sw = __builtin_amdgcn_permlane32_swap(lb, lb, false, false);
+        l_tot = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+    }
     const float inv = 1.f / l_tot;
     if (qm < L) {
         uint16_t *op = out + ((size_t)(row0 + qm) * Hq + h) * HD;
@@ -789,7 +770,7 @@ __global__ __launch_bounds__(kPPThreads) void attn_fwd_pp_kernel(
                 w.y = pack_bf16(acc_o[d][4 * r + 2] * inv, acc_o[d][4 * r + 3] * inv);
                 *(u32x2 *)(op + 32 * d + 8 * r + 4 * g) = w;
             }
-        if (!ORCH_DBG_TIMING && lse != nullptr && g == 0)
+        if (lse != nullptr && g == 0)
             lse[(size_t)h * total_tokens + row0 + qm] = m_run * scale + __logf(l_tot);
     }
 }
@@ -810,11 +791,11 @@ int launch_attn(const void *q, const void *k, const void *v, void *out, float *l
     if (ws_bytes < need) ORCH_FAIL(ORCH_ENOSPC, "orch_varlen_attn_fwd: workspace %zu < %zu bytes", ws_bytes, need);
     AttnHdr *hdr = (AttnHdr *)ws;
     int32_t *tile_off = (int32_t *)((char *)ws + align_up(sizeof(AttnHdr), 256));
-    // Row blocks per wavefront: 2 halves LDS traffic per FLOP but runs one
-    // wavefront per SIMD; 1 keeps two.  ORCH_ATTN_MB overrides for tuning runs.
-    int MB = 1;
-    bool pipe = true;
-    if (const char *e = getenv("ORCH_ATTN_MB")) { MB = atoi(e) == 2 ? 2 : 1; pipe = false; }
+    // head_dim 128: the 8-wavefront ping-pong kernel (MFMA-bound, overlap pays).
+    // head_dim 64: half the MFMA work per softmax, so the vector ALU dominates and
+    // the simpler 4-wavefront kernel with two row blocks per wavefront is faster.
+    const bool pipe = d == 128;
+    const int MB = 2;
     const int BM = pipe ? 256 : 128 * MB;
     hipLaunchKernelGGL(attn_prep_kernel, dim3(1), dim3(kPrepThreads), 0, stream, cu_seqlens, batch,
                        total_tokens, BM, hdr, tile_off, (int32_t *)nullptr);
@@ -833,27 +814,15 @@ int launch_attn(const void *q, const void *k, const void *v, void *out, float *l
 #define ORCH_ATTN_LAUNCH_PIPE(HD_, C_)                                                           \
     hipLaunchKernelGGL((attn_fwd_pp_kernel<HD_, C_>), dim3((unsigned)grid), dim3(kPPThreads), 0, \
                        stream, ORCH_ATTN_ARGS)
-        const int key = (d == 128 ? 4 : 0) | (causal ? 2 : 0) | (MB == 2 ? 1 : 0);
-        if (pipe) {
-            if (d == 128 && causal) ORCH_ATTN_LAUNCH_PIPE(128, true);
-            else if (d == 128) ORCH_ATTN_LAUNCH_PIPE(128, false);
-            else if (causal) ORCH_ATTN_LAUNCH_PIPE(64, true);
-            else ORCH_ATTN_LAUNCH_PIPE(64, false);
-        } else switch (key) {
-        case 0: ORCH_ATTN_LAUNCH(64, false, 1); break;
-        case 1: ORCH_ATTN_LAUNCH(64, false, 2); break;
-        case 2: ORCH_ATTN_LAUNCH(64, true, 1); break;
-        case 3: ORCH_ATTN_LAUNCH(64, true, 2); break;
-        case 4: ORCH_ATTN_LAUNCH(128, false, 1); break;
-        case 5: ORCH_ATTN_LAUNCH(128, false, 2); break;
-        case 6: ORCH_ATTN_LAUNCH(128, true, 1); break;
-        default: ORCH_ATTN_LAUNCH(128, true, 2); break;
-        }
+        if (d == 128 && causal) ORCH_ATTN_LAUNCH_PIPE(128, true);
+        else if (d == 128) ORCH_ATTN_LAUNCH_PIPE(128, false);
+        else if (causal) ORCH_ATTN_LAUNCH(64, true, 2);
+        else ORCH_ATTN_LAUNCH(64, false, 2);
 #undef ORCH_ATTN_LAUNCH
 #undef ORCH_ATTN_LAUNCH_PIPE
 #undef ORCH_ATTN_ARGS
     }
-    set_attn_variant(pipe ? "mfma32x32x16_bm256_pingpong" : MB == 2 ? "mfma32x32x16_bm256_bn64" : "mfma32x32x16_bm128_bn64");
+    set_attn_variant(pipe ? "mfma32x32x16_bm256_8wave_pingpong" : "mfma32x32x16_bm256_4wave");
     ORCH_HIP_CHECK(hipGetLastError());
     return ORCH_OK;
 }
