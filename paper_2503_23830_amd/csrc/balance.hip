@@ -6,9 +6,12 @@
 //   cost_sort_kernel   one 1024-thread workgroup: cost keys, then a stable LSD
 //                      radix sort (8-bit digits, only as many passes as the
 //                      largest key needs) of (~cost, index) pairs
-//   greedy_*_kernel    one wavefront: the n-step serial loop; each step is a
-//                      64-lane min-reduction over the instance loads with
-//                      lowest-index tie-break
+//   greedy_*_kernel    two wavefronts.  Wave 0 runs the n-step serial loop and
+//                      does nothing but choose the receiving instance; every 64
+//                      steps it publishes the 64 choices.  Wave 1 trails it and
+//                      turns the choices into (instance, rank within instance,
+//                      first token) per sequence, so that bookkeeping never
+//                      sits on the dependent chain.
 //   layout_kernel      n threads: scatter sequence ids and segment starts
 // n <= 32768 keys is latency-bound work, so everything is arranged to keep the
 // dependent chain short rather than to stream memory.
@@ -22,9 +25,11 @@ constexpr int kSortWaves = kSortThreads / 64;
 constexpr int kRadix = 256;
 
 struct BalanceWs {
-    uint64_t *cost, *keyA, *keyB;
+    uint64_t *csorted, *keyA, *keyB;  // csorted[t]: cost of the t-th sequence in descending order
     uint32_t *idxA, *idxB;
     int32_t *sorted, *rank, *start;
+    int32_t *ipos;   // ipos[t]: instance chosen for sorted position t
+    int32_t *flags;  // [0]: 1 when every load fits the packed (load << 12 | instance) key
 };
 
 size_t carve(BalanceWs &w, void *ws, int32_t n)
@@ -33,7 +38,7 @@ size_t carve(BalanceWs &w, void *ws, int32_t n)
     char *p = (char *)ws;
     size_t off = 0;
     auto take = [&](size_t bytes) { char *r = p ? p + off : nullptr; off += align_up(bytes, 256); return r; };
-    w.cost = (uint64_t *)take(nn * 8);
+    w.csorted = (uint64_t *)take(nn * 8);
     w.keyA = (uint64_t *)take(nn * 8);
     w.keyB = (uint64_t *)take(nn * 8);
     w.idxA = (uint32_t *)take(nn * 4);
@@ -41,6 +46,8 @@ size_t carve(BalanceWs &w, void *ws, int32_t n)
     w.sorted = (int32_t *)take(nn * 4);
     w.rank = (int32_t *)take(nn * 4);
     w.start = (int32_t *)take(nn * 4);
+    w.ipos = (int32_t *)take(nn * 4);
+    w.flags = (int32_t *)take(64);
     return off;
 }
 
@@ -53,9 +60,9 @@ __device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t x, int m)
 // cost + stable radix sort, one workgroup
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kSortThreads) void cost_sort_kernel(
-    const int32_t *__restrict__ lengths, int32_t n, uint64_t a, uint64_t b, uint64_t *cost,
+    const int32_t *__restrict__ lengths, int32_t n, uint64_t a, uint64_t b, uint64_t *csorted,
     uint64_t *keyA, uint64_t *keyB, uint32_t *idxA, uint32_t *idxB, int32_t *sorted,
-    int32_t *dev_status)
+    int32_t *flags, int32_t *dev_status)
 {
     __shared__ uint32_t hist[kSortWaves][kRadix];
     __shared__ uint32_t dig_base[kRadix];
@@ -80,7 +87,6 @@ __global__ __launch_bounds__(kSortThreads) void cost_sort_kernel(
             bool bad = __umul64hi(a, l2) != 0 || __umul64hi(b, l) != 0 || c < t1 || (c >> 63);
             if (bad) { err = 1; c = 0; }
         }
-        cost[i] = c;
         keyA[i] = ~c;  // ascending on ~c == descending on c
         idxA[i] = (uint32_t)i;
         my_or |= c;
@@ -106,6 +112,7 @@ __global__ __launch_bounds__(kSortThreads) void cost_sort_kernel(
             e |= red_err[w];
         }
         dev_status[0] = e ? (int32_t)ORCH_EDATA : (int32_t)ORCH_OK;
+        flags[0] = (!e && s < (1ull << 51)) ? 1 : 0;  // no instance load can exceed the total
         int nbits = o ? 64 - __clzll((long long)o) : 0;
         s_passes = (nbits + 7) / 8;
     }
@@ -184,7 +191,10 @@ __global__ __launch_bounds__(kSortThreads) void cost_sort_kernel(
         uint64_t *tk = ksrc; ksrc = kdst; kdst = tk;
         uint32_t *ti = isrc; isrc = idst; idst = ti;
     }
-    for (int64_t i = tid; i < n; i += kSortThreads) sorted[i] = (int32_t)isrc[i];
+    for (int64_t i = tid; i < n; i += kSortThreads) {
+        sorted[i] = (int32_t)isrc[i];
+        csorted[i] = ~ksrc[i];
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -220,13 +230,13 @@ __device__ __forceinline__ uint64_t readlane_u64(uint64_t x, int j)
     return ((uint64_t)hi << 32) | lo;
 }
 
-// Closing work shared by both greedy kernels: instance i's sequence count and
+// Closing work shared by the greedy kernels: instance i's sequence count and
 // token total become seq_off / tok_off and the last cu_seqlens entry.
-// `per` consecutive instances per lane, held in LDS arrays.
-__device__ void finish_layout(const uint32_t *cnt, const uint64_t *tok, int D, int32_t *seq_off,
+// `per` consecutive instances per lane, held in LDS arrays.  One wavefront.
+__device__ void finish_layout(const uint32_t *cnt, const unsigned long long *tok, int D, int32_t *seq_off,
                               int64_t *tok_off, int32_t *cu_seqlens, int32_t *dev_status)
 {
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63;
     const int per = (D + 63) / 64;
     const int b0 = min(D, lane * per), b1 = min(D, b0 + per);
     uint32_t csum = 0;
@@ -258,138 +268,439 @@ __device__ void finish_layout(const uint32_t *cnt, const uint64_t *tok, int D, i
 }
 
 // ---------------------------------------------------------------------------
-// Algorithm 1, lines 2-7: one wavefront, instance loads in registers.
-// Lane l owns instances l*K .. l*K+K-1, so "lowest lane, then lowest k" is the
-// lowest instance index among equal loads.
+// The two halves of a greedy workgroup talk through `ipos` (global, one entry
+// per sorted position) and a chunk counter in LDS.  The chooser never waits
+// for the bookkeeper, and the bookkeeper only waits for chunks the chooser is
+// certain to publish, so both always run to the end.
+// ---------------------------------------------------------------------------
+struct ChoiceLog {
+    int32_t *ipos;
+    int *progress;   // LDS: number of sorted positions whose choice is published
+    int32_t rec;     // lane j: instance chosen at step j of the current chunk
+};
+
+__device__ __forceinline__ void log_choice(ChoiceLog &g, int lane, int j, int32_t instance)
+{
+    g.rec = lane == j ? instance : g.rec;
+}
+
+__device__ __forceinline__ void publish_upto(int *progress, int64_t done)
+{
+    // release: the ipos stores before this are visible to the workgroup before the counter moves
+    __hip_atomic_store(progress, (int)done, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
+__device__ __forceinline__ void publish_chunk(ChoiceLog &g, int64_t t0, int32_t n, int lane, int chunk)
+{
+    (void)chunk;
+    if (t0 + lane < n) g.ipos[t0 + lane] = g.rec;
+    publish_upto(g.progress, min((int64_t)n, t0 + 64));
+}
+
+// Waves 1..kBookWaves.  Chunks of 64 sorted positions are dealt round-robin to
+// the bookkeeping waves.  For its chunk a wave waits until the choices are
+// published, counts for every lane the earlier lanes of the same instance
+// (lane order = assignment order) and their tokens, then takes its turn (chunks
+// in order, `booked` is the baton) to add the running per-instance count and
+// token total kept in LDS.  Only that last part is serial across waves.
+constexpr int kBookWaves = 3;
+constexpr int kGreedyThreads = 64 * (1 + kBookWaves);
+
+struct BookState {
+    int *progress;   // LDS: sorted positions published by the choosing wave
+    int *booked;     // LDS: chunks whose running totals are updated
+    uint32_t *cnt;   // LDS [D]: sequences per instance so far
+    unsigned long long *tok;  // LDS [D]: tokens per instance so far
+};
+
+__device__ void bookkeep_wave(const int32_t *ipos, const int32_t *__restrict__ sorted,
+                              const int32_t *__restrict__ lengths, int32_t n, int32_t D, int lane,
+                              int wid, BookState b, int32_t *inst, int32_t *rank, int32_t *start,
+                              int32_t *dev_status)
+{
+    int bad = 0;
+    for (int64_t q = wid; q * 64 < n; q += kBookWaves) {
+        const int64_t t0 = q * 64;
+        const bool valid = t0 + lane < n;
+        int32_t s = 0, l = 0;
+        if (valid) { s = sorted[t0 + lane]; l = lengths[s]; }
+        const int need = (int)min((int64_t)n, t0 + 64);
+        while (__hip_atomic_load(b.progress, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < need)
+            __builtin_amdgcn_s_sleep(2);
+        int32_t g = valid ? ipos[t0 + lane] : -1 - lane;  // idle lanes match nobody
+        if (valid && (uint32_t)g >= (uint32_t)D) { g = 0; bad = 1; }  // never index outside the tables
+        uint32_t before_c = 0;
+        uint64_t before_l = 0;
+        // all 64 lanes every time (idle lanes match nobody), in unrolled blocks so that the
+        // cross-lane reads of a block are in flight together
+        for (int j0 = 0; j0 < 64; j0 += 16) {
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int j = j0 + u;
+                const int32_t gj = __builtin_amdgcn_readlane(g, j);
+                const uint64_t lj = (uint64_t)(uint32_t)__builtin_amdgcn_readlane(l, j);
+                const bool bef = gj == g && j < lane;
+                before_c += bef ? 1u : 0u;
+                before_l += bef ? lj : 0ull;
+            }
+        }
+        while (__hip_atomic_load(b.booked, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < (int)q)
+            __builtin_amdgcn_s_sleep(1);
+        uint32_t bc = 0;
+        uint64_t bt = 0;
+        if (valid) {
+            bc = b.cnt[g];
+            bt = b.tok[g];
+            // the last lane of an instance carries the largest values: the maximum is its update
+            atomicMax(&b.cnt[g], bc + before_c + 1u);
+            atomicMax(&b.tok[g], (unsigned long long)(bt + before_l + (uint64_t)(uint32_t)l));
+        }
+        __hip_atomic_store(b.booked, (int)q + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (valid) {
+            inst[s] = g;
+            rank[s] = (int32_t)(bc + before_c);
+            start[s] = (int32_t)(bt + before_l);
+        }
+    }
+    if (bad) dev_status[0] = (int32_t)ORCH_EDATA;
+}
+
+
+#define ORCH_GREEDY_PARAMS                                                                          \
+    const uint64_t *__restrict__ csorted, const int32_t *__restrict__ sorted,                       \
+        const int32_t *__restrict__ lengths, int32_t n, int32_t D, int32_t *ipos, int32_t *inst,    \
+        int32_t *rank, int32_t *start, uint64_t *loads, int32_t *seq_off, int64_t *tok_off,         \
+        int32_t *cu_seqlens, const int32_t *flags, int32_t *dev_status
+
+// ---------------------------------------------------------------------------
+// Algorithm 1, lines 2-7, general form: instance loads in registers, lane l
+// owns instances l*K .. l*K+K-1, so "lowest lane, then lowest k" is the lowest
+// instance index among equal loads.  A step is a 64-lane min-reduction.
 // ---------------------------------------------------------------------------
 template <int K>
-__global__ __launch_bounds__(64) void greedy_reg_kernel(
-    const uint64_t *__restrict__ cost, const int32_t *__restrict__ sorted,
-    const int32_t *__restrict__ lengths, int32_t n, int32_t D, int32_t *inst, int32_t *rank,
-    int32_t *start, uint64_t *loads, int32_t *seq_off, int64_t *tok_off, int32_t *cu_seqlens,
-    int32_t *dev_status)
+__global__ __launch_bounds__(kGreedyThreads) void greedy_reg_kernel(ORCH_GREEDY_PARAMS)
 {
     __shared__ uint32_t s_cnt[64 * K];
-    __shared__ uint64_t s_tok[64 * K];
-    const int lane = threadIdx.x;
-    uint64_t load[K], tok[K];
-    uint32_t cnt[K];
+    __shared__ unsigned long long s_tok[64 * K];
+    __shared__ int s_progress, s_booked;
+    if (flags[0] != 0) return;  // the packed-key kernel handles this call
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    for (int i = threadIdx.x; i < 64 * K; i += kGreedyThreads) { s_cnt[i] = 0; s_tok[i] = 0; }
+    if (threadIdx.x == 0) { s_progress = 0; s_booked = 0; }
+    __syncthreads();
+    if (wave >= 1) {
+        bookkeep_wave(ipos, sorted, lengths, n, D, lane, wave - 1, BookState{&s_progress, &s_booked, s_cnt, s_tok},
+                      inst, rank, start, dev_status);
+    } else {
+        uint64_t load[K];
 #pragma unroll
-    for (int k = 0; k < K; ++k) {
-        load[k] = (lane * K + k < D) ? 0ull : ~0ull;
-        tok[k] = 0;
-        cnt[k] = 0;
-    }
-    int32_t s_cur = 0, l_cur = 0;
-    uint64_t c_cur = 0;
-    if (lane < n) { s_cur = sorted[lane]; c_cur = cost[s_cur]; l_cur = lengths[s_cur]; }
-    for (int64_t t0 = 0; t0 < n; t0 += 64) {
-        int32_t s_nxt = 0, l_nxt = 0;
-        uint64_t c_nxt = 0;
-        if (t0 + 64 + lane < n) {
-            s_nxt = sorted[t0 + 64 + lane];
-            c_nxt = cost[s_nxt];
-            l_nxt = lengths[s_nxt];
-        }
-        const int m = (int)min((int64_t)64, (int64_t)n - t0);
-        for (int j = 0; j < m; ++j) {
-            const uint64_t c = readlane_u64(c_cur, j);
-            const int32_t s = __builtin_amdgcn_readlane(s_cur, j);
-            const int32_t l = __builtin_amdgcn_readlane(l_cur, j);
-            uint64_t lm = load[0];
+        for (int k = 0; k < K; ++k) load[k] = (lane * K + k < D) ? 0ull : ~0ull;
+        ChoiceLog log{ipos, &s_progress, 0};
+        uint64_t c_cur = lane < n ? csorted[lane] : 0;
+        int chunk = 0;
+        for (int64_t t0 = 0; t0 < n; t0 += 64, ++chunk) {
+            const uint64_t c_nxt = (t0 + 64 + lane < n) ? csorted[t0 + 64 + lane] : 0;
+            const int m = (int)min((int64_t)64, (int64_t)n - t0);
+            for (int j = 0; j < m; ++j) {
+                const uint64_t c = readlane_u64(c_cur, j);
+                uint64_t lm = load[0];
 #pragma unroll
-            for (int k = 1; k < K; ++k) lm = load[k] < lm ? load[k] : lm;
-            const uint64_t g = wave_min_u64(lm);
-            const uint64_t ball = __ballot(lm == g);
-            const int win = __ffsll((unsigned long long)ball) - 1;
-            if (lane == win) {
+                for (int k = 1; k < K; ++k) lm = load[k] < lm ? load[k] : lm;
+                const uint64_t g = wave_min_u64(lm);
+                const uint64_t ball = __ballot(lm == g);
+                const int win = __ffsll((unsigned long long)ball) - 1;
                 int kk = K - 1;
 #pragma unroll
                 for (int k = K - 2; k >= 0; --k) kk = (load[k] == g) ? k : kk;
-                uint32_t r = 0;
-                uint64_t st = 0;
+                if (lane == win) {
 #pragma unroll
-                for (int k = 0; k < K; ++k) {
-                    if (k == kk) {
-                        r = cnt[k];
-                        st = tok[k];
-                        load[k] += c;
-                        cnt[k] += 1;
-                        tok[k] += (uint64_t)(int64_t)l;
-                    }
+                    for (int k = 0; k < K; ++k)
+                        if (k == kk) load[k] += c;
                 }
-                inst[s] = lane * K + kk;
-                rank[s] = (int32_t)r;
-                start[s] = (int32_t)st;
+                log_choice(log, lane, j, __builtin_amdgcn_readlane(lane * K + kk, win));
             }
+            publish_chunk(log, t0, n, lane, chunk);
+            c_cur = c_nxt;
         }
-        s_cur = s_nxt; c_cur = c_nxt; l_cur = l_nxt;
-    }
 #pragma unroll
-    for (int k = 0; k < K; ++k) {
-        const int i = lane * K + k;
-        s_cnt[i] = cnt[k];
-        s_tok[i] = tok[k];
-        if (i < D) loads[i] = load[k];
+        for (int k = 0; k < K; ++k)
+            if (lane * K + k < D) loads[lane * K + k] = load[k];
     }
     __syncthreads();
-    finish_layout(s_cnt, s_tok, D, seq_off, tok_off, cu_seqlens, dev_status);
+    if (wave == 0) finish_layout(s_cnt, s_tok, D, seq_off, tok_off, cu_seqlens, dev_status);
 }
 
-// Same loop for D beyond what registers hold: per-instance state in LDS,
+// ---------------------------------------------------------------------------
+// Algorithm 1, lines 2-7, fast form.  When every load fits in 51 bits the pair
+// (load, instance) packs into one u64 key, load << 12 | instance, whose order
+// is exactly "smaller load first, lower instance on ties".  The D keys are
+// kept SORTED across the wavefront (element e in register e/64, lane e%64).
+//
+// Rounds instead of steps.  With sorted keys k_0 < k_1 < ... and the next
+// items c_0 >= c_1 >= ..., the sequential loop gives item i to element i for
+// as long as k_i is still below every key produced so far in the round:
+//     k_i < min(k_0 + c_0, ..., k_{i-1} + c_{i-1})            (*)
+// An exclusive prefix minimum over the tentative keys k_e + c_e tests (*) for
+// all elements at once; the first m' items (the longest prefix on which it
+// holds, at least 1) are then assigned together and the keys are put back in
+// order, either by m' single insertions or, for a long prefix, by a rank sort
+// (every key counts the keys below it; keys are distinct).  The assignment is
+// the one the item-by-item loop makes: (*) is exactly its choice rule.
+// On balanced workloads a round hands one item to every instance.
+// ---------------------------------------------------------------------------
+// Lane i receives x from lane i + 1; lane 63, which has no source, receives `fill`.
+__device__ __forceinline__ uint64_t wave_shl1_u64(uint64_t x, uint64_t fill)
+{
+    uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp((int)(uint32_t)fill, (int)(uint32_t)x, 0x130, 0xf,
+                                                        0xf, false);  // wave_shl:1
+    uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp((int)(uint32_t)(fill >> 32),
+                                                        (int)(uint32_t)(x >> 32), 0x130, 0xf, 0xf, false);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+// Lane i receives x from lane i - 1; lane 0 receives `fill`.
+__device__ __forceinline__ uint64_t wave_shr1_u64(uint64_t x, uint64_t fill)
+{
+    uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp((int)(uint32_t)fill, (int)(uint32_t)x, 0x138, 0xf,
+                                                        0xf, false);  // wave_shr:1
+    uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp((int)(uint32_t)(fill >> 32),
+                                                        (int)(uint32_t)(x >> 32), 0x138, 0xf, 0xf, false);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+// Inclusive prefix minimum across the 64 lanes (the reduction above, before
+// its final broadcast, is a scan: lane i ends with min(x_0..x_i)).
+__device__ __forceinline__ uint64_t wave_prefix_min_u64(uint64_t x)
+{
+    x = dpp_min_step<0x111, 0xf>(x);
+    x = dpp_min_step<0x112, 0xf>(x);
+    x = dpp_min_step<0x114, 0xf>(x);
+    x = dpp_min_step<0x118, 0xf>(x);
+    x = dpp_min_step<0x142, 0xa>(x);
+    x = dpp_min_step<0x143, 0xc>(x);
+    return x;
+}
+
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+
+constexpr int kRing = 4096;         // LDS window over the sorted costs, entries (power of two)
+constexpr int kRefillChunks = 16;   // 64-entry chunks fetched per refill
+
+template <int K>
+__global__ __launch_bounds__(kGreedyThreads) void greedy_sorted_kernel(ORCH_GREEDY_PARAMS)
+{
+    __shared__ uint32_t s_cnt[64 * K];
+    __shared__ unsigned long long s_tok[64 * K];
+    __shared__ uint64_t s_perm[64 * K];   // rank-sort scatter, then loads by instance
+    __shared__ uint64_t s_ring[kRing];    // (cost << 12) of sorted positions [.., filled)
+    __shared__ int s_progress, s_booked;
+    if (flags[0] != 1) return;  // loads too wide for the packed key: the general kernel runs
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    for (int i = threadIdx.x; i < 64 * K; i += kGreedyThreads) { s_cnt[i] = 0; s_tok[i] = 0; }
+    if (threadIdx.x == 0) { s_progress = 0; s_booked = 0; }
+    __syncthreads();
+    if (wave >= 1) {
+        bookkeep_wave(ipos, sorted, lengths, n, D, lane, wave - 1, BookState{&s_progress, &s_booked, s_cnt, s_tok},
+                      inst, rank, start, dev_status);
+    } else {
+        uint64_t key[K];  // sorted position 64r + lane
+#pragma unroll
+        for (int r = 0; r < K; ++r) {
+            const int e = 64 * r + lane;
+            key[r] = e < D ? (uint64_t)e : ~0ull;
+        }
+        // one insertion costs about 10 + 12K instructions, a rank sort D(2 + 2K)
+        const int seq_limit = min(64, D * (2 + 2 * K) / (10 + 12 * K));
+        int64_t j = 0, filled = 0;  // items consumed; items staged in the ring (multiple of 64)
+
+        // one sequential step: the new key of element 0 moves up to its place
+        auto insert = [&](uint64_t c) {
+            const uint64_t k0 = readlane_u64(key[0], 0);
+            const uint64_t nk = k0 + c;
+            // sh = the keys moved down one place; with p = number of keys other than key_0
+            // below nk:  e < p <=> sh_e < nk,  e == p <=> key_e < nk <= sh_e.
+            // Registers whose first key is already above nk are left alone.
+            bool settled = false;
+#pragma unroll
+            for (int r = 0; r < K; ++r) {
+                if (!settled) {
+                    const uint64_t fill = (r + 1 < K) ? readlane_u64(key[(r + 1 < K) ? r + 1 : r], 0) : ~0ull;
+                    const uint64_t sh = wave_shl1_u64(key[r], fill);
+                    key[r] = sh < nk ? sh : (key[r] < nk ? nk : key[r]);
+                    settled = nk < fill;
+                }
+            }
+        };
+
+        while (j < n) {
+            const int m = (int)min((int64_t)D, (int64_t)n - j);
+            if (filled < j + m) {
+                // the ring holds [j, filled): top it up by as many chunks as fit and exist
+                const int room = (int)((kRing - (filled - j)) / 64);
+                const int want = (int)(((int64_t)n - filled + 63) / 64);
+                const int G = min(min(room, want), kRefillChunks);
+                uint64_t v[kRefillChunks];
+#pragma unroll
+                for (int g = 0; g < kRefillChunks; ++g) {
+                    // clamped, unconditional: all the loads are in flight together
+                    const int64_t pos = min(filled + 64 * g + lane, (int64_t)n - 1);
+                    v[g] = csorted[pos];
+                }
+#pragma unroll
+                for (int g = 0; g < kRefillChunks; ++g)
+                    if (g < G) s_ring[(filled + 64 * g + lane) & (kRing - 1)] = v[g] << 12;
+                filled += 64 * G;
+                wave_lds_fence();
+            }
+            uint64_t c[K], nk[K];
+#pragma unroll
+            for (int r = 0; r < K; ++r) {
+                const int e = 64 * r + lane;
+                c[r] = e < m ? s_ring[(j + e) & (kRing - 1)] : 0;
+                nk[r] = key[r] + c[r];
+            }
+            const int32_t idx0 = (int32_t)((uint32_t)readlane_u64(key[0], 0) & 4095u);
+            if (readlane_u64(c[0], 0) == 0) {
+                // costs are sorted: every remaining item is free, the minimum never moves
+                for (int64_t t = j + lane; t < n; t += 64) ipos[t] = idx0;
+                j = n;
+                publish_upto(&s_progress, j);
+                break;
+            }
+            // longest prefix on which (*) holds
+            int mp = m;
+            {
+                uint64_t carry = ~0ull;  // smallest tentative key of the registers before r
+                bool found = false;
+#pragma unroll
+                for (int r = 0; r < K; ++r) {
+                    if (64 * r < m && !found) {
+                        const int e = 64 * r + lane;
+                        const uint64_t inc = wave_prefix_min_u64(e < m ? nk[r] : ~0ull);
+                        uint64_t exc = wave_shr1_u64(inc, ~0ull);
+                        exc = carry < exc ? carry : exc;
+                        const uint64_t bad = __ballot(e < m && !(key[r] < exc));
+                        if (bad) { mp = 64 * r + (__ffsll((unsigned long long)bad) - 1); found = true; }
+                        const uint64_t tot = readlane_u64(inc, 63);
+                        carry = tot < carry ? tot : carry;
+                    }
+                }
+            }
+            // the first mp items go to elements 0..mp-1, in that order
+#pragma unroll
+            for (int r = 0; r < K; ++r) {
+                const int e = 64 * r + lane;
+                if (e < mp) ipos[j + e] = (int32_t)((uint32_t)key[r] & 4095u);
+            }
+            if (mp <= seq_limit) {
+                for (int i = 0; i < mp; ++i) insert(readlane_u64(c[0], i));
+            } else {
+                uint32_t below[K];
+#pragma unroll
+                for (int r = 0; r < K; ++r) {
+                    if (64 * r + lane < mp) key[r] = nk[r];
+                    below[r] = 0;
+                }
+#pragma unroll
+                for (int rp = 0; rp < K; ++rp) {
+                    // blocks of 16 lanes, unrolled: the cross-lane reads of a block are in
+                    // flight together; padding keys (~0) are below nothing
+                    const int cnt = min(64, D - 64 * rp);
+                    for (int l0 = 0; l0 < cnt; l0 += 16) {
+#pragma unroll
+                        for (int u = 0; u < 16; ++u) {
+                            const uint64_t s = readlane_u64(key[rp], l0 + u);
+#pragma unroll
+                            for (int r = 0; r < K; ++r) below[r] += (s < key[r]) ? 1u : 0u;
+                        }
+                    }
+                }
+#pragma unroll
+                for (int r = 0; r < K; ++r)
+                    if (64 * r + lane < D) s_perm[below[r]] = key[r];
+                wave_lds_fence();
+#pragma unroll
+                for (int r = 0; r < K; ++r)
+                    if (64 * r + lane < D) key[r] = s_perm[64 * r + lane];
+                wave_lds_fence();
+            }
+            j += mp;
+            publish_upto(&s_progress, j);
+        }
+#pragma unroll
+        for (int r = 0; r < K; ++r)
+            if (key[r] != ~0ull) s_perm[key[r] & 4095u] = key[r] >> 12;  // back to instance order
+    }
+    __syncthreads();
+    if (wave == 0) {
+        for (int i = lane; i < D; i += 64) loads[i] = s_perm[i];
+        finish_layout(s_cnt, s_tok, D, seq_off, tok_off, cu_seqlens, dev_status);
+    }
+}
+
+// Same loop for D beyond what registers hold: per-instance loads in LDS,
 // instance i lives at lane i%64, slot i/64.  Two reductions per step: the
 // minimal load, then the minimal instance index among lanes that hold it.
 constexpr int kMaxInstances = 4096;
 
-__global__ __launch_bounds__(64) void greedy_lds_kernel(
-    const uint64_t *__restrict__ cost, const int32_t *__restrict__ sorted,
-    const int32_t *__restrict__ lengths, int32_t n, int32_t D, int32_t *inst, int32_t *rank,
-    int32_t *start, uint64_t *loads, int32_t *seq_off, int64_t *tok_off, int32_t *cu_seqlens,
-    int32_t *dev_status)
+__global__ __launch_bounds__(kGreedyThreads) void greedy_lds_kernel(ORCH_GREEDY_PARAMS)
 {
+    (void)flags;
     __shared__ uint64_t s_load[kMaxInstances];
-    __shared__ uint64_t s_tok[kMaxInstances];
+    __shared__ unsigned long long s_tok[kMaxInstances];
     __shared__ uint32_t s_cnt[kMaxInstances];
-    const int lane = threadIdx.x;
+    __shared__ int s_progress, s_booked;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int K = (D + 63) / 64;
-    for (int i = lane; i < K * 64; i += 64) {
+    for (int i = threadIdx.x; i < K * 64; i += kGreedyThreads) {
         s_load[i] = i < D ? 0ull : ~0ull;
         s_tok[i] = 0;
         s_cnt[i] = 0;
     }
+    if (threadIdx.x == 0) { s_progress = 0; s_booked = 0; }
     __syncthreads();
-    for (int64_t t0 = 0; t0 < n; t0 += 64) {
-        int32_t s_cur = 0, l_cur = 0;
-        uint64_t c_cur = 0;
-        if (t0 + lane < n) { s_cur = sorted[t0 + lane]; c_cur = cost[s_cur]; l_cur = lengths[s_cur]; }
-        const int m = (int)min((int64_t)64, (int64_t)n - t0);
-        for (int j = 0; j < m; ++j) {
-            const uint64_t c = readlane_u64(c_cur, j);
-            const int32_t s = __builtin_amdgcn_readlane(s_cur, j);
-            const int32_t l = __builtin_amdgcn_readlane(l_cur, j);
-            uint64_t lm = ~0ull;
-            uint32_t li = 0xffffffffu;
-            for (int k = 0; k < K; ++k) {
-                const uint64_t v = s_load[k * 64 + lane];
-                if (v < lm) { lm = v; li = (uint32_t)(k * 64 + lane); }
+    if (wave >= 1) {
+        bookkeep_wave(ipos, sorted, lengths, n, D, lane, wave - 1, BookState{&s_progress, &s_booked, s_cnt, s_tok},
+                      inst, rank, start, dev_status);
+    } else {
+        ChoiceLog log{ipos, &s_progress, 0};
+        int chunk = 0;
+        for (int64_t t0 = 0; t0 < n; t0 += 64, ++chunk) {
+            const uint64_t c_cur = (t0 + lane < n) ? csorted[t0 + lane] : 0;
+            const int m = (int)min((int64_t)64, (int64_t)n - t0);
+            for (int j = 0; j < m; ++j) {
+                const uint64_t c = readlane_u64(c_cur, j);
+                uint64_t lm = ~0ull;
+                uint32_t li = 0xffffffffu;
+                for (int k = 0; k < K; ++k) {
+                    const uint64_t v = s_load[k * 64 + lane];
+                    if (v < lm) { lm = v; li = (uint32_t)(k * 64 + lane); }
+                }
+                const uint64_t g = wave_min_u64(lm);
+                const uint64_t cand = (lm == g) ? (uint64_t)li : ~0ull;
+                const uint32_t bi = (uint32_t)wave_min_u64(cand);
+                if (lane == (int)(bi & 63u)) s_load[bi] += c;
+                log_choice(log, lane, j, (int32_t)bi);
+                // one wave owns s_load: order the update before the next scan
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             }
-            const uint64_t g = wave_min_u64(lm);
-            const uint64_t cand = (lm == g) ? (uint64_t)li : ~0ull;
-            const uint32_t bi = (uint32_t)wave_min_u64(cand);
-            if (lane == (int)(bi & 63u)) {
-                inst[s] = (int32_t)bi;
-                rank[s] = (int32_t)s_cnt[bi];
-                start[s] = (int32_t)s_tok[bi];
-                s_load[bi] += c;
-                s_cnt[bi] += 1;
-                s_tok[bi] += (uint64_t)(int64_t)l;
-            }
-            __syncthreads();  // single wave: orders the LDS update before the next scan
+            publish_chunk(log, t0, n, lane, chunk);
         }
+        for (int i = lane; i < D; i += 64) loads[i] = s_load[i];
     }
-    for (int i = lane; i < D; i += 64) loads[i] = s_load[i];
     __syncthreads();
-    finish_layout(s_cnt, s_tok, D, seq_off, tok_off, cu_seqlens, dev_status);
+    if (wave == 0) finish_layout(s_cnt, s_tok, D, seq_off, tok_off, cu_seqlens, dev_status);
 }
 
 __global__ void layout_kernel(const int32_t *__restrict__ inst, const int32_t *__restrict__ rank,
@@ -421,16 +732,24 @@ int launch_balance(const int32_t *lengths, int32_t n, int32_t D, orch_phase phas
     if (ws_bytes < need) ORCH_FAIL(ORCH_ENOSPC, "orch_balance: workspace %zu < %zu bytes", ws_bytes, need);
 
     hipLaunchKernelGGL(cost_sort_kernel, dim3(1), dim3(kSortThreads), 0, stream, lengths, n, phase.a,
-                       phase.b, w.cost, w.keyA, w.keyB, w.idxA, w.idxB, w.sorted, out.dev_status);
+                       phase.b, w.csorted, w.keyA, w.keyB, w.idxA, w.idxB, w.sorted, w.flags, out.dev_status);
 #define ORCH_GREEDY_ARGS                                                                        \
-    w.cost, w.sorted, lengths, n, D, out.inst, w.rank, w.start, out.loads, out.seq_off,         \
-        out.tok_off, out.cu_seqlens, out.dev_status
-    if (D <= 64) hipLaunchKernelGGL(greedy_reg_kernel<1>, dim3(1), dim3(64), 0, stream, ORCH_GREEDY_ARGS);
-    else if (D <= 128) hipLaunchKernelGGL(greedy_reg_kernel<2>, dim3(1), dim3(64), 0, stream, ORCH_GREEDY_ARGS);
-    else if (D <= 256) hipLaunchKernelGGL(greedy_reg_kernel<4>, dim3(1), dim3(64), 0, stream, ORCH_GREEDY_ARGS);
-    else if (D <= 512) hipLaunchKernelGGL(greedy_reg_kernel<8>, dim3(1), dim3(64), 0, stream, ORCH_GREEDY_ARGS);
-    else if (D <= 1024) hipLaunchKernelGGL(greedy_reg_kernel<16>, dim3(1), dim3(64), 0, stream, ORCH_GREEDY_ARGS);
-    else hipLaunchKernelGGL(greedy_lds_kernel, dim3(1), dim3(64), 0, stream, ORCH_GREEDY_ARGS);
+    w.csorted, w.sorted, lengths, n, D, w.ipos, out.inst, w.rank, w.start, out.loads,           \
+        out.seq_off, out.tok_off, out.cu_seqlens, w.flags, out.dev_status
+    // both forms are enqueued; the flag written by the sort kernel decides on the
+    // device which of them does the work (the other returns at once)
+#define ORCH_GREEDY_BOTH(K_)                                                                    \
+    do {                                                                                        \
+        hipLaunchKernelGGL(greedy_sorted_kernel<K_>, dim3(1), dim3(kGreedyThreads), 0, stream, ORCH_GREEDY_ARGS); \
+        hipLaunchKernelGGL(greedy_reg_kernel<K_>, dim3(1), dim3(kGreedyThreads), 0, stream, ORCH_GREEDY_ARGS);    \
+    } while (0)
+    if (D <= 64) ORCH_GREEDY_BOTH(1);
+    else if (D <= 128) ORCH_GREEDY_BOTH(2);
+    else if (D <= 256) ORCH_GREEDY_BOTH(4);
+    else if (D <= 512) ORCH_GREEDY_BOTH(8);
+    else if (D <= 1024) ORCH_GREEDY_BOTH(16);
+    else hipLaunchKernelGGL(greedy_lds_kernel, dim3(1), dim3(kGreedyThreads), 0, stream, ORCH_GREEDY_ARGS);
+#undef ORCH_GREEDY_BOTH
 #undef ORCH_GREEDY_ARGS
     if (n > 0)
         hipLaunchKernelGGL(layout_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, out.inst, w.rank,

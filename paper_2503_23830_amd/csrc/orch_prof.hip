@@ -128,13 +128,33 @@ int main(int argc, char **argv)
     }
     const double flops = 4.0 * d * Hq * pairs;
 
-    // pack buffers: everything, or only the straggler instance's range
-    const int ib = pack_all ? 0 : istar, ie = pack_all ? D : istar + 1;
-    const int64_t prow = tok_off[ie] - tok_off[ib];
+    // pack scope: everything, or (when the whole batch does not fit) only the
+    // straggler instance's rows from a compacted source: the other sequences get
+    // length 0 and the compacted batch is balanced on its own
+    orch_assignment ap = as;
+    int32_t *dLp = dL;
+    int64_t Tp = T;
+    if (!pack_all) {
+        std::vector<int32_t> inst(n), Lp(L);
+        CK(hipMemcpy(inst.data(), as.inst, 4 * n, hipMemcpyDeviceToHost));
+        Tp = 0;
+        for (int s = 0; s < n; ++s) { if (inst[s] != istar) Lp[s] = 0; Tp += Lp[s]; }
+        CK(hipMalloc(&dLp, sizeof(int32_t) * std::max(n, 1)));
+        CK(hipMemcpy(dLp, Lp.data(), sizeof(int32_t) * n, hipMemcpyHostToDevice));
+        CK(hipMalloc(&ap.inst, 4 * std::max(n, 1)));
+        CK(hipMalloc(&ap.order, 4 * std::max(n, 1)));
+        CK(hipMalloc(&ap.seq_off, 4 * (D + 1)));
+        CK(hipMalloc(&ap.tok_off, 8 * (D + 1)));
+        CK(hipMalloc(&ap.cu_seqlens, 4 * (n + D)));
+        CK(hipMalloc(&ap.loads, 8 * D));
+        CK(hipMalloc(&ap.dev_status, 4));
+    }
+    const int ib = 0, ie = D;
+    const int64_t prow = Tp;
     uint16_t *tokens, *packed;
-    CK(hipMalloc(&tokens, (size_t)std::max<int64_t>(T, 1) * H * 2));
+    CK(hipMalloc(&tokens, (size_t)std::max<int64_t>(Tp, 1) * H * 2));
     CK(hipMalloc(&packed, (size_t)std::max<int64_t>(prow, 1) * H * 2));
-    hipLaunchKernelGGL(fill_words, dim3(4096), dim3(256), 0, st, tokens, (size_t)T * H, 1234ull);
+    hipLaunchKernelGGL(fill_words, dim3(4096), dim3(256), 0, st, tokens, (size_t)Tp * H, 1234ull);
 
     uint16_t *q, *k, *v, *o;
     const size_t qn = (size_t)Ti * Hq * d, kn = (size_t)Ti * Hkv * d;
@@ -150,14 +170,16 @@ int main(int argc, char **argv)
     CK(hipMalloc(&ws_a, wsa));
     CK(hipStreamSynchronize(st));
 
-    hipEvent_t e0, e1, e2, e3;
-    CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1)); CK(hipEventCreate(&e2)); CK(hipEventCreate(&e3));
+    hipEvent_t e0, e1, e1b, e2, e3;
+    CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1)); CK(hipEventCreate(&e1b)); CK(hipEventCreate(&e2)); CK(hipEventCreate(&e3));
     double tb = 0, tp = 0, ta = 0;
     for (int s = 0; s < steps + 1; ++s) {  // first pass is a warm-up
         CK(hipEventRecord(e0, st));
         OK(orch_balance(dL, n, D, orch_phase{a, b}, as, ws_b, wsb, st));
         CK(hipEventRecord(e1, st));
-        OK(orch_pack(tokens, packed, dL, n, D, T, H, prow, as, ib, ie, ws_p, wsp, st));
+        if (!pack_all) OK(orch_balance(dLp, n, D, orch_phase{a, b}, ap, ws_b, wsb, st));  // untimed
+        CK(hipEventRecord(e1b, st));
+        OK(orch_pack(tokens, packed, dLp, n, D, Tp, H, prow, ap, ib, ie, ws_p, wsp, st));
         CK(hipEventRecord(e2, st));
         OK(orch_varlen_attn_fwd(q, k, v, o, nullptr, cu_dev, batch, Ti, 0, Hq, Hkv, d, 0.f, causal, ws_a, wsa, st));
         CK(hipEventRecord(e3, st));
@@ -165,7 +187,7 @@ int main(int argc, char **argv)
         float m;
         if (s > 0) {
             CK(hipEventElapsedTime(&m, e0, e1)); tb += m;
-            CK(hipEventElapsedTime(&m, e1, e2)); tp += m;
+            CK(hipEventElapsedTime(&m, e1b, e2)); tp += m;
             CK(hipEventElapsedTime(&m, e2, e3)); ta += m;
         }
     }

@@ -40,6 +40,19 @@ def test_many_ties_and_equal_lengths(gpu_device):
     assert_assignment_equal(asg, oracle.balance(L, 48, 0, 1))
 
 
+@pytest.mark.parametrize("D", [8, 32, 64, 100, 256, 700])
+def test_mixed_round_lengths(gpu_device, D):
+    """Costs spanning many orders of magnitude: some rounds hand an item to every
+    instance, others stop after one or two, and a zero-cost tail ends the batch."""
+    rng = np.random.default_rng(1000 + D)
+    n = 6 * D + 37
+    L = np.exp(rng.normal(5.0, 2.5, n)).astype(np.int64).clip(0, 200000).astype(np.int32)
+    L[rng.random(n) < 0.05] = 0
+    for a, b in ((1, 0), (1, 4096), (0, 1)):
+        _, asg = run_balance(L, D, a, b, gpu_device)
+        assert_assignment_equal(asg, oracle.balance(L, D, a, b))
+
+
 def test_large_instance_counts_use_the_lds_kernel(gpu_device):
     for D in (1025, 2560, 4096):
         L = wl.random_lengths(D, 9000, 1, 3000)
