@@ -14,6 +14,7 @@
 // rescaling O is a per-lane multiply.  The running maximum is only moved when a
 // row's maximum grows by more than 2^8 (exact: the stale reference cancels in
 // the final division), so O is rarely rescaled after the first tile.
+#include <stdlib.h>
 #include <type_traits>
 
 #include "common.h"
@@ -775,6 +776,393 @@ __global__ __launch_bounds__(kPPThreads) void attn_fwd_pp_kernel(
     }
 }
 
+
+// ---------------------------------------------------------------------------
+// Interleaved variant (head_dim 128): 8 free-running wavefronts (two per SIMD)
+// own 32 query rows each.  No vector register ever stages K or V:
+//   * K and V tiles (64 keys x 256 B) go from global memory straight into LDS
+//     with 16-byte LDS-DMA loads.  A wave-wide load fills 1 KB of LDS in lane
+//     order, so bank conflicts are avoided by choosing WHICH 16-byte chunk of a
+//     row each lane fetches: row r keeps chunk c at slot c ^ swz(r).
+//       K: swz = r & 15              (A-operand reads: 16 rows, same chunk)
+//       V: swz = 4 (r & 3) + 2 ((r >> 2) & 1)   (transpose reads: 4 rows x 64 B)
+//   * V is consumed by ds_read_b64_tr_b16, which hands a lane four keys of one
+//     head-dim column from row-major [key][dim] storage: in a 16-lane block,
+//     lane i receives element i%4 of the 8-byte words addressed by lanes
+//     i/4, 4 + i/4, 8 + i/4, 12 + i/4.  Two such reads are the A operand of
+//     O^T += V^T P^T for the keys a lane's P registers hold.
+// Three-stage rings for K and V; one workgroup barrier per 64-key tile.
+//
+// Each wavefront software-pipelines over 32-key blocks b.  Iteration b issues
+//     half 1:  O^T   += V(b-1)^T P(b-1) 8 MFMAs | row maxima of S(b), then exp of
+//                                                 its keys 0..15
+//     half 2:  S(b+1) = K(b+1) Q^T      8 MFMAs | exp of S(b), keys 16..31
+// with the vector-ALU work cut into pieces that sit between consecutive MFMAs,
+// so the matrix core and the vector ALU of a SIMD are busy at the same time
+// within one instruction stream; the second wavefront of the SIMD fills what
+// stalls remain.  P is single-buffered: its first chunk is rewritten in the
+// second part of half 1, after the four MFMAs that read the old one, its second
+// chunk in half 2.  LDS fragments are single-buffered in registers too: K(b+1) is
+// requested at the start of half 1 (its registers were last read by the MFMAs of
+// the previous half 2), V(b) at the start of half 2.
+// Reference maximum: lazy (moves only on growth > 2^8).  The factor alpha_b that
+// carries O and l from the reference of block b-1 to that of block b is applied
+// in half 2 of iteration b: O has received P(b-1) V(b-1) and not yet P(b) V(b).
+// ---------------------------------------------------------------------------
+constexpr int kILThreads = 512;
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+#define ORCH_SB() __builtin_amdgcn_sched_barrier(0)
+
+template <int HD, bool CAUSAL>
+__global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
+    const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
+    uint16_t *__restrict__ out, float *__restrict__ lse, const int32_t *__restrict__ cu,
+    const AttnHdr *__restrict__ hdr, const int32_t *__restrict__ tile_off, int32_t batch,
+    int32_t total_tokens, int32_t Hq, int32_t Hkv, float scale, float scale_log2)
+{
+    static_assert(HD == 128, "layout constants below assume 256-byte rows");
+    constexpr int BM = 256;
+    constexpr int NC = HD / 16;    // k-chunks of Q K^T
+    constexpr int NDB = HD / 32;   // 32-row blocks of O^T
+    constexpr int ROWB = HD * 2;   // bytes per key row
+    constexpr int TILE_B = BN * ROWB;
+    constexpr int NST = 3;
+    __shared__ __attribute__((aligned(1024))) char lds_raw[2 * NST * TILE_B];
+    const uint32_t lds_k = (uint32_t)(uintptr_t)lds_raw;
+    const uint32_t lds_v = lds_k + NST * TILE_B;
+
+    const int total_tiles = hdr->total_tiles;
+    const int group = Hq / Hkv;
+    int u, h;
+    {
+        const int bid = blockIdx.x;
+        if ((Hkv & 7) == 0) {   // kv-head chosen by XCD: blocks sharing K/V share an L2
+            const int kvh = (bid & 7) + 8 * ((bid >> 3) % (Hkv >> 3));
+            const int rest = bid / Hkv;
+            h = kvh * group + rest % group;
+            u = rest / group;
+        } else {
+            h = bid % Hq;
+            u = bid / Hq;
+        }
+    }
+    if (u >= total_tiles) return;
+    const int g_kv = h / group;
+    int lo = 0, hi = batch - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (tile_off[mid] <= u) lo = mid; else hi = mid - 1;
+    }
+    const int seq = lo;
+    const int row0 = cu[seq];
+    const int L = cu[seq + 1] - row0;
+    const int ntile_q = (L + BM - 1) / BM;
+    const int qt = ntile_q - 1 - (u - tile_off[seq]);  // heaviest (last) tile first
+    const int q0 = qt * BM;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, g = lane >> 5;
+    // waves w and w+4 share a SIMD; row blocks w and 7-w even out the causal work per SIMD
+    const int rblk = wave < 4 ? wave : 11 - wave;
+    const int qrow0 = q0 + 32 * rblk;
+    const int qm = qrow0 + l32;
+
+    const int kend = CAUSAL ? min(L, q0 + BM) : L;
+    const int ntile_k = (kend + BN - 1) / BN;               // tiles the workgroup stages
+    const int kend_w = CAUSAL ? min(L, qrow0 + 32) : L;
+    const int nblk_w = qrow0 < L ? (kend_w + 31) / 32 : 0;  // 32-key blocks this wavefront computes
+
+    // ---- LDS-DMA: per tile this wavefront fetches rows 8w..8w+7 of K and of V
+    // (two loads of 4 rows each); lane -> (row, slot), slot -> chunk by the swizzle
+    const uint32_t rstride_b = (uint32_t)Hkv * HD * 2;
+    const char *kseq = (const char *)(k + ((size_t)row0 * Hkv + g_kv) * HD);
+    const char *vseq = (const char *)(v + ((size_t)row0 * Hkv + g_kv) * HD);
+    auto dma_tile = [&](int t, const char *seqbase, uint32_t lds_stage, bool is_v) {
+        const char *tb = seqbase + (size_t)t * BN * rstride_b;
+        const int lrem = L - 1 - t * BN;   // rows past the end repeat row L-1 (masked later)
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            const int r = 4 * (2 * wave + p) + (lane >> 4);
+            const int slot = lane & 15;
+            const int swz = is_v ? 4 * (r & 3) + 2 * ((r >> 2) & 1) : (r & 15);
+            const char *src = tb + (__umul24((uint32_t)min(r, lrem), rstride_b) + 16u * (uint32_t)(slot ^ swz));
+            // Written as asm so that the compiler does not tie later LDS reads (of other
+            // stages) to this load with a vmcnt(0); completion is waited for explicitly
+            // before the tile barrier.  M0 = LDS destination of lane 0; nothing else in
+            // this kernel uses M0.
+            const uint32_t dst = lds_stage + (uint32_t)(2 * wave + p) * 1024u;
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                         :: "s"(dst), "v"(src) : "memory");
+        }
+    };
+
+    // ---- per-lane LDS addresses of the fragments (stage 0, first 32-key block)
+    // K, A operand of MFMA j: row l32, chunk (2j+g) ^ (l32 & 15), i.e. byte
+    // 32 (j ^ y) + 16 (g ^ x) of the row with y = (l32 & 15) >> 1, x = l32 & 1
+    const uint32_t k_xor = 32u * (uint32_t)((l32 & 15) >> 1);
+    uint32_t k_base = lds_k + (uint32_t)(l32 * ROWB + 16 * (g ^ (l32 & 1)));
+    // V, transpose read for O block db: this lane addresses key row 4g + j4 (j4 = (lane%16)/4) and
+    // the 8 bytes of columns 32 db + 16 half + 4 a .. +3 (half = (lane/16)%2, a = lane%4).  The
+    // swizzle of that row is 4 j4 + 2 g for every block and chunk, so the chunk is
+    // 4 (db ^ j4) + ((2 half + a/2) ^ 2g): byte 64 (db ^ j4) + const within the row.
+    uint32_t v_xor, v_base;
+    {
+        const int j4 = (lane & 15) >> 2, a = lane & 3, half = (lane >> 4) & 1;
+        v_xor = 64u * (uint32_t)j4;
+        v_base = lds_v + (uint32_t)((4 * g + j4) * ROWB + 16 * ((2 * half + (a >> 1)) ^ (2 * g)) + 8 * (a & 1));
+    }
+
+    // ---- Q fragments: B operand, column m = lane%32, k = 16c + 8g + [0..7]
+    bf16x8 qf[NC];
+    {
+        const int qm_c = qm < L ? qm : L - 1;
+        const uint16_t *qp = q + ((size_t)(row0 + qm_c) * Hq + h) * HD + 8 * g;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) qf[c] = *(const bf16x8 *)(qp + 16 * c);
+    }
+    f32x16 acc_o[NDB];
+#pragma unroll
+    for (int d = 0; d < NDB; ++d)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc_o[d][e] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+    const float lazy_thr = 8.0f / scale_log2;
+
+    f32x16 S[2];     // scores of blocks b (current) and b+1 (next), by parity
+    bf16x8 P[2];     // probabilities, two 16-key chunks: block b-1 until rewritten for block b
+    bf16x8 kf[NC], vf[2 * NDB];
+    float alpha = 1.f, mbias = 0.f, psum = 0.f;
+    bool moved = false;
+
+    auto lds_rd128 = [](uint32_t addr, int off) {
+        return *(const __attribute__((address_space(3))) bf16x8 *)(uintptr_t)(addr + (uint32_t)off);
+    };
+    auto lds_rd_tr = [](uint32_t addr, int off) {
+        return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) s16x4 *)(uintptr_t)(addr + (uint32_t)off));
+    };
+    // K fragments of the block at row offset `ro` (0 or 32 rows) of the stage k_base points at
+    auto read_k = [&](int ro) {
+#pragma unroll
+        for (int j = 0; j < NC; ++j) {
+            uint32_t a;   // (k_xor ^ 32 j) + k_base in one instruction
+            asm("v_xad_u32 %0, %1, %2, %3" : "=v"(a) : "v"(k_xor), "s"(32 * j), "v"(k_base));
+            kf[j] = lds_rd128(a, ro * ROWB);
+        }
+    };
+    // V fragments: chunk kk (16 keys), O block db: keys 16kk + 4g + [0..3] and 16kk + 8 + 4g + [0..3]
+    auto read_v = [&](int ro) {
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) {
+            uint32_t a;   // (v_xor ^ 64 db) + v_base
+            asm("v_xad_u32 %0, %1, %2, %3" : "=v"(a) : "v"(v_xor), "s"(64 * db), "v"(v_base));
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk) {
+                const s16x4 lo4 = lds_rd_tr(a, (ro + 16 * kk) * ROWB);
+                const s16x4 hi4 = lds_rd_tr(a, (ro + 16 * kk + 8) * ROWB);
+                const s16x8 both = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
+                vf[2 * db + kk] = __builtin_bit_cast(bf16x8, both);
+            }
+        }
+    };
+    // keys of block b beyond the sequence or above the diagonal get -inf
+    auto mask_block = [&](f32x16 &Sx, int b) {
+        const bool masked = (32 * b + 32 > L) || (CAUSAL && 32 * b + 31 > qrow0);
+        if (masked) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int n = 32 * b + 8 * (e >> 2) + 4 * g + (e & 3);
+                const bool vis = n < L && (!CAUSAL || n <= qm);
+                if (!vis) Sx[e] = -INFINITY;
+            }
+        }
+    };
+    // row maximum of a block and the (lazy) reference it is exponentiated against;
+    // split in three so that the pieces fit between MFMAs
+    float tmax_part;
+    auto max_a = [&](const f32x16 &Sx) {
+        float t = fmaxf(fmaxf(Sx[0], Sx[1]), Sx[2]);
+        t = fmaxf(fmaxf(t, Sx[3]), Sx[4]);
+        t = fmaxf(fmaxf(t, Sx[5]), Sx[6]);
+        t = fmaxf(fmaxf(t, Sx[7]), Sx[8]);
+        asm volatile("" : "+v"(t));
+        tmax_part = t;
+    };
+    auto max_b = [&](const f32x16 &Sx) {
+        float t = fmaxf(fmaxf(tmax_part, Sx[9]), Sx[10]);
+        t = fmaxf(fmaxf(t, Sx[11]), Sx[12]);
+        t = fmaxf(fmaxf(t, Sx[13]), Sx[14]);
+        t = fmaxf(t, Sx[15]);
+        asm volatile("" : "+v"(t));
+        tmax_part = t;
+    };
+    auto max_c = [&]() {
+        float tmax = tmax_part;
+        {   // the other half of the row lives in lane ^ 32
+            const uint32_t tb = __float_as_uint(tmax);
+            const auto sw = __builtin_amdgcn_permlane32_swap(tb, tb, false, false);
+            tmax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+        }
+        const bool upd = tmax > m_run + lazy_thr;
+        const float m_new = upd ? tmax : m_run;
+        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+        alpha = upd ? __builtin_amdgcn_exp2f((m_run - m_use) * scale_log2) : 1.0f;
+        moved = __any(upd);
+        m_run = m_new;
+        mbias = m_use * scale_log2;
+        asm volatile("" : "+v"(mbias), "+v"(alpha));
+    };
+    // exp of one score of the current block (element e of S[cur]); pairs are packed to bf16.
+    // The empty asm statement pins the piece where it is written (between two MFMAs):
+    // its results must exist there, so the work cannot sink to where P is consumed.
+    float p_even;
+    auto exp_piece = [&](const f32x16 &Sc, int e) {
+        float pe = __builtin_amdgcn_exp2f(Sc[e] * scale_log2 - mbias);
+        psum += pe;
+        if ((e & 1) == 0) {
+            asm volatile("" : "+v"(pe), "+v"(psum));
+            p_even = pe;
+        } else {
+            uint32_t pk = pack_bf16(p_even, pe);
+            asm volatile("" : "+v"(pk), "+v"(psum));
+            u32x4 w = __builtin_bit_cast(u32x4, P[e >> 3]);
+            w[(e & 7) >> 1] = pk;
+            P[e >> 3] = __builtin_bit_cast(bf16x8, w);
+        }
+    };
+    auto mfma = [](const bf16x8 &a, const bf16x8 &b, const f32x16 &c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+    };
+
+    // one pipeline iteration for block b of parity PAR: S[PAR] holds S(b), P holds P(b-1),
+    // vf holds V(b-1)
+    auto body = [&](auto par_c, int b) {
+        constexpr int PAR = decltype(par_c)::value;
+        f32x16 &Sc = S[PAR];
+        f32x16 &Sn = S[PAR ^ 1];
+        psum = 0.f;
+        // ---- half 1: O^T += V(b-1)^T P(b-1); maxima of S(b); exp of keys 0..15
+#pragma unroll
+        for (int j = 0; j < 2 * NDB; ++j) {
+            const int db = j % NDB, kk = j / NDB;
+            acc_o[db] = mfma(vf[2 * db + kk], P[kk], acc_o[db]);
+            ORCH_SB();
+            if (j == 0) {   // K(b+1): odd half of this tile, or even half of the next one
+                read_k(PAR == 0 ? 32 : 0);
+                ORCH_SB();
+                mask_block(Sc, b);
+            }
+            if (j == 1) max_a(Sc);
+            if (j == 2) max_b(Sc);
+            if (j == 3) max_c();
+            if (j >= 4) {   // chunk 0 of P is free: MFMAs 0..3 have read it
+                exp_piece(Sc, 2 * (j - 4));
+                exp_piece(Sc, 2 * (j - 4) + 1);
+            }
+            ORCH_SB();
+        }
+        // ---- half 2: S(b+1) = K(b+1) Q^T; exp of keys 16..31
+#pragma unroll
+        for (int j = 0; j < NC; ++j) {
+            if (j == 0) {
+                f32x16 z;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) z[e] = 0.f;
+                Sn = mfma(kf[0], qf[0], z);
+                ORCH_SB();
+                read_v(PAR == 0 ? 0 : 32);   // V(b)
+            } else {
+                Sn = mfma(kf[j], qf[j], Sn);
+            }
+            ORCH_SB();
+            exp_piece(Sc, 8 + j);
+            ORCH_SB();
+        }
+        // ---- carry O and l to the reference of block b (rarely != 1), add this block's sum
+        if (moved) {
+#pragma unroll
+            for (int d = 0; d < NDB; ++d)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc_o[d][e] *= alpha;
+        }
+        l_run = l_run * alpha + psum;
+    };
+
+    // ---- prologue: K tiles 0 and 1, V tile 0 on their way; S(0); V(0) fragments meet P = 0
+    dma_tile(0, kseq, lds_k, false);
+    dma_tile(0, vseq, lds_v, true);
+    if (ntile_k > 1) dma_tile(1, kseq, lds_k + TILE_B, false);
+    __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): this wavefront's DMA has landed
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) P[kk] = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
+    if (nblk_w > 0) {
+        read_k(0);
+        read_v(0);
+        f32x16 z;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) z[e] = 0.f;
+        S[0] = mfma(kf[0], qf[0], z);
+#pragma unroll
+        for (int j = 1; j < NC; ++j) S[0] = mfma(kf[j], qf[j], S[0]);
+    }
+
+    // k_base / v_base point at the stage of the tile the next fragment reads come from
+    int kstage = 0;
+    for (int i = 0; i < ntile_k; ++i) {
+        if (i > 0) {
+            // tile i+1 of K and tile i of V were requested a step ago
+            __builtin_amdgcn_s_waitcnt(0x0f70);
+            __builtin_amdgcn_s_barrier();
+        }
+        // K tile i+2 replaces K tile i-1, V tile i+1 replaces V tile i-2: nobody reads those any more
+        if (i + 2 < ntile_k) dma_tile(i + 2, kseq, lds_k + (uint32_t)((i + 2) % NST) * TILE_B, false);
+        if (i + 1 < ntile_k) dma_tile(i + 1, vseq, lds_v + (uint32_t)((i + 1) % NST) * TILE_B, true);
+        if (2 * i < nblk_w) body(std::integral_constant<int, 0>{}, 2 * i);
+        const int ns = kstage == NST - 1 ? 0 : kstage + 1;
+        const uint32_t dstage = (uint32_t)((ns - kstage) * TILE_B);
+        kstage = ns;
+        k_base += dstage;   // tile i -> tile i+1: the odd block reads K(2i+2)
+        if (2 * i + 1 < nblk_w) body(std::integral_constant<int, 1>{}, 2 * i + 1);
+        v_base += dstage;   // tile i -> tile i+1
+    }
+    // ---- drain: O^T += V(B-1)^T P(B-1) for the wavefront's last block; both are in registers
+    if (nblk_w > 0) {
+#pragma unroll
+        for (int j = 0; j < 2 * NDB; ++j) {
+            const int db = j % NDB, kk = j / NDB;
+            acc_o[db] = mfma(vf[2 * db + kk], P[kk], acc_o[db]);
+        }
+    }
+
+    // ---- epilogue
+    float l_tot;
+    {
+        const uint32_t lb = __float_as_uint(l_run);
+        const auto sw = __builtin_amdgcn_permlane32_swap(lb, lb, false, false);
+        l_tot = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+    }
+    const float inv = 1.f / l_tot;
+    if (qm < L) {
+        uint16_t *op = out + ((size_t)(row0 + qm) * Hq + h) * HD;
+#pragma unroll
+        for (int d = 0; d < NDB; ++d)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                u32x2 w;
+                w.x = pack_bf16(acc_o[d][4 * r] * inv, acc_o[d][4 * r + 1] * inv);
+                w.y = pack_bf16(acc_o[d][4 * r + 2] * inv, acc_o[d][4 * r + 3] * inv);
+                *(u32x2 *)(op + 32 * d + 8 * r + 4 * g) = w;
+            }
+        if (lse != nullptr && g == 0)
+            lse[(size_t)h * total_tokens + row0 + qm] = m_run * scale + __logf(l_tot);
+    }
+}
+#undef ORCH_SB
+
 }  // namespace
 
 size_t attn_ws_bytes(int32_t batch)
@@ -814,7 +1202,13 @@ int launch_attn(const void *q, const void *k, const void *v, void *out, float *l
 #define ORCH_ATTN_LAUNCH_PIPE(HD_, C_)                                                           \
     hipLaunchKernelGGL((attn_fwd_pp_kernel<HD_, C_>), dim3((unsigned)grid), dim3(kPPThreads), 0, \
                        stream, ORCH_ATTN_ARGS)
-        if (d == 128 && causal) ORCH_ATTN_LAUNCH_PIPE(128, true);
+        const char *sel = getenv("ORCH_ATTN_KERNEL");
+        const bool il = d == 128 && !(sel && sel[0] == 'p');
+        if (il && causal)
+            hipLaunchKernelGGL((attn_fwd_il_kernel<128, true>), dim3((unsigned)grid), dim3(kILThreads), 0, stream, ORCH_ATTN_ARGS);
+        else if (il)
+            hipLaunchKernelGGL((attn_fwd_il_kernel<128, false>), dim3((unsigned)grid), dim3(kILThreads), 0, stream, ORCH_ATTN_ARGS);
+        else if (d == 128 && causal) ORCH_ATTN_LAUNCH_PIPE(128, true);
         else if (d == 128) ORCH_ATTN_LAUNCH_PIPE(128, false);
         else if (causal) ORCH_ATTN_LAUNCH(64, true, 2);
         else ORCH_ATTN_LAUNCH(64, false, 2);
@@ -822,7 +1216,12 @@ int launch_attn(const void *q, const void *k, const void *v, void *out, float *l
 #undef ORCH_ATTN_LAUNCH_PIPE
 #undef ORCH_ATTN_ARGS
     }
-    set_attn_variant(pipe ? "mfma32x32x16_bm256_8wave_pingpong" : "mfma32x32x16_bm256_4wave");
+    {
+        const char *sel = getenv("ORCH_ATTN_KERNEL");
+        const bool il = d == 128 && !(sel && sel[0] == 'p');
+        set_attn_variant(il ? "mfma32x32x16_bm256_8wave_ldsdma_interleaved"
+                            : pipe ? "mfma32x32x16_bm256_8wave_pingpong" : "mfma32x32x16_bm256_4wave");
+    }
     ORCH_HIP_CHECK(hipGetLastError());
     return ORCH_OK;
 }
