@@ -810,6 +810,9 @@ __global__ __launch_bounds__(kPPThreads) void attn_fwd_pp_kernel(
 // in half 2 of iteration b: O has received P(b-1) V(b-1) and not yet P(b) V(b).
 // ---------------------------------------------------------------------------
 constexpr int kILThreads = 512;
+#ifdef ORCH_ATTN_TIMING2
+__device__ unsigned long long g_tk[8];
+#endif
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
@@ -828,11 +831,21 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
     constexpr int NDB = HD / 32;   // 32-row blocks of O^T
     constexpr int ROWB = HD * 2;   // bytes per key row
     constexpr int TILE_B = BN * ROWB;
-    constexpr int NST = 3;
-    __shared__ __attribute__((aligned(1024))) char lds_raw[2 * NST * TILE_B];
+    constexpr int KST = 4, VST = 4;   // ring depths (K is requested three tiles ahead, V two); the tile
+                                      // loop is unrolled by the depth so that stage offsets are immediates
+    __shared__ __attribute__((aligned(1024))) char lds_raw[(KST + VST) * TILE_B];
     const uint32_t lds_k = (uint32_t)(uintptr_t)lds_raw;
-    const uint32_t lds_v = lds_k + NST * TILE_B;
+    const uint32_t lds_v = lds_k + KST * TILE_B;
 
+#ifdef ORCH_ATTN_TIMING2
+    const long long t2_entry = clock64();
+    if (blockIdx.x == 0 && threadIdx.x == 0)
+        printf("totals so far: WGs %llu | prologue %llu loop %llu epilogue %llu ticks | blocks(max wave) %llu\n", g_tk[0],
+               g_tk[1], g_tk[2], g_tk[3], g_tk[4]);
+#endif
+#ifdef ORCH_ATTN_TIMING
+    const long long tk_entry = clock64();
+#endif
     const int total_tiles = hdr->total_tiles;
     const int group = Hq / Hkv;
     int u, h;
@@ -873,46 +886,53 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
     const int kend = CAUSAL ? min(L, q0 + BM) : L;
     const int ntile_k = (kend + BN - 1) / BN;               // tiles the workgroup stages
     const int kend_w = CAUSAL ? min(L, qrow0 + 32) : L;
+#ifdef ORCH_X_HALFWAVES
+    const int nblk_w = (qrow0 < L && wave >= 4) ? (kend_w + 31) / 32 : 0;
+#else
     const int nblk_w = qrow0 < L ? (kend_w + 31) / 32 : 0;  // 32-key blocks this wavefront computes
+#endif
 
     // ---- LDS-DMA: per tile this wavefront fetches rows 8w..8w+7 of K and of V
     // (two loads of 4 rows each); lane -> (row, slot), slot -> chunk by the swizzle
     const uint32_t rstride_b = (uint32_t)Hkv * HD * 2;
     const char *kseq = (const char *)(k + ((size_t)row0 * Hkv + g_kv) * HD);
     const char *vseq = (const char *)(v + ((size_t)row0 * Hkv + g_kv) * HD);
-    auto dma_tile = [&](int t, const char *seqbase, uint32_t lds_stage, bool is_v) {
+    auto dma_one = [&](int t, const char *seqbase, uint32_t lds_stage, bool is_v, int p) {
         const char *tb = seqbase + (size_t)t * BN * rstride_b;
         const int lrem = L - 1 - t * BN;   // rows past the end repeat row L-1 (masked later)
-#pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            const int r = 4 * (2 * wave + p) + (lane >> 4);
-            const int slot = lane & 15;
-            const int swz = is_v ? 4 * (r & 3) + 2 * ((r >> 2) & 1) : (r & 15);
-            const char *src = tb + (__umul24((uint32_t)min(r, lrem), rstride_b) + 16u * (uint32_t)(slot ^ swz));
-            // Written as asm so that the compiler does not tie later LDS reads (of other
-            // stages) to this load with a vmcnt(0); completion is waited for explicitly
-            // before the tile barrier.  M0 = LDS destination of lane 0; nothing else in
-            // this kernel uses M0.
-            const uint32_t dst = lds_stage + (uint32_t)(2 * wave + p) * 1024u;
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                         :: "s"(dst), "v"(src) : "memory");
-        }
+        const int r = 4 * (2 * wave + p) + (lane >> 4);
+        const int slot = lane & 15;
+        const int swz = is_v ? 4 * (r & 3) + 2 * ((r >> 2) & 1) : (r & 15);
+        const char *src = tb + (__umul24((uint32_t)min(r, lrem), rstride_b) + 16u * (uint32_t)(slot ^ swz));
+        // Written as asm so that the compiler does not tie later LDS reads (of other
+        // stages) to this load with a vmcnt(0); completion is waited for explicitly
+        // before the tile barrier.  M0 = LDS destination of lane 0; nothing else in
+        // this kernel uses M0.
+        const uint32_t dst = lds_stage + (uint32_t)(2 * wave + p) * 1024u;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                     :: "s"(dst), "v"(src) : "memory");
+    };
+    auto dma_tile = [&](int t, const char *seqbase, uint32_t lds_stage, bool is_v) {
+        dma_one(t, seqbase, lds_stage, is_v, 0);
+        dma_one(t, seqbase, lds_stage, is_v, 1);
     };
 
     // ---- per-lane LDS addresses of the fragments (stage 0, first 32-key block)
-    // K, A operand of MFMA j: row l32, chunk (2j+g) ^ (l32 & 15), i.e. byte
-    // 32 (j ^ y) + 16 (g ^ x) of the row with y = (l32 & 15) >> 1, x = l32 & 1
-    const uint32_t k_xor = 32u * (uint32_t)((l32 & 15) >> 1);
-    uint32_t k_base = lds_k + (uint32_t)(l32 * ROWB + 16 * (g ^ (l32 & 1)));
+    // K, A operand of MFMA j: row l32, chunk (2j+g) ^ (l32 & 15)
+    uint32_t kaddr[NC];
+#pragma unroll
+    for (int j = 0; j < NC; ++j) kaddr[j] = lds_k + (uint32_t)(l32 * ROWB + 16 * ((2 * j + g) ^ (l32 & 15)));
     // V, transpose read for O block db: this lane addresses key row 4g + j4 (j4 = (lane%16)/4) and
     // the 8 bytes of columns 32 db + 16 half + 4 a .. +3 (half = (lane/16)%2, a = lane%4).  The
-    // swizzle of that row is 4 j4 + 2 g for every block and chunk, so the chunk is
-    // 4 (db ^ j4) + ((2 half + a/2) ^ 2g): byte 64 (db ^ j4) + const within the row.
-    uint32_t v_xor, v_base;
+    // swizzle of that row is 4 j4 + 2 g for every block and chunk.
+    uint32_t vaddr[NDB];
     {
         const int j4 = (lane & 15) >> 2, a = lane & 3, half = (lane >> 4) & 1;
-        v_xor = 64u * (uint32_t)j4;
-        v_base = lds_v + (uint32_t)((4 * g + j4) * ROWB + 16 * ((2 * half + (a >> 1)) ^ (2 * g)) + 8 * (a & 1));
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) {
+            const int c = (4 * db + 2 * half + (a >> 1)) ^ (4 * j4 + 2 * g);
+            vaddr[db] = lds_v + (uint32_t)((4 * g + j4) * ROWB + 16 * c + 8 * (a & 1));
+        }
     }
 
     // ---- Q fragments: B operand, column m = lane%32, k = 16c + 8g + [0..7]
@@ -944,29 +964,24 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
         return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
             (__attribute__((address_space(3))) s16x4 *)(uintptr_t)(addr + (uint32_t)off));
     };
-    // K fragments of the block at row offset `ro` (0 or 32 rows) of the stage k_base points at
-    auto read_k = [&](int ro) {
+    // fragment reads; `off` = stage * TILE_B + (row offset of the block in its tile) * ROWB, an immediate
+    auto read_k1 = [&](int j, int off) { kf[j] = lds_rd128(kaddr[j], off); };
+    auto read_k = [&](int off) {
 #pragma unroll
-        for (int j = 0; j < NC; ++j) {
-            uint32_t a;   // (k_xor ^ 32 j) + k_base in one instruction
-            asm("v_xad_u32 %0, %1, %2, %3" : "=v"(a) : "v"(k_xor), "s"(32 * j), "v"(k_base));
-            kf[j] = lds_rd128(a, ro * ROWB);
-        }
+        for (int j = 0; j < NC; ++j) read_k1(j, off);
     };
     // V fragments: chunk kk (16 keys), O block db: keys 16kk + 4g + [0..3] and 16kk + 8 + 4g + [0..3]
-    auto read_v = [&](int ro) {
+    auto read_v1 = [&](int db, int kk, int off) {
+        const s16x4 lo4 = lds_rd_tr(vaddr[db], off + (16 * kk) * ROWB);
+        const s16x4 hi4 = lds_rd_tr(vaddr[db], off + (16 * kk + 8) * ROWB);
+        const s16x8 both = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
+        vf[2 * db + kk] = __builtin_bit_cast(bf16x8, both);
+    };
+    auto read_v = [&](int off) {
 #pragma unroll
-        for (int db = 0; db < NDB; ++db) {
-            uint32_t a;   // (v_xor ^ 64 db) + v_base
-            asm("v_xad_u32 %0, %1, %2, %3" : "=v"(a) : "v"(v_xor), "s"(64 * db), "v"(v_base));
+        for (int db = 0; db < NDB; ++db)
 #pragma unroll
-            for (int kk = 0; kk < 2; ++kk) {
-                const s16x4 lo4 = lds_rd_tr(a, (ro + 16 * kk) * ROWB);
-                const s16x4 hi4 = lds_rd_tr(a, (ro + 16 * kk + 8) * ROWB);
-                const s16x8 both = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
-                vf[2 * db + kk] = __builtin_bit_cast(bf16x8, both);
-            }
-        }
+            for (int kk = 0; kk < 2; ++kk) read_v1(db, kk, off);
     };
     // keys of block b beyond the sequence or above the diagonal get -inf
     auto mask_block = [&](f32x16 &Sx, int b) {
@@ -980,32 +995,29 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
             }
         }
     };
-    // row maximum of a block and the (lazy) reference it is exponentiated against;
-    // split in three so that the pieces fit between MFMAs
-    float tmax_part;
+    // Row maximum of a block and the (lazy) reference it is exponentiated against, in three
+    // pieces that fit between MFMAs.  Trees, not chains: the instructions of a piece are
+    // independent of one another, so the wavefront does not stall on its own results.
+    float tm[5];
     auto max_a = [&](const f32x16 &Sx) {
-        float t = fmaxf(fmaxf(Sx[0], Sx[1]), Sx[2]);
-        t = fmaxf(fmaxf(t, Sx[3]), Sx[4]);
-        t = fmaxf(fmaxf(t, Sx[5]), Sx[6]);
-        t = fmaxf(fmaxf(t, Sx[7]), Sx[8]);
-        asm volatile("" : "+v"(t));
-        tmax_part = t;
+#pragma unroll
+        for (int i = 0; i < 5; ++i) tm[i] = fmaxf(fmaxf(Sx[3 * i], Sx[3 * i + 1]), Sx[3 * i + 2]);
+        asm volatile("" : "+v"(tm[0]), "+v"(tm[1]), "+v"(tm[2]), "+v"(tm[3]), "+v"(tm[4]));
     };
     auto max_b = [&](const f32x16 &Sx) {
-        float t = fmaxf(fmaxf(tmax_part, Sx[9]), Sx[10]);
-        t = fmaxf(fmaxf(t, Sx[11]), Sx[12]);
-        t = fmaxf(fmaxf(t, Sx[13]), Sx[14]);
-        t = fmaxf(t, Sx[15]);
-        asm volatile("" : "+v"(t));
-        tmax_part = t;
-    };
-    auto max_c = [&]() {
-        float tmax = tmax_part;
+        float u0 = fmaxf(fmaxf(tm[0], tm[1]), tm[2]);
+        float u1 = fmaxf(fmaxf(tm[3], tm[4]), Sx[15]);
+        float tmax = fmaxf(u0, u1);
         {   // the other half of the row lives in lane ^ 32
             const uint32_t tb = __float_as_uint(tmax);
             const auto sw = __builtin_amdgcn_permlane32_swap(tb, tb, false, false);
             tmax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
         }
+        asm volatile("" : "+v"(tmax));
+        tm[0] = tmax;
+    };
+    auto max_c = [&]() {
+        const float tmax = tm[0];
         const bool upd = tmax > m_run + lazy_thr;
         const float m_new = upd ? tmax : m_run;
         const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
@@ -1015,22 +1027,43 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
         mbias = m_use * scale_log2;
         asm volatile("" : "+v"(mbias), "+v"(alpha));
     };
-    // exp of one score of the current block (element e of S[cur]); pairs are packed to bf16.
-    // The empty asm statement pins the piece where it is written (between two MFMAs):
-    // its results must exist there, so the work cannot sink to where P is consumed.
-    float p_even;
-    auto exp_piece = [&](const f32x16 &Sc, int e) {
-        float pe = __builtin_amdgcn_exp2f(Sc[e] * scale_log2 - mbias);
-        psum += pe;
-        if ((e & 1) == 0) {
-            asm volatile("" : "+v"(pe), "+v"(psum));
-            p_even = pe;
-        } else {
-            uint32_t pk = pack_bf16(p_even, pe);
-            asm volatile("" : "+v"(pk), "+v"(psum));
-            u32x4 w = __builtin_bit_cast(u32x4, P[e >> 3]);
-            w[(e & 7) >> 1] = pk;
-            P[e >> 3] = __builtin_bit_cast(bf16x8, w);
+    // The 16 exponentials of the current block as a four-stage pipeline over "ticks" (one tick
+    // per MFMA slot): element e enters at tick(e); A: x = S*c - m, B (next tick): p = 2^x,
+    // C (tick after): sum += p, D (with C of the odd element): pack the pair to bf16 into P.
+    // A tick's instructions belong to different elements, so none waits for another.  Elements
+    // 0..7 enter two per tick (ticks 0..3), elements 8..15 one per tick (ticks 4..11); ticks 12
+    // and 13 drain.  The empty asm pins a tick's results where the tick is written (between two
+    // MFMAs): they must exist there, so the work cannot sink to where P is consumed.
+    float xs[16], ps[16];
+    auto tick_of = [](int e) { return e < 8 ? e / 2 : e - 4; };
+    auto exp_tick = [&](const f32x16 &Sc, int t) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int te = tick_of(e);
+            if (te == t) {   // A
+                xs[e] = Sc[e] * scale_log2 - mbias;
+                asm volatile("" : "+v"(xs[e]));
+            }
+            if (te + 1 == t) {   // B
+#ifdef ORCH_X_NOEXP
+                ps[e] = xs[e];
+#else
+                ps[e] = __builtin_amdgcn_exp2f(xs[e]);
+#endif
+                asm volatile("" : "+v"(ps[e]));
+            }
+            if (te + 2 == t) {   // C, and D for a completed pair
+#ifndef ORCH_X_NOPSUM
+                psum += ps[e];
+#endif
+                if (e & 1) {
+                    uint32_t pk = pack_bf16(ps[e - 1], ps[e]);
+                    asm volatile("" : "+v"(pk), "+v"(psum));
+                    u32x4 w = __builtin_bit_cast(u32x4, P[e >> 3]);
+                    w[(e & 7) >> 1] = pk;
+                    P[e >> 3] = __builtin_bit_cast(bf16x8, w);
+                }
+            }
         }
     };
     auto mfma = [](const bf16x8 &a, const bf16x8 &b, const f32x16 &c) {
@@ -1039,31 +1072,59 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
 
     // one pipeline iteration for block b of parity PAR: S[PAR] holds S(b), P holds P(b-1),
     // vf holds V(b-1)
-    auto body = [&](auto par_c, int b) {
+#ifdef ORCH_ATTN_TIMING
+    long long tk_h1 = 0, tk_h2 = 0, tk_top = 0, tk_t0 = 0, tk_wait = 0, tk_bar = 0, tk_dma = 0;
+    int tk_n = 0;
+#define ORCH_TK(acc_) do { const long long t_ = clock64(); acc_ += t_ - tk_t0; tk_t0 = t_; } while (0)
+#else
+#define ORCH_TK(acc_) do { } while (0)
+#endif
+    // The LDS-DMA unit is shared by the workgroup and a wavefront stalls at issue while it is
+    // busy, so a wavefront's four loads per step are spread over the step: one in the middle
+    // of each half of its two iterations (K in the even block, V in the odd one).
+    auto body = [&](auto par_c, auto st_c, int b, int dma_t, uint32_t dma_stage) {
         constexpr int PAR = decltype(par_c)::value;
+        constexpr int ST = decltype(st_c)::value;   // ring stage of the tile block b lies in
+        // K(b+1): odd half of this tile, or even half of the next one; V(b): this tile
+        constexpr int K_OFF = PAR == 0 ? ST * TILE_B + 32 * ROWB : ((ST + 1) % KST) * TILE_B;
+        constexpr int V_OFF = ST * TILE_B + (PAR == 0 ? 0 : 32 * ROWB);
+        const char *dma_seq = PAR == 0 ? kseq : vseq;
         f32x16 &Sc = S[PAR];
         f32x16 &Sn = S[PAR ^ 1];
+#ifdef ORCH_X_TWOCHAIN
+        f32x16 S2;
+#endif
         psum = 0.f;
+        // The two wavefronts of a SIMD take turns at the higher issue priority, one block
+        // each, so that both reach the tile barrier together (left alone the older one is
+        // always served first and then idles at the barrier).
+        if ((PAR ^ (wave >> 2)) & 1) __builtin_amdgcn_s_setprio(1);
+        else __builtin_amdgcn_s_setprio(0);
+        ORCH_TK(tk_top);
         // ---- half 1: O^T += V(b-1)^T P(b-1); maxima of S(b); exp of keys 0..15
 #pragma unroll
         for (int j = 0; j < 2 * NDB; ++j) {
             const int db = j % NDB, kk = j / NDB;
             acc_o[db] = mfma(vf[2 * db + kk], P[kk], acc_o[db]);
             ORCH_SB();
-            if (j == 0) {   // K(b+1): odd half of this tile, or even half of the next one
-                read_k(PAR == 0 ? 32 : 0);
-                ORCH_SB();
-                mask_block(Sc, b);
-            }
+            // K(b+1), one fragment per slot (odd half of this tile, or even half of the next
+            // one); the MFMA that last read kf[j] was issued in the previous half 2
+#ifndef ORCH_X_NOLDS
+            read_k1(j, K_OFF);
+            ORCH_SB();
+#endif
+            if (j == 0) mask_block(Sc, b);
             if (j == 1) max_a(Sc);
             if (j == 2) max_b(Sc);
             if (j == 3) max_c();
-            if (j >= 4) {   // chunk 0 of P is free: MFMAs 0..3 have read it
-                exp_piece(Sc, 2 * (j - 4));
-                exp_piece(Sc, 2 * (j - 4) + 1);
-            }
+            // chunk 0 of P is rewritten from tick 2 on: MFMAs 0..3 have read it by then
+            if (j >= 4) exp_tick(Sc, j - 4);
+#ifndef ORCH_X_NODMA
+            if (j == 4) dma_one(dma_t, dma_seq, dma_stage, PAR == 1, 0);
+#endif
             ORCH_SB();
         }
+        ORCH_TK(tk_h1);
         // ---- half 2: S(b+1) = K(b+1) Q^T; exp of keys 16..31
 #pragma unroll
         for (int j = 0; j < NC; ++j) {
@@ -1072,15 +1133,36 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
 #pragma unroll
                 for (int e = 0; e < 16; ++e) z[e] = 0.f;
                 Sn = mfma(kf[0], qf[0], z);
-                ORCH_SB();
-                read_v(PAR == 0 ? 0 : 32);   // V(b)
+#ifdef ORCH_X_TWOCHAIN
+            } else if (j == 1) {
+                f32x16 z;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) z[e] = 0.f;
+                S2 = mfma(kf[1], qf[1], z);
+            } else if (j & 1) {
+                S2 = mfma(kf[j], qf[j], S2);
+#endif
             } else {
                 Sn = mfma(kf[j], qf[j], Sn);
             }
             ORCH_SB();
-            exp_piece(Sc, 8 + j);
+            // V(b), the fragment that MFMA j of the next half 1 reads
+#ifndef ORCH_X_NOLDS
+            read_v1(j % NDB, j / NDB, V_OFF);
+            ORCH_SB();
+#endif
+            exp_tick(Sc, 4 + j);
+#ifndef ORCH_X_NODMA
+            if (j == 4) dma_one(dma_t, dma_seq, dma_stage, PAR == 1, 1);
+#endif
             ORCH_SB();
         }
+        exp_tick(Sc, 12);
+        exp_tick(Sc, 13);
+#ifdef ORCH_X_TWOCHAIN
+#pragma unroll
+        for (int e = 0; e < 16; ++e) Sn[e] += S2[e];
+#endif
         // ---- carry O and l to the reference of block b (rarely != 1), add this block's sum
         if (moved) {
 #pragma unroll
@@ -1089,12 +1171,21 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
                 for (int e = 0; e < 16; ++e) acc_o[d][e] *= alpha;
         }
         l_run = l_run * alpha + psum;
+        ORCH_TK(tk_h2);
+#ifdef ORCH_ATTN_TIMING
+        ++tk_n;
+#endif
     };
 
     // ---- prologue: K tiles 0 and 1, V tile 0 on their way; S(0); V(0) fragments meet P = 0
+    // (tile indices past the end are clamped: the copy lands in a stage nobody reads, and every
+    // step issues the same number of loads, which the vmcnt arithmetic below relies on)
+    auto tile_c = [&](int t) { return t < ntile_k ? t : ntile_k - 1; };
     dma_tile(0, kseq, lds_k, false);
     dma_tile(0, vseq, lds_v, true);
-    if (ntile_k > 1) dma_tile(1, kseq, lds_k + TILE_B, false);
+    dma_tile(tile_c(1), kseq, lds_k + TILE_B, false);
+    dma_tile(tile_c(1), vseq, lds_v + TILE_B, true);
+    dma_tile(tile_c(2), kseq, lds_k + 2 * TILE_B, false);
     __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): this wavefront's DMA has landed
     __builtin_amdgcn_s_barrier();
 #pragma unroll
@@ -1110,25 +1201,56 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
         for (int j = 1; j < NC; ++j) S[0] = mfma(kf[j], qf[j], S[0]);
     }
 
-    // k_base / v_base point at the stage of the tile the next fragment reads come from
-    int kstage = 0;
-    for (int i = 0; i < ntile_k; ++i) {
+#ifdef ORCH_ATTN_TIMING
+    tk_t0 = clock64();
+    const long long tk_start = tk_t0, tk_wstart = wall_clock64();
+#endif
+#ifdef ORCH_ATTN_TIMING2
+    const long long t2_loop = clock64();
+#endif
+    // one 64-key tile (two blocks) whose ring stage ST = i % 4 is a compile-time constant
+    auto step = [&](auto st_c, int i) {
+        constexpr int ST = decltype(st_c)::value;
         if (i > 0) {
-            // tile i+1 of K and tile i of V were requested a step ago
-            __builtin_amdgcn_s_waitcnt(0x0f70);
+            ORCH_TK(tk_top);
+            // K(i+1) and V(i) were requested two steps ago; the four loads of the last step
+            // (K(i+2), V(i+1)) may stay in flight: vmcnt(4)
+            __builtin_amdgcn_s_waitcnt(0x0f74);
+            ORCH_TK(tk_wait);
+#ifndef ORCH_X_NOBARRIER
             __builtin_amdgcn_s_barrier();
+#endif
+            ORCH_TK(tk_bar);
         }
-        // K tile i+2 replaces K tile i-1, V tile i+1 replaces V tile i-2: nobody reads those any more
-        if (i + 2 < ntile_k) dma_tile(i + 2, kseq, lds_k + (uint32_t)((i + 2) % NST) * TILE_B, false);
-        if (i + 1 < ntile_k) dma_tile(i + 1, vseq, lds_v + (uint32_t)((i + 1) % NST) * TILE_B, true);
-        if (2 * i < nblk_w) body(std::integral_constant<int, 0>{}, 2 * i);
-        const int ns = kstage == NST - 1 ? 0 : kstage + 1;
-        const uint32_t dstage = (uint32_t)((ns - kstage) * TILE_B);
-        kstage = ns;
-        k_base += dstage;   // tile i -> tile i+1: the odd block reads K(2i+2)
-        if (2 * i + 1 < nblk_w) body(std::integral_constant<int, 1>{}, 2 * i + 1);
-        v_base += dstage;   // tile i -> tile i+1
+        // K(i+3) replaces K(i-1), V(i+2) replaces V(i-2): nobody reads those any more
+        const int kt = tile_c(i + 3), vt = tile_c(i + 2);
+        const uint32_t kdst = lds_k + (uint32_t)(((ST + 3) % KST) * TILE_B);
+        const uint32_t vdst = lds_v + (uint32_t)(((ST + 2) % VST) * TILE_B);
+        if (2 * i < nblk_w) body(std::integral_constant<int, 0>{}, st_c, 2 * i, kt, kdst);
+#ifndef ORCH_X_NODMA
+        else dma_tile(kt, kseq, kdst, false);   // a wavefront past its causal range still feeds the ring
+#endif
+        if (2 * i + 1 < nblk_w) body(std::integral_constant<int, 1>{}, st_c, 2 * i + 1, vt, vdst);
+#ifndef ORCH_X_NODMA
+        else dma_tile(vt, vseq, vdst, true);
+#endif
+    };
+    for (int i0 = 0; i0 < ntile_k; i0 += 4) {
+        step(std::integral_constant<int, 0>{}, i0);
+        if (i0 + 1 < ntile_k) step(std::integral_constant<int, 1>{}, i0 + 1);
+        if (i0 + 2 < ntile_k) step(std::integral_constant<int, 2>{}, i0 + 2);
+        if (i0 + 3 < ntile_k) step(std::integral_constant<int, 3>{}, i0 + 3);
     }
+#ifdef ORCH_ATTN_TIMING
+    if ((blockIdx.x == 0 || blockIdx.x == 20000) && lane == 0)
+        printf("blk %d wave %d rblk %d blocks %d tiles %d | per block: half1 %lld half2 %lld other %lld | per tile: wait %lld barrier %lld dma %lld | loop ticks %lld wall(100MHz) %lld\n",
+               blockIdx.x, wave, rblk, tk_n, ntile_k, tk_n ? tk_h1 / tk_n : 0, tk_n ? tk_h2 / tk_n : 0,
+               tk_n ? tk_top / tk_n : 0, tk_wait / ntile_k, tk_bar / ntile_k, tk_dma / ntile_k, clock64() - tk_start, wall_clock64() - tk_wstart);
+    const long long tk_loop_end = clock64();
+#endif
+#ifdef ORCH_ATTN_TIMING2
+    const long long t2_loop_end = clock64();
+#endif
     // ---- drain: O^T += V(B-1)^T P(B-1) for the wavefront's last block; both are in registers
     if (nblk_w > 0) {
 #pragma unroll
@@ -1160,6 +1282,22 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
         if (lse != nullptr && g == 0)
             lse[(size_t)h * total_tokens + row0 + qm] = m_run * scale + __logf(l_tot);
     }
+#ifdef ORCH_ATTN_TIMING2
+    if (wave == 4 && lane == 0) {   // the wavefront with the most blocks
+        const long long t2_end = clock64();
+        atomicAdd(&g_tk[0], 1ull);
+        atomicAdd(&g_tk[1], (unsigned long long)(t2_loop - t2_entry));
+        atomicAdd(&g_tk[2], (unsigned long long)(t2_loop_end - t2_loop));
+        atomicAdd(&g_tk[3], (unsigned long long)(t2_end - t2_loop_end));
+        atomicAdd(&g_tk[4], (unsigned long long)nblk_w);
+    }
+#endif
+#ifdef ORCH_ATTN_TIMING
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if ((blockIdx.x == 3 || blockIdx.x == 20003 || blockIdx.x == 40003) && lane == 0 && (wave == 0 || wave == 4))
+        printf("blk %d wave %d: entry->loop %lld, loop %lld, drain+epilogue %lld ticks (tiles %d)\n", blockIdx.x, wave,
+               tk_start - tk_entry, tk_loop_end - tk_start, clock64() - tk_loop_end, ntile_k);
+#endif
 }
 #undef ORCH_SB
 
