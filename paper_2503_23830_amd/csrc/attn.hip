@@ -897,20 +897,36 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
     const uint32_t rstride_b = (uint32_t)Hkv * HD * 2;
     const char *kseq = (const char *)(k + ((size_t)row0 * Hkv + g_kv) * HD);
     const char *vseq = (const char *)(v + ((size_t)row0 * Hkv + g_kv) * HD);
+    // per-lane byte offset of the 16 bytes this lane fetches, relative to the tile's first row
+    uint32_t dma_off[2][2];
+#pragma unroll
+    for (int is_v = 0; is_v < 2; ++is_v)
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            const int r = 4 * (2 * wave + p) + (lane >> 4);
+            const int slot = lane & 15;
+            const int swz = is_v ? 4 * (r & 3) + 2 * ((r >> 2) & 1) : (r & 15);
+            dma_off[is_v][p] = __umul24((uint32_t)r, rstride_b) + 16u * (uint32_t)(slot ^ swz);
+        }
     auto dma_one = [&](int t, const char *seqbase, uint32_t lds_stage, bool is_v, int p) {
         const char *tb = seqbase + (size_t)t * BN * rstride_b;
-        const int lrem = L - 1 - t * BN;   // rows past the end repeat row L-1 (masked later)
-        const int r = 4 * (2 * wave + p) + (lane >> 4);
-        const int slot = lane & 15;
-        const int swz = is_v ? 4 * (r & 3) + 2 * ((r >> 2) & 1) : (r & 15);
-        const char *src = tb + (__umul24((uint32_t)min(r, lrem), rstride_b) + 16u * (uint32_t)(slot ^ swz));
+        const int lrem = L - 1 - t * BN;
         // Written as asm so that the compiler does not tie later LDS reads (of other
         // stages) to this load with a vmcnt(0); completion is waited for explicitly
         // before the tile barrier.  M0 = LDS destination of lane 0; nothing else in
         // this kernel uses M0.
         const uint32_t dst = lds_stage + (uint32_t)(2 * wave + p) * 1024u;
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                     :: "s"(dst), "v"(src) : "memory");
+        if (lrem >= BN - 1) {   // whole tile inside the sequence: scalar base + fixed lane offset
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :: "s"(dst), "v"(dma_off[is_v ? 1 : 0][p]), "s"(tb) : "memory");
+        } else {                // last tile: rows past the end repeat row L-1 (masked later)
+            const int r = 4 * (2 * wave + p) + (lane >> 4);
+            const int slot = lane & 15;
+            const int swz = is_v ? 4 * (r & 3) + 2 * ((r >> 2) & 1) : (r & 15);
+            const char *src = tb + (__umul24((uint32_t)min(r, lrem), rstride_b) + 16u * (uint32_t)(slot ^ swz));
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                         :: "s"(dst), "v"(src) : "memory");
+        }
     };
     auto dma_tile = [&](int t, const char *seqbase, uint32_t lds_stage, bool is_v) {
         dma_one(t, seqbase, lds_stage, is_v, 0);
