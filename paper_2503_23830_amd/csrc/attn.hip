@@ -897,40 +897,53 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
     const uint32_t rstride_b = (uint32_t)Hkv * HD * 2;
     const char *kseq = (const char *)(k + ((size_t)row0 * Hkv + g_kv) * HD);
     const char *vseq = (const char *)(v + ((size_t)row0 * Hkv + g_kv) * HD);
-    // per-lane byte offset of the 16 bytes this lane fetches, relative to the tile's first row
-    uint32_t dma_off[2][2];
+    // per-lane byte offset of the 16 bytes this lane fetches, relative to the tile's first row:
+    // [0] for tiles inside the sequence, [1] for the last tile this workgroup stages, whose rows
+    // past the end repeat row L-1 (they are masked later)
+    uint32_t dma_off[2][2][2];
+    {
+        const int lrem_last = L - 1 - (ntile_k - 1) * BN;
 #pragma unroll
-    for (int is_v = 0; is_v < 2; ++is_v)
+        for (int is_v = 0; is_v < 2; ++is_v)
 #pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            const int r = 4 * (2 * wave + p) + (lane >> 4);
-            const int slot = lane & 15;
-            const int swz = is_v ? 4 * (r & 3) + 2 * ((r >> 2) & 1) : (r & 15);
-            dma_off[is_v][p] = __umul24((uint32_t)r, rstride_b) + 16u * (uint32_t)(slot ^ swz);
-        }
-    auto dma_one = [&](int t, const char *seqbase, uint32_t lds_stage, bool is_v, int p) {
-        const char *tb = seqbase + (size_t)t * BN * rstride_b;
-        const int lrem = L - 1 - t * BN;
-        // Written as asm so that the compiler does not tie later LDS reads (of other
-        // stages) to this load with a vmcnt(0); completion is waited for explicitly
-        // before the tile barrier.  M0 = LDS destination of lane 0; nothing else in
-        // this kernel uses M0.
-        const uint32_t dst = lds_stage + (uint32_t)(2 * wave + p) * 1024u;
-        if (lrem >= BN - 1) {   // whole tile inside the sequence: scalar base + fixed lane offset
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                         :: "s"(dst), "v"(dma_off[is_v ? 1 : 0][p]), "s"(tb) : "memory");
-        } else {                // last tile: rows past the end repeat row L-1 (masked later)
-            const int r = 4 * (2 * wave + p) + (lane >> 4);
-            const int slot = lane & 15;
-            const int swz = is_v ? 4 * (r & 3) + 2 * ((r >> 2) & 1) : (r & 15);
-            const char *src = tb + (__umul24((uint32_t)min(r, lrem), rstride_b) + 16u * (uint32_t)(slot ^ swz));
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                         :: "s"(dst), "v"(src) : "memory");
-        }
+            for (int p = 0; p < 2; ++p) {
+                const int r = 4 * (2 * wave + p) + (lane >> 4);
+                const int slot = lane & 15;
+                const int swz = is_v ? 4 * (r & 3) + 2 * ((r >> 2) & 1) : (r & 15);
+                const uint32_t col = 16u * (uint32_t)(slot ^ swz);
+                dma_off[0][is_v][p] = __umul24((uint32_t)r, rstride_b) + col;
+                dma_off[1][is_v][p] = __umul24((uint32_t)min(r, lrem_last), rstride_b) + col;
+            }
+    }
+    // One LDS-DMA load: 64 lanes x 16 bytes from tile base `tb` (scalar) + per-lane offset into
+    // 1 KB of LDS at `dst`.  Written as asm so that the compiler does not tie later LDS reads
+    // (of other stages) to this load with a vmcnt(0); completion is waited for explicitly
+    // before the tile barrier.  M0 = LDS destination of lane 0; nothing else in this kernel
+    // uses M0.
+    auto dma_issue = [&](const char *tb, uint32_t off, uint32_t dst) {
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                     :: "s"(dst), "v"(off), "s"(tb) : "memory");
     };
-    auto dma_tile = [&](int t, const char *seqbase, uint32_t lds_stage, bool is_v) {
-        dma_one(t, seqbase, lds_stage, is_v, 0);
-        dma_one(t, seqbase, lds_stage, is_v, 1);
+    struct DmaJob {
+        const char *tb;     // first row of the tile
+        uint32_t off[2];    // this lane's offsets for the wavefront's two loads
+        uint32_t dst;       // LDS stage
+    };
+    auto dma_job = [&](int t, bool is_v, uint32_t lds_stage) {
+        const int tc = t < ntile_k ? t : ntile_k - 1;   // past the end: repeat the last tile
+        const bool last = tc == ntile_k - 1;
+        DmaJob j;
+        j.tb = (is_v ? vseq : kseq) + (size_t)tc * BN * rstride_b;
+        j.off[0] = last ? dma_off[1][is_v][0] : dma_off[0][is_v][0];
+        j.off[1] = last ? dma_off[1][is_v][1] : dma_off[0][is_v][1];
+        j.dst = lds_stage + (uint32_t)(2 * wave) * 1024u;
+        return j;
+    };
+    auto dma_run = [&](const DmaJob &j, int p) { dma_issue(j.tb, j.off[p], j.dst + (uint32_t)p * 1024u); };
+    auto dma_tile = [&](int t, bool is_v, uint32_t lds_stage) {
+        const DmaJob j = dma_job(t, is_v, lds_stage);
+        dma_run(j, 0);
+        dma_run(j, 1);
     };
 
     // ---- per-lane LDS addresses of the fragments (stage 0, first 32-key block)
@@ -1098,13 +1111,12 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
     // The LDS-DMA unit is shared by the workgroup and a wavefront stalls at issue while it is
     // busy, so a wavefront's four loads per step are spread over the step: one in the middle
     // of each half of its two iterations (K in the even block, V in the odd one).
-    auto body = [&](auto par_c, auto st_c, int b, int dma_t, uint32_t dma_stage) {
+    auto body = [&](auto par_c, auto st_c, int b, const DmaJob &dj) {
         constexpr int PAR = decltype(par_c)::value;
         constexpr int ST = decltype(st_c)::value;   // ring stage of the tile block b lies in
         // K(b+1): odd half of this tile, or even half of the next one; V(b): this tile
         constexpr int K_OFF = PAR == 0 ? ST * TILE_B + 32 * ROWB : ((ST + 1) % KST) * TILE_B;
         constexpr int V_OFF = ST * TILE_B + (PAR == 0 ? 0 : 32 * ROWB);
-        const char *dma_seq = PAR == 0 ? kseq : vseq;
         f32x16 &Sc = S[PAR];
         f32x16 &Sn = S[PAR ^ 1];
 #ifdef ORCH_X_TWOCHAIN
@@ -1136,7 +1148,7 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
             // chunk 0 of P is rewritten from tick 2 on: MFMAs 0..3 have read it by then
             if (j >= 4) exp_tick(Sc, j - 4);
 #ifndef ORCH_X_NODMA
-            if (j == 4) dma_one(dma_t, dma_seq, dma_stage, PAR == 1, 0);
+            if (j == 4) dma_run(dj, 0);
 #endif
             ORCH_SB();
         }
@@ -1169,7 +1181,7 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
 #endif
             exp_tick(Sc, 4 + j);
 #ifndef ORCH_X_NODMA
-            if (j == 4) dma_one(dma_t, dma_seq, dma_stage, PAR == 1, 1);
+            if (j == 4) dma_run(dj, 1);
 #endif
             ORCH_SB();
         }
@@ -1196,12 +1208,11 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
     // ---- prologue: K tiles 0 and 1, V tile 0 on their way; S(0); V(0) fragments meet P = 0
     // (tile indices past the end are clamped: the copy lands in a stage nobody reads, and every
     // step issues the same number of loads, which the vmcnt arithmetic below relies on)
-    auto tile_c = [&](int t) { return t < ntile_k ? t : ntile_k - 1; };
-    dma_tile(0, kseq, lds_k, false);
-    dma_tile(0, vseq, lds_v, true);
-    dma_tile(tile_c(1), kseq, lds_k + TILE_B, false);
-    dma_tile(tile_c(1), vseq, lds_v + TILE_B, true);
-    dma_tile(tile_c(2), kseq, lds_k + 2 * TILE_B, false);
+    dma_tile(0, false, lds_k);
+    dma_tile(0, true, lds_v);
+    dma_tile(1, false, lds_k + TILE_B);
+    dma_tile(1, true, lds_v + TILE_B);
+    dma_tile(2, false, lds_k + 2 * TILE_B);
     __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): this wavefront's DMA has landed
     __builtin_amdgcn_s_barrier();
 #pragma unroll
@@ -1239,17 +1250,24 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
             ORCH_TK(tk_bar);
         }
         // K(i+3) replaces K(i-1), V(i+2) replaces V(i-2): nobody reads those any more
-        const int kt = tile_c(i + 3), vt = tile_c(i + 2);
-        const uint32_t kdst = lds_k + (uint32_t)(((ST + 3) % KST) * TILE_B);
-        const uint32_t vdst = lds_v + (uint32_t)(((ST + 2) % VST) * TILE_B);
-        if (2 * i < nblk_w) body(std::integral_constant<int, 0>{}, st_c, 2 * i, kt, kdst);
+        const DmaJob kj = dma_job(i + 3, false, lds_k + (uint32_t)(((ST + 3) % KST) * TILE_B));
+        const DmaJob vj = dma_job(i + 2, true, lds_v + (uint32_t)(((ST + 2) % VST) * TILE_B));
+        if (2 * i < nblk_w) {
+            body(std::integral_constant<int, 0>{}, st_c, 2 * i, kj);
+        } else {   // a wavefront past its causal range still feeds the ring
 #ifndef ORCH_X_NODMA
-        else dma_tile(kt, kseq, kdst, false);   // a wavefront past its causal range still feeds the ring
+            dma_run(kj, 0);
+            dma_run(kj, 1);
 #endif
-        if (2 * i + 1 < nblk_w) body(std::integral_constant<int, 1>{}, st_c, 2 * i + 1, vt, vdst);
+        }
+        if (2 * i + 1 < nblk_w) {
+            body(std::integral_constant<int, 1>{}, st_c, 2 * i + 1, vj);
+        } else {
 #ifndef ORCH_X_NODMA
-        else dma_tile(vt, vseq, vdst, true);
+            dma_run(vj, 0);
+            dma_run(vj, 1);
 #endif
+        }
     };
     for (int i0 = 0; i0 < ntile_k; i0 += 4) {
         step(std::integral_constant<int, 0>{}, i0);
