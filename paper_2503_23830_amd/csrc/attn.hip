@@ -1027,20 +1027,32 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
     // Row maximum of a block and the (lazy) reference it is exponentiated against, in three
     // pieces that fit between MFMAs.  Trees, not chains: the instructions of a piece are
     // independent of one another, so the wavefront does not stall on its own results.
+    // (maxima as instructions: the scores are never NaN here, so the canonicalising copies
+    // the compiler adds around fmaxf are not wanted)
+    auto vmax3 = [](float a, float b, float c) {
+        float r;
+        asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+        return r;
+    };
+    auto vmax2 = [](float a, float b) {
+        float r;
+        asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+        return r;
+    };
     float tm[5];
     auto max_a = [&](const f32x16 &Sx) {
 #pragma unroll
-        for (int i = 0; i < 5; ++i) tm[i] = fmaxf(fmaxf(Sx[3 * i], Sx[3 * i + 1]), Sx[3 * i + 2]);
+        for (int i = 0; i < 5; ++i) tm[i] = vmax3(Sx[3 * i], Sx[3 * i + 1], Sx[3 * i + 2]);
         asm volatile("" : "+v"(tm[0]), "+v"(tm[1]), "+v"(tm[2]), "+v"(tm[3]), "+v"(tm[4]));
     };
     auto max_b = [&](const f32x16 &Sx) {
-        float u0 = fmaxf(fmaxf(tm[0], tm[1]), tm[2]);
-        float u1 = fmaxf(fmaxf(tm[3], tm[4]), Sx[15]);
-        float tmax = fmaxf(u0, u1);
+        const float u0 = vmax3(tm[0], tm[1], tm[2]);
+        const float u1 = vmax3(tm[3], tm[4], Sx[15]);
+        float tmax = vmax2(u0, u1);
         {   // the other half of the row lives in lane ^ 32
             const uint32_t tb = __float_as_uint(tmax);
             const auto sw = __builtin_amdgcn_permlane32_swap(tb, tb, false, false);
-            tmax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+            tmax = vmax2(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
         }
         asm volatile("" : "+v"(tmax));
         tm[0] = tmax;
@@ -1123,11 +1135,6 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
         f32x16 S2;
 #endif
         psum = 0.f;
-        // The two wavefronts of a SIMD take turns at the higher issue priority, one block
-        // each, so that both reach the tile barrier together (left alone the older one is
-        // always served first and then idles at the barrier).
-        if ((PAR ^ (wave >> 2)) & 1) __builtin_amdgcn_s_setprio(1);
-        else __builtin_amdgcn_s_setprio(0);
         ORCH_TK(tk_top);
         // ---- half 1: O^T += V(b-1)^T P(b-1); maxima of S(b); exp of keys 0..15
 #pragma unroll
