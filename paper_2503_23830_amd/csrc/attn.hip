@@ -2,8 +2,12 @@
 // back to back (the batching the paper uses for every phase that runs without
 // paddings, Sec. 7; the quadratic term of Eq. 2).
 //
-// One workgroup (4 wavefronts) owns 128*MB consecutive query rows of one
-// sequence and one q-head; each wavefront owns MB blocks of 32 rows.  K/V tiles
+// Common to both kernels below (head_dim 64: attn_fwd_kernel; head_dim 128:
+// attn_fwd_il_kernel, described at its definition): the transposed score
+// product, per-lane softmax statistics and the lazy reference maximum.
+//
+// attn_fwd_kernel: one workgroup (4 wavefronts) owns 128*MB consecutive query rows
+// of one sequence and one q-head; each wavefront owns MB blocks of 32 rows.  K/V tiles
 // of BN = 64 keys are staged through LDS (V transposed on the way in) and shared
 // by the four wavefronts; with MB = 2 every K/V fragment read from LDS feeds two
 // MFMAs, which halves LDS traffic per FLOP.  The scores are computed transposed,
@@ -14,7 +18,6 @@
 // rescaling O is a per-lane multiply.  The running maximum is only moved when a
 // row's maximum grows by more than 2^8 (exact: the stale reference cancels in
 // the final division), so O is rarely rescaled after the first tile.
-#include <stdlib.h>
 #include <type_traits>
 
 #include "common.h"
@@ -371,413 +374,6 @@ __global__ __launch_bounds__(kThreads, (MB * HD > 128 ? 1 : 2)) void attn_fwd_ke
 
 
 // ---------------------------------------------------------------------------
-// Ping-pong variant: 8 wavefronts (two per SIMD) own 256 query rows, 32 each,
-// and share double-buffered K / V^T tiles of 64 keys.  The key sequence is walked
-// in 32-key blocks b; a wavefront alternates
-//     M(b): S = QK(b), O += PV(b-1)      16 MFMAs (HD = 128), plus its share of
-//                                        the global -> LDS staging
-//     V(b): online softmax of block b    vector ALU; first it requests the LDS
-//                                        fragments of M(b+1), which arrive meanwhile
-// with a workgroup barrier after every phase.  Wavefronts 4..7 run one phase
-// behind wavefronts 0..3, so on every SIMD one wavefront is in its MFMA phase
-// while the other is in its vector-ALU phase: matrix cores and vector ALU work
-// at the same time without relying on instruction scheduling.  (Left to
-// themselves the two wavefronts of a SIMD stay in lockstep and the units take
-// turns.)
-//
-// LDS hazards, with phases numbered t (group 0: M(b) at 2b, V(b) at 2b+1; group
-// 1 one later): K_{i+1} is stored in M(2i) (t = 4i, 4i+1) into the buffer of
-// K_{i-1}, whose last fragment read was requested in V(2i-2) (t <= 4i-2); its
-// first read is requested in V(2i+1) (t >= 4i+3).  V_{i+1} is stored in M(2i+1)
-// (t = 4i+2, 4i+3) over V_{i-1}, last requested in V(2i-1) (t <= 4i); first
-// requested in V(2i+2) (t >= 4i+5).
-//
-// The MFMA groups are inline asm: MFMAs go back to back, and the hazards the
-// compiler would pad for a builtin MFMA (vector-ALU write -> MFMA read, MFMA
-// write -> vector-ALU read) are padded by hand with s_nop.
-// ---------------------------------------------------------------------------
-constexpr int kPPThreads = 512;
-
-__device__ __forceinline__ void lds_barrier()
-{
-    // LDS writes of this wavefront are complete before the barrier; global loads
-    // in flight (the prefetch of a later tile) are not waited for
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
-
-// four 16-byte LDS reads at addr + O0..O3
-template <int O0, int O1, int O2, int O3>
-__device__ __forceinline__ void lds_rd4(bf16x8 &f0, bf16x8 &f1, bf16x8 &f2, bf16x8 &f3, uint32_t addr)
-{
-    asm volatile(
-        "ds_read_b128 %0, %4 offset:%5\n\t"
-        "ds_read_b128 %1, %4 offset:%6\n\t"
-        "ds_read_b128 %2, %4 offset:%7\n\t"
-        "ds_read_b128 %3, %4 offset:%8\n\t"
-        : "=&v"(f0), "=&v"(f1), "=&v"(f2), "=&v"(f3)
-        : "v"(addr), "n"(O0), "n"(O1), "n"(O2), "n"(O3)
-        : "memory");
-}
-
-#define ORCH_MFMA "v_mfma_f32_32x32x16_bf16 "
-// S = (FIRST ? 0 : S) + sum_j f_j q_j ; with W >= 0 the j-th MFMA first waits
-// until at most W-j LDS reads are outstanding (reads return in order)
-template <bool FIRST, int W>
-__device__ __forceinline__ void mfma_qk4(f32x16 &S, const bf16x8 &f0, const bf16x8 &f1, const bf16x8 &f2,
-                                         const bf16x8 &f3, const bf16x8 &q0, const bf16x8 &q1,
-                                         const bf16x8 &q2, const bf16x8 &q3)
-{
-    if constexpr (FIRST) {
-        if constexpr (W >= 0)
-            asm volatile("s_waitcnt lgkmcnt(%9)\n\t" ORCH_MFMA "%0, %1, %5, 0\n\t"
-                         "s_waitcnt lgkmcnt(%10)\n\t" ORCH_MFMA "%0, %2, %6, %0\n\t"
-                         "s_waitcnt lgkmcnt(%11)\n\t" ORCH_MFMA "%0, %3, %7, %0\n\t"
-                         "s_waitcnt lgkmcnt(%12)\n\t" ORCH_MFMA "%0, %4, %8, %0\n\t"
-                         : "=&v"(S)
-                         : "v"(f0), "v"(f1), "v"(f2), "v"(f3), "v"(q0), "v"(q1), "v"(q2), "v"(q3),
-                           "n"(W), "n"(W - 1), "n"(W - 2), "n"(W - 3));
-        else
-            asm volatile(ORCH_MFMA "%0, %1, %5, 0\n\t" ORCH_MFMA "%0, %2, %6, %0\n\t"
-                         ORCH_MFMA "%0, %3, %7, %0\n\t" ORCH_MFMA "%0, %4, %8, %0\n\t"
-                         : "=&v"(S)
-                         : "v"(f0), "v"(f1), "v"(f2), "v"(f3), "v"(q0), "v"(q1), "v"(q2), "v"(q3));
-    } else {
-        if constexpr (W >= 0)
-            asm volatile("s_waitcnt lgkmcnt(%9)\n\t" ORCH_MFMA "%0, %1, %5, %0\n\t"
-                         "s_waitcnt lgkmcnt(%10)\n\t" ORCH_MFMA "%0, %2, %6, %0\n\t"
-                         "s_waitcnt lgkmcnt(%11)\n\t" ORCH_MFMA "%0, %3, %7, %0\n\t"
-                         "s_waitcnt lgkmcnt(%12)\n\t" ORCH_MFMA "%0, %4, %8, %0\n\t"
-                         : "+v"(S)
-                         : "v"(f0), "v"(f1), "v"(f2), "v"(f3), "v"(q0), "v"(q1), "v"(q2), "v"(q3),
-                           "n"(W), "n"(W - 1), "n"(W - 2), "n"(W - 3));
-        else
-            asm volatile(ORCH_MFMA "%0, %1, %5, %0\n\t" ORCH_MFMA "%0, %2, %6, %0\n\t"
-                         ORCH_MFMA "%0, %3, %7, %0\n\t" ORCH_MFMA "%0, %4, %8, %0\n\t"
-                         : "+v"(S)
-                         : "v"(f0), "v"(f1), "v"(f2), "v"(f3), "v"(q0), "v"(q1), "v"(q2), "v"(q3));
-    }
-}
-// oa += f0 p0 + f1 p1 ; ob += f2 p0 + f3 p1
-__device__ __forceinline__ void mfma_pv4(f32x16 &oa, f32x16 &ob, const bf16x8 &f0, const bf16x8 &f1,
-                                         const bf16x8 &f2, const bf16x8 &f3, const bf16x8 &p0,
-                                         const bf16x8 &p1)
-{
-    asm volatile(ORCH_MFMA "%0, %2, %6, %0\n\t" ORCH_MFMA "%1, %4, %6, %1\n\t"
-                 ORCH_MFMA "%0, %3, %7, %0\n\t" ORCH_MFMA "%1, %5, %7, %1\n\t"
-                 : "+v"(oa), "+v"(ob)
-                 : "v"(f0), "v"(f1), "v"(f2), "v"(f3), "v"(p0), "v"(p1));
-}
-#undef ORCH_MFMA
-// all LDS reads issued so far have landed; vector-ALU results written just before
-// (P, rescaled O) are safe to read from an MFMA
-__device__ __forceinline__ void mfma_group_begin() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_nop 7" ::: "memory"); }
-// MFMA results are safe to read from the vector ALU
-__device__ __forceinline__ void mfma_group_end() { asm volatile("s_nop 15\n\ts_nop 7" ::: "memory"); }
-
-template <int HD, bool CAUSAL>
-__global__ __launch_bounds__(kPPThreads) void attn_fwd_pp_kernel(
-    const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
-    uint16_t *__restrict__ out, float *__restrict__ lse, const int32_t *__restrict__ cu,
-    const AttnHdr *__restrict__ hdr, const int32_t *__restrict__ tile_off, int32_t batch,
-    int32_t total_tokens, int32_t Hq, int32_t Hkv, float scale, float scale_log2)
-{
-    constexpr int BM = 256;
-    constexpr int KS = HD + 8;    // K tile row stride (elements): 16-byte rows land on distinct banks
-    constexpr int VS = BN + 8;    // V^T tile row stride
-    constexpr int NC = HD / 16;   // 16-wide chunks of the head dimension
-    constexpr int NDB = HD / 32;  // 32-row blocks of O^T
-    constexpr int KTILE = BN * KS, VTILE = HD * VS;
-    __shared__ __attribute__((aligned(16))) uint16_t Ks[2 * KTILE];
-    __shared__ __attribute__((aligned(16))) uint16_t Vt[2 * VTILE];
-
-    const int total_tiles = hdr->total_tiles;
-    const int group = Hq / Hkv;
-    // block -> (query tile u, head h).  With Hkv a multiple of 8 the kv-head is
-    // chosen by blockIdx % 8, i.e. by XCD, so the blocks that share a K/V stream
-    // share an L2.
-    int u, h;
-    {
-        const int bid = blockIdx.x;
-        if ((Hkv & 7) == 0) {
-            const int kvh = (bid & 7) + 8 * ((bid >> 3) % (Hkv >> 3));
-            const int rest = bid / Hkv;
-            h = kvh * group + rest % group;
-            u = rest / group;
-        } else {
-            h = bid % Hq;
-            u = bid / Hq;
-        }
-    }
-    if (u >= total_tiles) return;
-    const int g_kv = h / group;
-    int lo = 0, hi = batch - 1;
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (tile_off[mid] <= u) lo = mid; else hi = mid - 1;
-    }
-    const int seq = lo;
-    const int row0 = cu[seq];
-    const int L = cu[seq + 1] - row0;
-    const int ntile_q = (L + BM - 1) / BM;
-    const int qt = ntile_q - 1 - (u - tile_off[seq]);  // heaviest (last) tile first
-    const int q0 = qt * BM;
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    // wave-uniform values live in scalar registers: per-wavefront decisions are scalar branches
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int l32 = lane & 31, g = lane >> 5;
-    const int grp = wave >> 2;   // 0: leading group, 1: one phase behind
-    // waves w and w+4 share a SIMD; row blocks w and 7-w even out the causal work per SIMD
-    const int rblk = wave < 4 ? wave : 11 - wave;
-    const int qrow0 = q0 + 32 * rblk;
-    const int qm = qrow0 + l32;
-
-    // ---- Q fragments: B operand, column m = lane%32, k = 16c + 8g + [0..7]
-    bf16x8 qf[NC];
-    {
-        const int qm_c = qm < L ? qm : L - 1;
-        const uint16_t *qp = q + ((size_t)(row0 + qm_c) * Hq + h) * HD + 8 * g;
-#pragma unroll
-        for (int c = 0; c < NC; ++c) qf[c] = *(const bf16x8 *)(qp + 16 * c);
-    }
-    f32x16 acc_o[NDB];
-#pragma unroll
-    for (int d = 0; d < NDB; ++d)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc_o[d][e] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
-    // a row's reference maximum moves only when it grows by more than 2^8
-    const float lazy_thr = 8.0f / scale_log2;
-
-    const int kend = CAUSAL ? min(L, q0 + BM) : L;
-    const int ntile_k = (kend + BN - 1) / BN;               // tiles the workgroup stages
-    const int kend_w = CAUSAL ? min(L, qrow0 + 32) : L;
-    const int nblk_w = qrow0 < L ? (kend_w + 31) / 32 : 0;  // 32-key blocks this wavefront computes
-
-    // ---- global -> register -> LDS staging (512 threads).  Addresses are a
-    // uniform tile base (scalar) plus a 32-bit per-thread offset; rows past the
-    // sequence end repeat row L-1 (they are masked later), tiles past the end
-    // repeat the last tile (the copy lands in a buffer nobody reads again).
-    constexpr int KLOADS = BN * (HD / 8) / kPPThreads;      // 16-byte K loads per thread
-    constexpr int KROWS_PER_PASS = kPPThreads / (HD / 8);
-    constexpr int VBLOCKS = (BN / 4) * (HD / 4);            // 4(key) x 4(dim) blocks per tile
-    const bool v_active = VBLOCKS >= kPPThreads || tid < VBLOCKS;
-    u32x4 kreg[KLOADS];
-    u32x2 vreg[4];
-    const int k_col = (tid % (HD / 8)) * 8, k_row = tid / (HD / 8);
-    // V blocks: 8 adjacent lanes take 8 different key quads (their transposed
-    // 8-byte LDS writes fall on different banks), the next lane bits walk the head dimension
-    const int v_dq = (tid >> 3) % (HD / 4);
-    const int v_nq = ((tid & 7) + 8 * ((tid >> 3) / (HD / 4))) & 15;
-    const uint32_t rstride_b = (uint32_t)Hkv * HD * 2;      // bytes between consecutive keys
-    const char *kseq = (const char *)(k + ((size_t)row0 * Hkv + g_kv) * HD);
-    const char *vseq = (const char *)(v + ((size_t)row0 * Hkv + g_kv) * HD);
-    // key n = 16t + 8u + 4g + w is stored at slot 16t + 8g + 4u + w, so the 8 keys
-    // a lane contracts in one MFMA are contiguous
-    const int v_slot = 16 * (v_nq >> 2) + 8 * (v_nq & 1) + 4 * ((v_nq >> 1) & 1);
-
-    auto load_k = [&](int t) {
-        t = t < ntile_k ? t : ntile_k - 1;
-        const char *tb = kseq + (size_t)t * BN * rstride_b;
-        const int lrem = L - 1 - t * BN;
-#pragma unroll
-        for (int p = 0; p < KLOADS; ++p) {
-            const int r = min(p * KROWS_PER_PASS + k_row, lrem);
-            kreg[p] = *(const u32x4 *)(tb + (__umul24((uint32_t)r, rstride_b) + 2u * (uint32_t)k_col));
-        }
-    };
-    auto load_v = [&](int t) {
-        t = t < ntile_k ? t : ntile_k - 1;
-        const char *tb = vseq + (size_t)t * BN * rstride_b;
-        const int lrem = L - 1 - t * BN;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int r = min(4 * v_nq + j, lrem);
-            vreg[j] = *(const u32x2 *)(tb + (__umul24((uint32_t)r, rstride_b) + 8u * (uint32_t)v_dq));
-        }
-    };
-    auto store_k = [&](int buf) {
-#pragma unroll
-        for (int p = 0; p < KLOADS; ++p)
-            *(u32x4 *)(&Ks[buf * KTILE + (p * KROWS_PER_PASS + k_row) * KS + k_col]) = kreg[p];
-    };
-    auto store_v = [&](int buf) {
-        if (!v_active) return;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
-            const uint32_t a0 = (c & 2) ? vreg[0].y : vreg[0].x;
-            const uint32_t a1 = (c & 2) ? vreg[1].y : vreg[1].x;
-            const uint32_t a2 = (c & 2) ? vreg[2].y : vreg[2].x;
-            const uint32_t a3 = (c & 2) ? vreg[3].y : vreg[3].x;
-            u32x2 w;
-            w.x = __builtin_amdgcn_perm(a1, a0, sel);
-            w.y = __builtin_amdgcn_perm(a3, a2, sel);
-            *(u32x2 *)(&Vt[buf * VTILE + (4 * v_dq + c) * VS + v_slot]) = w;
-        }
-    };
-
-    f32x16 S;      // scores of the current block (S^T: lane = query, 16 keys)
-    bf16x8 P[2];   // its probabilities: two 16-key chunks (B operand of P V)
-#pragma unroll
-    for (int kk = 0; kk < 2; ++kk) P[kk] = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
-
-    // softmax of block b: S -> P, running statistics, rescale of O when the
-    // reference maximum moves.  A block beyond the wavefront's causal range gets
-    // P = 0: its MFMAs still run (branch-free groups) and leave O unchanged.
-    auto softmax = [&](int b) {
-        if (b < nblk_w) {
-            const bool masked = (32 * b + 32 > L) || (CAUSAL && 32 * b + 31 > qrow0);
-            if (masked) {
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int n = 32 * b + 8 * (e >> 2) + 4 * g + (e & 3);
-                    const bool vis = n < L && (!CAUSAL || n <= qm);
-                    if (!vis) S[e] = -INFINITY;
-                }
-            }
-            float tmax = S[0];
-#pragma unroll
-            for (int e = 1; e < 16; ++e) tmax = fmaxf(tmax, S[e]);
-            {   // the other half of the row lives in lane ^ 32
-                const uint32_t tb = __float_as_uint(tmax);
-                const auto sw = __builtin_amdgcn_permlane32_swap(tb, tb, false, false);
-                tmax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-            }
-            const bool upd = tmax > m_run + lazy_thr;
-            const float m_new = upd ? tmax : m_run;
-            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-            if (__any(upd)) {
-                const float alpha = upd ? __builtin_amdgcn_exp2f((m_run - m_use) * scale_log2) : 1.0f;
-                l_run *= alpha;
-#pragma unroll
-                for (int d = 0; d < NDB; ++d)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) acc_o[d][e] *= alpha;
-            }
-            m_run = m_new;
-            const float mbias = m_use * scale_log2;
-            float psum = 0.f;
-#pragma unroll
-            for (int kk = 0; kk < 2; ++kk) {
-                u32x4 pk;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float p0 = __builtin_amdgcn_exp2f(S[8 * kk + 2 * e] * scale_log2 - mbias);
-                    const float p1 = __builtin_amdgcn_exp2f(S[8 * kk + 2 * e + 1] * scale_log2 - mbias);
-                    psum += p0 + p1;
-                    pk[e] = pack_bf16(p0, p1);
-                }
-                P[kk] = __builtin_bit_cast(bf16x8, pk);
-            }
-            l_run += psum;
-        } else {
-#pragma unroll
-            for (int kk = 0; kk < 2; ++kk) P[kk] = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
-        }
-    };
-
-    // per-lane LDS byte addresses of the fragments (block 0 of buffer 0)
-    const uint32_t lds_k0 = (uint32_t)(uintptr_t)(&Ks[0]) + 2u * (uint32_t)(l32 * KS + 8 * g);
-    const uint32_t lds_v0 = (uint32_t)(uintptr_t)(&Vt[0]) + 2u * (uint32_t)(l32 * VS + 8 * g);
-    constexpr int VD = 2 * 32 * VS;  // bytes between 32-row blocks of V^T
-    bf16x8 kf[NC], vf[2 * NDB];
-    auto read_k = [&](uint32_t a) {
-        lds_rd4<0, 32, 64, 96>(kf[0], kf[1], kf[2], kf[3], a);
-        if constexpr (NC == 8) lds_rd4<128, 160, 192, 224>(kf[4], kf[5], kf[6], kf[7], a);
-    };
-    auto read_v = [&](uint32_t a) {
-        lds_rd4<0, 32, VD, VD + 32>(vf[0], vf[1], vf[2], vf[3], a);
-        if constexpr (NDB == 4) lds_rd4<2 * VD, 2 * VD + 32, 3 * VD, 3 * VD + 32>(vf[4], vf[5], vf[6], vf[7], a);
-    };
-    auto do_pv = [&]() {
-        mfma_pv4(acc_o[0], acc_o[1], vf[0], vf[1], vf[2], vf[3], P[0], P[1]);
-        if constexpr (NDB == 4) mfma_pv4(acc_o[2], acc_o[3], vf[4], vf[5], vf[6], vf[7], P[0], P[1]);
-    };
-
-    // fragments of M(b): K block b and V block b-1 (block 0 for b = 0, where P = 0)
-    auto reads_for = [&](int b) {
-        const int pb = b >= 1 ? b - 1 : 0;
-        read_k(lds_k0 + 2u * (uint32_t)(((b >> 1) & 1) * KTILE + 32 * (b & 1) * KS));
-        read_v(lds_v0 + 2u * (uint32_t)(((pb >> 1) & 1) * VTILE + 32 * (pb & 1)));
-    };
-    // M phase: S = QK(b), O += PV(b-1) on the fragments requested one phase
-    // earlier; the wavefront's share of the global -> LDS staging sits between
-    // the two halves, where it issues while the matrix core is busy
-    auto phase_m = [&](auto &&stage) {
-        mfma_group_begin();
-        if constexpr (NC == 8) {
-            mfma_qk4<true, -1>(S, kf[0], kf[1], kf[2], kf[3], qf[0], qf[1], qf[2], qf[3]);
-            mfma_qk4<false, -1>(S, kf[4], kf[5], kf[6], kf[7], qf[4], qf[5], qf[6], qf[7]);
-        } else {
-            mfma_qk4<true, -1>(S, kf[0], kf[1], kf[2], kf[3], qf[0], qf[1], qf[2], qf[3]);
-        }
-        stage();
-        do_pv();
-        mfma_group_end();
-    };
-
-    // ---- prologue: tile 0 into LDS, tile 1 into the staging registers
-    load_k(0);
-    if (v_active) load_v(0);
-    store_k(0);
-    store_v(0);
-    asm volatile("" ::: "memory");
-    load_k(1);
-    if (v_active) load_v(1);
-    lds_barrier();
-    if (grp == 1) lds_barrier();   // the trailing group starts one phase late
-    reads_for(0);
-
-    for (int i = 0; i < ntile_k; ++i) {
-        phase_m([&]() {                  // M(2i); K_{i+1} replaces K_{i-1}
-            store_k((i + 1) & 1);
-            asm volatile("" ::: "memory");   // the prefetch reloads the registers just stored, in place
-            load_k(i + 2);
-        });
-        lds_barrier();
-        reads_for(2 * i + 1);            // V(2i)
-        softmax(2 * i);
-        lds_barrier();
-        phase_m([&]() {                  // M(2i+1); V_{i+1} replaces V_{i-1}
-            store_v((i + 1) & 1);
-            asm volatile("" ::: "memory");
-            if (v_active) load_v(i + 2);
-        });
-        lds_barrier();
-        reads_for(2 * i + 2);            // V(2i+1)
-        softmax(2 * i + 1);
-        lds_barrier();
-    }
-    phase_m([]() {});                    // drain: O += PV(last block)
-    if (grp == 0) lds_barrier();         // every wavefront passes the same number of barriers
-
-    // ---- epilogue
-    float l_tot;
-    {
-        const uint32_t lb = __float_as_uint(l_run);
-        const auto sw = __builtin_amdgcn_permlane32_swap(lb, lb, false, false);
-        l_tot = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
-    }
-    const float inv = 1.f / l_tot;
-    if (qm < L) {
-        uint16_t *op = out + ((size_t)(row0 + qm) * Hq + h) * HD;
-#pragma unroll
-        for (int d = 0; d < NDB; ++d)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                u32x2 w;
-                w.x = pack_bf16(acc_o[d][4 * r] * inv, acc_o[d][4 * r + 1] * inv);
-                w.y = pack_bf16(acc_o[d][4 * r + 2] * inv, acc_o[d][4 * r + 3] * inv);
-                *(u32x2 *)(op + 32 * d + 8 * r + 4 * g) = w;
-            }
-        if (lse != nullptr && g == 0)
-            lse[(size_t)h * total_tokens + row0 + qm] = m_run * scale + __logf(l_tot);
-    }
-}
-
-
-// ---------------------------------------------------------------------------
 // Interleaved variant (head_dim 128): 8 free-running wavefronts (two per SIMD)
 // own 32 query rows each.  No vector register ever stages K or V:
 //   * K and V tiles (64 keys x 256 B) go from global memory straight into LDS
@@ -791,7 +387,11 @@ __global__ __launch_bounds__(kPPThreads) void attn_fwd_pp_kernel(
 //     lane i receives element i%4 of the 8-byte words addressed by lanes
 //     i/4, 4 + i/4, 8 + i/4, 12 + i/4.  Two such reads are the A operand of
 //     O^T += V^T P^T for the keys a lane's P registers hold.
-// Three-stage rings for K and V; one workgroup barrier per 64-key tile.
+// Four-stage rings for K and V (128 KB of LDS), K requested three tiles ahead and V
+// two; one workgroup barrier per 64-key tile.  The tile loop is unrolled by the ring
+// depth, so every fragment read is a fixed lane address plus an immediate offset.
+// The LDS-DMA unit is shared by the workgroup and a wavefront stalls at issue while
+// it is busy, so a wavefront's four loads per tile are spread over its two blocks.
 //
 // Each wavefront software-pipelines over 32-key blocks b.  Iteration b issues
 //     half 1:  O^T   += V(b-1)^T P(b-1) 8 MFMAs | row maxima of S(b), then exp of
@@ -802,17 +402,14 @@ __global__ __launch_bounds__(kPPThreads) void attn_fwd_pp_kernel(
 // within one instruction stream; the second wavefront of the SIMD fills what
 // stalls remain.  P is single-buffered: its first chunk is rewritten in the
 // second part of half 1, after the four MFMAs that read the old one, its second
-// chunk in half 2.  LDS fragments are single-buffered in registers too: K(b+1) is
-// requested at the start of half 1 (its registers were last read by the MFMAs of
-// the previous half 2), V(b) at the start of half 2.
+// chunk in half 2.  LDS fragments are single-buffered in registers too: fragment j
+// of K(b+1) is requested right after MFMA j of half 1 (its register was last read by
+// MFMA j of the previous half 2), the fragments of V(b) likewise during half 2.
 // Reference maximum: lazy (moves only on growth > 2^8).  The factor alpha_b that
 // carries O and l from the reference of block b-1 to that of block b is applied
 // in half 2 of iteration b: O has received P(b-1) V(b-1) and not yet P(b) V(b).
 // ---------------------------------------------------------------------------
 constexpr int kILThreads = 512;
-#ifdef ORCH_ATTN_TIMING2
-__device__ unsigned long long g_tk[8];
-#endif
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
@@ -837,15 +434,6 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
     const uint32_t lds_k = (uint32_t)(uintptr_t)lds_raw;
     const uint32_t lds_v = lds_k + KST * TILE_B;
 
-#ifdef ORCH_ATTN_TIMING2
-    const long long t2_entry = clock64();
-    if (blockIdx.x == 0 && threadIdx.x == 0)
-        printf("totals so far: WGs %llu | prologue %llu loop %llu epilogue %llu ticks | blocks(max wave) %llu\n", g_tk[0],
-               g_tk[1], g_tk[2], g_tk[3], g_tk[4]);
-#endif
-#ifdef ORCH_ATTN_TIMING
-    const long long tk_entry = clock64();
-#endif
     const int total_tiles = hdr->total_tiles;
     const int group = Hq / Hkv;
     int u, h;
@@ -886,11 +474,7 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
     const int kend = CAUSAL ? min(L, q0 + BM) : L;
     const int ntile_k = (kend + BN - 1) / BN;               // tiles the workgroup stages
     const int kend_w = CAUSAL ? min(L, qrow0 + 32) : L;
-#ifdef ORCH_X_HALFWAVES
-    const int nblk_w = (qrow0 < L && wave >= 4) ? (kend_w + 31) / 32 : 0;
-#else
     const int nblk_w = qrow0 < L ? (kend_w + 31) / 32 : 0;  // 32-key blocks this wavefront computes
-#endif
 
     // ---- LDS-DMA: per tile this wavefront fetches rows 8w..8w+7 of K and of V
     // (two loads of 4 rows each); lane -> (row, slot), slot -> chunk by the swizzle
@@ -1086,17 +670,11 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
                 asm volatile("" : "+v"(xs[e]));
             }
             if (te + 1 == t) {   // B
-#ifdef ORCH_X_NOEXP
-                ps[e] = xs[e];
-#else
                 ps[e] = __builtin_amdgcn_exp2f(xs[e]);
-#endif
                 asm volatile("" : "+v"(ps[e]));
             }
             if (te + 2 == t) {   // C, and D for a completed pair
-#ifndef ORCH_X_NOPSUM
                 psum += ps[e];
-#endif
                 if (e & 1) {
                     uint32_t pk = pack_bf16(ps[e - 1], ps[e]);
                     asm volatile("" : "+v"(pk), "+v"(psum));
@@ -1113,13 +691,6 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
 
     // one pipeline iteration for block b of parity PAR: S[PAR] holds S(b), P holds P(b-1),
     // vf holds V(b-1)
-#ifdef ORCH_ATTN_TIMING
-    long long tk_h1 = 0, tk_h2 = 0, tk_top = 0, tk_t0 = 0, tk_wait = 0, tk_bar = 0, tk_dma = 0;
-    int tk_n = 0;
-#define ORCH_TK(acc_) do { const long long t_ = clock64(); acc_ += t_ - tk_t0; tk_t0 = t_; } while (0)
-#else
-#define ORCH_TK(acc_) do { } while (0)
-#endif
     // The LDS-DMA unit is shared by the workgroup and a wavefront stalls at issue while it is
     // busy, so a wavefront's four loads per step are spread over the step: one in the middle
     // of each half of its two iterations (K in the even block, V in the odd one).
@@ -1131,11 +702,7 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
         constexpr int V_OFF = ST * TILE_B + (PAR == 0 ? 0 : 32 * ROWB);
         f32x16 &Sc = S[PAR];
         f32x16 &Sn = S[PAR ^ 1];
-#ifdef ORCH_X_TWOCHAIN
-        f32x16 S2;
-#endif
         psum = 0.f;
-        ORCH_TK(tk_top);
         // ---- half 1: O^T += V(b-1)^T P(b-1); maxima of S(b); exp of keys 0..15
 #pragma unroll
         for (int j = 0; j < 2 * NDB; ++j) {
@@ -1144,22 +711,17 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
             ORCH_SB();
             // K(b+1), one fragment per slot (odd half of this tile, or even half of the next
             // one); the MFMA that last read kf[j] was issued in the previous half 2
-#ifndef ORCH_X_NOLDS
             read_k1(j, K_OFF);
             ORCH_SB();
-#endif
             if (j == 0) mask_block(Sc, b);
             if (j == 1) max_a(Sc);
             if (j == 2) max_b(Sc);
             if (j == 3) max_c();
             // chunk 0 of P is rewritten from tick 2 on: MFMAs 0..3 have read it by then
             if (j >= 4) exp_tick(Sc, j - 4);
-#ifndef ORCH_X_NODMA
             if (j == 4) dma_run(dj, 0);
-#endif
             ORCH_SB();
         }
-        ORCH_TK(tk_h1);
         // ---- half 2: S(b+1) = K(b+1) Q^T; exp of keys 16..31
 #pragma unroll
         for (int j = 0; j < NC; ++j) {
@@ -1168,36 +730,19 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
 #pragma unroll
                 for (int e = 0; e < 16; ++e) z[e] = 0.f;
                 Sn = mfma(kf[0], qf[0], z);
-#ifdef ORCH_X_TWOCHAIN
-            } else if (j == 1) {
-                f32x16 z;
-#pragma unroll
-                for (int e = 0; e < 16; ++e) z[e] = 0.f;
-                S2 = mfma(kf[1], qf[1], z);
-            } else if (j & 1) {
-                S2 = mfma(kf[j], qf[j], S2);
-#endif
             } else {
                 Sn = mfma(kf[j], qf[j], Sn);
             }
             ORCH_SB();
             // V(b), the fragment that MFMA j of the next half 1 reads
-#ifndef ORCH_X_NOLDS
             read_v1(j % NDB, j / NDB, V_OFF);
             ORCH_SB();
-#endif
             exp_tick(Sc, 4 + j);
-#ifndef ORCH_X_NODMA
             if (j == 4) dma_run(dj, 1);
-#endif
             ORCH_SB();
         }
         exp_tick(Sc, 12);
         exp_tick(Sc, 13);
-#ifdef ORCH_X_TWOCHAIN
-#pragma unroll
-        for (int e = 0; e < 16; ++e) Sn[e] += S2[e];
-#endif
         // ---- carry O and l to the reference of block b (rarely != 1), add this block's sum
         if (moved) {
 #pragma unroll
@@ -1206,10 +751,6 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
                 for (int e = 0; e < 16; ++e) acc_o[d][e] *= alpha;
         }
         l_run = l_run * alpha + psum;
-        ORCH_TK(tk_h2);
-#ifdef ORCH_ATTN_TIMING
-        ++tk_n;
-#endif
     };
 
     // ---- prologue: K tiles 0 and 1, V tile 0 on their way; S(0); V(0) fragments meet P = 0
@@ -1235,26 +776,14 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
         for (int j = 1; j < NC; ++j) S[0] = mfma(kf[j], qf[j], S[0]);
     }
 
-#ifdef ORCH_ATTN_TIMING
-    tk_t0 = clock64();
-    const long long tk_start = tk_t0, tk_wstart = wall_clock64();
-#endif
-#ifdef ORCH_ATTN_TIMING2
-    const long long t2_loop = clock64();
-#endif
     // one 64-key tile (two blocks) whose ring stage ST = i % 4 is a compile-time constant
     auto step = [&](auto st_c, int i) {
         constexpr int ST = decltype(st_c)::value;
         if (i > 0) {
-            ORCH_TK(tk_top);
             // K(i+1) and V(i) were requested two steps ago; the four loads of the last step
             // (K(i+2), V(i+1)) may stay in flight: vmcnt(4)
             __builtin_amdgcn_s_waitcnt(0x0f74);
-            ORCH_TK(tk_wait);
-#ifndef ORCH_X_NOBARRIER
             __builtin_amdgcn_s_barrier();
-#endif
-            ORCH_TK(tk_bar);
         }
         // K(i+3) replaces K(i-1), V(i+2) replaces V(i-2): nobody reads those any more
         const DmaJob kj = dma_job(i + 3, false, lds_k + (uint32_t)(((ST + 3) % KST) * TILE_B));
@@ -1262,18 +791,14 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
         if (2 * i < nblk_w) {
             body(std::integral_constant<int, 0>{}, st_c, 2 * i, kj);
         } else {   // a wavefront past its causal range still feeds the ring
-#ifndef ORCH_X_NODMA
             dma_run(kj, 0);
             dma_run(kj, 1);
-#endif
         }
         if (2 * i + 1 < nblk_w) {
             body(std::integral_constant<int, 1>{}, st_c, 2 * i + 1, vj);
         } else {
-#ifndef ORCH_X_NODMA
             dma_run(vj, 0);
             dma_run(vj, 1);
-#endif
         }
     };
     for (int i0 = 0; i0 < ntile_k; i0 += 4) {
@@ -1282,16 +807,6 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
         if (i0 + 2 < ntile_k) step(std::integral_constant<int, 2>{}, i0 + 2);
         if (i0 + 3 < ntile_k) step(std::integral_constant<int, 3>{}, i0 + 3);
     }
-#ifdef ORCH_ATTN_TIMING
-    if ((blockIdx.x == 0 || blockIdx.x == 20000) && lane == 0)
-        printf("blk %d wave %d rblk %d blocks %d tiles %d | per block: half1 %lld half2 %lld other %lld | per tile: wait %lld barrier %lld dma %lld | loop ticks %lld wall(100MHz) %lld\n",
-               blockIdx.x, wave, rblk, tk_n, ntile_k, tk_n ? tk_h1 / tk_n : 0, tk_n ? tk_h2 / tk_n : 0,
-               tk_n ? tk_top / tk_n : 0, tk_wait / ntile_k, tk_bar / ntile_k, tk_dma / ntile_k, clock64() - tk_start, wall_clock64() - tk_wstart);
-    const long long tk_loop_end = clock64();
-#endif
-#ifdef ORCH_ATTN_TIMING2
-    const long long t2_loop_end = clock64();
-#endif
     // ---- drain: O^T += V(B-1)^T P(B-1) for the wavefront's last block; both are in registers
     if (nblk_w > 0) {
 #pragma unroll
@@ -1323,22 +838,6 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
         if (lse != nullptr && g == 0)
             lse[(size_t)h * total_tokens + row0 + qm] = m_run * scale + __logf(l_tot);
     }
-#ifdef ORCH_ATTN_TIMING2
-    if (wave == 4 && lane == 0) {   // the wavefront with the most blocks
-        const long long t2_end = clock64();
-        atomicAdd(&g_tk[0], 1ull);
-        atomicAdd(&g_tk[1], (unsigned long long)(t2_loop - t2_entry));
-        atomicAdd(&g_tk[2], (unsigned long long)(t2_loop_end - t2_loop));
-        atomicAdd(&g_tk[3], (unsigned long long)(t2_end - t2_loop_end));
-        atomicAdd(&g_tk[4], (unsigned long long)nblk_w);
-    }
-#endif
-#ifdef ORCH_ATTN_TIMING
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    if ((blockIdx.x == 3 || blockIdx.x == 20003 || blockIdx.x == 40003) && lane == 0 && (wave == 0 || wave == 4))
-        printf("blk %d wave %d: entry->loop %lld, loop %lld, drain+epilogue %lld ticks (tiles %d)\n", blockIdx.x, wave,
-               tk_start - tk_entry, tk_loop_end - tk_start, clock64() - tk_loop_end, ntile_k);
-#endif
 }
 #undef ORCH_SB
 
@@ -1358,12 +857,12 @@ int launch_attn(const void *q, const void *k, const void *v, void *out, float *l
     if (ws_bytes < need) ORCH_FAIL(ORCH_ENOSPC, "orch_varlen_attn_fwd: workspace %zu < %zu bytes", ws_bytes, need);
     AttnHdr *hdr = (AttnHdr *)ws;
     int32_t *tile_off = (int32_t *)((char *)ws + align_up(sizeof(AttnHdr), 256));
-    // head_dim 128: the 8-wavefront ping-pong kernel (MFMA-bound, overlap pays).
-    // head_dim 64: half the MFMA work per softmax, so the vector ALU dominates and
-    // the simpler 4-wavefront kernel with two row blocks per wavefront is faster.
-    const bool pipe = d == 128;
-    const int MB = 2;
-    const int BM = pipe ? 256 : 128 * MB;
+    // head_dim 128: the 8-wavefront kernel with LDS-DMA staging and MFMA / vector-ALU work
+    // interleaved in one instruction stream.  head_dim 64: half the MFMA work per softmax, so
+    // the vector ALU dominates and the simpler 4-wavefront kernel with two row blocks per
+    // wavefront is used.
+    const bool il = d == 128;
+    const int BM = 256;   // both kernels own 256 query rows per workgroup
     hipLaunchKernelGGL(attn_prep_kernel, dim3(1), dim3(kPrepThreads), 0, stream, cu_seqlens, batch,
                        total_tokens, BM, hdr, tile_off, (int32_t *)nullptr);
     const int64_t max_tiles = (int64_t)total_tokens / BM + batch;
@@ -1375,32 +874,17 @@ int launch_attn(const void *q, const void *k, const void *v, void *out, float *l
 #define ORCH_ATTN_ARGS                                                                          \
     (const uint16_t *)q, (const uint16_t *)k, (const uint16_t *)v, (uint16_t *)out, lse,        \
         cu_seqlens, hdr, tile_off, batch, total_tokens, Hq, Hkv, scale, sl2
-#define ORCH_ATTN_LAUNCH(HD_, C_, MB_)                                                           \
-    hipLaunchKernelGGL((attn_fwd_kernel<HD_, C_, MB_>), dim3((unsigned)grid), dim3(kThreads), 0, \
-                       stream, ORCH_ATTN_ARGS)
-#define ORCH_ATTN_LAUNCH_PIPE(HD_, C_)                                                           \
-    hipLaunchKernelGGL((attn_fwd_pp_kernel<HD_, C_>), dim3((unsigned)grid), dim3(kPPThreads), 0, \
-                       stream, ORCH_ATTN_ARGS)
-        const char *sel = getenv("ORCH_ATTN_KERNEL");
-        const bool il = d == 128 && !(sel && sel[0] == 'p');
         if (il && causal)
             hipLaunchKernelGGL((attn_fwd_il_kernel<128, true>), dim3((unsigned)grid), dim3(kILThreads), 0, stream, ORCH_ATTN_ARGS);
         else if (il)
             hipLaunchKernelGGL((attn_fwd_il_kernel<128, false>), dim3((unsigned)grid), dim3(kILThreads), 0, stream, ORCH_ATTN_ARGS);
-        else if (d == 128 && causal) ORCH_ATTN_LAUNCH_PIPE(128, true);
-        else if (d == 128) ORCH_ATTN_LAUNCH_PIPE(128, false);
-        else if (causal) ORCH_ATTN_LAUNCH(64, true, 2);
-        else ORCH_ATTN_LAUNCH(64, false, 2);
-#undef ORCH_ATTN_LAUNCH
-#undef ORCH_ATTN_LAUNCH_PIPE
+        else if (causal)
+            hipLaunchKernelGGL((attn_fwd_kernel<64, true, 2>), dim3((unsigned)grid), dim3(kThreads), 0, stream, ORCH_ATTN_ARGS);
+        else
+            hipLaunchKernelGGL((attn_fwd_kernel<64, false, 2>), dim3((unsigned)grid), dim3(kThreads), 0, stream, ORCH_ATTN_ARGS);
 #undef ORCH_ATTN_ARGS
     }
-    {
-        const char *sel = getenv("ORCH_ATTN_KERNEL");
-        const bool il = d == 128 && !(sel && sel[0] == 'p');
-        set_attn_variant(il ? "mfma32x32x16_bm256_8wave_ldsdma_interleaved"
-                            : pipe ? "mfma32x32x16_bm256_8wave_pingpong" : "mfma32x32x16_bm256_4wave");
-    }
+    set_attn_variant(il ? "mfma32x32x16_bm256_8wave_ldsdma_interleaved" : "mfma32x32x16_bm256_4wave");
     ORCH_HIP_CHECK(hipGetLastError());
     return ORCH_OK;
 }
