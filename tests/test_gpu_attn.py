@@ -50,6 +50,17 @@ def test_small_ragged(gpu_device, causal, Hq, Hkv, d):
     run_full(cu, Hq, Hkv, d, causal, gpu_device)
 
 
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("Hq,Hkv", [(8, 8), (4, 2)])
+def test_head_dim_128_ring_boundaries(gpu_device, causal, Hq, Hkv):
+    """Lengths around every boundary of the head_dim-128 kernel: 32-key blocks, 64-key tiles, the
+    four-stage K/V rings (1 to 17 tiles per sequence) and 256-row query tiles; Hkv = 8 takes the
+    per-XCD head mapping, Hkv = 2 the plain one."""
+    L = [1, 31, 32, 33, 63, 64, 65, 127, 128, 129, 191, 192, 193, 255, 256, 257, 320, 511, 512, 767, 1025]
+    cu = np.concatenate([[0], np.cumsum(L)])
+    run_full(cu, Hq, Hkv, 128, causal, gpu_device, seed=7)
+
+
 def test_c1_all_instances(gpu_device):
     w = wl.WORKLOADS[1]
     L = wl.draw_lengths(w)
