@@ -41,7 +41,7 @@ def lib():
     if _lib is None:
         _lib = C.CDLL(build())
         for name in ("orc_cost", "orc_sort_desc", "orc_greedy", "orc_balance", "orc_pack",
-                     "orc_row_map", "orc_attn_fwd", "orc_attn_rows"):
+                     "orc_row_map", "orc_pack_composed", "orc_attn_fwd", "orc_attn_rows"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -124,6 +124,31 @@ def pack(tokens: np.ndarray, lengths, asg: Assignment, inst_begin: int = 0, inst
                           _p(asg.order), _p(asg.seq_off), _p(asg.tok_off), _p(asg.cu_seqlens),
                           C.c_int32(inst_begin), C.c_int32(inst_end)))
     return out
+
+
+def pack_composed(enc_rows: np.ndarray, packed: np.ndarray, sub_len, sub_off, enc_asg, llm_asg: Assignment,
+                  inst_begin: int = 0, inst_end: int | None = None) -> np.ndarray:
+    """Rearrangement composition (Sec. 5.3): rows in the encoder phase's packed order
+    (`enc_asg`, or None for original example order) are placed inside the interleaved
+    sequences of the LLM-phase assignment `llm_asg`, example s at row `sub_off[s]` of its
+    sequence.  Writes into `packed` (rows of instances [inst_begin, inst_end)) in place and
+    returns it; rows of other modalities are left as they are."""
+    sl, so = _i32(sub_len), _i32(sub_off)
+    Dm = len(llm_asg.loads)
+    if inst_end is None:
+        inst_end = Dm
+    enc_rows = np.ascontiguousarray(enc_rows)
+    assert packed.flags.c_contiguous and packed.dtype == enc_rows.dtype
+    rb = enc_rows.shape[1] * enc_rows.dtype.itemsize
+    if enc_asg is None:
+        e = (0, None, None, None, None)
+    else:
+        e = (len(enc_asg.loads), _p(enc_asg.order), _p(enc_asg.seq_off), _p(enc_asg.tok_off), _p(enc_asg.cu_seqlens))
+    _check(lib().orc_pack_composed(_p(enc_rows), _p(packed), _p(sl), _p(so), C.c_int32(len(sl)), C.c_int64(rb),
+                                   C.c_int32(e[0]), e[1], e[2], e[3], e[4], C.c_int32(Dm), _p(llm_asg.order),
+                                   _p(llm_asg.seq_off), _p(llm_asg.tok_off), _p(llm_asg.cu_seqlens),
+                                   C.c_int32(inst_begin), C.c_int32(inst_end)))
+    return packed
 
 
 def row_map(lengths, asg: Assignment) -> np.ndarray:

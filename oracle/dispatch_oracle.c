@@ -188,3 +188,71 @@ int orc_row_map(const int32_t *lengths, int32_t n, int32_t D, const int32_t *ord
     free(src_cu);
     return 0;
 }
+
+/* Rearrangement composition (Sec. 5.3, "MLLM Global Orchestrator").  The rows an
+ * encoder produced lie in THAT phase's packed order (its own dispatcher's
+ * rearrangement Pi_E, given by e_order / e_seq_off / e_tok_off / e_cu over the
+ * per-example sub-lengths).  The result the composition must equal is defined by
+ * the two steps the paper composes, taken one after the other here:
+ *   1. reset: Pi_E^-1 brings every example's rows back to original example order
+ *      (a temporary buffer, examples concatenated in index order);
+ *   2. rearrange: Pi_M places example s's rows inside its interleaved sequence on
+ *      the destination instance, at row sub_off[s] of that sequence
+ *      (m_order / m_seq_off / m_tok_off / m_cu describe the LLM-phase assignment
+ *      over the interleaved lengths).
+ * e_order == NULL means the rows already are in original order (text: it never
+ * left its instance), so step 1 is the identity.
+ * Destination rows that belong to other modalities are left untouched.
+ * Returns -5 if a sub-sequence does not fit in its interleaved sequence or the
+ * encoder assignment's segment lengths disagree with sub_len. */
+int orc_pack_composed(const void *enc_rows, void *packed, const int32_t *sub_len,
+                      const int32_t *sub_off, int32_t n, int64_t row_bytes, int32_t De,
+                      const int32_t *e_order, const int32_t *e_seq_off, const int64_t *e_tok_off,
+                      const int32_t *e_cu, int32_t Dm, const int32_t *m_order,
+                      const int32_t *m_seq_off, const int64_t *m_tok_off, const int32_t *m_cu,
+                      int32_t inst_begin, int32_t inst_end)
+{
+    if (n < 0 || Dm < 1 || inst_begin < 0 || inst_end > Dm || inst_begin > inst_end || row_bytes < 1)
+        return -1;
+    if (e_order && De < 1) return -1;
+    int64_t *sub_cu = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n + 1));
+    if (!sub_cu) return -1;
+    sub_cu[0] = 0;
+    for (int32_t s = 0; s < n; ++s) {
+        if (sub_len[s] < 0 || sub_off[s] < 0) { free(sub_cu); return -5; }
+        sub_cu[s + 1] = sub_cu[s] + sub_len[s];
+    }
+    const char *src = (const char *)enc_rows;
+    char *tmp = NULL;
+    /* step 1: reset to original example order */
+    if (e_order) {
+        tmp = (char *)malloc((size_t)(sub_cu[n] > 0 ? sub_cu[n] : 1) * (size_t)row_bytes);
+        if (!tmp) { free(sub_cu); return -1; }
+        for (int32_t i = 0; i < De; ++i) {
+            const int32_t *cu = e_cu + e_seq_off[i] + i;
+            for (int32_t j = 0; j < e_seq_off[i + 1] - e_seq_off[i]; ++j) {
+                int32_t s = e_order[e_seq_off[i] + j];
+                if (cu[j + 1] - cu[j] != sub_len[s]) { free(tmp); free(sub_cu); return -5; }
+                memcpy(tmp + sub_cu[s] * row_bytes, src + (e_tok_off[i] + cu[j]) * row_bytes,
+                       (size_t)sub_len[s] * (size_t)row_bytes);
+            }
+        }
+        src = tmp;
+    }
+    /* step 2: place inside the interleaved sequences of the destination instances */
+    char *dst = (char *)packed;
+    int rc = 0;
+    for (int32_t i = inst_begin; i < inst_end && rc == 0; ++i) {
+        const int32_t *cu = m_cu + m_seq_off[i] + i;
+        for (int32_t j = 0; j < m_seq_off[i + 1] - m_seq_off[i]; ++j) {
+            int32_t s = m_order[m_seq_off[i] + j];
+            if ((int64_t)sub_off[s] + sub_len[s] > (int64_t)cu[j + 1] - cu[j]) { rc = -5; break; }
+            int64_t drow = m_tok_off[i] - m_tok_off[inst_begin] + cu[j] + sub_off[s];
+            memcpy(dst + drow * row_bytes, src + sub_cu[s] * row_bytes,
+                   (size_t)sub_len[s] * (size_t)row_bytes);
+        }
+    }
+    free(tmp);
+    free(sub_cu);
+    return rc;
+}

@@ -238,3 +238,136 @@ def test_workload_laws():
     assert np.mean(split.max(axis=1) / L4 > 0.6) > 0.5
     L5 = wl.draw_lengths(wl.WORKLOADS[5])
     assert L5.max() <= 32768 and L5.min() >= 64
+
+
+# ----------------------------------------------------------------------------
+# Rearrangement composition (Sec. 5.3): Pi_M o Pi_E^-1 in one pass
+# ----------------------------------------------------------------------------
+def modality_case(cid, shrink=1, keep=None, seed=0):
+    """Lengths, three-way modality split, a per-example modality order (seeded) and the
+    row offset of every modality inside the example's interleaved sequence."""
+    w = wl.WORKLOADS[cid]
+    L = wl.draw_lengths(w)
+    if keep is not None:
+        L = L[:keep]
+    L = (L // shrink).astype(np.int32)
+    split = wl.draw_modality_split(w, L)
+    n = len(L)
+    perm_id = (wl.uniform01(1000 + seed, 21, n) * 6).astype(np.int64)
+    perms = np.array(list(itertools.permutations(range(3))), dtype=np.int64)[perm_id]  # [n,3]: slot -> modality
+    sub_off = np.zeros((n, 3), dtype=np.int32)
+    for s in range(n):
+        run = 0
+        for slot in range(3):
+            m = perms[s, slot]
+            sub_off[s, m] = run
+            run += split[s, m]
+    return w, L, split, sub_off
+
+
+def dst_starts(asg, D):
+    """Row of the first token of every example in the packed LLM batch, from the
+    assignment's fields alone."""
+    start = np.zeros(len(asg.order), dtype=np.int64)
+    for i in range(D):
+        cu = asg.cu_of(i)
+        for j, s in enumerate(asg.seqs_of(i)):
+            start[s] = int(asg.tok_off[i]) + int(cu[j])
+    return start
+
+
+def encoder_rows(sub, easg, De, H, salt):
+    """The encoder phase's output in ITS packed order: row r of example s carries the tag of
+    (salt + original-order row).  Built without the oracle's pack."""
+    cu0 = np.concatenate([[0], np.cumsum(sub, dtype=np.int64)])
+    src = np.empty(int(cu0[-1]), dtype=np.int64)
+    if easg is None:
+        src[:] = np.arange(cu0[-1])
+    else:
+        st = dst_starts(easg, De)
+        for s in range(len(sub)):
+            src[st[s]: st[s] + sub[s]] = np.arange(cu0[s], cu0[s + 1])
+    return wl.token_tag_np(salt + src, H), cu0
+
+
+@pytest.mark.parametrize("cid,shrink,keep", [(1, 1, None), (4, 16, 400), (2, 4, 600)])
+def test_pack_composed_tag(cid, shrink, keep):
+    w, L, split, sub_off = modality_case(cid, shrink, keep)
+    H, Dm, De = 24, w.D, max(2, w.D // 2)
+    masg = oracle.balance(L, Dm, w.a, w.b)
+    start = dst_starts(masg, Dm)
+    T = int(L.sum())
+    packed = np.full((T, H), 0xFFFF, dtype=np.uint16)
+    want = np.empty((T, H), dtype=np.uint16)
+    for m in range(3):
+        sub = split[:, m].copy()
+        # text (m = 0) never left its instance: original order; encoders have their own dispatch
+        easg = None if m == 0 else oracle.balance(sub, De, 1, 4 + m)
+        salt = m * (1 << 30)
+        rows, cu0 = encoder_rows(sub, easg, De, H, salt)
+        oracle.pack_composed(rows, packed, sub, sub_off[:, m], easg, masg)
+        for s in range(len(L)):
+            d0 = start[s] + sub_off[s, m]
+            want[d0: d0 + sub[s]] = wl.token_tag_np(salt + np.arange(cu0[s], cu0[s + 1]), H)
+    # the three modalities tile every destination row exactly once and carry the right rows
+    assert np.array_equal(packed, want)
+
+
+def test_pack_composed_equals_reset_interleave_pack():
+    """Two-step definition: undo Pi_E, interleave in original order, then apply Pi_M with the
+    plain pack; one composed pass per modality must give the same buffer."""
+    w, L, split, sub_off = modality_case(3, 2, 500, seed=3)
+    H, Dm, De = 16, w.D, 5
+    masg = oracle.balance(L, Dm, w.a, w.b)
+    T = int(L.sum())
+    src_cu = np.concatenate([[0], np.cumsum(L, dtype=np.int64)])
+    inter = np.empty((T, H), dtype=np.uint16)
+    packed = np.zeros((T, H), dtype=np.uint16)
+    for m in range(3):
+        sub = split[:, m].copy()
+        easg = oracle.balance(sub, De, 2, 1) if m else None
+        rows, cu0 = encoder_rows(sub, easg, De, H, 7 * m)
+        for s in range(len(L)):
+            a = src_cu[s] + sub_off[s, m]
+            inter[a: a + sub[s]] = wl.token_tag_np(7 * m + np.arange(cu0[s], cu0[s + 1]), H)
+        oracle.pack_composed(rows, packed, sub, sub_off[:, m], easg, masg)
+    assert np.array_equal(packed, oracle.pack(inter, L, masg))
+    # an instance sub-range is the matching slice and leaves nothing else touched
+    part = np.zeros((int(masg.tok_off[4] - masg.tok_off[2]), H), dtype=np.uint16)
+    for m in range(3):
+        sub = split[:, m].copy()
+        easg = oracle.balance(sub, De, 2, 1) if m else None
+        rows, _ = encoder_rows(sub, easg, De, H, 7 * m)
+        oracle.pack_composed(rows, part, sub, sub_off[:, m], easg, masg, 2, 4)
+    assert np.array_equal(part, packed[int(masg.tok_off[2]): int(masg.tok_off[4])])
+
+
+def test_pack_composed_special_cases():
+    w = wl.WORKLOADS[1]
+    L = wl.draw_lengths(w)
+    H = 8
+    asg = oracle.balance(L, w.D, w.a, w.b)
+    T = int(L.sum())
+    tokens = wl.token_tag_np(np.arange(T), H)
+    zero = np.zeros(len(L), dtype=np.int32)
+    # identity source, whole sequences, offset 0: the plain pack
+    out = np.zeros_like(tokens)
+    oracle.pack_composed(tokens, out, L, zero, None, asg)
+    assert np.array_equal(out, oracle.pack(tokens, L, asg))
+    # source order = destination order: the composition is the identity map
+    out2 = np.zeros_like(tokens)
+    oracle.pack_composed(out, out2, L, zero, asg, asg)
+    assert np.array_equal(out2, out)
+    # empty modality: nothing is written
+    sent = np.full_like(tokens, 0xABCD)
+    oracle.pack_composed(tokens[:0], sent, zero, zero, None, asg)
+    assert (sent == 0xABCD).all()
+    # a sub-sequence that overruns its interleaved sequence is refused
+    off = zero.copy()
+    off[int(np.argmax(L))] = 1
+    with pytest.raises(oracle.OracleError):
+        oracle.pack_composed(tokens, out, L, off, None, asg)
+    # encoder assignment built for other lengths is refused
+    sub = np.maximum(L - 1, 0).astype(np.int32)
+    with pytest.raises(oracle.OracleError):
+        oracle.pack_composed(tokens, out, sub, zero, asg, asg)
