@@ -7,6 +7,9 @@
  *                         padding-free batch layout of Sec. 7.
  *   orch_pack             Sec. 5.2.1: the row movement of the All-to-All Batch
  *                         Communicator, performed on one device.
+ *   orch_pack_composed    Sec. 5.3 (rearrangement composition): rows in an encoder
+ *                         phase's packed order go straight into the LLM phase's
+ *                         packed, interleaved sequences: one row pass, not two.
  *   orch_varlen_attn_fwd  the padding-free ("batched along the sequence
  *                         length") attention each instance then runs; its
  *                         quadratic term is beta*sum(l^2) in Eq. 2.
@@ -92,6 +95,35 @@ size_t orch_pack_workspace(int32_t n, int32_t D);
 int orch_pack(const void *tokens, void *packed, const int32_t *lengths, int32_t n, int32_t D,
               int64_t T, int32_t H, int64_t packed_rows, orch_assignment a, int32_t inst_begin,
               int32_t inst_end, void *ws, size_t ws_bytes, void *stream);
+
+/* Bytes of workspace orch_pack_composed needs for n examples. */
+size_t orch_pack_composed_workspace(int32_t n);
+
+/* Sec. 5.3, "Rearrangement composition": Pi_M o Pi_E^-1 applied in one pass.  One
+ * call moves ONE modality's rows; a batch with several modalities calls it once per
+ * modality into the same `packed` buffer.
+ *   enc_rows [src_rows, H] 16-bit words: example s's sub_len[s] rows of this modality,
+ *            laid out by `src` (the assignment orch_balance produced for sub_len on
+ *            D_src instances: instance-major, rows of example s starting at
+ *            src->tok_off[i] + cu_i[j]), or, when src is NULL, concatenated in
+ *            original example order (a modality that never left its instance)
+ *   src      HOST pointer to a struct of device pointers, or NULL
+ *   dst      the LLM-phase assignment over the interleaved lengths (D_dst instances)
+ *   sub_off[s]  row inside example s's interleaved sequence where this modality's
+ *            sub-sequence starts; sub_off[s] + sub_len[s] must not exceed the
+ *            sequence's length
+ * Result: packed[dst.tok_off[i] - dst.tok_off[inst_begin] + cu_i[j] + sub_off[s] + r, :]
+ * = enc_rows[start_src(s) + r, :] for s the j-th sequence of destination instance i,
+ * 0 <= r < sub_len[s], inst_begin <= i < inst_end.  Rows of `packed` that belong to
+ * other modalities are not touched.  Rows are copied bit for bit.
+ * Inconsistent data (a segment outside either buffer, an encoder segment whose
+ * length is not sub_len, a failed assignment on either side) sets dst.dev_status
+ * to ORCH_EDATA and copies nothing. */
+int orch_pack_composed(const void *enc_rows, void *packed, const int32_t *sub_len,
+                       const int32_t *sub_off, int32_t n, int32_t D_src, const orch_assignment *src,
+                       int32_t D_dst, orch_assignment dst, int64_t src_rows, int32_t H,
+                       int64_t packed_rows, int32_t inst_begin, int32_t inst_end, void *ws,
+                       size_t ws_bytes, void *stream);
 
 /* Bytes of workspace orch_varlen_attn_fwd needs. */
 size_t orch_varlen_attn_workspace(int32_t batch);

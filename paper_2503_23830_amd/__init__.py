@@ -9,6 +9,8 @@ from .binding import (  # noqa: F401
     library_path,
     load_library,
     pack,
+    pack_composed,
+    pack_composed_workspace,
     pack_workspace,
     varlen_attn_fwd,
     varlen_attn_workspace,

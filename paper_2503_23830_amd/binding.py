@@ -18,6 +18,7 @@ _LIB_PATH = os.path.join(_PKG, "liborch.so")
 _lib = None
 
 EXPORTS = ("orch_balance_workspace", "orch_balance", "orch_pack_workspace", "orch_pack",
+           "orch_pack_composed_workspace", "orch_pack_composed",
            "orch_varlen_attn_workspace", "orch_varlen_attn_fwd", "orch_last_error",
            "orch_attn_variant")
 
@@ -63,6 +64,12 @@ def load_library():
     lib.orch_pack.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int64,
                               C.c_int32, C.c_int64, _Assignment, C.c_int32, C.c_int32, C.c_void_p,
                               C.c_size_t, C.c_void_p]
+    lib.orch_pack_composed_workspace.restype = C.c_size_t
+    lib.orch_pack_composed_workspace.argtypes = [C.c_int32]
+    lib.orch_pack_composed.restype = C.c_int
+    lib.orch_pack_composed.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                       C.POINTER(_Assignment), C.c_int32, _Assignment, C.c_int64, C.c_int32,
+                                       C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.orch_varlen_attn_fwd.restype = C.c_int
     lib.orch_varlen_attn_fwd.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                          C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
@@ -125,6 +132,10 @@ def pack_workspace(n: int, D: int) -> int:
     return load_library().orch_pack_workspace(n, D)
 
 
+def pack_composed_workspace(n: int) -> int:
+    return load_library().orch_pack_composed_workspace(n)
+
+
 def varlen_attn_workspace(batch: int) -> int:
     return load_library().orch_varlen_attn_workspace(batch)
 
@@ -163,6 +174,31 @@ def pack(tokens: torch.Tensor, lengths: torch.Tensor, asg: Assignment, inst_begi
         ws = _workspace(lib.orch_pack_workspace(asg.n, asg.D), dev)
     _check(lib.orch_pack(_ptr(tokens), _ptr(out), _ptr(lengths), asg.n, asg.D, T, H, out.shape[0],
                          asg._c(), inst_begin, inst_end, _ptr(ws), ws.numel(), C.c_void_p(_stream(dev))))
+    return out
+
+
+def pack_composed(enc_rows: torch.Tensor, out: torch.Tensor, sub_len: torch.Tensor, sub_off: torch.Tensor,
+                  src: Assignment | None, dst: Assignment, inst_begin: int = 0, inst_end: int | None = None,
+                  ws: torch.Tensor | None = None) -> torch.Tensor:
+    """orch_pack_composed (Sec. 5.3): one modality's rows, in the order of the encoder-phase
+    assignment `src` (None = original example order), written in place into `out`, the packed
+    LLM batch of assignment `dst`, at row `sub_off[s]` of every example's sequence."""
+    lib = load_library()
+    assert enc_rows.is_cuda and enc_rows.is_contiguous() and enc_rows.element_size() == 2 and enc_rows.dim() == 2
+    assert out.is_contiguous() and out.dtype == enc_rows.dtype and out.dim() == 2 and out.shape[1] == enc_rows.shape[1]
+    for t in (sub_len, sub_off):
+        assert t.dtype == torch.int32 and t.is_cuda and t.is_contiguous() and t.numel() == dst.n
+    assert src is None or src.n == dst.n
+    dev = enc_rows.device
+    if inst_end is None:
+        inst_end = dst.D
+    if ws is None:
+        ws = _workspace(lib.orch_pack_composed_workspace(dst.n), dev)
+    src_c = src._c() if src is not None else None
+    _check(lib.orch_pack_composed(_ptr(enc_rows), _ptr(out), _ptr(sub_len), _ptr(sub_off), dst.n,
+                                  src.D if src is not None else 0, C.byref(src_c) if src_c is not None else None,
+                                  dst.D, dst._c(), enc_rows.shape[0], enc_rows.shape[1], out.shape[0],
+                                  inst_begin, inst_end, _ptr(ws), ws.numel(), C.c_void_p(_stream(dev))))
     return out
 
 

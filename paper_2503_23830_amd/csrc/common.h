@@ -33,12 +33,18 @@ int launch_balance(const int32_t *lengths, int32_t n, int32_t D, orch_phase phas
 int launch_pack(const void *tokens, void *packed, const int32_t *lengths, int32_t n, int32_t D,
                 int64_t T, int32_t H, int64_t packed_rows, orch_assignment a, int32_t inst_begin,
                 int32_t inst_end, void *ws, size_t ws_bytes, hipStream_t stream);
+int launch_pack_composed(const void *enc_rows, void *packed, const int32_t *sub_len,
+                         const int32_t *sub_off, int32_t n, int32_t D_src, const orch_assignment *src,
+                         int32_t D_dst, orch_assignment dst, int64_t src_rows, int32_t H,
+                         int64_t packed_rows, int32_t inst_begin, int32_t inst_end, void *ws,
+                         size_t ws_bytes, hipStream_t stream);
 int launch_attn(const void *q, const void *k, const void *v, void *out, float *lse,
                 const int32_t *cu_seqlens, int32_t batch, int32_t total_tokens, int32_t Hq,
                 int32_t Hkv, int32_t d, float scale, int32_t causal, void *ws, size_t ws_bytes,
                 hipStream_t stream);
 size_t balance_ws_bytes(int32_t n, int32_t D);
 size_t pack_ws_bytes(int32_t n, int32_t D);
+size_t pack_composed_ws_bytes(int32_t n);
 size_t attn_ws_bytes(int32_t batch);
 
 }  // namespace orch

@@ -6,6 +6,14 @@
 // walks the chunks, finds the segment(s) under each chunk by binary search in a
 // small segment table and streams 16 bytes per lane.  Pure HBM traffic:
 // 2 * row_bytes per row, no arithmetic.
+//
+// orch_pack_composed: the rearrangement composition of Sec. 5.3.  The source rows lie
+// in an encoder phase's packed order and go straight to their place inside the
+// interleaved sequences of the LLM-phase assignment, so every example is still one
+// contiguous segment copy; only the segment table differs (source start from the
+// encoder assignment, destination start shifted by the modality's offset inside the
+// sequence).  Segments no longer tile the destination, so the copy kernel cuts the
+// COPIED bytes (a running prefix over segment lengths) into chunks instead.
 #include "common.h"
 
 namespace orch {
@@ -13,7 +21,7 @@ namespace {
 
 struct PackHdr {
     int64_t nseg;        // segments in the table
-    int64_t total_rows;  // destination rows covered by the chosen instances
+    int64_t total_rows;  // rows the copy kernel moves
     int32_t ok;          // 0 -> the copy kernel must not touch memory
     int32_t pad;
 };
@@ -38,7 +46,44 @@ size_t carve(PackWs &w, void *ws, int32_t n)
     return off;
 }
 
+struct ComposeWs {
+    PackHdr *hdr;
+    int64_t *src_start;  // [n]   first source row of example s
+    int64_t *seg_pos;    // [n+1] exclusive prefix of segment lengths (rows), [nseg] = total
+    int64_t *seg_dst;    // [n]   destination row of segment p (relative)
+    int64_t *seg_src;    // [n]   source row of segment p
+};
+
+size_t carve(ComposeWs &w, void *ws, int32_t n)
+{
+    size_t nn = (size_t)(n > 0 ? n : 0) + 1;
+    char *p = (char *)ws;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { char *r = p ? p + off : nullptr; off += align_up(bytes, 256); return r; };
+    w.hdr = (PackHdr *)take(sizeof(PackHdr));
+    w.src_start = (int64_t *)take(nn * 8);
+    w.seg_pos = (int64_t *)take(nn * 8);
+    w.seg_dst = (int64_t *)take(nn * 8);
+    w.seg_src = (int64_t *)take(nn * 8);
+    return off;
+}
+
 constexpr int kPrepThreads = 1024;
+
+// Inclusive scan of one value per thread over the workgroup; returns this thread's
+// inclusive sum, total in part[kPrepThreads - 1].
+__device__ __forceinline__ int64_t block_scan(int64_t *part, int tid, int64_t v)
+{
+    part[tid] = v;
+    __syncthreads();
+    for (int m = 1; m < kPrepThreads; m <<= 1) {
+        int64_t o = tid >= m ? part[tid - m] : 0;
+        __syncthreads();
+        part[tid] += o;
+        __syncthreads();
+    }
+    return part[tid];
+}
 
 // One workgroup: prefix-sum the lengths (source row of every sequence), then
 // build the segment table of the chosen instances and validate every segment
@@ -109,28 +154,137 @@ __global__ __launch_bounds__(kPrepThreads) void pack_prep_kernel(
     }
 }
 
+// The source and destination sides of a composition, as the kernel needs them.
+struct ComposeSide {
+    const int32_t *inst, *order, *seq_off, *cu;
+    const int64_t *tok_off;
+    const int32_t *status;
+    int32_t D;
+};
+
+// One workgroup.  (1) first source row of every example: from the encoder
+// assignment (position p of its order holds example order[p]; its rows start at
+// tok_off[i] + cu_i[j]), or the running sum of sub_len when the source is in
+// original order; (2) one segment per example of the chosen destination instances,
+// validated against both buffers and against the interleaved sequence it must fit
+// in; (3) the running sum of segment lengths the copy kernel chunks over.
+__global__ __launch_bounds__(kPrepThreads) void compose_prep_kernel(
+    const int32_t *__restrict__ sub_len, const int32_t *__restrict__ sub_off, int32_t n,
+    int64_t src_rows, int64_t packed_rows, int has_src, ComposeSide e, ComposeSide m,
+    int32_t *dev_status, int32_t inst_begin, int32_t inst_end, PackHdr *hdr, int64_t *src_start,
+    int64_t *seg_pos, int64_t *seg_dst, int64_t *seg_src)
+{
+    __shared__ int64_t part[kPrepThreads];
+    __shared__ int s_bad;
+    const int tid = threadIdx.x;
+    if (tid == 0) s_bad = (m.status[0] != 0) || (has_src && e.status[0] != 0);
+    int bad = 0;
+
+    if (has_src) {
+        for (int64_t s = tid; s < n; s += kPrepThreads) src_start[s] = -1;
+        __syncthreads();
+        const int32_t pe = e.seq_off[e.D];
+        if (pe != n) bad = 1;
+        else
+            for (int64_t p = tid; p < n; p += kPrepThreads) {
+                const int32_t s = e.order[p];
+                if (s < 0 || s >= n) { bad = 1; continue; }
+                const int32_t i = e.inst[s];
+                if (i < 0 || i >= e.D) { bad = 1; continue; }
+                if (p < e.seq_off[i] || p >= e.seq_off[i + 1]) { bad = 1; continue; }
+                const int64_t c0 = e.cu[p + i], c1 = e.cu[p + i + 1];
+                const int64_t start = e.tok_off[i] + c0;
+                if (c1 - c0 != sub_len[s] || c0 < 0 || start < 0 || start + (c1 - c0) > src_rows) { bad = 1; continue; }
+                src_start[s] = start;
+            }
+    } else {
+        const int64_t per = ((int64_t)n + kPrepThreads - 1) / kPrepThreads;
+        const int64_t b0 = min((int64_t)n, per * tid), b1 = min((int64_t)n, b0 + per);
+        int64_t sum = 0;
+        for (int64_t s = b0; s < b1; ++s) {
+            int32_t L = sub_len[s];
+            if (L < 0) { bad = 1; L = 0; }
+            sum += L;
+        }
+        int64_t run = block_scan(part, tid, sum) - sum;
+        for (int64_t s = b0; s < b1; ++s) {
+            src_start[s] = run;
+            run += sub_len[s] > 0 ? sub_len[s] : 0;
+        }
+        if (part[kPrepThreads - 1] > src_rows) bad = 1;
+    }
+    __syncthreads();
+
+    const int32_t p0 = m.seq_off[inst_begin], p1 = m.seq_off[inst_end];
+    const int64_t row0 = m.tok_off[inst_begin], rows = m.tok_off[inst_end] - row0;
+    if (p0 < 0 || p1 < p0 || p1 > n || rows < 0 || rows > packed_rows) bad = 1;
+    const int64_t nseg = bad ? 0 : p1 - p0;
+    const int64_t per = (nseg + kPrepThreads - 1) / kPrepThreads;
+    const int64_t b0 = min(nseg, per * tid), b1 = min(nseg, b0 + per);
+    int64_t sum = 0;
+    for (int64_t q = b0; q < b1; ++q) {
+        const int64_t p = p0 + q;
+        seg_dst[q] = 0;
+        seg_src[q] = 0;
+        const int32_t s = m.order[p];
+        if (s < 0 || s >= n) { bad = 1; continue; }
+        const int32_t i = m.inst[s];
+        if (i < inst_begin || i >= inst_end) { bad = 1; continue; }
+        if (p < m.seq_off[i] || p >= m.seq_off[i + 1]) { bad = 1; continue; }
+        const int64_t c0 = m.cu[p + i], seq_len = (int64_t)m.cu[p + i + 1] - c0;
+        const int64_t L = sub_len[s], off = sub_off[s];
+        const int64_t dst = m.tok_off[i] - row0 + c0 + off;
+        const int64_t src = src_start[s];
+        if (L < 0 || off < 0 || c0 < 0 || off + L > seq_len || dst < 0 || dst + L > rows || src < 0 ||
+            src + L > src_rows) { bad = 1; continue; }
+        seg_dst[q] = dst;
+        seg_src[q] = src;
+        sum += L;
+    }
+    if (bad) atomicOr(&s_bad, 1);
+    int64_t run = block_scan(part, tid, sum) - sum;
+    const int ok = !s_bad;  // every atomicOr above precedes the barriers inside block_scan
+    if (ok)
+        for (int64_t q = b0; q < b1; ++q) {
+            seg_pos[q] = run;
+            run += sub_len[m.order[p0 + q]];
+        }
+    if (tid == 0) {
+        hdr->nseg = ok ? nseg : 0;
+        hdr->total_rows = ok ? part[kPrepThreads - 1] : 0;
+        hdr->ok = ok;
+        if (ok) seg_pos[nseg] = part[kPrepThreads - 1];
+        else dev_status[0] = (int32_t)ORCH_EDATA;
+    }
+}
+
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kCopyThreads = 256;
 constexpr int kPer = 8;  // accesses in flight per lane
 
-// last p in [lo, hi] with seg_dst[p] * row_bytes <= x
-__device__ __forceinline__ int64_t seg_of(const int64_t *__restrict__ seg_dst, int64_t lo, int64_t hi,
+// last p in [lo, hi] with seg_pos[p] * row_bytes <= x
+__device__ __forceinline__ int64_t seg_of(const int64_t *__restrict__ seg_pos, int64_t lo, int64_t hi,
                                           int64_t row_bytes, int64_t x)
 {
     while (lo < hi) {
         const int64_t mid = (lo + hi + 1) >> 1;
-        if (seg_dst[mid] * row_bytes <= x) lo = mid;
+        if (seg_pos[mid] * row_bytes <= x) lo = mid;
         else hi = mid - 1;
     }
     return lo;
 }
 
+// Chunks are cut in the space of copied bytes: segment p covers
+// [seg_pos[p], seg_pos[p+1]) rows of it, read from row seg_src[p] and written to row
+// seg_dst[p].  For the plain pack the segments tile the destination and the caller
+// passes seg_pos = seg_dst.
 template <typename V>
 __global__ __launch_bounds__(kCopyThreads) void pack_copy_kernel(
     const char *__restrict__ src, char *__restrict__ dst, const PackHdr *__restrict__ hdr,
-    const int64_t *__restrict__ seg_dst, const int64_t *__restrict__ seg_src, int64_t row_bytes)
+    const int64_t *__restrict__ seg_pos, const int64_t *__restrict__ seg_dst,
+    const int64_t *__restrict__ seg_src, int64_t row_bytes)
 {
     if (!hdr->ok) return;
     constexpr int64_t VB = sizeof(V);
@@ -141,13 +295,15 @@ __global__ __launch_bounds__(kCopyThreads) void pack_copy_kernel(
     const int64_t nchunks = (total + CB - 1) / CB;
     for (int64_t c = blockIdx.x; c < nchunks; c += gridDim.x) {
         const int64_t cb = c * CB, ce = min(cb + CB, total);
-        const int64_t plo = seg_of(seg_dst, 0, nseg - 1, row_bytes, cb);
-        const int64_t phi = seg_of(seg_dst, plo, nseg - 1, row_bytes, ce - 1);
+        const int64_t plo = seg_of(seg_pos, 0, nseg - 1, row_bytes, cb);
+        const int64_t phi = seg_of(seg_pos, plo, nseg - 1, row_bytes, ce - 1);
         // usually one segment covers the whole chunk; otherwise walk the pieces
         for (int64_t p = plo; p <= phi; ++p) {
-            const int64_t a = max(cb, seg_dst[p] * row_bytes), b = min(ce, seg_dst[p + 1] * row_bytes);
+            const int64_t pos = seg_pos[p];
+            const int64_t a = max(cb, pos * row_bytes), b = min(ce, seg_pos[p + 1] * row_bytes);
             if (a >= b) continue;
-            const char *sp = src + (seg_src[p] - seg_dst[p]) * row_bytes;
+            const char *sp = src + (seg_src[p] - pos) * row_bytes;
+            char *dp = dst + (seg_dst[p] - pos) * row_bytes;
             for (int64_t x0 = a + (int64_t)threadIdx.x * VB; x0 < b; x0 += CB) {
                 V val[kPer];
 #pragma unroll
@@ -158,11 +314,40 @@ __global__ __launch_bounds__(kCopyThreads) void pack_copy_kernel(
 #pragma unroll
                 for (int u = 0; u < kPer; ++u) {
                     const int64_t x = x0 + (int64_t)u * kCopyThreads * VB;
-                    if (x < b) __builtin_nontemporal_store(val[u], (V *)(dst + x));
+                    if (x < b) __builtin_nontemporal_store(val[u], (V *)(dp + x));
                 }
             }
         }
     }
+}
+
+// Copy kernel over at most max_bytes copied bytes, with the widest access that divides
+// the row size and both base addresses.
+void launch_copy(const void *src, void *dst, int64_t max_bytes, int64_t row_bytes, const PackHdr *hdr,
+                 const int64_t *seg_pos, const int64_t *seg_dst, const int64_t *seg_src,
+                 hipStream_t stream)
+{
+    if (max_bytes <= 0) return;
+    const uintptr_t mis = (uintptr_t)src | (uintptr_t)dst | (uintptr_t)row_bytes;
+    int vb = 16;
+    while (mis & (uintptr_t)(vb - 1)) vb >>= 1;
+    const int64_t cb = (int64_t)kCopyThreads * kPer * vb;
+    const int64_t nchunks = (max_bytes + cb - 1) / cb;
+    const int grid = (int)(nchunks < 256 * 8 ? nchunks : 256 * 8);
+    const char *s = (const char *)src;
+    char *d = (char *)dst;
+    if (vb == 16)
+        hipLaunchKernelGGL(pack_copy_kernel<u32x4>, dim3(grid), dim3(kCopyThreads), 0, stream, s, d, hdr,
+                           seg_pos, seg_dst, seg_src, row_bytes);
+    else if (vb == 8)
+        hipLaunchKernelGGL(pack_copy_kernel<u32x2>, dim3(grid), dim3(kCopyThreads), 0, stream, s, d, hdr,
+                           seg_pos, seg_dst, seg_src, row_bytes);
+    else if (vb == 4)
+        hipLaunchKernelGGL(pack_copy_kernel<uint32_t>, dim3(grid), dim3(kCopyThreads), 0, stream, s, d, hdr,
+                           seg_pos, seg_dst, seg_src, row_bytes);
+    else
+        hipLaunchKernelGGL(pack_copy_kernel<uint16_t>, dim3(grid), dim3(kCopyThreads), 0, stream, s, d, hdr,
+                           seg_pos, seg_dst, seg_src, row_bytes);
 }
 
 }  // namespace
@@ -187,30 +372,35 @@ int launch_pack(const void *tokens, void *packed, const int32_t *lengths, int32_
                        packed_rows, a.inst, a.order, a.seq_off, a.tok_off, a.cu_seqlens, a.dev_status,
                        inst_begin, inst_end, w.hdr, w.src_cu, w.seg_dst, w.seg_src);
 
-    const int64_t max_bytes = (packed_rows < T ? packed_rows : T) * row_bytes;
-    if (max_bytes > 0) {
-        // widest access that divides the row size and both base addresses
-        const uintptr_t mis = (uintptr_t)tokens | (uintptr_t)packed | (uintptr_t)row_bytes;
-        int vb = 16;
-        while (mis & (uintptr_t)(vb - 1)) vb >>= 1;
-        const int64_t cb = (int64_t)kCopyThreads * kPer * vb;
-        int64_t nchunks = (max_bytes + cb - 1) / cb;
-        const int grid = (int)(nchunks < 256 * 8 ? nchunks : 256 * 8);
-        const char *s = (const char *)tokens;
-        char *d = (char *)packed;
-        if (vb == 16)
-            hipLaunchKernelGGL(pack_copy_kernel<u32x4>, dim3(grid), dim3(kCopyThreads), 0, stream, s, d,
-                               w.hdr, w.seg_dst, w.seg_src, row_bytes);
-        else if (vb == 8)
-            hipLaunchKernelGGL(pack_copy_kernel<u32x2>, dim3(grid), dim3(kCopyThreads), 0, stream, s, d,
-                               w.hdr, w.seg_dst, w.seg_src, row_bytes);
-        else if (vb == 4)
-            hipLaunchKernelGGL(pack_copy_kernel<uint32_t>, dim3(grid), dim3(kCopyThreads), 0, stream, s, d,
-                               w.hdr, w.seg_dst, w.seg_src, row_bytes);
-        else
-            hipLaunchKernelGGL(pack_copy_kernel<uint16_t>, dim3(grid), dim3(kCopyThreads), 0, stream, s, d,
-                               w.hdr, w.seg_dst, w.seg_src, row_bytes);
-    }
+    launch_copy(tokens, packed, (packed_rows < T ? packed_rows : T) * row_bytes, row_bytes, w.hdr,
+                w.seg_dst, w.seg_dst, w.seg_src, stream);
+    ORCH_HIP_CHECK(hipGetLastError());
+    return ORCH_OK;
+}
+
+size_t pack_composed_ws_bytes(int32_t n)
+{
+    ComposeWs w;
+    return carve(w, nullptr, n);
+}
+
+int launch_pack_composed(const void *enc_rows, void *packed, const int32_t *sub_len,
+                         const int32_t *sub_off, int32_t n, int32_t D_src, const orch_assignment *src,
+                         int32_t D_dst, orch_assignment dst, int64_t src_rows, int32_t H,
+                         int64_t packed_rows, int32_t inst_begin, int32_t inst_end, void *ws,
+                         size_t ws_bytes, hipStream_t stream)
+{
+    ComposeWs w;
+    size_t need = carve(w, ws, n);
+    if (ws_bytes < need) ORCH_FAIL(ORCH_ENOSPC, "orch_pack_composed: workspace %zu < %zu bytes", ws_bytes, need);
+    const int64_t row_bytes = (int64_t)H * 2;
+    ComposeSide e{}, m{dst.inst, dst.order, dst.seq_off, dst.cu_seqlens, dst.tok_off, dst.dev_status, D_dst};
+    if (src) e = ComposeSide{src->inst, src->order, src->seq_off, src->cu_seqlens, src->tok_off, src->dev_status, D_src};
+    hipLaunchKernelGGL(compose_prep_kernel, dim3(1), dim3(kPrepThreads), 0, stream, sub_len, sub_off, n,
+                       src_rows, packed_rows, src ? 1 : 0, e, m, dst.dev_status, inst_begin, inst_end, w.hdr,
+                       w.src_start, w.seg_pos, w.seg_dst, w.seg_src);
+    launch_copy(enc_rows, packed, (packed_rows < src_rows ? packed_rows : src_rows) * row_bytes, row_bytes,
+                w.hdr, w.seg_pos, w.seg_dst, w.seg_src, stream);
     ORCH_HIP_CHECK(hipGetLastError());
     return ORCH_OK;
 }

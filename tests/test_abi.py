@@ -17,7 +17,7 @@ def declared_functions():
 
 def test_header_declares_the_boundary():
     names = declared_functions()
-    for want in ("orch_balance", "orch_pack", "orch_varlen_attn_fwd", "orch_balance_workspace",
+    for want in ("orch_balance", "orch_pack", "orch_pack_composed", "orch_pack_composed_workspace", "orch_varlen_attn_fwd", "orch_balance_workspace",
                  "orch_pack_workspace", "orch_varlen_attn_workspace", "orch_last_error"):
         assert want in names
 
@@ -62,6 +62,16 @@ def test_workspace_queries_and_host_side_errors():
     assert rc == -1
     rc = lib.orch_pack(fake, fake, fake, 8, 4, 10, 64, 10, asg, 2, 5, fake, 1 << 20, None)
     assert rc == -1
+    assert lib.orch_pack_composed_workspace(32768) >= 32768 * 32
+    rc = lib.orch_pack_composed(fake, fake, fake, fake, 8, 0, None, 4, asg, 10, 64, 10, 2, 5, fake, 1 << 20, None)
+    assert rc == -1 and b"instance range" in lib.orch_last_error()
+    rc = lib.orch_pack_composed(fake, fake, fake, fake, 8, 0, ctypes.byref(asg), 4, asg, 10, 64, 10, 0, 4, fake,
+                                1 << 20, None)
+    assert rc == -1 and b"D_src" in lib.orch_last_error()
+    rc = lib.orch_pack_composed(fake, fake, fake, None, 8, 0, None, 4, asg, 10, 64, 10, 0, 4, fake, 1 << 20, None)
+    assert rc == -1 and b"sub_off" in lib.orch_last_error()
+    rc = lib.orch_pack_composed(fake, fake, fake, fake, 8, 0, None, 4, asg, 10, 64, 10, 0, 4, fake, 64, None)
+    assert rc == -2 and b"workspace" in lib.orch_last_error()
     rc = lib.orch_varlen_attn_fwd(fake, fake, fake, fake, None, fake, 2, 64, 0, 8, 3, 64, 0.0, 1, fake,
                                   1 << 20, None)
     assert rc == -1

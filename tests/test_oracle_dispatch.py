@@ -244,24 +244,15 @@ def test_workload_laws():
 # Rearrangement composition (Sec. 5.3): Pi_M o Pi_E^-1 in one pass
 # ----------------------------------------------------------------------------
 def modality_case(cid, shrink=1, keep=None, seed=0):
-    """Lengths, three-way modality split, a per-example modality order (seeded) and the
-    row offset of every modality inside the example's interleaved sequence."""
+    """Lengths, three-way modality split and the row offset of every modality inside the
+    example's interleaved sequence (modalities ordered per example by a seeded draw)."""
     w = wl.WORKLOADS[cid]
     L = wl.draw_lengths(w)
     if keep is not None:
         L = L[:keep]
     L = (L // shrink).astype(np.int32)
     split = wl.draw_modality_split(w, L)
-    n = len(L)
-    perm_id = (wl.uniform01(1000 + seed, 21, n) * 6).astype(np.int64)
-    perms = np.array(list(itertools.permutations(range(3))), dtype=np.int64)[perm_id]  # [n,3]: slot -> modality
-    sub_off = np.zeros((n, 3), dtype=np.int32)
-    for s in range(n):
-        run = 0
-        for slot in range(3):
-            m = perms[s, slot]
-            sub_off[s, m] = run
-            run += split[s, m]
+    sub_off = wl.draw_interleave_offsets(split, 1000 + seed)
     return w, L, split, sub_off
 
 

@@ -167,6 +167,20 @@ def draw_modality_split(w: Workload, lengths: np.ndarray, base_seed: int = BASE_
     return base.astype(np.int32)
 
 
+def draw_interleave_offsets(split: np.ndarray, seed: int) -> np.ndarray:
+    """int32[n,3]: the row at which each modality's sub-sequence starts inside its example's
+    interleaved sequence.  Every example orders its three modalities by a seeded permutation
+    and lays them out back to back (Sec. 3.1: sub-sequences are interleaved per example)."""
+    n = split.shape[0]
+    perms = np.array([[0, 1, 2], [0, 2, 1], [1, 0, 2], [1, 2, 0], [2, 0, 1], [2, 1, 0]], dtype=np.int64)
+    slot_mod = perms[(uniform01(seed, 21, n) * 6).astype(np.int64)]  # [n,3]: slot -> modality
+    lens = np.take_along_axis(split.astype(np.int64), slot_mod, axis=1)
+    starts = np.cumsum(lens, axis=1) - lens
+    off = np.empty((n, 3), dtype=np.int32)
+    np.put_along_axis(off, slot_mod, starts.astype(np.int32), axis=1)
+    return off
+
+
 def random_lengths(seed: int, n: int, lo: int, hi: int, zero_frac: float = 0.0) -> np.ndarray:
     """Generic test helper: uniform ints in [lo, hi], a fraction forced to 0."""
     u = uniform01(seed, 11, n)
