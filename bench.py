@@ -6,7 +6,10 @@ One step = one pass of the whole hot path over one seeded synthetic batch:
   ->  orch_varlen_attn_fwd on the most loaded instance's packed share.
 Inputs are resident in HBM before the timed region.  Default workload: C4 (LLM
 phase with modality-composition incoherence), the configuration the targets are
-stated on.  Prints ONE JSON line.
+stated on.  After the timed steps the rearrangement composition (orch_pack_composed,
+three modality buffers into the same packed batch) is timed and checked on its own and
+reported under "composed_pack"; it is not part of `value` or `ms_per_step`.
+Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -166,6 +169,59 @@ def main():
     bits = lambda t: t.cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
     for r0 in [0, max(0, T_pack - 128)] + [int(x) for x in wl.uniform01(5, 1, 14) * max(1, T_pack - 128)]:
         ok &= np.array_equal(bits(packed[r0: r0 + 128]), wl.token_tag_np(rmap[r0: r0 + 128], H))
+
+    # ---------------- rearrangement composition (Sec. 5.3), outside the timed step -------------
+    # The same rows seen as three modality buffers (text in original order, image and audio in
+    # their own encoder-phase packed order) go to their place inside the packed LLM batch.
+    composed = None
+    if whole and T_pack > 0:
+        split = wl.draw_modality_split(w, L, base_seed)
+        sub_off = wl.draw_interleave_offsets(split, base_seed)
+        ws_comp = torch.empty(orch.pack_composed_workspace(n), dtype=torch.uint8, device=dev)
+        row_begin = np.concatenate([[0], np.cumsum(split.sum(axis=0, dtype=np.int64))])
+        enc_cost = {1: (1, 6144), 2: (1, 7680)}
+        mods = []
+        for m in range(3):
+            sub = np.ascontiguousarray(split[:, m])
+            easg = None
+            if m:
+                easg = orch.balance(torch.from_numpy(sub).to(dev), D, *enc_cost[m])
+            mods.append((tokens[int(row_begin[m]): int(row_begin[m + 1])], torch.from_numpy(sub).to(dev),
+                         torch.from_numpy(np.ascontiguousarray(sub_off[:, m])).to(dev), easg, sub))
+
+        def compose():
+            for rows_m, sl, so, easg, _ in mods:
+                orch.pack_composed(rows_m, packed, sl, so, easg, asg, ws=ws_comp)
+
+        packed.fill_(0x7C7C)
+        compose()
+        torch.cuda.synchronize()
+        cev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        cev[0].record()
+        for _ in range(args.steps):
+            compose()
+        cev[1].record()
+        torch.cuda.synchronize()
+        comp_ms = cev[0].elapsed_time(cev[1]) / args.steps
+        cok = int(asg.dev_status.item()) == 0
+        src_row = np.full(T_pack, -1, dtype=np.int64)
+        for m, (_, _, _, easg, sub) in enumerate(mods):
+            eref = oracle.balance(sub, D, *enc_cost[m]) if m else None
+            idx = np.arange(int(sub.sum()), dtype=np.int64).view(np.uint16).reshape(-1, 4)
+            o = np.full((T_pack, 4), 0xFFFF, dtype=np.uint16)
+            oracle.pack_composed(idx, o, sub, sub_off[:, m], eref, ref)
+            o = o.view(np.int64).reshape(T_pack)
+            cok &= bool((src_row[o >= 0] == -1).all())
+            src_row[o >= 0] = o[o >= 0] + row_begin[m]
+        cok &= bool((src_row >= 0).all())
+        for r0 in [0, max(0, T_pack - 128)] + [int(x) for x in wl.uniform01(6, 1, 14) * max(1, T_pack - 128)]:
+            cok &= np.array_equal(bits(packed[r0: r0 + 128]), wl.token_tag_np(src_row[r0: r0 + 128], H))
+        ok &= cok
+        composed = {"ms": comp_ms, "GBps": pack_bytes / (comp_ms * 1e-3) / 1e9,
+                    "frac_hbm_peak": pack_bytes / (comp_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, "calls": 3,
+                    "rows": [int(x) for x in np.diff(row_begin)], "verified": bool(cok),
+                    "note": "three orch_pack_composed calls (text, image, audio) fill the packed LLM batch once; "
+                            "reset-then-rearrange would move every row twice"}
     before = oracle.load_ratio(L, (np.arange(n, dtype=np.int64) * D) // n, D, w.a, w.b)
     after = float(loads.max() / loads.mean())
 
@@ -255,6 +311,7 @@ def main():
         "attn": {"tflops": attn_tflops, "frac_mfma_peak": attn_tflops / MFMA_BF16_PEAK_TFLOPS, "ms": attn_ms,
                  "variant": orch.attn_variant()},
         "pack": {"GBps": pack_gbps, "frac_hbm_peak": pack_gbps / HBM_PEAK_GBPS, "ms": pack_ms, "bytes": pack_bytes},
+        "composed_pack": composed,
         "dispatch": {"ms": bal_ms, "calls_per_step": 1 if whole else 2},
         "load_max_over_mean": {"before": before, "after": after},
         "verified": bool(ok), "attn_err": {"max_abs": float(err.max()), "mean_abs": float(err.mean())},

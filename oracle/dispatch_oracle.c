@@ -12,7 +12,10 @@
  *     a = 0, b = 1 this is Algorithm 1 literally;
  *   - the packed, padding-free layout each instance then batches along the
  *     sequence dimension (Sec. 7, input preprocessing) and the row movement the
- *     All-to-All Batch Communicator performs (Sec. 5.2.1), on one device.
+ *     All-to-All Batch Communicator performs (Sec. 5.2.1), on one device;
+ *   - the rearrangement composition of Sec. 5.3 (an encoder phase's packed rows
+ *     straight into the LLM phase's packed batch), written as the two steps it
+ *     composes: reset to original order, then rearrange.
  *
  * Readings where the paper is silent: equal keys keep ascending index order
  * (stable sort); among equally loaded batches the lowest-numbered one is the

@@ -65,7 +65,7 @@ __global__ void calib_copy_kernel(const uint4 *__restrict__ src, uint4 *__restri
 int main(int argc, char **argv)
 {
     if (argc < 11) {
-        fprintf(stderr, "usage: %s lengths.bin D a b H Hq Hkv d causal steps [pack_all=1]\n", argv[0]);
+        fprintf(stderr, "usage: %s lengths.bin D a b H Hq Hkv d causal steps [pack_all=1] [split.bin]\n", argv[0]);
         return 2;
     }
     const char *path = argv[1];
@@ -74,6 +74,7 @@ int main(int argc, char **argv)
     const int H = atoi(argv[5]), Hq = atoi(argv[6]), Hkv = atoi(argv[7]), d = atoi(argv[8]);
     const int causal = atoi(argv[9]), steps = atoi(argv[10]);
     const int pack_all = argc > 11 ? atoi(argv[11]) : 1;
+    const char *split_path = argc > 12 ? argv[12] : nullptr;
 
     FILE *f = fopen(path, "rb");
     if (!f) { perror(path); return 1; }
@@ -197,6 +198,57 @@ int main(int argc, char **argv)
     printf("dev_status=%d instance=%d attn_tokens=%d\n", status, istar, Ti);
     printf("balance %.3f ms | pack %.3f ms %.1f GB/s (%.3e B) | attn %.3f ms %.1f TFLOP/s (%.3e FLOP) [%s]\n", tb, tp,
            pbytes / tp / 1e6, pbytes, ta, flops / ta / 1e9, flops, orch_attn_variant());
+
+    // rearrangement composition (Sec. 5.3): the same rows, now three modality buffers in
+    // their encoders' packed order (text in original order), composed into the LLM batch
+    if (split_path && pack_all) {
+        std::vector<int32_t> sp((size_t)n * 6);
+        FILE *g = fopen(split_path, "rb");
+        if (!g || fread(sp.data(), 4, sp.size(), g) != sp.size()) { fprintf(stderr, "%s: short read\n", split_path); return 1; }
+        fclose(g);
+        size_t wsc = orch_pack_composed_workspace(n);
+        void *ws_c;
+        CK(hipMalloc(&ws_c, wsc));
+        int32_t *sub[3], *off[3];
+        orch_assignment ea[3];
+        int64_t rows_m[3], row_begin[3], acc = 0;
+        for (int m = 0; m < 3; ++m) {
+            std::vector<int32_t> sl(n), so(n);
+            rows_m[m] = 0;
+            for (int s = 0; s < n; ++s) { sl[s] = sp[(size_t)s * 6 + m]; so[s] = sp[(size_t)s * 6 + 3 + m]; rows_m[m] += sl[s]; }
+            row_begin[m] = acc;
+            acc += rows_m[m];
+            CK(hipMalloc(&sub[m], 4 * std::max(n, 1)));
+            CK(hipMalloc(&off[m], 4 * std::max(n, 1)));
+            CK(hipMemcpy(sub[m], sl.data(), 4 * n, hipMemcpyHostToDevice));
+            CK(hipMemcpy(off[m], so.data(), 4 * n, hipMemcpyHostToDevice));
+            if (m == 0) continue;
+            CK(hipMalloc(&ea[m].inst, 4 * std::max(n, 1)));
+            CK(hipMalloc(&ea[m].order, 4 * std::max(n, 1)));
+            CK(hipMalloc(&ea[m].seq_off, 4 * (D + 1)));
+            CK(hipMalloc(&ea[m].tok_off, 8 * (D + 1)));
+            CK(hipMalloc(&ea[m].cu_seqlens, 4 * (n + D)));
+            CK(hipMalloc(&ea[m].loads, 8 * D));
+            CK(hipMalloc(&ea[m].dev_status, 4));
+            OK(orch_balance(sub[m], n, D, orch_phase{a, b}, ea[m], ws_b, wsb, st));
+        }
+        if (acc != T) { fprintf(stderr, "split rows %lld != T %lld\n", (long long)acc, (long long)T); return 1; }
+        double tc = 0;
+        for (int s = 0; s < steps + 1; ++s) {
+            CK(hipEventRecord(e0, st));
+            for (int m = 0; m < 3; ++m)
+                OK(orch_pack_composed(tokens + (size_t)row_begin[m] * H, packed, sub[m], off[m], n, m ? D : 0,
+                                      m ? &ea[m] : nullptr, D, as, rows_m[m], H, prow, 0, D, ws_c, wsc, st));
+            CK(hipEventRecord(e1, st));
+            CK(hipStreamSynchronize(st));
+            float ms;
+            if (s > 0) { CK(hipEventElapsedTime(&ms, e0, e1)); tc += ms; }
+        }
+        tc /= steps;
+        CK(hipMemcpy(&status, as.dev_status, 4, hipMemcpyDeviceToHost));
+        printf("composed (3 modalities: %lld + %lld + %lld rows) %.3f ms %.1f GB/s, dev_status=%d\n",
+               (long long)rows_m[0], (long long)rows_m[1], (long long)rows_m[2], tc, pbytes / tc / 1e6, status);
+    }
 
     // calibration: 1 GiB read + 1 GiB written by a plain copy
     const size_t cbytes = (size_t)1 << 30;
