@@ -142,6 +142,29 @@ def main():
     pack_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
     attn_ms = float(np.mean([e[2].elapsed_time(e[3]) for e in events]))
 
+    # the straggler of the split BEFORE balancing (sequence s on instance floor(s*D/n)), same kernel
+    src_inst = (np.arange(n, dtype=np.int64) * D) // n
+    tok_before = np.bincount(src_inst, weights=L.astype(np.float64) ** 2 * w.a + L.astype(np.float64) * w.b, minlength=D)
+    i_before = int(np.argmax(tok_before))
+    cu_b = np.concatenate([[0], np.cumsum(L[src_inst == i_before], dtype=np.int64)]).astype(np.int32)
+    T_b = int(cu_b[-1])
+    qb = wl.normal_bf16_torch((T_b, w.Hq, w.d), base_seed, 4, dev)
+    kb = wl.normal_bf16_torch((T_b, w.Hkv, w.d), base_seed, 5, dev)
+    vb = wl.normal_bf16_torch((T_b, w.Hkv, w.d), base_seed, 6, dev)
+    ob = torch.empty_like(qb)
+    cu_bd = torch.from_numpy(cu_b).to(dev)
+    ws_b = torch.empty(orch.varlen_attn_workspace(len(cu_b) - 1), dtype=torch.uint8, device=dev)
+    orch.varlen_attn_fwd(qb, kb, vb, cu_bd, w.causal, out=ob, ws=ws_b)
+    bev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    bev[0].record()
+    for _ in range(3):
+        orch.varlen_attn_fwd(qb, kb, vb, cu_bd, w.causal, out=ob, ws=ws_b)
+    bev[1].record()
+    torch.cuda.synchronize()
+    attn_before_ms = bev[0].elapsed_time(bev[1]) / 3
+    flops_before = attn_flops(cu_b, w.Hq, w.d, w.causal)
+    del qb, kb, vb, ob
+
     if args.calib_copy:
         ca = torch.zeros(1 << 29, dtype=torch.int16, device=dev)
         cb = torch.empty_like(ca)
@@ -217,9 +240,18 @@ def main():
         for r0 in [0, max(0, T_pack - 128)] + [int(x) for x in wl.uniform01(6, 1, 14) * max(1, T_pack - 128)]:
             cok &= np.array_equal(bits(packed[r0: r0 + 128]), wl.token_tag_np(src_row[r0: r0 + 128], H))
         ok &= cok
+        # modality-composition incoherence (Sec. 3.2; the argument behind Fig. 10): an encoder's
+        # load spread if it had to live with the LLM phase's assignment, vs its own balance
+        inst_llm = asg.inst.cpu().numpy()[:n]
+        mci = {}
+        for m, name in ((1, "image"), (2, "audio")):
+            el = mods[m][3].loads.cpu().numpy().view(np.uint64).astype(np.float64)
+            mci[name] = {"under_llm_assignment": oracle.load_ratio(mods[m][4], inst_llm, D, *enc_cost[m]),
+                         "own_balance": float(el.max() / el.mean())}
         composed = {"ms": comp_ms, "GBps": pack_bytes / (comp_ms * 1e-3) / 1e9,
                     "frac_hbm_peak": pack_bytes / (comp_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, "calls": 3,
                     "rows": [int(x) for x in np.diff(row_begin)], "verified": bool(cok),
+                    "encoder_load_max_over_mean": mci,
                     "note": "three orch_pack_composed calls (text, image, audio) fill the packed LLM batch once; "
                             "reset-then-rearrange would move every row twice"}
     before = oracle.load_ratio(L, (np.arange(n, dtype=np.int64) * D) // n, D, w.a, w.b)
@@ -309,7 +341,9 @@ def main():
                    "attn_instance": i_star, "attn_tokens": T_i, "attn_sequences": batch_i,
                    "heads": [w.Hq, w.Hkv], "head_dim": w.d, "causal": w.causal},
         "attn": {"tflops": attn_tflops, "frac_mfma_peak": attn_tflops / MFMA_BF16_PEAK_TFLOPS, "ms": attn_ms,
-                 "variant": orch.attn_variant()},
+                 "variant": orch.attn_variant(),
+                 "straggler_before_balancing": {"instance": i_before, "tokens": T_b, "ms": attn_before_ms,
+                                                "tflops": flops_before / (attn_before_ms * 1e-3) / 1e12}},
         "pack": {"GBps": pack_gbps, "frac_hbm_peak": pack_gbps / HBM_PEAK_GBPS, "ms": pack_ms, "bytes": pack_bytes},
         "composed_pack": composed,
         "dispatch": {"ms": bal_ms, "calls_per_step": 1 if whole else 2},
