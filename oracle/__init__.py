@@ -41,8 +41,10 @@ def lib():
     if _lib is None:
         _lib = C.CDLL(build())
         for name in ("orc_cost", "orc_sort_desc", "orc_greedy", "orc_balance", "orc_pack",
-                     "orc_row_map", "orc_pack_composed", "orc_attn_fwd", "orc_attn_rows"):
+                     "orc_row_map", "orc_pack_composed", "orc_sort_asc", "orc_balance_padded", "orc_attn_fwd",
+                     "orc_attn_rows"):
             getattr(_lib, name).restype = C.c_int
+        _lib.orc_least_batches.restype = C.c_int64
     return _lib
 
 
@@ -107,6 +109,37 @@ def balance(lengths, D: int, a: int, b: int) -> Assignment:
                              _p(out.inst), _p(out.order), _p(out.seq_off), _p(out.tok_off),
                              _p(out.cu_seqlens), _p(out.loads)))
     return out
+
+
+def sort_asc(lengths) -> np.ndarray:
+    L = _i32(lengths)
+    out = np.empty(len(L), np.int32)
+    _check(lib().orc_sort_asc(_p(L), C.c_int32(len(L)), _p(out)))
+    return out
+
+
+def least_batches(lengths, sorted_idx, bound: int):
+    """GetLeastBatches(bound) of Algorithm 2: (number of batches, batch of every sorted position)."""
+    L, srt = _i32(lengths), _i32(sorted_idx)
+    batch_of = np.empty(len(L), np.int32)
+    cnt = lib().orc_least_batches(_p(L), _p(srt), C.c_int32(len(L)), C.c_uint64(bound), _p(batch_of))
+    return int(cnt), batch_of
+
+
+def balance_padded(lengths, D: int, a: int, b: int):
+    """Algorithm 2 (Sec. 5.1, batching with paddings): returns (Assignment, bound).  The
+    assignment's cu_seqlens are the padded slots j * max_i and tok_off the padded batch lengths."""
+    L = _i32(lengths)
+    n = len(L)
+    if D < 1:
+        raise OracleError(-1)
+    out = Assignment(np.empty(n, np.int32), np.empty(n, np.int32), np.empty(D + 1, np.int32),
+                     np.empty(D + 1, np.int64), np.empty(n + D, np.int32), np.empty(D, np.uint64))
+    bound = C.c_uint64(0)
+    _check(lib().orc_balance_padded(_p(L), C.c_int32(n), C.c_int32(D), C.c_uint64(a), C.c_uint64(b),
+                                    _p(out.inst), _p(out.order), _p(out.seq_off), _p(out.tok_off),
+                                    _p(out.cu_seqlens), _p(out.loads), C.byref(bound)))
+    return out, int(bound.value)
 
 
 def pack(tokens: np.ndarray, lengths, asg: Assignment, inst_begin: int = 0, inst_end: int | None = None):

@@ -206,8 +206,11 @@ int orc_row_map(const int32_t *lengths, int32_t n, int32_t D, const int32_t *ord
  * e_order == NULL means the rows already are in original order (text: it never
  * left its instance), so step 1 is the identity.
  * Destination rows that belong to other modalities are left untouched.
- * Returns -5 if a sub-sequence does not fit in its interleaved sequence or the
- * encoder assignment's segment lengths disagree with sub_len. */
+ * An encoder segment may be longer than sub_len[s] (a padded encoder batch, Sec. 7
+ * input preprocessing: audio is batched with paddings); its first sub_len[s] rows
+ * are the example's.
+ * Returns -5 if a sub-sequence does not fit in its interleaved sequence or in its
+ * encoder segment. */
 int orc_pack_composed(const void *enc_rows, void *packed, const int32_t *sub_len,
                       const int32_t *sub_off, int32_t n, int64_t row_bytes, int32_t De,
                       const int32_t *e_order, const int32_t *e_seq_off, const int64_t *e_tok_off,
@@ -235,7 +238,7 @@ int orc_pack_composed(const void *enc_rows, void *packed, const int32_t *sub_len
             const int32_t *cu = e_cu + e_seq_off[i] + i;
             for (int32_t j = 0; j < e_seq_off[i + 1] - e_seq_off[i]; ++j) {
                 int32_t s = e_order[e_seq_off[i] + j];
-                if (cu[j + 1] - cu[j] != sub_len[s]) { free(tmp); free(sub_cu); return -5; }
+                if (cu[j + 1] - cu[j] < sub_len[s]) { free(tmp); free(sub_cu); return -5; }
                 memcpy(tmp + sub_cu[s] * row_bytes, src + (e_tok_off[i] + cu[j]) * row_bytes,
                        (size_t)sub_len[s] * (size_t)row_bytes);
             }
@@ -257,5 +260,136 @@ int orc_pack_composed(const void *enc_rows, void *packed, const int32_t *sub_len
     }
     free(tmp);
     free(sub_cu);
+    return rc;
+}
+
+/* ---------------------------------------------------------------------------
+ * Algorithm 2, "Post-Balancing Algorithm with Paddings" (Sec. 5.1).  A padded
+ * batch of k sequences costs k * (its longest sequence) rows (Eq. 1, padding
+ * branch); the algorithm sorts ascending, and for an upper bound b on that
+ * batch length cuts the sorted list greedily into the fewest batches, then
+ * binary-searches the smallest b that needs at most d batches.
+ * ------------------------------------------------------------------------- */
+
+/* Algorithm 2, line 1: indices in ascending length order; equal lengths keep
+ * ascending index order (stable bottom-up merge sort). */
+int orc_sort_asc(const int32_t *lengths, int32_t n, int32_t *sorted)
+{
+    if (n < 0 || (n > 0 && (!lengths || !sorted))) return -1;
+    int32_t *a = sorted, *b = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n > 0 ? n : 1));
+    if (!b) return -1;
+    for (int32_t i = 0; i < n; ++i) a[i] = i;
+    for (int64_t w = 1; w < n; w *= 2) {
+        for (int64_t lo = 0; lo < n; lo += 2 * w) {
+            int64_t mid = lo + w < n ? lo + w : n, hi = lo + 2 * w < n ? lo + 2 * w : n;
+            int64_t i = lo, j = mid, k = lo;
+            while (i < mid && j < hi) {
+                /* take from the right run only when it is strictly shorter */
+                if (lengths[a[j]] < lengths[a[i]]) b[k++] = a[j++];
+                else b[k++] = a[i++];
+            }
+            while (i < mid) b[k++] = a[i++];
+            while (j < hi) b[k++] = a[j++];
+        }
+        int32_t *t = a; a = b; b = t;
+    }
+    if (a != sorted) { memcpy(sorted, a, sizeof(int32_t) * (size_t)n); b = a; }
+    free(b);
+    return 0;
+}
+
+/* GetLeastBatches(b) of Algorithm 2: walk the ascending list; the current batch
+ * is closed (a new, empty one opened) when one more sequence would push its
+ * padded length (count + 1) * length above b; the sequence is then put into the
+ * last batch whatever its length.  batch_of[t] (may be NULL) receives the batch
+ * of sorted position t.  Returns the number of batches, counting the initial
+ * one even when it stays empty. */
+int64_t orc_least_batches(const int32_t *lengths, const int32_t *sorted, int32_t n, uint64_t bound,
+                          int32_t *batch_of)
+{
+    int64_t batches = 1;  /* ret_batches = {{}} */
+    uint64_t in_last = 0;
+    for (int32_t t = 0; t < n; ++t) {
+        uint64_t len = (uint64_t)(uint32_t)lengths[sorted[t]];
+        if ((in_last + 1) * len > bound) {
+            ++batches;
+            in_last = 0;
+        }
+        ++in_last;
+        if (batch_of) batch_of[t] = (int32_t)(batches - 1);
+    }
+    return batches;
+}
+
+/* The whole of Algorithm 2 plus the layout of the padded batches.
+ * Readings where the printed listing is garbled or silent:
+ *   - the search starts at left = the shortest length, as printed, and
+ *     right = (the LONGEST length) * (floor(n/d) + 1): the printed right bound
+ *     takes the first (shortest) element, which need not be feasible, while with
+ *     the longest one every batch can hold floor(n/d) + 1 >= ceil(n/d) sequences,
+ *     so at most d batches are needed and the search has an answer;
+ *   - loop body: mid = floor((left + right) / 2); if GetLeastBatches(mid) has at
+ *     most d batches then right = mid, else left = mid + 1;
+ *   - the batches returned are GetLeastBatches at the final bound (the last mid
+ *     tried may have been an infeasible one);
+ *   - the k-th batch is instance k; when fewer than d batches result the last
+ *     instances stay empty;
+ *   - zero-length sequences are ordinary elements (they sort first and occupy a
+ *     padded slot each).
+ * Outputs (same shapes as orc_balance): inst, order (= the ascending order),
+ * seq_off; cu_seqlens: instance i's slice holds j * max_i for j = 0..cnt_i, i.e.
+ * every sequence owns max_i rows of the padded batch; tok_off: prefix of the
+ * padded batch lengths cnt_i * max_i; loads[i] = Eq. 2's padding branch,
+ * a * L_i^2 / cnt_i + b * L_i = cnt_i * (a * max_i^2 + b * max_i); *bound = the
+ * smallest feasible b. */
+int orc_balance_padded(const int32_t *lengths, int32_t n, int32_t D, uint64_t a, uint64_t b,
+                       int32_t *inst, int32_t *order, int32_t *seq_off, int64_t *tok_off,
+                       int32_t *cu_seqlens, uint64_t *loads, uint64_t *bound)
+{
+    if (n < 0 || D < 1) return -1;
+    for (int32_t s = 0; s < n; ++s)
+        if (lengths[s] < 0) return -5;
+    size_t nn = (size_t)(n > 0 ? n : 1);
+    int32_t *sorted = (int32_t *)malloc(nn * sizeof(int32_t));
+    int32_t *batch_of = (int32_t *)malloc(nn * sizeof(int32_t));
+    int rc = -1;
+    if (!sorted || !batch_of) goto done;
+    if ((rc = orc_sort_asc(lengths, n, sorted)) != 0) goto done;
+
+    uint64_t left = 0, right = 0;
+    if (n > 0) {
+        left = (uint64_t)lengths[sorted[0]];
+        right = (uint64_t)lengths[sorted[n - 1]] * ((uint64_t)(n / D) + 1);
+    }
+    while (left < right) {
+        uint64_t mid = (left + right) / 2;
+        if (orc_least_batches(lengths, sorted, n, mid, NULL) <= D) right = mid;
+        else left = mid + 1;
+    }
+    if (orc_least_batches(lengths, sorted, n, left, batch_of) > D) { rc = -5; goto done; }
+    if (bound) *bound = left;
+
+    for (int32_t i = 0; i <= D; ++i) seq_off[i] = 0;
+    for (int32_t t = 0; t < n; ++t) {
+        order[t] = sorted[t];
+        inst[sorted[t]] = batch_of[t];
+        seq_off[batch_of[t] + 1]++;
+    }
+    for (int32_t i = 0; i < D; ++i) seq_off[i + 1] += seq_off[i];
+    tok_off[0] = 0;
+    rc = 0;
+    for (int32_t i = 0; i < D; ++i) {
+        int32_t cnt = seq_off[i + 1] - seq_off[i];
+        uint64_t mx = cnt ? (uint64_t)lengths[order[seq_off[i + 1] - 1]] : 0;
+        int32_t *cu = cu_seqlens + seq_off[i] + i;
+        if ((uint64_t)cnt * mx > INT32_MAX) { rc = -5; goto done; }
+        for (int32_t j = 0; j <= cnt; ++j) cu[j] = (int32_t)((uint64_t)j * mx);
+        tok_off[i + 1] = tok_off[i] + (int64_t)((uint64_t)cnt * mx);
+        unsigned __int128 c = ((unsigned __int128)a * mx * mx + (unsigned __int128)b * mx) * (unsigned __int128)cnt;
+        if (c >> 63) { rc = -5; goto done; }
+        loads[i] = (uint64_t)c;
+    }
+done:
+    free(sorted); free(batch_of);
     return rc;
 }

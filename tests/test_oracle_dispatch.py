@@ -358,7 +358,10 @@ def test_pack_composed_special_cases():
     off[int(np.argmax(L))] = 1
     with pytest.raises(oracle.OracleError):
         oracle.pack_composed(tokens, out, L, off, None, asg)
-    # encoder assignment built for other lengths is refused
-    sub = np.maximum(L - 1, 0).astype(np.int32)
+    # an encoder segment shorter than the sub-sequence is refused (a longer one is a padded slot)
+    longer = (L + 1).astype(np.int32)
+    big = np.zeros((int(longer.sum()), H), dtype=tokens.dtype)
     with pytest.raises(oracle.OracleError):
-        oracle.pack_composed(tokens, out, sub, zero, asg, asg)
+        oracle.pack_composed(tokens, big, longer, zero, asg, oracle.balance(longer, w.D, w.a, w.b))
+    shorter = np.maximum(L - 1, 0).astype(np.int32)
+    oracle.pack_composed(tokens, big, shorter, zero, asg, asg)
