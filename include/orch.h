@@ -5,6 +5,9 @@
  *                         cost, Algorithm 1 (sort descending, give each
  *                         sequence to the least-loaded new batch) and the
  *                         padding-free batch layout of Sec. 7.
+ *   orch_balance_padded   Sec. 5.1, Algorithm 2: the policy for phases that batch with
+ *                         paddings (ascending sort, smallest feasible bound on
+ *                         count * longest, greedy contiguous cut).
  *   orch_pack             Sec. 5.2.1: the row movement of the All-to-All Batch
  *                         Communicator, performed on one device.
  *   orch_pack_composed    Sec. 5.3 (rearrangement composition): rows in an encoder
@@ -79,6 +82,28 @@ size_t orch_balance_workspace(int32_t n, int32_t D);
 int orch_balance(const int32_t *lengths, int32_t n, int32_t D, orch_phase phase,
                  orch_assignment out, void *ws, size_t ws_bytes, void *stream);
 
+/* Sec. 5.1, Algorithm 2 ("Post-Balancing Algorithm with Paddings"): for phases that batch
+ * with paddings (the auditory encoder, Sec. 7), where a batch of cnt sequences costs
+ * cnt * (its longest sequence) rows (Eq. 1, padding branch).  Sorts ascending by length
+ * (ties: ascending index), finds the smallest bound b for which the greedy cut of that list
+ * ("close the batch when (count + 1) * length > b") needs at most D batches, and returns the
+ * batches at that bound; batch k is instance k, trailing instances may be empty.
+ * The search range is [shortest length, longest length * (n / D + 1)].
+ * Outputs, in the same structure as orch_balance:
+ *   inst, seq_off   as there;  order = the ascending order
+ *   cu_seqlens      instance i's slice holds j * max_i for j = 0..cnt_i (max_i = its longest
+ *                   sequence): sequence j owns rows [j * max_i, (j + 1) * max_i) of the padded
+ *                   batch, of which the first length rows are data
+ *   tok_off         prefix sums of the padded batch lengths cnt_i * max_i
+ *   loads[i]        Eq. 2, padding branch: a * L_i^2 / cnt_i + b * L_i with L_i = cnt_i * max_i,
+ *                   i.e. cnt_i * (a * max_i^2 + b * max_i), exact u64
+ *   bound[1]        device, may be NULL: the bound found
+ * Rows are moved into that layout by orch_pack_composed (src = NULL for rows in original
+ * order); orch_pack refuses such an assignment.  Uses orch_balance_workspace(n, D) bytes.
+ * A padded batch of more than 2^31 - 1 rows or a cost >= 2^63 sets dev_status = ORCH_EDATA. */
+int orch_balance_padded(const int32_t *lengths, int32_t n, int32_t D, orch_phase phase,
+                        orch_assignment out, uint64_t *bound, void *ws, size_t ws_bytes, void *stream);
+
 /* Bytes of workspace orch_pack needs. */
 size_t orch_pack_workspace(int32_t n, int32_t D);
 
@@ -90,7 +115,8 @@ size_t orch_pack_workspace(int32_t n, int32_t D);
  *   tokens  [T, H] 16-bit words, row-major; T = sum of lengths
  *   packed  [packed_rows, H]; packed_rows must cover the rows of the chosen
  *           instances, else dev_status is set and nothing past it is written
- *   a       the assignment orch_balance produced for these lengths
+ *   a       the assignment orch_balance produced for these lengths (every segment exactly
+ *           as long as its sequence: a padded assignment sets dev_status = ORCH_EDATA)
  * Rows are copied bit for bit. */
 int orch_pack(const void *tokens, void *packed, const int32_t *lengths, int32_t n, int32_t D,
               int64_t T, int32_t H, int64_t packed_rows, orch_assignment a, int32_t inst_begin,
@@ -105,7 +131,8 @@ size_t orch_pack_composed_workspace(int32_t n);
  *   enc_rows [src_rows, H] 16-bit words: example s's sub_len[s] rows of this modality,
  *            laid out by `src` (the assignment orch_balance produced for sub_len on
  *            D_src instances: instance-major, rows of example s starting at
- *            src->tok_off[i] + cu_i[j]), or, when src is NULL, concatenated in
+ *            src->tok_off[i] + cu_i[j]; a segment may be longer than sub_len[s], as in a
+ *            padded batch from orch_balance_padded, and its first sub_len[s] rows are used), or, when src is NULL, concatenated in
  *            original example order (a modality that never left its instance)
  *   src      HOST pointer to a struct of device pointers, or NULL
  *   dst      the LLM-phase assignment over the interleaved lengths (D_dst instances)
@@ -116,8 +143,8 @@ size_t orch_pack_composed_workspace(int32_t n);
  * = enc_rows[start_src(s) + r, :] for s the j-th sequence of destination instance i,
  * 0 <= r < sub_len[s], inst_begin <= i < inst_end.  Rows of `packed` that belong to
  * other modalities are not touched.  Rows are copied bit for bit.
- * Inconsistent data (a segment outside either buffer, an encoder segment whose
- * length is not sub_len, a failed assignment on either side) sets dst.dev_status
+ * Inconsistent data (a segment outside either buffer, an encoder segment shorter
+ * than sub_len, a failed assignment on either side) sets dst.dev_status
  * to ORCH_EDATA and copies nothing. */
 int orch_pack_composed(const void *enc_rows, void *packed, const int32_t *sub_len,
                        const int32_t *sub_off, int32_t n, int32_t D_src, const orch_assignment *src,

@@ -5,6 +5,7 @@ from .binding import (  # noqa: F401
     OrchError,
     attn_variant,
     balance,
+    balance_padded,
     balance_workspace,
     library_path,
     load_library,

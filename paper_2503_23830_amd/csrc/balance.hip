@@ -2,7 +2,10 @@
 // longest-first greedy onto the least-loaded instance) and the packed layout.
 // (OrchMLLM Sec. 5.1; layout per Sec. 7 "batched along the sequence length".)
 //
-// Three launches on the caller's stream:
+// orch_balance_padded: Algorithm 2 (the same sort, ascending, then the bound search
+// and the padded layout in one kernel; see padded_split_kernel).
+//
+// orch_balance, three launches on the caller's stream:
 //   cost_sort_kernel   one 1024-thread workgroup: cost keys, then a stable LSD
 //                      radix sort (8-bit digits, only as many passes as the
 //                      largest key needs) of (~cost, index) pairs
@@ -60,9 +63,9 @@ __device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t x, int m)
 // cost + stable radix sort, one workgroup
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kSortThreads) void cost_sort_kernel(
-    const int32_t *__restrict__ lengths, int32_t n, uint64_t a, uint64_t b, uint64_t *csorted,
-    uint64_t *keyA, uint64_t *keyB, uint32_t *idxA, uint32_t *idxB, int32_t *sorted,
-    int32_t *flags, int32_t *dev_status)
+    const int32_t *__restrict__ lengths, int32_t n, uint64_t a, uint64_t b, int ascending,
+    uint64_t *csorted, uint64_t *keyA, uint64_t *keyB, uint32_t *idxA, uint32_t *idxB,
+    int32_t *sorted, int32_t *flags, int32_t *dev_status)
 {
     __shared__ uint32_t hist[kSortWaves][kRadix];
     __shared__ uint32_t dig_base[kRadix];
@@ -87,7 +90,7 @@ __global__ __launch_bounds__(kSortThreads) void cost_sort_kernel(
             bool bad = __umul64hi(a, l2) != 0 || __umul64hi(b, l) != 0 || c < t1 || (c >> 63);
             if (bad) { err = 1; c = 0; }
         }
-        keyA[i] = ~c;  // ascending on ~c == descending on c
+        keyA[i] = ascending ? c : ~c;  // ascending on ~c == descending on c
         idxA[i] = (uint32_t)i;
         my_or |= c;
         my_sum += c;
@@ -193,7 +196,7 @@ __global__ __launch_bounds__(kSortThreads) void cost_sort_kernel(
     }
     for (int64_t i = tid; i < n; i += kSortThreads) {
         sorted[i] = (int32_t)isrc[i];
-        csorted[i] = ~ksrc[i];
+        csorted[i] = ascending ? ksrc[i] : ~ksrc[i];
     }
 }
 
@@ -703,6 +706,177 @@ __global__ __launch_bounds__(kGreedyThreads) void greedy_lds_kernel(ORCH_GREEDY_
     if (wave == 0) finish_layout(s_cnt, s_tok, D, seq_off, tok_off, cu_seqlens, dev_status);
 }
 
+// ---------------------------------------------------------------------------
+// Algorithm 2 (Sec. 5.1, "Post-Balancing Algorithm with Paddings")
+// ---------------------------------------------------------------------------
+// The sequences arrive sorted ascending by length.  For a bound b on the padded
+// batch length (count * longest), GetLeastBatches(b) cuts the list greedily: a batch
+// that starts at position p always takes p and then extends while
+// (q - p + 1) * len[q] <= b.  That product never decreases with q, so the end of a
+// batch is found by bisection instead of a walk, and one evaluation of the bound
+// costs at most (D + 1) bisections.  The number of batches never grows with b, so
+// the smallest b that needs at most D batches is well defined; the listing finds it
+// by binary search, here 1024 candidate bounds are tried per round (one per thread),
+// which reaches the same value in log_1025 instead of log_2 of the range rounds.
+constexpr int kPadThreads = 1024;
+constexpr int kPadLdsKeys = 32768;  // sorted lengths kept in LDS up to this n
+
+template <bool LDS>
+struct SortedLen {
+    const uint32_t *lds;
+    const uint64_t *glob;
+    __device__ __forceinline__ uint64_t operator()(int t) const { return LDS ? (uint64_t)lds[t] : glob[t]; }
+};
+
+// last position of the batch that starts at p under bound b
+template <bool LDS>
+__device__ __forceinline__ int batch_end(const SortedLen<LDS> &len, int p, int n, uint64_t b)
+{
+    int lo = p, hi = n - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if ((uint64_t)(mid - p + 1) * len(mid) <= b) lo = mid;
+        else hi = mid - 1;
+    }
+    return lo;
+}
+
+template <bool LDS>
+__device__ __forceinline__ bool at_most_D_batches(const SortedLen<LDS> &len, int n, int D, uint64_t b)
+{
+    int p = 0, cnt = 0;
+    while (p < n) {
+        if (++cnt > D) return false;
+        p = batch_end(len, p, n, b) + 1;
+    }
+    return true;
+}
+
+template <bool LDS>
+__global__ __launch_bounds__(kPadThreads) void padded_split_kernel(
+    const uint64_t *__restrict__ csorted, const int32_t *__restrict__ sorted, int32_t n, int32_t D,
+    uint64_t a, uint64_t b, int32_t *inst, int32_t *order, int32_t *seq_off, int64_t *tok_off,
+    int32_t *cu_seqlens, uint64_t *loads, unsigned long long *bound_out, int32_t *dev_status)
+{
+    __shared__ uint32_t s_len[LDS ? kPadLdsKeys : 1];
+    __shared__ int32_t s_bstart[kMaxInstances + 1];  // first sorted position of batch i; n past the last
+    __shared__ unsigned long long s_scan[kPadThreads];
+    __shared__ unsigned long long s_left, s_right;
+    __shared__ int s_first, s_err;
+
+    const int tid = threadIdx.x;
+    if (LDS)
+        for (int t = tid; t < n; t += kPadThreads) s_len[t] = (uint32_t)csorted[t];
+    const SortedLen<LDS> len{s_len, csorted};
+    if (tid == 0) {
+        s_err = 0;
+        // as printed: left = the shortest length; right = longest * (n / d + 1), which every
+        // batch of floor(n/d) + 1 sequences satisfies, so it needs at most d batches
+        s_left = n > 0 ? csorted[0] : 0;
+        s_right = n > 0 ? csorted[n - 1] * ((uint64_t)(n / D) + 1) : 0;
+    }
+    __syncthreads();
+
+    for (;;) {
+        const uint64_t left = s_left, right = s_right;
+        if (left >= right) break;
+        const uint64_t span = right - left;
+        const bool dense = span <= (uint64_t)kPadThreads;  // every remaining bound gets a thread
+        const uint64_t step = span / (kPadThreads + 1);
+        const uint64_t cand = dense ? left + tid : left + step * (uint64_t)(tid + 1);
+        const bool valid = !dense || (uint64_t)tid < span;
+        if (tid == 0) s_first = kPadThreads;
+        __syncthreads();
+        if (valid && at_most_D_batches(len, n, D, cand)) atomicMin(&s_first, tid);
+        __syncthreads();
+        if (tid == 0) {
+            const int t = s_first;
+            if (dense) {
+                s_left = s_right = t < kPadThreads ? left + t : right;
+            } else if (t < kPadThreads) {
+                s_right = left + step * (uint64_t)(t + 1);
+                if (t > 0) s_left = left + step * (uint64_t)t + 1;
+            } else {
+                s_left = left + step * (uint64_t)kPadThreads + 1;
+            }
+        }
+        __syncthreads();
+    }
+    const uint64_t bound = s_left;
+
+    // the batches at the final bound
+    if (tid == 0) {
+        int p = 0, k = 0;
+        while (p < n && k < D) {
+            s_bstart[k++] = p;
+            p = batch_end(len, p, n, bound) + 1;
+        }
+        if (p < n) s_err = 1;  // cannot happen for a feasible bound; keeps every index in range
+        for (; k <= D; ++k) s_bstart[k] = n;
+        if (bound_out) bound_out[0] = bound;
+    }
+    __syncthreads();
+
+    // per instance: count, longest, padded rows, Eq. 2 padding branch
+    // a * L^2 / cnt + b * L with L = cnt * max  ==  cnt * (a * max^2 + b * max)
+    const int per = (D + kPadThreads - 1) / kPadThreads;
+    const int i0 = min(D, per * tid), i1 = min(D, i0 + per);
+    unsigned long long rows_sum = 0;
+    int err = 0;
+    for (int i = i0; i < i1; ++i) {
+        const int c = s_bstart[i + 1] - s_bstart[i];
+        const uint64_t mx = c ? len(s_bstart[i + 1] - 1) : 0;
+        const uint64_t rows = (uint64_t)c * mx;
+        if (rows > 0x7fffffffull) err = 1;
+        const uint64_t mx2 = mx * mx, t1 = a * mx2, t2 = b * mx, per_seq = t1 + t2;
+        const uint64_t load = per_seq * (uint64_t)c;
+        if (__umul64hi(a, mx2) != 0 || __umul64hi(b, mx) != 0 || per_seq < t1 ||
+            __umul64hi(per_seq, (uint64_t)c) != 0 || (load >> 63))
+            err = 1;
+        loads[i] = load;
+        seq_off[i] = s_bstart[i];
+        cu_seqlens[s_bstart[i + 1] + i] = (int32_t)rows;  // the slice's last entry: cnt * max (0 when empty)
+        rows_sum += rows;
+    }
+    s_scan[tid] = rows_sum;
+    __syncthreads();
+    for (int m = 1; m < kPadThreads; m <<= 1) {
+        const unsigned long long o = tid >= m ? s_scan[tid - m] : 0;
+        __syncthreads();
+        s_scan[tid] += o;
+        __syncthreads();
+    }
+    unsigned long long run = s_scan[tid] - rows_sum;
+    for (int i = i0; i < i1; ++i) {
+        tok_off[i] = (int64_t)run;
+        const int c = s_bstart[i + 1] - s_bstart[i];
+        run += (uint64_t)c * (c ? len(s_bstart[i + 1] - 1) : 0);
+    }
+    if (tid == kPadThreads - 1) {
+        tok_off[D] = (int64_t)s_scan[tid];
+        seq_off[D] = n;
+    }
+    if (err) atomicOr(&s_err, 1);
+
+    // per sorted position: its batch (bisection over the batch starts), slot j * max
+    for (int t = tid; t < n; t += kPadThreads) {
+        int lo = 0, hi = D - 1;
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (s_bstart[mid] <= t) lo = mid;
+            else hi = mid - 1;
+        }
+        const int i = lo;
+        const int32_t s = sorted[t];
+        const uint64_t mx = len(s_bstart[i + 1] - 1);
+        inst[s] = i;
+        order[t] = s;
+        cu_seqlens[t + i] = (int32_t)((uint64_t)(t - s_bstart[i]) * mx);
+    }
+    __syncthreads();
+    if (tid == 0 && s_err) dev_status[0] = (int32_t)ORCH_EDATA;
+}
+
 __global__ void layout_kernel(const int32_t *__restrict__ inst, const int32_t *__restrict__ rank,
                               const int32_t *__restrict__ start, const int32_t *__restrict__ seq_off,
                               int32_t n, int32_t *order, int32_t *cu_seqlens)
@@ -732,7 +906,7 @@ int launch_balance(const int32_t *lengths, int32_t n, int32_t D, orch_phase phas
     if (ws_bytes < need) ORCH_FAIL(ORCH_ENOSPC, "orch_balance: workspace %zu < %zu bytes", ws_bytes, need);
 
     hipLaunchKernelGGL(cost_sort_kernel, dim3(1), dim3(kSortThreads), 0, stream, lengths, n, phase.a,
-                       phase.b, w.csorted, w.keyA, w.keyB, w.idxA, w.idxB, w.sorted, w.flags, out.dev_status);
+                       phase.b, 0, w.csorted, w.keyA, w.keyB, w.idxA, w.idxB, w.sorted, w.flags, out.dev_status);
 #define ORCH_GREEDY_ARGS                                                                        \
     w.csorted, w.sorted, lengths, n, D, w.ipos, out.inst, w.rank, w.start, out.loads,           \
         out.seq_off, out.tok_off, out.cu_seqlens, w.flags, out.dev_status
@@ -754,6 +928,29 @@ int launch_balance(const int32_t *lengths, int32_t n, int32_t D, orch_phase phas
     if (n > 0)
         hipLaunchKernelGGL(layout_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, out.inst, w.rank,
                            w.start, out.seq_off, n, out.order, out.cu_seqlens);
+    ORCH_HIP_CHECK(hipGetLastError());
+    return ORCH_OK;
+}
+
+int launch_balance_padded(const int32_t *lengths, int32_t n, int32_t D, orch_phase phase,
+                          orch_assignment out, uint64_t *bound, void *ws, size_t ws_bytes,
+                          hipStream_t stream)
+{
+    BalanceWs w;
+    size_t need = carve(w, ws, n);
+    if (ws_bytes < need) ORCH_FAIL(ORCH_ENOSPC, "orch_balance_padded: workspace %zu < %zu bytes", ws_bytes, need);
+    // Algorithm 2 sorts by length: key = 0 * l^2 + 1 * l, ascending, ties by index
+    hipLaunchKernelGGL(cost_sort_kernel, dim3(1), dim3(kSortThreads), 0, stream, lengths, n, (uint64_t)0,
+                       (uint64_t)1, 1, w.csorted, w.keyA, w.keyB, w.idxA, w.idxB, w.sorted, w.flags,
+                       out.dev_status);
+    if (n <= kPadLdsKeys)
+        hipLaunchKernelGGL(padded_split_kernel<true>, dim3(1), dim3(kPadThreads), 0, stream, w.csorted,
+                           w.sorted, n, D, phase.a, phase.b, out.inst, out.order, out.seq_off, out.tok_off,
+                           out.cu_seqlens, out.loads, (unsigned long long *)bound, out.dev_status);
+    else
+        hipLaunchKernelGGL(padded_split_kernel<false>, dim3(1), dim3(kPadThreads), 0, stream, w.csorted,
+                           w.sorted, n, D, phase.a, phase.b, out.inst, out.order, out.seq_off, out.tok_off,
+                           out.cu_seqlens, out.loads, (unsigned long long *)bound, out.dev_status);
     ORCH_HIP_CHECK(hipGetLastError());
     return ORCH_OK;
 }

@@ -161,9 +161,21 @@ def test_inconsistent_data_is_refused_on_device(gpu_device):
     # destination too small / source shorter than sub_len says
     assert refused(tokens, buf[: T - 1], Ld, zero, None, asg)
     assert refused(tokens[: T - 1], buf, Ld, zero, None, asg)
-    # an encoder assignment made for other lengths
-    sub = torch.clamp(Ld - 1, min=0)
-    assert refused(tokens, buf, sub, zero, asg, asg)
+    # an encoder segment shorter than the sub-sequence (a longer one is a padded slot and is fine)
+    longer = (L + 1).astype(np.int32)
+    Lg, dst_longer = run_balance(longer, 4, 1, 1, dev)
+    big = torch.full((int(longer.sum()), H), GUARD, dtype=torch.int16, device=dev)
+    orch.pack_composed(tokens, big, Lg, zero, asg, dst_longer)
+    torch.cuda.synchronize()
+    assert int(dst_longer.dev_status.item()) == -5 and bool((big == GUARD).all())
+    shorter = np.maximum(L - 1, 0).astype(np.int32)
+    orch.pack_composed(tokens, big, to_dev(shorter, dev), zero, asg, asg)
+    torch.cuda.synchronize()
+    assert int(asg.dev_status.item()) == 0
+    want = np.full((int(longer.sum()), H), GUARD, dtype=np.uint16)
+    ref = oracle.balance(L, 4, 1, 1)
+    oracle.pack_composed(wl.token_tag_np(np.arange(T), H), want, shorter, np.zeros(len(L), np.int32), ref, ref)
+    assert np.array_equal(bits(big), want)
     # an encoder assignment whose balance failed
     _, easg = run_balance(L, 3, 1, 1, dev)
     easg.dev_status.fill_(-5)
