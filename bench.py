@@ -8,7 +8,8 @@ Inputs are resident in HBM before the timed region.  Default workload: C4 (LLM
 phase with modality-composition incoherence), the configuration the targets are
 stated on.  After the timed steps the rearrangement composition (orch_pack_composed,
 three modality buffers into the same packed batch) is timed and checked on its own and
-reported under "composed_pack"; it is not part of `value` or `ms_per_step`.
+reported under "composed_pack", and Algorithm 2 (orch_balance_padded) under "balance_padded";
+neither is part of `value` or `ms_per_step`.
 Prints ONE JSON line.
 """
 from __future__ import annotations
@@ -254,6 +255,42 @@ def main():
                     "encoder_load_max_over_mean": mci,
                     "note": "three orch_pack_composed calls (text, image, audio) fill the packed LLM batch once; "
                             "reset-then-rearrange would move every row twice"}
+    # ---------------- Algorithm 2 (batching with paddings), outside the timed step ------------
+    def padded_leg(Lx, a_, b_):
+        Lx = np.ascontiguousarray(Lx, dtype=np.int32)
+        Lx_d = torch.from_numpy(Lx).to(dev)
+        pasg = orch.Assignment.empty(len(Lx), D, dev)
+        bound_d = torch.zeros(1, dtype=torch.int64, device=dev)
+        for _ in range(2):
+            orch.balance_padded(Lx_d, D, a_, b_, out=pasg, bound=bound_d, ws=ws_bal)
+        pev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        pev[0].record()
+        for _ in range(args.steps):
+            orch.balance_padded(Lx_d, D, a_, b_, out=pasg, bound=bound_d, ws=ws_bal)
+        pev[1].record()
+        torch.cuda.synchronize()
+        tt = time.perf_counter()
+        pref, pbound = oracle.balance_padded(Lx, D, a_, b_)
+        cpu_ms = (time.perf_counter() - tt) * 1e3
+        pok = int(pasg.dev_status.item()) == 0 and int(bound_d.item()) == pbound
+        for got, want in ((pasg.inst, pref.inst), (pasg.order, pref.order), (pasg.seq_off, pref.seq_off),
+                          (pasg.tok_off, pref.tok_off), (pasg.cu_seqlens, pref.cu_seqlens)):
+            pok &= np.array_equal(got.cpu().numpy()[: len(want)], want)
+        pok &= np.array_equal(pasg.loads.cpu().numpy().view(np.uint64), pref.loads)
+        per = max(1, len(Lx) // D)
+        rows_before = np.array([len(Lx[i * per: (i + 1) * per]) * int(Lx[i * per: (i + 1) * per].max(initial=0))
+                                for i in range(D)], dtype=np.float64)
+        rows_after = np.diff(pref.tok_off).astype(np.float64)
+        return {"ms": pev[0].elapsed_time(pev[1]) / args.steps, "cpu_oracle_ms": cpu_ms, "n": len(Lx), "bound": pbound,
+                "real_rows": int(Lx.sum(dtype=np.int64)),
+                "padded_rows": {"before": float(rows_before.sum()), "after": float(rows_after.sum())},
+                "largest_padded_batch": {"before": float(rows_before.max()), "after": float(rows_after.max())},
+                "verified": bool(pok)}
+
+    padded = {"lengths": padded_leg(L, w.a, w.b)}
+    if composed is not None:
+        padded["audio_part"] = padded_leg(split[:, 2], *enc_cost[2])
+    ok &= all(v["verified"] for v in padded.values())
     before = oracle.load_ratio(L, (np.arange(n, dtype=np.int64) * D) // n, D, w.a, w.b)
     after = float(loads.max() / loads.mean())
 
@@ -346,6 +383,7 @@ def main():
                                                 "tflops": flops_before / (attn_before_ms * 1e-3) / 1e12}},
         "pack": {"GBps": pack_gbps, "frac_hbm_peak": pack_gbps / HBM_PEAK_GBPS, "ms": pack_ms, "bytes": pack_bytes},
         "composed_pack": composed,
+        "balance_padded": padded,
         "dispatch": {"ms": bal_ms, "calls_per_step": 1 if whole else 2},
         "load_max_over_mean": {"before": before, "after": after},
         "verified": bool(ok), "attn_err": {"max_abs": float(err.max()), "mean_abs": float(err.mean())},

@@ -728,11 +728,27 @@ struct SortedLen {
     __device__ __forceinline__ uint64_t operator()(int t) const { return LDS ? (uint64_t)lds[t] : glob[t]; }
 };
 
-// last position of the batch that starts at p under bound b
+// Last position of the batch that starts at p under bound b.  A batch never holds more
+// sequences than the one before it (if it held k + 1, then (k + 1) * len[p + k] <= b, but the
+// previous batch of k stopped because (k + 1) * (a length no longer than that) > b), so the
+// answer lies in [p, p + kprev - 1] and usually at its top: probe there first, then gallop
+// down, then bisect what is left.  kprev = n for the first batch (plain bisection).
 template <bool LDS>
-__device__ __forceinline__ int batch_end(const SortedLen<LDS> &len, int p, int n, uint64_t b)
+__device__ __forceinline__ int batch_end(const SortedLen<LDS> &len, int p, int n, uint64_t b, int kprev)
 {
     int lo = p, hi = n - 1;
+    if (kprev < n) {
+        hi = min(hi, p + kprev - 1);
+        if (hi == p || (uint64_t)(hi - p + 1) * len(hi) <= b) return hi;
+        int rej = hi;  // rejected
+        for (int step = 1;; step <<= 1) {
+            const int q = rej - step;
+            if (q <= p) break;
+            if ((uint64_t)(q - p + 1) * len(q) <= b) { lo = q; break; }
+            rej = q;
+        }
+        hi = rej - 1;
+    }
     while (lo < hi) {
         const int mid = (lo + hi + 1) >> 1;
         if ((uint64_t)(mid - p + 1) * len(mid) <= b) lo = mid;
@@ -744,10 +760,12 @@ __device__ __forceinline__ int batch_end(const SortedLen<LDS> &len, int p, int n
 template <bool LDS>
 __device__ __forceinline__ bool at_most_D_batches(const SortedLen<LDS> &len, int n, int D, uint64_t b)
 {
-    int p = 0, cnt = 0;
+    int p = 0, cnt = 0, k = n;
     while (p < n) {
         if (++cnt > D) return false;
-        p = batch_end(len, p, n, b) + 1;
+        const int e = batch_end(len, p, n, b, k);
+        k = e - p + 1;
+        p = e + 1;
     }
     return true;
 }
@@ -806,10 +824,12 @@ __global__ __launch_bounds__(kPadThreads) void padded_split_kernel(
 
     // the batches at the final bound
     if (tid == 0) {
-        int p = 0, k = 0;
+        int p = 0, k = 0, cnt = n;
         while (p < n && k < D) {
             s_bstart[k++] = p;
-            p = batch_end(len, p, n, bound) + 1;
+            const int e = batch_end(len, p, n, bound, cnt);
+            cnt = e - p + 1;
+            p = e + 1;
         }
         if (p < n) s_err = 1;  // cannot happen for a feasible bound; keeps every index in range
         for (; k <= D; ++k) s_bstart[k] = n;

@@ -250,6 +250,37 @@ int main(int argc, char **argv)
                (long long)rows_m[0], (long long)rows_m[1], (long long)rows_m[2], tc, pbytes / tc / 1e6, status);
     }
 
+    // Algorithm 2 (Sec. 5.1, batching with paddings) on the same lengths
+    {
+        orch_assignment pa;
+        CK(hipMalloc(&pa.inst, 4 * std::max(n, 1)));
+        CK(hipMalloc(&pa.order, 4 * std::max(n, 1)));
+        CK(hipMalloc(&pa.seq_off, 4 * (D + 1)));
+        CK(hipMalloc(&pa.tok_off, 8 * (D + 1)));
+        CK(hipMalloc(&pa.cu_seqlens, 4 * (n + D)));
+        CK(hipMalloc(&pa.loads, 8 * D));
+        CK(hipMalloc(&pa.dev_status, 4));
+        uint64_t *dbound;
+        CK(hipMalloc(&dbound, 8));
+        double tpad = 0;
+        for (int s = 0; s < steps + 1; ++s) {
+            CK(hipEventRecord(e0, st));
+            OK(orch_balance_padded(dL, n, D, orch_phase{a, b}, pa, dbound, ws_b, wsb, st));
+            CK(hipEventRecord(e1, st));
+            CK(hipStreamSynchronize(st));
+            float ms;
+            if (s > 0) { CK(hipEventElapsedTime(&ms, e0, e1)); tpad += ms; }
+        }
+        uint64_t hb;
+        int64_t prows;
+        int32_t pst;
+        CK(hipMemcpy(&hb, dbound, 8, hipMemcpyDeviceToHost));
+        CK(hipMemcpy(&prows, pa.tok_off + D, 8, hipMemcpyDeviceToHost));
+        CK(hipMemcpy(&pst, pa.dev_status, 4, hipMemcpyDeviceToHost));
+        printf("balance_padded %.3f ms, bound %llu, padded rows %lld (real %lld), dev_status=%d\n", tpad / steps,
+               (unsigned long long)hb, (long long)prows, (long long)T, pst);
+    }
+
     // calibration: 1 GiB read + 1 GiB written by a plain copy
     const size_t cbytes = (size_t)1 << 30;
     uint4 *ca, *cb;
