@@ -41,7 +41,7 @@ def lib():
     if _lib is None:
         _lib = C.CDLL(build())
         for name in ("orc_cost", "orc_sort_desc", "orc_greedy", "orc_balance", "orc_pack",
-                     "orc_row_map", "orc_pack_composed", "orc_sort_asc", "orc_balance_padded", "orc_attn_fwd",
+                     "orc_row_map", "orc_pack_composed", "orc_sort_asc", "orc_balance_padded", "orc_balance_tolerance", "orc_attn_fwd",
                      "orc_attn_rows"):
             getattr(_lib, name).restype = C.c_int
         _lib.orc_least_batches.restype = C.c_int64
@@ -140,6 +140,22 @@ def balance_padded(lengths, D: int, a: int, b: int):
                                     _p(out.inst), _p(out.order), _p(out.seq_off), _p(out.tok_off),
                                     _p(out.cu_seqlens), _p(out.loads), C.byref(bound)))
     return out, int(bound.value)
+
+
+def balance_tolerance(lengths, D: int, v: int, a: int, b: int) -> Assignment:
+    """The appendix's third algorithm: longest-first greedy whose "lightest batch" is, among the
+    batches within the tolerance interval v of the smallest length sum, the one with the
+    smallest sum of squared lengths."""
+    L = _i32(lengths)
+    n = len(L)
+    if D < 1:
+        raise OracleError(-1)
+    out = Assignment(np.empty(n, np.int32), np.empty(n, np.int32), np.empty(D + 1, np.int32),
+                     np.empty(D + 1, np.int64), np.empty(n + D, np.int32), np.empty(D, np.uint64))
+    _check(lib().orc_balance_tolerance(_p(L), C.c_int32(n), C.c_int32(D), C.c_uint64(v), C.c_uint64(a),
+                                       C.c_uint64(b), _p(out.inst), _p(out.order), _p(out.seq_off),
+                                       _p(out.tok_off), _p(out.cu_seqlens), _p(out.loads)))
+    return out
 
 
 def pack(tokens: np.ndarray, lengths, asg: Assignment, inst_begin: int = 0, inst_end: int | None = None):

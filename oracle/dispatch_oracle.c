@@ -393,3 +393,81 @@ done:
     free(sorted); free(batch_of);
     return rc;
 }
+
+/* ---------------------------------------------------------------------------
+ * "Post-Balancing Algorithm 3rd" (Appendix A): Algorithm 1 with the priority
+ * queue ordered by CMP(a, b): when two batches' length sums differ by less than
+ * the tolerance interval v, the one with the smaller sum of squared lengths comes
+ * first, otherwise the one with the smaller length sum.  It serves the objective
+ * max_i (L_i + lambda * sum_j l_ij^2) when beta << alpha does not hold.
+ *
+ * CMP is not a strict weak order (a ~ b and b ~ c within v do not give a ~ c), so
+ * "the top of a priority queue sorted by CMP" is not defined by the listing.
+ * Reading used here, two passes over the d batches:
+ *   1. m = the smallest length sum;
+ *   2. among the batches whose length sum is less than m + max(v, 1), take the
+ *      one with the smallest sum of squares; ties go to the lowest batch index.
+ * The chosen batch is never beaten under CMP by any batch inside that window, and
+ * every batch outside the window has a length sum at least v above the minimum.
+ * v <= 1 makes the window "length sum == m": Algorithm 1 on lengths, with the sum
+ * of squares breaking ties; a v above the total length makes it the greedy on the
+ * sum of squares alone.
+ * Sorting is by length, descending, ties by ascending index (as Algorithm 1).
+ * loads[i] = a * sum_sq_i + b * sum_i (Eq. 2, no-padding branch); the layout is
+ * that of orc_balance. */
+int orc_balance_tolerance(const int32_t *lengths, int32_t n, int32_t D, uint64_t v, uint64_t a,
+                          uint64_t b, int32_t *inst, int32_t *order, int32_t *seq_off,
+                          int64_t *tok_off, int32_t *cu_seqlens, uint64_t *loads)
+{
+    if (n < 0 || D < 1) return -1;
+    size_t nn = (size_t)(n > 0 ? n : 1);
+    uint64_t *key = (uint64_t *)malloc(nn * sizeof(uint64_t));
+    int32_t *sorted = (int32_t *)malloc(nn * sizeof(int32_t));
+    int32_t *rank = (int32_t *)malloc(nn * sizeof(int32_t));
+    int32_t *counts = (int32_t *)calloc((size_t)D, sizeof(int32_t));
+    uint64_t *sum = (uint64_t *)calloc((size_t)D, sizeof(uint64_t));
+    uint64_t *sq = (uint64_t *)calloc((size_t)D, sizeof(uint64_t));
+    int rc = -1;
+    if (!key || !sorted || !rank || !counts || !sum || !sq) goto done;
+    if ((rc = orc_cost(lengths, n, 0, 1, key)) != 0) goto done;      /* key = length */
+    if ((rc = orc_sort_desc(key, n, sorted)) != 0) goto done;
+    const uint64_t window = v > 1 ? v : 1;
+    for (int32_t t = 0; t < n; ++t) {
+        int32_t s = sorted[t];
+        uint64_t m = sum[0];
+        for (int32_t i = 1; i < D; ++i)
+            if (sum[i] < m) m = sum[i];
+        int32_t best = -1;
+        for (int32_t i = 0; i < D; ++i)
+            if (sum[i] - m < window && (best < 0 || sq[i] < sq[best])) best = i;
+        uint64_t l = (uint64_t)lengths[s];
+        unsigned __int128 nsq = (unsigned __int128)sq[best] + (unsigned __int128)l * l;
+        if (nsq >> 63) { rc = -5; goto done; }
+        inst[s] = best;
+        rank[s] = counts[best]++;
+        sum[best] += l;
+        sq[best] = (uint64_t)nsq;
+    }
+    seq_off[0] = 0;
+    for (int32_t i = 0; i < D; ++i) seq_off[i + 1] = seq_off[i] + counts[i];
+    for (int32_t s = 0; s < n; ++s) order[seq_off[inst[s]] + rank[s]] = s;
+    tok_off[0] = 0;
+    rc = 0;
+    for (int32_t i = 0; i < D; ++i) {
+        int32_t *cu = cu_seqlens + seq_off[i] + i;
+        int64_t run = 0;
+        cu[0] = 0;
+        for (int32_t j = 0; j < counts[i]; ++j) {
+            run += lengths[order[seq_off[i] + j]];
+            if (run > INT32_MAX) { rc = -5; goto done; }
+            cu[j + 1] = (int32_t)run;
+        }
+        tok_off[i + 1] = tok_off[i] + run;
+        unsigned __int128 c = (unsigned __int128)a * sq[i] + (unsigned __int128)b * sum[i];
+        if (c >> 63) { rc = -5; goto done; }
+        loads[i] = (uint64_t)c;
+    }
+done:
+    free(key); free(sorted); free(rank); free(counts); free(sum); free(sq);
+    return rc;
+}
