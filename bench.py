@@ -8,8 +8,8 @@ Inputs are resident in HBM before the timed region.  Default workload: C4 (LLM
 phase with modality-composition incoherence), the configuration the targets are
 stated on.  After the timed steps the rearrangement composition (orch_pack_composed,
 three modality buffers into the same packed batch) is timed and checked on its own and
-reported under "composed_pack", and Algorithm 2 (orch_balance_padded) under "balance_padded";
-neither is part of `value` or `ms_per_step`.
+reported under "composed_pack", and Algorithm 2 (orch_balance_padded) under "balance_padded", the appendix's third algorithm
+(orch_balance_tolerance) under "balance_tolerance"; none of them is part of `value` or `ms_per_step`.
 Prints ONE JSON line.
 """
 from __future__ import annotations
@@ -291,6 +291,37 @@ def main():
     if composed is not None:
         padded["audio_part"] = padded_leg(split[:, 2], *enc_cost[2])
     ok &= all(v["verified"] for v in padded.values())
+    # ---------------- the appendix's third algorithm (tolerance comparator), outside the step ----
+    tolerance = None
+    if D <= 1024:
+        v_tol = 2048
+        tasg = orch.Assignment.empty(n, D, dev)
+        for _ in range(2):
+            orch.balance_tolerance(Ld, D, v_tol, w.a, w.b, out=tasg, ws=ws_bal)
+        tev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        tev[0].record()
+        for _ in range(args.steps):
+            orch.balance_tolerance(Ld, D, v_tol, w.a, w.b, out=tasg, ws=ws_bal)
+        tev[1].record()
+        torch.cuda.synchronize()
+        tt = time.perf_counter()
+        tref = oracle.balance_tolerance(L, D, v_tol, w.a, w.b)
+        t_cpu = (time.perf_counter() - tt) * 1e3
+        tok = int(tasg.dev_status.item()) == 0
+        for got, want in ((tasg.inst, tref.inst), (tasg.order, tref.order), (tasg.seq_off, tref.seq_off),
+                          (tasg.tok_off, tref.tok_off), (tasg.cu_seqlens, tref.cu_seqlens)):
+            tok &= np.array_equal(got.cpu().numpy()[: len(want)], want)
+        tok &= np.array_equal(tasg.loads.cpu().numpy().view(np.uint64), tref.loads)
+
+        def spreads(a_):
+            sums = np.diff(a_.tok_off).astype(np.float64)
+            sq = np.bincount(a_.inst, weights=L.astype(np.float64) ** 2, minlength=D)
+            return {"tokens_max_over_mean": float(sums.max() / sums.mean()),
+                    "squares_max_over_mean": float(sq.max() / sq.mean())}
+
+        tolerance = {"ms": tev[0].elapsed_time(tev[1]) / args.steps, "cpu_oracle_ms": t_cpu, "v": v_tol,
+                     "spread": spreads(tref), "spread_algorithm_1_cost": spreads(ref), "verified": bool(tok)}
+        ok &= tok
     before = oracle.load_ratio(L, (np.arange(n, dtype=np.int64) * D) // n, D, w.a, w.b)
     after = float(loads.max() / loads.mean())
 
@@ -384,6 +415,7 @@ def main():
         "pack": {"GBps": pack_gbps, "frac_hbm_peak": pack_gbps / HBM_PEAK_GBPS, "ms": pack_ms, "bytes": pack_bytes},
         "composed_pack": composed,
         "balance_padded": padded,
+        "balance_tolerance": tolerance,
         "dispatch": {"ms": bal_ms, "calls_per_step": 1 if whole else 2},
         "load_max_over_mean": {"before": before, "after": after},
         "verified": bool(ok), "attn_err": {"max_abs": float(err.max()), "mean_abs": float(err.mean())},

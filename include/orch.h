@@ -8,6 +8,8 @@
  *   orch_balance_padded   Sec. 5.1, Algorithm 2: the policy for phases that batch with
  *                         paddings (ascending sort, smallest feasible bound on
  *                         count * longest, greedy contiguous cut).
+ *   orch_balance_tolerance  Appendix A, third algorithm: longest-first greedy ordered by
+ *                         length sums within a tolerance interval, else by squares.
  *   orch_pack             Sec. 5.2.1: the row movement of the All-to-All Batch
  *                         Communicator, performed on one device.
  *   orch_pack_composed    Sec. 5.3 (rearrangement composition): rows in an encoder
@@ -103,6 +105,20 @@ int orch_balance(const int32_t *lengths, int32_t n, int32_t D, orch_phase phase,
  * A padded batch of more than 2^31 - 1 rows or a cost >= 2^63 sets dev_status = ORCH_EDATA. */
 int orch_balance_padded(const int32_t *lengths, int32_t n, int32_t D, orch_phase phase,
                         orch_assignment out, uint64_t *bound, void *ws, size_t ws_bytes, void *stream);
+
+/* Appendix A, "Post-Balancing Algorithm 3rd": Algorithm 1 for models where the quadratic
+ * term is not negligible (objective max_i L_i + lambda * sum_j l_ij^2).  Sequences are taken
+ * longest first (ties: ascending index); each goes to the batch that the listing's comparator
+ * CMP puts first.  CMP is not a strict weak order, so top() is fixed here by two passes:
+ * m = the smallest length sum; among the batches whose length sum is below m + max(v, 1) the
+ * one with the smallest sum of squared lengths receives the sequence, the lowest index on
+ * ties.  v <= 1 is Algorithm 1 on lengths with squares as tie-break.
+ *   v      tolerance interval, in tokens
+ *   phase  only for loads[i] = a * (sum of squares) + b * (length sum)  (Eq. 2, no padding)
+ * Outputs and layout as orch_balance.  1 <= D <= 1024.  Uses orch_balance_workspace(n, D) bytes.
+ * A sum of squares or a load >= 2^63 sets dev_status = ORCH_EDATA. */
+int orch_balance_tolerance(const int32_t *lengths, int32_t n, int32_t D, uint64_t v, orch_phase phase,
+                           orch_assignment out, void *ws, size_t ws_bytes, void *stream);
 
 /* Bytes of workspace orch_pack needs. */
 size_t orch_pack_workspace(int32_t n, int32_t D);

@@ -6,6 +6,7 @@ from .binding import (  # noqa: F401
     attn_variant,
     balance,
     balance_padded,
+    balance_tolerance,
     balance_workspace,
     library_path,
     load_library,

@@ -18,7 +18,7 @@ _LIB_PATH = os.path.join(_PKG, "liborch.so")
 _lib = None
 
 EXPORTS = ("orch_balance_workspace", "orch_balance", "orch_pack_workspace", "orch_pack",
-           "orch_balance_padded",
+           "orch_balance_padded", "orch_balance_tolerance",
            "orch_pack_composed_workspace", "orch_pack_composed",
            "orch_varlen_attn_workspace", "orch_varlen_attn_fwd", "orch_last_error",
            "orch_attn_variant")
@@ -64,6 +64,9 @@ def load_library():
     lib.orch_balance_padded.restype = C.c_int
     lib.orch_balance_padded.argtypes = [C.c_void_p, C.c_int32, C.c_int32, _Phase, _Assignment, C.c_void_p,
                                         C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.orch_balance_tolerance.restype = C.c_int
+    lib.orch_balance_tolerance.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_uint64, _Phase, _Assignment,
+                                           C.c_void_p, C.c_size_t, C.c_void_p]
     lib.orch_pack.restype = C.c_int
     lib.orch_pack.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int64,
                               C.c_int32, C.c_int64, _Assignment, C.c_int32, C.c_int32, C.c_void_p,
@@ -175,6 +178,22 @@ def balance_padded(lengths: torch.Tensor, D: int, a: int, b: int, out: Assignmen
         ws = _workspace(lib.orch_balance_workspace(n, max(D, 1)), dev)
     _check(lib.orch_balance_padded(_ptr(lengths), n, D, _Phase(a, b), out._c(), _ptr(bound), _ptr(ws),
                                    ws.numel(), C.c_void_p(_stream(dev))))
+    return out
+
+
+def balance_tolerance(lengths: torch.Tensor, D: int, v: int, a: int, b: int, out: Assignment | None = None,
+                      ws: torch.Tensor | None = None) -> Assignment:
+    """orch_balance_tolerance: the appendix's third algorithm with tolerance interval v."""
+    lib = load_library()
+    assert lengths.dtype == torch.int32 and lengths.is_cuda and lengths.is_contiguous()
+    n = lengths.numel()
+    dev = lengths.device
+    if out is None:
+        out = Assignment.empty(n, D, dev)
+    if ws is None:
+        ws = _workspace(lib.orch_balance_workspace(n, max(D, 1)), dev)
+    _check(lib.orch_balance_tolerance(_ptr(lengths), n, D, v, _Phase(a, b), out._c(), _ptr(ws), ws.numel(),
+                                      C.c_void_p(_stream(dev))))
     return out
 
 

@@ -67,6 +67,19 @@ int orch_balance_padded(const int32_t *lengths, int32_t n, int32_t D, orch_phase
     return launch_balance_padded(lengths, n, D, phase, out, bound, ws, ws_bytes, (hipStream_t)stream);
 }
 
+int orch_balance_tolerance(const int32_t *lengths, int32_t n, int32_t D, uint64_t v, orch_phase phase,
+                           orch_assignment out, void *ws, size_t ws_bytes, void *stream)
+{
+    if (n < 0) ORCH_FAIL(ORCH_EINVAL, "orch_balance_tolerance: n = %d < 0", n);
+    if (D < 1) ORCH_FAIL(ORCH_EINVAL, "orch_balance_tolerance: D = %d < 1", D);
+    if (D > 1024) ORCH_FAIL(ORCH_EUNSUPPORTED, "orch_balance_tolerance: D = %d > 1024", D);
+    if (n > 0 && !lengths) ORCH_FAIL(ORCH_EINVAL, "orch_balance_tolerance: lengths is NULL");
+    if (!assignment_complete(out)) ORCH_FAIL(ORCH_EINVAL, "orch_balance_tolerance: an output pointer is NULL");
+    if (!ws) ORCH_FAIL(ORCH_EINVAL, "orch_balance_tolerance: workspace is NULL");
+    if ((uintptr_t)ws & 255) ORCH_FAIL(ORCH_EINVAL, "orch_balance_tolerance: workspace not 256-byte aligned");
+    return launch_balance_tolerance(lengths, n, D, v, phase, out, ws, ws_bytes, (hipStream_t)stream);
+}
+
 int orch_pack(const void *tokens, void *packed, const int32_t *lengths, int32_t n, int32_t D, int64_t T,
               int32_t H, int64_t packed_rows, orch_assignment a, int32_t inst_begin, int32_t inst_end,
               void *ws, size_t ws_bytes, void *stream)

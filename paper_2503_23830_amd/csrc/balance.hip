@@ -33,6 +33,7 @@ struct BalanceWs {
     int32_t *sorted, *rank, *start;
     int32_t *ipos;   // ipos[t]: instance chosen for sorted position t
     int32_t *flags;  // [0]: 1 when every load fits the packed (load << 12 | instance) key
+                     // [1]: 1 when the sum of all keys is below 2^32
 };
 
 size_t carve(BalanceWs &w, void *ws, int32_t n)
@@ -116,6 +117,7 @@ __global__ __launch_bounds__(kSortThreads) void cost_sort_kernel(
         }
         dev_status[0] = e ? (int32_t)ORCH_EDATA : (int32_t)ORCH_OK;
         flags[0] = (!e && s < (1ull << 51)) ? 1 : 0;  // no instance load can exceed the total
+        flags[1] = (!e && s < (1ull << 32)) ? 1 : 0;  // every partial sum of keys fits 32 bits
         int nbits = o ? 64 - __clzll((long long)o) : 0;
         s_passes = (nbits + 7) / 8;
     }
@@ -224,6 +226,27 @@ __device__ __forceinline__ uint64_t wave_min_u64(uint64_t x)
     uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)x, 63);
     uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(x >> 32), 63);
     return ((uint64_t)hi << 32) | lo;
+}
+
+// 32-bit wave minimum, result uniform.  Each stage is one v_min_u32 with a DPP source operand
+// (lanes whose DPP source does not exist keep their value); a VALU result needs two wait
+// states before a DPP read of it.  The n-step loops that use this are bound by the number of
+// dependent instructions per step, so the fused form matters.
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t x)
+{
+    uint32_t r;
+    asm volatile(
+        "s_nop 1\n\t"
+        "v_min_u32_dpp %0, %0, %0 row_shr:1 row_mask:0xf bank_mask:0xf\n\ts_nop 1\n\t"
+        "v_min_u32_dpp %0, %0, %0 row_shr:2 row_mask:0xf bank_mask:0xf\n\ts_nop 1\n\t"
+        "v_min_u32_dpp %0, %0, %0 row_shr:4 row_mask:0xf bank_mask:0xf\n\ts_nop 1\n\t"
+        "v_min_u32_dpp %0, %0, %0 row_shr:8 row_mask:0xf bank_mask:0xf\n\ts_nop 1\n\t"
+        "v_min_u32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\ts_nop 1\n\t"
+        "v_min_u32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\ts_nop 1\n\t"
+        "v_readlane_b32 %1, %0, 63\n\t"
+        "s_nop 3"
+        : "+v"(x), "=s"(r));
+    return r;
 }
 
 __device__ __forceinline__ uint64_t readlane_u64(uint64_t x, int j)
@@ -707,6 +730,177 @@ __global__ __launch_bounds__(kGreedyThreads) void greedy_lds_kernel(ORCH_GREEDY_
 }
 
 // ---------------------------------------------------------------------------
+// The appendix's third algorithm: Algorithm 1 whose "lightest batch" is, among the
+// batches with a length sum less than (smallest length sum) + max(v, 1), the one with
+// the smallest sum of squared lengths (lowest index on ties).  Same workgroup shape as
+// greedy_reg_kernel: wave 0 chooses, the other waves turn choices into the layout.
+// A step is three 64-lane reductions: smallest sum, smallest squares inside the
+// window, lowest lane holding it.
+// ---------------------------------------------------------------------------
+template <int K>
+__global__ __launch_bounds__(kGreedyThreads) void greedy_tolerance_kernel(
+    const uint64_t *__restrict__ csorted, const int32_t *__restrict__ sorted,
+    const int32_t *__restrict__ lengths, int32_t n, int32_t D, uint64_t window, uint64_t a, uint64_t b,
+    int32_t *ipos, int32_t *inst, int32_t *rank, int32_t *start, uint64_t *loads, int32_t *seq_off,
+    int64_t *tok_off, int32_t *cu_seqlens, const int32_t *flags, int32_t *dev_status)
+{
+    __shared__ uint32_t s_cnt[64 * K];
+    __shared__ unsigned long long s_tok[64 * K];
+    __shared__ int s_progress, s_booked;
+    if (flags[1] != 0) return;  // the 32-bit kernel handles this call
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    for (int i = threadIdx.x; i < 64 * K; i += kGreedyThreads) { s_cnt[i] = 0; s_tok[i] = 0; }
+    if (threadIdx.x == 0) { s_progress = 0; s_booked = 0; }
+    __syncthreads();
+    if (wave >= 1) {
+        bookkeep_wave(ipos, sorted, lengths, n, D, lane, wave - 1, BookState{&s_progress, &s_booked, s_cnt, s_tok},
+                      inst, rank, start, dev_status);
+    } else {
+        // lane l owns instances l*K .. l*K+K-1; slots past D never enter a window
+        uint64_t sum[K], sq[K];
+#pragma unroll
+        for (int k = 0; k < K; ++k) { sum[k] = (lane * K + k < D) ? 0ull : ~0ull; sq[k] = 0; }
+        int err = 0;
+        ChoiceLog log{ipos, &s_progress, 0};
+        uint64_t c_cur = lane < n ? csorted[lane] : 0;
+        int chunk = 0;
+        for (int64_t t0 = 0; t0 < n; t0 += 64, ++chunk) {
+            const uint64_t c_nxt = (t0 + 64 + lane < n) ? csorted[t0 + 64 + lane] : 0;
+            const int m = (int)min((int64_t)64, (int64_t)n - t0);
+            for (int j = 0; j < m; ++j) {
+                const uint64_t c = readlane_u64(c_cur, j);  // the length
+                uint64_t lm = sum[0];
+#pragma unroll
+                for (int k = 1; k < K; ++k) lm = sum[k] < lm ? sum[k] : lm;
+                const uint64_t least = wave_min_u64(lm);
+                uint64_t lq = ~0ull;
+#pragma unroll
+                for (int k = 0; k < K; ++k) {
+                    const bool in = sum[k] != ~0ull && sum[k] - least < window;
+                    lq = (in && sq[k] < lq) ? sq[k] : lq;
+                }
+                const uint64_t q = wave_min_u64(lq);  // < 2^63: some real instance holds `least`
+                const uint64_t ball = __ballot(lq == q);
+                const int win = __ffsll((unsigned long long)ball) - 1;
+                int kk = K - 1;
+#pragma unroll
+                for (int k = K - 2; k >= 0; --k)
+                    kk = (sum[k] != ~0ull && sum[k] - least < window && sq[k] == q) ? k : kk;
+                if (lane == win) {
+#pragma unroll
+                    for (int k = 0; k < K; ++k)
+                        if (k == kk) {
+                            sum[k] += c;
+                            sq[k] += c * c;
+                            if (sq[k] >> 63) { err = 1; sq[k] = 0; }
+                        }
+                }
+                log_choice(log, lane, j, __builtin_amdgcn_readlane(lane * K + kk, win));
+            }
+            publish_chunk(log, t0, n, lane, chunk);
+            c_cur = c_nxt;
+        }
+        // Eq. 2, no-padding branch per instance: a * sum of squares + b * length sum
+#pragma unroll
+        for (int k = 0; k < K; ++k)
+            if (lane * K + k < D) {
+                const uint64_t t1 = a * sq[k], t2 = b * sum[k], load = t1 + t2;
+                if (__umul64hi(a, sq[k]) != 0 || __umul64hi(b, sum[k]) != 0 || load < t1 || (load >> 63)) err = 1;
+                loads[lane * K + k] = load;
+            }
+        if (__any(err) && lane == 0) dev_status[0] = (int32_t)ORCH_EDATA;
+    }
+    __syncthreads();
+    if (wave == 0) finish_layout(s_cnt, s_tok, D, seq_off, tok_off, cu_seqlens, dev_status);
+}
+
+// The same algorithm when all lengths together stay below 2^32 tokens (flags[1]): length sums
+// are 32-bit, and the smallest sum of squares is found in two 32-bit reductions (high words,
+// then low words among the lanes that hold the smallest high word), so a step is three
+// single-instruction-per-stage DPP reductions instead of two 64-bit ones.
+template <int K>
+__global__ __launch_bounds__(kGreedyThreads) void greedy_tolerance32_kernel(
+    const uint64_t *__restrict__ csorted, const int32_t *__restrict__ sorted,
+    const int32_t *__restrict__ lengths, int32_t n, int32_t D, uint64_t window, uint64_t a, uint64_t b,
+    int32_t *ipos, int32_t *inst, int32_t *rank, int32_t *start, uint64_t *loads, int32_t *seq_off,
+    int64_t *tok_off, int32_t *cu_seqlens, const int32_t *flags, int32_t *dev_status)
+{
+    __shared__ uint32_t s_cnt[64 * K];
+    __shared__ unsigned long long s_tok[64 * K];
+    __shared__ int s_progress, s_booked;
+    if (flags[1] == 0) return;  // the 64-bit kernel handles this call
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    for (int i = threadIdx.x; i < 64 * K; i += kGreedyThreads) { s_cnt[i] = 0; s_tok[i] = 0; }
+    if (threadIdx.x == 0) { s_progress = 0; s_booked = 0; }
+    __syncthreads();
+    if (wave >= 1) {
+        bookkeep_wave(ipos, sorted, lengths, n, D, lane, wave - 1, BookState{&s_progress, &s_booked, s_cnt, s_tok},
+                      inst, rank, start, dev_status);
+    } else {
+        const uint32_t win32 = window > 0xffffffffull ? 0xffffffffu : (uint32_t)window;
+        uint32_t sum[K];  // slots past D hold 2^32 - 1 and are masked out explicitly
+        uint64_t sq[K];
+        bool real[K];
+#pragma unroll
+        for (int k = 0; k < K; ++k) { real[k] = lane * K + k < D; sum[k] = real[k] ? 0u : 0xffffffffu; sq[k] = 0; }
+        int err = 0;
+        ChoiceLog log{ipos, &s_progress, 0};
+        uint32_t c_cur = lane < n ? (uint32_t)csorted[lane] : 0;
+        int chunk = 0;
+        for (int64_t t0 = 0; t0 < n; t0 += 64, ++chunk) {
+            const uint32_t c_nxt = (t0 + 64 + lane < n) ? (uint32_t)csorted[t0 + 64 + lane] : 0;
+            const int m = (int)min((int64_t)64, (int64_t)n - t0);
+            for (int j = 0; j < m; ++j) {
+                const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)c_cur, j);  // the length
+                uint32_t lm = sum[0];
+#pragma unroll
+                for (int k = 1; k < K; ++k) lm = sum[k] < lm ? sum[k] : lm;
+                const uint32_t least = wave_min_u32(lm);
+                uint64_t lq = ~0ull;  // this lane's smallest squares inside the window
+#pragma unroll
+                for (int k = 0; k < K; ++k) {
+                    const bool in = real[k] && sum[k] - least < win32;
+                    lq = (in && sq[k] < lq) ? sq[k] : lq;
+                }
+                const uint32_t lh = (uint32_t)(lq >> 32), ll = (uint32_t)lq;
+                const uint32_t qh = wave_min_u32(lh);  // < 2^31: some real instance holds `least`
+                const uint32_t ql = wave_min_u32(lh == qh ? ll : 0xffffffffu);
+                const uint64_t ball = __ballot(lh == qh && ll == ql);
+                const int win = __ffsll((unsigned long long)ball) - 1;
+                int kk = K - 1;
+#pragma unroll
+                for (int k = K - 2; k >= 0; --k)
+                    kk = (real[k] && sum[k] - least < win32 && sq[k] == lq) ? k : kk;
+                if (lane == win) {
+#pragma unroll
+                    for (int k = 0; k < K; ++k)
+                        if (k == kk) {
+                            sum[k] += c;
+                            sq[k] += (uint64_t)c * c;
+                            if (sq[k] >> 63) { err = 1; sq[k] = 0; }
+                        }
+                }
+                log_choice(log, lane, j, __builtin_amdgcn_readlane(lane * K + kk, win));
+            }
+            publish_chunk(log, t0, n, lane, chunk);
+            c_cur = c_nxt;
+        }
+#pragma unroll
+        for (int k = 0; k < K; ++k)
+            if (real[k]) {
+                const uint64_t t1 = a * sq[k], t2 = b * (uint64_t)sum[k], load = t1 + t2;
+                if (__umul64hi(a, sq[k]) != 0 || __umul64hi(b, (uint64_t)sum[k]) != 0 || load < t1 || (load >> 63)) err = 1;
+                loads[lane * K + k] = load;
+            }
+        if (__any(err) && lane == 0) dev_status[0] = (int32_t)ORCH_EDATA;
+    }
+    __syncthreads();
+    if (wave == 0) finish_layout(s_cnt, s_tok, D, seq_off, tok_off, cu_seqlens, dev_status);
+}
+
+// ---------------------------------------------------------------------------
 // Algorithm 2 (Sec. 5.1, "Post-Balancing Algorithm with Paddings")
 // ---------------------------------------------------------------------------
 // The sequences arrive sorted ascending by length.  For a bound b on the padded
@@ -971,6 +1165,44 @@ int launch_balance_padded(const int32_t *lengths, int32_t n, int32_t D, orch_pha
         hipLaunchKernelGGL(padded_split_kernel<false>, dim3(1), dim3(kPadThreads), 0, stream, w.csorted,
                            w.sorted, n, D, phase.a, phase.b, out.inst, out.order, out.seq_off, out.tok_off,
                            out.cu_seqlens, out.loads, (unsigned long long *)bound, out.dev_status);
+    ORCH_HIP_CHECK(hipGetLastError());
+    return ORCH_OK;
+}
+
+int launch_balance_tolerance(const int32_t *lengths, int32_t n, int32_t D, uint64_t v, orch_phase phase,
+                             orch_assignment out, void *ws, size_t ws_bytes, hipStream_t stream)
+{
+    BalanceWs w;
+    size_t need = carve(w, ws, n);
+    if (ws_bytes < need) ORCH_FAIL(ORCH_ENOSPC, "orch_balance_tolerance: workspace %zu < %zu bytes", ws_bytes, need);
+    // sorted by length, descending, ties by index: key = 0 * l^2 + 1 * l
+    hipLaunchKernelGGL(cost_sort_kernel, dim3(1), dim3(kSortThreads), 0, stream, lengths, n, (uint64_t)0,
+                       (uint64_t)1, 0, w.csorted, w.keyA, w.keyB, w.idxA, w.idxB, w.sorted, w.flags,
+                       out.dev_status);
+    const uint64_t window = v > 1 ? v : 1;
+    // both forms are enqueued; the flag written by the sort kernel decides on the device which
+    // of them does the work (the other returns at once)
+#define ORCH_TOL(K_)                                                                                        \
+    do {                                                                                                    \
+        hipLaunchKernelGGL(greedy_tolerance32_kernel<K_>, dim3(1), dim3(kGreedyThreads), 0, stream,         \
+                           w.csorted, w.sorted, lengths, n, D, window, phase.a, phase.b, w.ipos, out.inst, \
+                           w.rank, w.start, out.loads, out.seq_off, out.tok_off, out.cu_seqlens, w.flags,  \
+                           out.dev_status);                                                                 \
+        hipLaunchKernelGGL(greedy_tolerance_kernel<K_>, dim3(1), dim3(kGreedyThreads), 0, stream,           \
+                           w.csorted, w.sorted, lengths, n, D, window, phase.a, phase.b, w.ipos, out.inst, \
+                           w.rank, w.start, out.loads, out.seq_off, out.tok_off, out.cu_seqlens, w.flags,  \
+                           out.dev_status);                                                                 \
+    } while (0)
+    if (D <= 64) ORCH_TOL(1);
+    else if (D <= 128) ORCH_TOL(2);
+    else if (D <= 256) ORCH_TOL(4);
+    else if (D <= 512) ORCH_TOL(8);
+    else if (D <= 1024) ORCH_TOL(16);
+    else ORCH_FAIL(ORCH_EUNSUPPORTED, "orch_balance_tolerance: D = %d > 1024", D);
+#undef ORCH_TOL
+    if (n > 0)
+        hipLaunchKernelGGL(layout_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, out.inst, w.rank,
+                           w.start, out.seq_off, n, out.order, out.cu_seqlens);
     ORCH_HIP_CHECK(hipGetLastError());
     return ORCH_OK;
 }

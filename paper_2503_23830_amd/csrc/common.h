@@ -33,6 +33,8 @@ int launch_balance(const int32_t *lengths, int32_t n, int32_t D, orch_phase phas
 int launch_balance_padded(const int32_t *lengths, int32_t n, int32_t D, orch_phase phase,
                           orch_assignment out, uint64_t *bound, void *ws, size_t ws_bytes,
                           hipStream_t stream);
+int launch_balance_tolerance(const int32_t *lengths, int32_t n, int32_t D, uint64_t v, orch_phase phase,
+                             orch_assignment out, void *ws, size_t ws_bytes, hipStream_t stream);
 int launch_pack(const void *tokens, void *packed, const int32_t *lengths, int32_t n, int32_t D,
                 int64_t T, int32_t H, int64_t packed_rows, orch_assignment a, int32_t inst_begin,
                 int32_t inst_end, void *ws, size_t ws_bytes, hipStream_t stream);

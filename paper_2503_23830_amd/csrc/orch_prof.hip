@@ -277,6 +277,20 @@ int main(int argc, char **argv)
         CK(hipMemcpy(&hb, dbound, 8, hipMemcpyDeviceToHost));
         CK(hipMemcpy(&prows, pa.tok_off + D, 8, hipMemcpyDeviceToHost));
         CK(hipMemcpy(&pst, pa.dev_status, 4, hipMemcpyDeviceToHost));
+        if (D <= 1024) {
+            double ttol = 0;
+            for (int s = 0; s < steps + 1; ++s) {
+                CK(hipEventRecord(e0, st));
+                OK(orch_balance_tolerance(dL, n, D, 2048, orch_phase{a, b}, pa, ws_b, wsb, st));
+                CK(hipEventRecord(e1, st));
+                CK(hipStreamSynchronize(st));
+                float ms;
+                if (s > 0) { CK(hipEventElapsedTime(&ms, e0, e1)); ttol += ms; }
+            }
+            int32_t tst;
+            CK(hipMemcpy(&tst, pa.dev_status, 4, hipMemcpyDeviceToHost));
+            printf("balance_tolerance (v = 2048) %.3f ms, dev_status=%d\n", ttol / steps, tst);
+        }
         printf("balance_padded %.3f ms, bound %llu, padded rows %lld (real %lld), dev_status=%d\n", tpad / steps,
                (unsigned long long)hb, (long long)prows, (long long)T, pst);
     }
