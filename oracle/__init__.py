@@ -41,7 +41,7 @@ def lib():
     if _lib is None:
         _lib = C.CDLL(build())
         for name in ("orc_cost", "orc_sort_desc", "orc_greedy", "orc_balance", "orc_pack",
-                     "orc_row_map", "orc_pack_composed", "orc_sort_asc", "orc_balance_padded", "orc_balance_tolerance", "orc_attn_fwd",
+                     "orc_row_map", "orc_pack_composed", "orc_sort_asc", "orc_balance_padded", "orc_balance_tolerance", "orc_comm_volume", "orc_attn_fwd",
                      "orc_attn_rows"):
             getattr(_lib, name).restype = C.c_int
         _lib.orc_least_batches.restype = C.c_int64
@@ -156,6 +156,19 @@ def balance_tolerance(lengths, D: int, v: int, a: int, b: int) -> Assignment:
                                        C.c_uint64(b), _p(out.inst), _p(out.order), _p(out.seq_off),
                                        _p(out.tok_off), _p(out.cu_seqlens), _p(out.loads)))
     return out
+
+
+def comm_volume(lengths, asg: Assignment, D_src: int, src_inst=None, node: int = 0):
+    """V[from][to] in tokens (Sec. 5.2.2, the cost matrix of the node-wise rearrangement), and, for
+    node > 0, per source instance the tokens sent to instances on other nodes of `node` instances."""
+    L = _i32(lengths)
+    D = len(asg.loads)
+    V = np.empty((D_src, D), dtype=np.uint64)
+    inter = np.zeros(D_src, dtype=np.uint64)
+    f = None if src_inst is None else _i32(src_inst)
+    _check(lib().orc_comm_volume(_p(L), C.c_int32(len(L)), C.c_int32(D_src), _p(f) if f is not None else None,
+                                 C.c_int32(D), _p(asg.order), _p(asg.seq_off), _p(V), C.c_int32(node), _p(inter)))
+    return V, inter
 
 
 def pack(tokens: np.ndarray, lengths, asg: Assignment, inst_begin: int = 0, inst_end: int | None = None):

@@ -471,3 +471,33 @@ done:
     free(key); free(sorted); free(rank); free(counts); free(sum); free(sq);
     return rc;
 }
+
+/* Communication-volume matrix of a rearrangement (Sec. 5.2.2, the node-wise rearrangement
+ * algorithm's first loop): for every new batch i and every sequence l in it,
+ * cost_matrix[l.from][i] += l.length.  `from` gives the instance a sequence was sampled on;
+ * NULL means contiguous equal blocks, sequence s on instance floor(s * D_src / n).
+ * Also the quantity the All-to-All overhead is proportional to when nodes hold c
+ * consecutive instances (the section's overhead relation): for each source instance,
+ * the tokens it sends to instances on OTHER nodes; out_inter may be NULL, c <= 0 skips it.
+ * V is row-major [D_src][D_dst]. */
+int orc_comm_volume(const int32_t *lengths, int32_t n, int32_t D_src, const int32_t *from,
+                    int32_t D_dst, const int32_t *order, const int32_t *seq_off, uint64_t *V,
+                    int32_t c, uint64_t *out_inter)
+{
+    if (n < 0 || D_src < 1 || D_dst < 1) return -1;
+    for (int64_t e = 0; e < (int64_t)D_src * D_dst; ++e) V[e] = 0;
+    for (int32_t i = 0; i < D_dst; ++i)
+        for (int32_t p = seq_off[i]; p < seq_off[i + 1]; ++p) {
+            int32_t s = order[p];
+            int32_t f = from ? from[s] : (int32_t)(((int64_t)s * D_src) / n);
+            if (lengths[s] < 0 || f < 0 || f >= D_src) return -5;
+            V[(int64_t)f * D_dst + i] += (uint64_t)lengths[s];
+        }
+    if (out_inter && c > 0)
+        for (int32_t f = 0; f < D_src; ++f) {
+            out_inter[f] = 0;
+            for (int32_t i = 0; i < D_dst; ++i)
+                if (i / c != f / c) out_inter[f] += V[(int64_t)f * D_dst + i];
+        }
+    return 0;
+}

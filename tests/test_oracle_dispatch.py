@@ -365,3 +365,34 @@ def test_pack_composed_special_cases():
         oracle.pack_composed(tokens, big, longer, zero, asg, oracle.balance(longer, w.D, w.a, w.b))
     shorter = np.maximum(L - 1, 0).astype(np.int32)
     oracle.pack_composed(tokens, big, shorter, zero, asg, asg)
+
+
+# ----------------------------------------------------------------------------
+# communication-volume matrix (Sec. 5.2.2)
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("cid", [1, 2, 3, 4])
+def test_comm_volume(cid):
+    w = wl.WORKLOADS[cid]
+    L = wl.draw_lengths(w)
+    asg = oracle.balance(L, w.D, w.a, w.b)
+    V, inter = oracle.comm_volume(L, asg, w.D, node=4)
+    src = (np.arange(w.n, dtype=np.int64) * w.D) // w.n
+    # a library scatter-add gives the same matrix
+    want = np.zeros((w.D, w.D), dtype=np.int64)
+    np.add.at(want, (src, asg.inst), L.astype(np.int64))
+    assert np.array_equal(V.astype(np.int64), want)
+    # rows: what an instance sampled; columns: what an instance ends up with
+    assert np.array_equal(V.sum(axis=1).astype(np.int64), np.bincount(src, weights=L, minlength=w.D).astype(np.int64))
+    assert np.array_equal(V.sum(axis=0).astype(np.int64), np.diff(asg.tok_off))
+    off_node = (np.arange(w.D)[:, None] // 4) != (np.arange(w.D)[None, :] // 4)
+    assert np.array_equal(inter.astype(np.int64), (want * off_node).sum(axis=1))
+    # explicit source instances; nothing moves when every sequence stays where it was sampled
+    perm = (np.arange(w.n) * 7 + 3) % w.D
+    V2, _ = oracle.comm_volume(L, asg, w.D, src_inst=perm)
+    want2 = np.zeros((w.D, w.D), dtype=np.int64)
+    np.add.at(want2, (perm, asg.inst), L.astype(np.int64))
+    assert np.array_equal(V2.astype(np.int64), want2)
+    V3, inter3 = oracle.comm_volume(L, asg, w.D, src_inst=asg.inst, node=1)
+    assert np.array_equal(V3.astype(np.int64), np.diag(np.diff(asg.tok_off))) and not inter3.any()
+    with pytest.raises(oracle.OracleError):
+        oracle.comm_volume(L, asg, w.D, src_inst=np.full(w.n, w.D, np.int32))
