@@ -322,6 +322,22 @@ def main():
         tolerance = {"ms": tev[0].elapsed_time(tev[1]) / args.steps, "cpu_oracle_ms": t_cpu, "v": v_tol,
                      "spread": spreads(tref), "spread_algorithm_1_cost": spreads(ref), "verified": bool(tok)}
         ok &= tok
+    # ---------------- communication-volume matrix (Sec. 5.2.2), outside the step ---------------
+    node = 8 if D % 8 == 0 else 1
+    for _ in range(2):
+        Vd, interd = orch.comm_volume(Ld, asg, D, node=node)
+    vev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    vev[0].record()
+    for _ in range(args.steps):
+        Vd, interd = orch.comm_volume(Ld, asg, D, node=node)
+    vev[1].record()
+    torch.cuda.synchronize()
+    Vr, ir = oracle.comm_volume(L, ref, D, node=node)
+    vok = np.array_equal(Vd.cpu().numpy().view(np.uint64), Vr) and np.array_equal(interd.cpu().numpy().view(np.uint64), ir)
+    ok &= vok
+    comm = {"ms": vev[0].elapsed_time(vev[1]) / args.steps, "instances_per_node": node,
+            "tokens_staying_on_their_instance": float(np.trace(Vr.astype(np.float64)) / max(1.0, float(Vr.sum()))),
+            "largest_inter_node_volume_tokens": int(ir.max()), "verified": bool(vok)}
     before = oracle.load_ratio(L, (np.arange(n, dtype=np.int64) * D) // n, D, w.a, w.b)
     after = float(loads.max() / loads.mean())
 
@@ -416,6 +432,7 @@ def main():
         "composed_pack": composed,
         "balance_padded": padded,
         "balance_tolerance": tolerance,
+        "comm_volume": comm,
         "dispatch": {"ms": bal_ms, "calls_per_step": 1 if whole else 2},
         "load_max_over_mean": {"before": before, "after": after},
         "verified": bool(ok), "attn_err": {"max_abs": float(err.max()), "mean_abs": float(err.mean())},

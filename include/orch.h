@@ -15,6 +15,7 @@
  *   orch_pack_composed    Sec. 5.3 (rearrangement composition): rows in an encoder
  *                         phase's packed order go straight into the LLM phase's
  *                         packed, interleaved sequences: one row pass, not two.
+ *   orch_comm_volume      Sec. 5.2.2: the communication-volume matrix V of a rearrangement.
  *   orch_varlen_attn_fwd  the padding-free ("batched along the sequence
  *                         length") attention each instance then runs; its
  *                         quadratic term is beta*sum(l^2) in Eq. 2.
@@ -167,6 +168,20 @@ int orch_pack_composed(const void *enc_rows, void *packed, const int32_t *sub_le
                        int32_t D_dst, orch_assignment dst, int64_t src_rows, int32_t H,
                        int64_t packed_rows, int32_t inst_begin, int32_t inst_end, void *ws,
                        size_t ws_bytes, void *stream);
+
+/* Sec. 5.2.2, first loop of the node-wise rearrangement algorithm: the communication-volume
+ * matrix of a rearrangement, V[from][to] = tokens that move from the instance they were
+ * sampled on to the instance the assignment gives them to.
+ *   from[n]   instance each sequence was sampled on, or NULL: contiguous equal blocks,
+ *             sequence s on instance floor(s * D_src / n)
+ *   dst       an assignment over D_dst instances (only inst and dev_status are used)
+ *   V         [D_src * D_dst] u64, row-major, overwritten
+ *   node, inter   if inter != NULL and node > 0: inter[D_src] receives, per source instance,
+ *             the tokens sent to instances on other nodes (nodes = node consecutive
+ *             instances): the quantity the section's All-to-All overhead is proportional to
+ * An index outside its range sets dst.dev_status = ORCH_EDATA.  No workspace. */
+int orch_comm_volume(const int32_t *lengths, int32_t n, int32_t D_src, const int32_t *from, int32_t D_dst,
+                     orch_assignment dst, uint64_t *V, int32_t node, uint64_t *inter, void *stream);
 
 /* Bytes of workspace orch_varlen_attn_fwd needs. */
 size_t orch_varlen_attn_workspace(int32_t batch);

@@ -7,6 +7,7 @@ from .binding import (  # noqa: F401
     balance,
     balance_padded,
     balance_tolerance,
+    comm_volume,
     balance_workspace,
     library_path,
     load_library,

@@ -19,7 +19,7 @@ _lib = None
 
 EXPORTS = ("orch_balance_workspace", "orch_balance", "orch_pack_workspace", "orch_pack",
            "orch_balance_padded", "orch_balance_tolerance",
-           "orch_pack_composed_workspace", "orch_pack_composed",
+           "orch_pack_composed_workspace", "orch_pack_composed", "orch_comm_volume",
            "orch_varlen_attn_workspace", "orch_varlen_attn_fwd", "orch_last_error",
            "orch_attn_variant")
 
@@ -77,6 +77,9 @@ def load_library():
     lib.orch_pack_composed.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                        C.POINTER(_Assignment), C.c_int32, _Assignment, C.c_int64, C.c_int32,
                                        C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.orch_comm_volume.restype = C.c_int
+    lib.orch_comm_volume.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, _Assignment,
+                                     C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
     lib.orch_varlen_attn_fwd.restype = C.c_int
     lib.orch_varlen_attn_fwd.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                          C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
@@ -241,6 +244,20 @@ def pack_composed(enc_rows: torch.Tensor, out: torch.Tensor, sub_len: torch.Tens
                                   dst.D, dst._c(), enc_rows.shape[0], enc_rows.shape[1], out.shape[0],
                                   inst_begin, inst_end, _ptr(ws), ws.numel(), C.c_void_p(_stream(dev))))
     return out
+
+
+def comm_volume(lengths: torch.Tensor, asg: Assignment, D_src: int, src_inst: torch.Tensor | None = None,
+                node: int = 0):
+    """orch_comm_volume (Sec. 5.2.2): returns (V int64[D_src, D], inter int64[D_src]) holding u64 values."""
+    lib = load_library()
+    assert lengths.dtype == torch.int32 and lengths.is_cuda and lengths.is_contiguous()
+    assert src_inst is None or (src_inst.dtype == torch.int32 and src_inst.is_cuda and src_inst.numel() == asg.n)
+    dev = lengths.device
+    V = torch.empty((D_src, asg.D), dtype=torch.int64, device=dev)
+    inter = torch.empty(D_src, dtype=torch.int64, device=dev)
+    _check(lib.orch_comm_volume(_ptr(lengths), asg.n, D_src, _ptr(src_inst), asg.D, asg._c(), _ptr(V), node,
+                                _ptr(inter), C.c_void_p(_stream(dev))))
+    return V, inter
 
 
 def varlen_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cu_seqlens: torch.Tensor,

@@ -122,6 +122,17 @@ int orch_pack_composed(const void *enc_rows, void *packed, const int32_t *sub_le
                                 packed_rows, inst_begin, inst_end, ws, ws_bytes, (hipStream_t)stream);
 }
 
+int orch_comm_volume(const int32_t *lengths, int32_t n, int32_t D_src, const int32_t *from, int32_t D_dst,
+                     orch_assignment dst, uint64_t *V, int32_t node, uint64_t *inter, void *stream)
+{
+    if (n < 0 || D_src < 1 || D_dst < 1) ORCH_FAIL(ORCH_EINVAL, "orch_comm_volume: n = %d, D_src = %d, D_dst = %d", n, D_src, D_dst);
+    if (node < 0) ORCH_FAIL(ORCH_EINVAL, "orch_comm_volume: node = %d < 0", node);
+    if (n > 0 && !lengths) ORCH_FAIL(ORCH_EINVAL, "orch_comm_volume: lengths is NULL");
+    if (!V) ORCH_FAIL(ORCH_EINVAL, "orch_comm_volume: V is NULL");
+    if (!dst.inst || !dst.dev_status) ORCH_FAIL(ORCH_EINVAL, "orch_comm_volume: an assignment pointer is NULL");
+    return launch_comm_volume(lengths, n, D_src, from, D_dst, dst, V, node, inter, (hipStream_t)stream);
+}
+
 int orch_varlen_attn_fwd(const void *q, const void *k, const void *v, void *out, float *lse,
                          const int32_t *cu_seqlens, int32_t batch, int32_t total_tokens,
                          int32_t max_seqlen, int32_t Hq, int32_t Hkv, int32_t d, float scale,

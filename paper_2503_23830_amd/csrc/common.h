@@ -43,6 +43,8 @@ int launch_pack_composed(const void *enc_rows, void *packed, const int32_t *sub_
                          int32_t D_dst, orch_assignment dst, int64_t src_rows, int32_t H,
                          int64_t packed_rows, int32_t inst_begin, int32_t inst_end, void *ws,
                          size_t ws_bytes, hipStream_t stream);
+int launch_comm_volume(const int32_t *lengths, int32_t n, int32_t D_src, const int32_t *from, int32_t D_dst,
+                       orch_assignment dst, uint64_t *V, int32_t node, uint64_t *inter, hipStream_t stream);
 int launch_attn(const void *q, const void *k, const void *v, void *out, float *lse,
                 const int32_t *cu_seqlens, int32_t batch, int32_t total_tokens, int32_t Hq,
                 int32_t Hkv, int32_t d, float scale, int32_t causal, void *ws, size_t ws_bytes,

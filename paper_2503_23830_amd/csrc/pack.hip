@@ -351,6 +351,33 @@ void launch_copy(const void *src, void *dst, int64_t max_bytes, int64_t row_byte
                            seg_pos, seg_dst, seg_src, row_bytes);
 }
 
+// Communication-volume matrix (Sec. 5.2.2, first loop of the node-wise rearrangement
+// algorithm): V[from][to] += length, and per source instance the tokens that leave its node.
+__global__ void comm_clear_kernel(unsigned long long *V, int64_t cells, unsigned long long *inter, int32_t D_src)
+{
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e < cells) V[e] = 0;
+    if (inter && e < D_src) inter[e] = 0;
+}
+
+__global__ void comm_volume_kernel(const int32_t *__restrict__ lengths, int32_t n, int32_t D_src,
+                                   const int32_t *__restrict__ from, int32_t D_dst,
+                                   const int32_t *__restrict__ inst, unsigned long long *V, int32_t c,
+                                   unsigned long long *inter, int32_t *dev_status)
+{
+    const int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (s >= n) return;
+    const int32_t L = lengths[s], to = inst[s];
+    const int32_t f = from ? from[s] : (int32_t)((s * D_src) / n);
+    if (L < 0 || f < 0 || f >= D_src || to < 0 || to >= D_dst) {
+        dev_status[0] = (int32_t)ORCH_EDATA;
+        return;
+    }
+    if (L == 0) return;
+    atomicAdd(&V[(int64_t)f * D_dst + to], (unsigned long long)L);
+    if (inter && c > 0 && to / c != f / c) atomicAdd(&inter[f], (unsigned long long)L);
+}
+
 }  // namespace
 
 size_t pack_ws_bytes(int32_t n, int32_t D)
@@ -402,6 +429,21 @@ int launch_pack_composed(const void *enc_rows, void *packed, const int32_t *sub_
                        w.src_start, w.seg_pos, w.seg_dst, w.seg_src);
     launch_copy(enc_rows, packed, (packed_rows < src_rows ? packed_rows : src_rows) * row_bytes, row_bytes,
                 w.hdr, w.seg_pos, w.seg_dst, w.seg_src, stream);
+    ORCH_HIP_CHECK(hipGetLastError());
+    return ORCH_OK;
+}
+
+int launch_comm_volume(const int32_t *lengths, int32_t n, int32_t D_src, const int32_t *from, int32_t D_dst,
+                       orch_assignment dst, uint64_t *V, int32_t node, uint64_t *inter, hipStream_t stream)
+{
+    const int64_t cells = (int64_t)D_src * D_dst;
+    const int64_t clear = cells > D_src ? cells : D_src;
+    hipLaunchKernelGGL(comm_clear_kernel, dim3((unsigned)((clear + 255) / 256)), dim3(256), 0, stream,
+                       (unsigned long long *)V, cells, (unsigned long long *)inter, D_src);
+    if (n > 0)
+        hipLaunchKernelGGL(comm_volume_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, lengths, n, D_src, from,
+                           D_dst, dst.inst, (unsigned long long *)V, node, (unsigned long long *)inter,
+                           dst.dev_status);
     ORCH_HIP_CHECK(hipGetLastError());
     return ORCH_OK;
 }

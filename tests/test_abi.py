@@ -17,7 +17,7 @@ def declared_functions():
 
 def test_header_declares_the_boundary():
     names = declared_functions()
-    for want in ("orch_balance", "orch_pack", "orch_pack_composed", "orch_pack_composed_workspace", "orch_balance_padded", "orch_balance_tolerance", "orch_varlen_attn_fwd", "orch_balance_workspace",
+    for want in ("orch_balance", "orch_pack", "orch_pack_composed", "orch_pack_composed_workspace", "orch_balance_padded", "orch_balance_tolerance", "orch_comm_volume", "orch_varlen_attn_fwd", "orch_balance_workspace",
                  "orch_pack_workspace", "orch_varlen_attn_workspace", "orch_last_error"):
         assert want in names
 
@@ -68,6 +68,10 @@ def test_workspace_queries_and_host_side_errors():
     assert rc == -3 and b"1024" in lib.orch_last_error()
     rc = lib.orch_balance_tolerance(fake, -2, 4, 5, B._Phase(1, 1), asg, fake, 1 << 20, None)
     assert rc == -1
+    rc = lib.orch_comm_volume(fake, 8, 0, None, 4, asg, fake, 0, None, None)
+    assert rc == -1 and b"D_src" in lib.orch_last_error()
+    rc = lib.orch_comm_volume(fake, 8, 4, None, 4, asg, None, 0, None, None)
+    assert rc == -1 and b"V is NULL" in lib.orch_last_error()
     rc = lib.orch_pack(fake, fake, fake, 8, 4, 10, 0, 10, asg, 0, 4, fake, 1 << 20, None)
     assert rc == -1
     rc = lib.orch_pack(fake, fake, fake, 8, 4, 10, 64, 10, asg, 2, 5, fake, 1 << 20, None)

@@ -91,3 +91,30 @@ def test_deterministic_rerun(gpu_device):
     _, a2 = run_balance(L, w.D, w.a, w.b, gpu_device)
     for f in ("inst", "order", "seq_off", "tok_off", "cu_seqlens", "loads"):
         assert torch.equal(getattr(a1, f), getattr(a2, f))
+
+
+@pytest.mark.parametrize("cid", [1, 2, 3, 4, 5])
+def test_comm_volume(gpu_device, cid):
+    """orch_comm_volume (Sec. 5.2.2) vs the oracle: every cell and the inter-node sums, bit-exact."""
+    import torch
+
+    w = wl.WORKLOADS[cid]
+    L = wl.draw_lengths(w)
+    Ld, asg = run_balance(L, w.D, w.a, w.b, gpu_device)
+    ref = oracle.balance(L, w.D, w.a, w.b)
+    V, inter = orch.comm_volume(Ld, asg, w.D, node=8)
+    torch.cuda.synchronize()
+    Vr, ir = oracle.comm_volume(L, ref, w.D, node=8)
+    assert np.array_equal(V.cpu().numpy().view(np.uint64), Vr)
+    assert np.array_equal(inter.cpu().numpy().view(np.uint64), ir)
+    # explicit source instances, another source count, no node output asked for
+    src = ((np.arange(w.n) * 5 + 1) % 3).astype(np.int32)
+    V2, _ = orch.comm_volume(Ld, asg, 3, src_inst=torch.from_numpy(src).to(gpu_device))
+    torch.cuda.synchronize()
+    assert np.array_equal(V2.cpu().numpy().view(np.uint64), oracle.comm_volume(L, ref, 3, src_inst=src)[0])
+    assert int(asg.dev_status.item()) == 0
+    # a source instance outside its range is a data error
+    bad = torch.from_numpy(np.full(w.n, 3, np.int32)).to(gpu_device)
+    orch.comm_volume(Ld, asg, 3, src_inst=bad)
+    torch.cuda.synchronize()
+    assert int(asg.dev_status.item()) == -5
