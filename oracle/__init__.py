@@ -42,7 +42,7 @@ def lib():
         _lib = C.CDLL(build())
         for name in ("orc_cost", "orc_sort_desc", "orc_greedy", "orc_balance", "orc_pack",
                      "orc_row_map", "orc_pack_composed", "orc_sort_asc", "orc_balance_padded", "orc_balance_tolerance", "orc_comm_volume", "orc_attn_fwd",
-                     "orc_attn_rows"):
+                     "orc_attn_rows", "orc_attn_bwd_unit"):
             getattr(_lib, name).restype = C.c_int
         _lib.orc_least_batches.restype = C.c_int64
     return _lib
@@ -262,6 +262,41 @@ def attn_rows(q, k, v, cu_seqlens, causal: bool, seq, head, abs_row, scale: floa
                                C.c_int(1 if causal else 0), _p(seq), _p(head), _p(abs_row),
                                C.c_int32(M), _p(out), _p(lse), C.c_int(nthreads)))
     return (out, lse) if want_lse else out
+
+
+def attn_bwd_unit(q, k, v, dout, r0: int, r1: int, g: int, causal: bool, scale: float = 0.0, nthreads: int = 1):
+    """Gradients of one (sequence rows [r0, r1), kv-head g) unit: dq fp64 [L, group, d] for the
+    q-heads of g's group, dk and dv fp64 [L, d]."""
+    q, k, v, dout = _u16(q), _u16(k), _u16(v), _u16(dout)
+    _, Hq, d = q.shape
+    Hkv = k.shape[1]
+    L = r1 - r0
+    dq = np.zeros((L, Hq // Hkv, d), dtype=np.float64)
+    dk = np.zeros((L, d), dtype=np.float64)
+    dv = np.zeros((L, d), dtype=np.float64)
+    _check(lib().orc_attn_bwd_unit(_p(q), _p(k), _p(v), _p(dout), C.c_int64(r0), C.c_int64(r1), C.c_int32(g),
+                                   C.c_int32(Hq), C.c_int32(Hkv), C.c_int32(d), C.c_double(scale),
+                                   C.c_int(1 if causal else 0), _p(dq), _p(dk), _p(dv), C.c_int(nthreads)))
+    return dq, dk, dv
+
+
+def attn_bwd(q, k, v, dout, cu_seqlens, causal: bool, scale: float = 0.0, nthreads: int = 1):
+    """Full backward: dq fp64 [T,Hq,d], dk, dv fp64 [T,Hkv,d] (rows outside every sequence stay 0)."""
+    qa = _u16(q)
+    T, Hq, d = qa.shape
+    Hkv = _u16(k).shape[1]
+    group = Hq // Hkv
+    cu = _i32(cu_seqlens)
+    dq = np.zeros((T, Hq, d)), np.zeros((T, Hkv, d)), np.zeros((T, Hkv, d))
+    dq, dk, dv = dq
+    for t in range(len(cu) - 1):
+        r0, r1 = int(cu[t]), int(cu[t + 1])
+        for g in range(Hkv):
+            a, b, c = attn_bwd_unit(q, k, v, dout, r0, r1, g, causal, scale, nthreads)
+            dq[r0:r1, g * group: (g + 1) * group] = a
+            dk[r0:r1, g] = b
+            dv[r0:r1, g] = c
+    return dq, dk, dv
 
 
 def load_ratio(lengths, inst, D: int, a: int, b: int) -> float:
