@@ -16,6 +16,7 @@
  *                         phase's packed order go straight into the LLM phase's
  *                         packed, interleaved sequences: one row pass, not two.
  *   orch_comm_volume      Sec. 5.2.2: the communication-volume matrix V of a rearrangement.
+ *   orch_varlen_attn_bwd  its backward (dq, dk, dv from dout, out and lse).
  *   orch_varlen_attn_fwd  the padding-free ("batched along the sequence
  *                         length") attention each instance then runs; its
  *                         quadratic term is beta*sum(l^2) in Eq. 2.
@@ -208,6 +209,25 @@ const char *orch_last_error(void);
 /* Name of the kernel variant the last orch_varlen_attn_fwd on this thread
  * launched (for profiling logs); never NULL. */
 const char *orch_attn_variant(void);
+
+/* Bytes of workspace orch_varlen_attn_bwd needs (it holds delta[Hq, total_tokens] in fp32). */
+size_t orch_varlen_attn_bwd_workspace(int32_t batch, int32_t total_tokens, int32_t Hq);
+
+/* Backward of orch_varlen_attn_fwd: the gradients of sum(dout * out) with respect to q, k and v
+ * (Sec. 5.3: back-propagation mirrors the forward pass; the operator is Sec. 7's).  With
+ * p_ij = exp(scale * q_i.k_j - lse_i), dp_ij = dout_i.v_j, delta_i = dout_i.out_i and
+ * ds_ij = p_ij (dp_ij - delta_i), over the visible pairs of every sequence:
+ *   dq[i,h,:] = scale * sum_j ds_ij k[j,g,:]
+ *   dk[j,g,:] = scale * sum_{h in the group of g} sum_i ds_ij q[i,h,:]
+ *   dv[j,g,:] =         sum_{h in the group of g} sum_i p_ij dout[i,h,:]
+ *   q, out, dout, dq  [total_tokens, Hq, d] bf16     k, v, dk, dv  [total_tokens, Hkv, d] bf16
+ *   lse   [Hq, total_tokens] fp32 as written by the forward pass (required)
+ * Same cu_seqlens, scale, causal and head-dim rules as the forward pass.  Rows outside every
+ * sequence are not written.  No atomics: results are bit-reproducible. */
+int orch_varlen_attn_bwd(const void *q, const void *k, const void *v, const void *out, const float *lse,
+                         const void *dout, void *dq, void *dk, void *dv, const int32_t *cu_seqlens,
+                         int32_t batch, int32_t total_tokens, int32_t max_seqlen, int32_t Hq, int32_t Hkv,
+                         int32_t d, float scale, int32_t causal, void *ws, size_t ws_bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -15,6 +15,8 @@ from .binding import (  # noqa: F401
     pack_composed,
     pack_composed_workspace,
     pack_workspace,
+    varlen_attn_bwd,
+    varlen_attn_bwd_workspace,
     varlen_attn_fwd,
     varlen_attn_workspace,
 )

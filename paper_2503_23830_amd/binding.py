@@ -20,7 +20,8 @@ _lib = None
 EXPORTS = ("orch_balance_workspace", "orch_balance", "orch_pack_workspace", "orch_pack",
            "orch_balance_padded", "orch_balance_tolerance",
            "orch_pack_composed_workspace", "orch_pack_composed", "orch_comm_volume",
-           "orch_varlen_attn_workspace", "orch_varlen_attn_fwd", "orch_last_error",
+           "orch_varlen_attn_workspace", "orch_varlen_attn_fwd", "orch_varlen_attn_bwd_workspace",
+           "orch_varlen_attn_bwd", "orch_last_error",
            "orch_attn_variant")
 
 
@@ -85,6 +86,11 @@ def load_library():
                                          C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                          C.c_int32, C.c_int32, C.c_float, C.c_int32, C.c_void_p,
                                          C.c_size_t, C.c_void_p]
+    lib.orch_varlen_attn_bwd_workspace.restype = C.c_size_t
+    lib.orch_varlen_attn_bwd_workspace.argtypes = [C.c_int32, C.c_int32, C.c_int32]
+    lib.orch_varlen_attn_bwd.restype = C.c_int
+    lib.orch_varlen_attn_bwd.argtypes = [C.c_void_p] * 10 + [C.c_int32] * 6 + [C.c_float, C.c_int32, C.c_void_p,
+                                                                                C.c_size_t, C.c_void_p]
     lib.orch_last_error.restype = C.c_char_p
     lib.orch_attn_variant.restype = C.c_char_p
     _lib = lib
@@ -283,6 +289,38 @@ def varlen_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cu_seqlen
                                     batch, T, max_seqlen, Hq, Hkv, d, float(scale), 1 if causal else 0,
                                     _ptr(ws), ws.numel(), C.c_void_p(_stream(dev))))
     return out
+
+
+def varlen_attn_bwd_workspace(batch: int, total_tokens: int, Hq: int) -> int:
+    return load_library().orch_varlen_attn_bwd_workspace(batch, total_tokens, Hq)
+
+
+def varlen_attn_bwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, out: torch.Tensor, lse: torch.Tensor,
+                    dout: torch.Tensor, cu_seqlens: torch.Tensor, causal: bool, scale: float = 0.0,
+                    max_seqlen: int = 0, dq: torch.Tensor | None = None, dk: torch.Tensor | None = None,
+                    dv: torch.Tensor | None = None, ws: torch.Tensor | None = None):
+    """orch_varlen_attn_bwd: (dq, dk, dv) from the forward pass's inputs, out and lse, and dout."""
+    lib = load_library()
+    for t in (q, k, v, out, dout):
+        assert t.is_cuda and t.is_contiguous() and t.dtype == torch.bfloat16 and t.dim() == 3
+    assert cu_seqlens.dtype == torch.int32 and cu_seqlens.is_cuda and cu_seqlens.is_contiguous()
+    T, Hq, d = q.shape
+    Hkv = k.shape[1]
+    assert k.shape == v.shape == (T, Hkv, d) and out.shape == dout.shape == q.shape
+    assert lse.dtype == torch.float32 and lse.is_cuda and lse.is_contiguous() and lse.numel() == Hq * T
+    dev = q.device
+    batch = cu_seqlens.numel() - 1
+    dq = torch.empty_like(q) if dq is None else dq
+    dk = torch.empty_like(k) if dk is None else dk
+    dv = torch.empty_like(v) if dv is None else dv
+    for t, ref in ((dq, q), (dk, k), (dv, v)):
+        assert t.is_contiguous() and t.dtype == torch.bfloat16 and t.shape == ref.shape
+    if ws is None:
+        ws = _workspace(lib.orch_varlen_attn_bwd_workspace(batch, T, Hq), dev)
+    _check(lib.orch_varlen_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(dout), _ptr(dq), _ptr(dk),
+                                    _ptr(dv), _ptr(cu_seqlens), batch, T, max_seqlen, Hq, Hkv, d, float(scale),
+                                    1 if causal else 0, _ptr(ws), ws.numel(), C.c_void_p(_stream(dev))))
+    return dq, dk, dv
 
 
 def attn_variant() -> str:

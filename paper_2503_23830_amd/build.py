@@ -9,7 +9,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB_PATH = os.path.join(PKG, "liborch.so")
 PROF_PATH = os.path.join(PKG, "orch_prof")
-SOURCES = ["api.hip", "balance.hip", "pack.hip", "attn.hip"]
+SOURCES = ["api.hip", "balance.hip", "pack.hip", "attn.hip", "attn_bwd.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]

@@ -40,6 +40,10 @@ size_t orch_balance_workspace(int32_t n, int32_t D) { return balance_ws_bytes(n,
 size_t orch_pack_workspace(int32_t n, int32_t D) { return pack_ws_bytes(n, D); }
 size_t orch_pack_composed_workspace(int32_t n) { return pack_composed_ws_bytes(n); }
 size_t orch_varlen_attn_workspace(int32_t batch) { return attn_ws_bytes(batch); }
+size_t orch_varlen_attn_bwd_workspace(int32_t batch, int32_t total_tokens, int32_t Hq)
+{
+    return attn_bwd_ws_bytes(batch, total_tokens, Hq);
+}
 
 int orch_balance(const int32_t *lengths, int32_t n, int32_t D, orch_phase phase, orch_assignment out,
                  void *ws, size_t ws_bytes, void *stream)
@@ -150,6 +154,26 @@ int orch_varlen_attn_fwd(const void *q, const void *k, const void *v, void *out,
     if ((uintptr_t)ws & 255) ORCH_FAIL(ORCH_EINVAL, "orch_varlen_attn_fwd: workspace not 256-byte aligned");
     return launch_attn(q, k, v, out, lse, cu_seqlens, batch, total_tokens, Hq, Hkv, d, scale, causal, ws,
                        ws_bytes, (hipStream_t)stream);
+}
+
+int orch_varlen_attn_bwd(const void *q, const void *k, const void *v, const void *out, const float *lse,
+                         const void *dout, void *dq, void *dk, void *dv, const int32_t *cu_seqlens,
+                         int32_t batch, int32_t total_tokens, int32_t max_seqlen, int32_t Hq, int32_t Hkv,
+                         int32_t d, float scale, int32_t causal, void *ws, size_t ws_bytes, void *stream)
+{
+    if (batch < 0 || total_tokens < 0) ORCH_FAIL(ORCH_EINVAL, "orch_varlen_attn_bwd: batch = %d, total_tokens = %d", batch, total_tokens);
+    if (max_seqlen < 0 || max_seqlen > total_tokens) ORCH_FAIL(ORCH_EINVAL, "orch_varlen_attn_bwd: max_seqlen = %d outside [0, %d]", max_seqlen, total_tokens);
+    if (Hq < 1 || Hkv < 1 || Hq % Hkv) ORCH_FAIL(ORCH_EINVAL, "orch_varlen_attn_bwd: Hq = %d, Hkv = %d", Hq, Hkv);
+    if (d != 64 && d != 128) ORCH_FAIL(ORCH_EUNSUPPORTED, "orch_varlen_attn_bwd: head_dim %d (64 and 128 are built)", d);
+    if (!cu_seqlens) ORCH_FAIL(ORCH_EINVAL, "orch_varlen_attn_bwd: cu_seqlens is NULL");
+    if (total_tokens > 0 && (!q || !k || !v || !out || !lse || !dout || !dq || !dk || !dv))
+        ORCH_FAIL(ORCH_EINVAL, "orch_varlen_attn_bwd: a tensor pointer is NULL (lse from the forward pass is required)");
+    if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out | (uintptr_t)dout | (uintptr_t)dq | (uintptr_t)dk | (uintptr_t)dv) & 15)
+        ORCH_FAIL(ORCH_EINVAL, "orch_varlen_attn_bwd: tensors must be 16-byte aligned");
+    if (!ws) ORCH_FAIL(ORCH_EINVAL, "orch_varlen_attn_bwd: workspace is NULL");
+    if ((uintptr_t)ws & 255) ORCH_FAIL(ORCH_EINVAL, "orch_varlen_attn_bwd: workspace not 256-byte aligned");
+    return launch_attn_bwd(q, k, v, out, lse, dout, dq, dk, dv, cu_seqlens, batch, total_tokens, Hq, Hkv, d, scale,
+                           causal, ws, ws_bytes, (hipStream_t)stream);
 }
 
 }  // extern "C"

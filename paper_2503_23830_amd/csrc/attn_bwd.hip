@@ -1,0 +1,592 @@
+// orch_varlen_attn_bwd: backward of the padding-free attention (the back-propagation that
+// mirrors the forward pass, OrchMLLM Sec. 5.3; the operator itself is the one of Sec. 7).
+//
+//   p_ij = exp(scale * q_i.k_j - lse_i)         dp_ij = dout_i . v_j
+//   delta_i = dout_i . out_i  (= sum_j p_ij dp_ij)      ds_ij = p_ij (dp_ij - delta_i)
+//   dq_i = scale * sum_j ds_ij k_j     dk_j = scale * sum_i ds_ij q_i     dv_j = sum_i p_ij dout_i
+//
+// Three kernels, no atomics, so the result is deterministic:
+//   attn_bwd_delta_kernel  delta[h, i] in fp32, one pass over dout and out (HBM-bound).
+//   attn_bwd_dq_kernel     query-stationary, shaped like the forward kernel: a workgroup of 4
+//                          wavefronts owns 128 query rows of one q-head, streams K/V tiles of
+//                          64 keys through LDS, recomputes the transposed scores
+//                          S^T = K Q^T and dP^T = V dout^T (a lane holds 16 keys of ONE query,
+//                          so lse and delta are per-lane scalars), and accumulates
+//                          dQ^T += K^T dS^T with K^T fragments read from a transposed LDS copy.
+//   attn_bwd_dkv_kernel    key-stationary: a workgroup owns 128 keys of one kv-head (32 per
+//                          wavefront, K and V fragments live in registers), loops over the
+//                          q-heads of the group and over 64-row tiles of Q and dout, computes
+//                          S = Q K^T and dP = dout V^T (a lane holds 16 queries of ONE key, which
+//                          is the B-operand layout for contractions over queries) and
+//                          accumulates dV^T += dout^T P and dK^T += Q^T dS with Q^T / dout^T
+//                          fragments read from transposed LDS copies.
+// Every product is v_mfma_f32_32x32x16_bf16 with fp32 accumulation; P and dS are rounded to
+// bf16 before the second products, as P is in the forward pass.
+#include "common.h"
+
+namespace orch {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kT = 64;          // rows of a streamed LDS tile (keys for dq, queries for dk/dv)
+constexpr int kOwn = 128;       // rows a workgroup owns (queries for dq, keys for dk/dv)
+constexpr int kThreads = 256;
+constexpr int kPrepThreads = 1024;
+constexpr float kLog2e = 1.4426950408889634f;
+
+struct BwdHdr {
+    int32_t total_tiles;
+    int32_t ok;
+};
+
+// tile_off[t] = number of 128-row tiles in sequences before t; validates cu_seqlens.
+__global__ __launch_bounds__(kPrepThreads) void bwd_prep_kernel(const int32_t *__restrict__ cu, int32_t batch,
+                                                               int32_t total_tokens, BwdHdr *hdr,
+                                                               int32_t *tile_off)
+{
+    __shared__ int32_t part[kPrepThreads];
+    __shared__ int s_bad;
+    const int tid = threadIdx.x;
+    if (tid == 0) s_bad = 0;
+    __syncthreads();
+    const int per = (batch + kPrepThreads - 1) / kPrepThreads;
+    const int b0 = min(batch, per * tid), b1 = min(batch, b0 + per);
+    int32_t sum = 0;
+    int bad = 0;
+    for (int t = b0; t < b1; ++t) {
+        const int32_t lo = cu[t], hi = cu[t + 1];
+        if (lo < 0 || hi < lo || hi > total_tokens) { bad = 1; continue; }
+        sum += (hi - lo + kOwn - 1) / kOwn;
+    }
+    if (bad) atomicOr(&s_bad, 1);
+    part[tid] = sum;
+    __syncthreads();
+    for (int m = 1; m < kPrepThreads; m <<= 1) {
+        int32_t o = tid >= m ? part[tid - m] : 0;
+        __syncthreads();
+        part[tid] += o;
+        __syncthreads();
+    }
+    int32_t run = part[tid] - sum;
+    if (!s_bad)
+        for (int t = b0; t < b1; ++t) {
+            tile_off[t] = run;
+            run += (cu[t + 1] - cu[t] + kOwn - 1) / kOwn;
+        }
+    if (tid == 0) {
+        const int ok = !s_bad;
+        hdr->ok = ok;
+        hdr->total_tiles = ok ? part[kPrepThreads - 1] : 0;
+        if (ok) tile_off[batch] = part[kPrepThreads - 1];
+    }
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b)
+{
+    f32x2 f = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+}
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __builtin_bit_cast(float, w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __builtin_bit_cast(float, w & 0xffff0000u); }
+
+// delta[h, i] = sum_x dout[i,h,x] * out[i,h,x]; HD/8 lanes share one (row, head).
+template <int HD>
+__global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const uint16_t *__restrict__ dout,
+                                                            const uint16_t *__restrict__ out,
+                                                            float *__restrict__ delta, int64_t total_tokens,
+                                                            int32_t Hq)
+{
+    constexpr int LPR = HD / 8;  // lanes per row
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t rh = gid / LPR;  // row * Hq + head
+    const int part = (int)(gid % LPR);
+    float acc = 0.f;
+    const bool valid = rh < total_tokens * Hq;
+    if (valid) {
+        const u32x4 a = *(const u32x4 *)(dout + rh * HD + 8 * part);
+        const u32x4 b = *(const u32x4 *)(out + rh * HD + 8 * part);
+        acc = bf16_lo(a.x) * bf16_lo(b.x) + bf16_hi(a.x) * bf16_hi(b.x) + bf16_lo(a.y) * bf16_lo(b.y) +
+              bf16_hi(a.y) * bf16_hi(b.y) + bf16_lo(a.z) * bf16_lo(b.z) + bf16_hi(a.z) * bf16_hi(b.z) +
+              bf16_lo(a.w) * bf16_lo(b.w) + bf16_hi(a.w) * bf16_hi(b.w);
+    }
+#pragma unroll
+    for (int m = 1; m < LPR; m <<= 1) acc += __shfl_xor(acc, m);
+    if (valid && part == 0) {
+        const int64_t row = rh / Hq;
+        const int h = (int)(rh % Hq);
+        delta[(size_t)h * total_tokens + row] = acc;
+    }
+}
+
+// block -> (tile u, head).  With the kv-head count a multiple of 8 the kv-head is chosen by
+// blockIdx % 8, i.e. by XCD, so the workgroups that stream the same rows share an L2.
+__device__ __forceinline__ void block_to_tile(int bid, int heads, int Hkv, int group_of_heads, int &u, int &h)
+{
+    if ((Hkv & 7) == 0) {
+        const int kvh = (bid & 7) + 8 * ((bid >> 3) % (Hkv >> 3));
+        const int rest = bid / Hkv;
+        h = kvh * group_of_heads + rest % group_of_heads;
+        u = rest / group_of_heads;
+    } else {
+        h = bid % heads;
+        u = bid / heads;
+    }
+}
+
+// Staging of one 64-row tile of a [T, heads, HD] tensor: row-major (16-byte vectors) and
+// transposed (4 x 4 blocks turned in registers).  In the transposed copy row
+// m = 16t + 8u + 4g + w sits at slot 16t + 8g + 4u + w, so that the 8 rows one lane of an
+// MFMA contracts (its registers 0..7 or 8..15 of a 32x32 accumulator) are contiguous.
+template <int HD>
+struct TileStage {
+    static constexpr int RS = HD + 8;                          // row-major stride (elements)
+    static constexpr int TS = kT + 8;                          // transposed stride
+    static constexpr int ROWS_PER_PASS = kThreads / (HD / 8);
+    static constexpr int PASS = kT / ROWS_PER_PASS;
+    static constexpr int TBLK = (kT / 4) * (HD / 4) / kThreads;
+    static_assert(TBLK * (kThreads / 8 / (HD / 4)) * 8 == kT / 4, "transposed staging must cover the tile");
+
+    u32x4 rreg[PASS];
+    u32x2 treg[TBLK][4];
+
+    // rows [m0, m0 + 64) of the sequence that starts at row0 and has L rows (clamped), head hd
+    __device__ __forceinline__ void load_rows(const uint16_t *__restrict__ src, int row0, int L, int m0, int heads,
+                                              int hd)
+    {
+        const int col = (threadIdx.x % (HD / 8)) * 8, r = threadIdx.x / (HD / 8);
+#pragma unroll
+        for (int p = 0; p < PASS; ++p) {
+            int m = m0 + p * ROWS_PER_PASS + r;
+            m = m < L ? m : L - 1;
+            rreg[p] = *(const u32x4 *)(src + ((size_t)(row0 + m) * heads + hd) * HD + col);
+        }
+    }
+    __device__ __forceinline__ void store_rows(uint16_t *lds) const
+    {
+        const int col = (threadIdx.x % (HD / 8)) * 8, r = threadIdx.x / (HD / 8);
+#pragma unroll
+        for (int p = 0; p < PASS; ++p) *(u32x4 *)(&lds[(p * ROWS_PER_PASS + r) * RS + col]) = rreg[p];
+    }
+    __device__ __forceinline__ void load_transposed(const uint16_t *__restrict__ src, int row0, int L, int m0,
+                                                    int heads, int hd)
+    {
+        const int tid = threadIdx.x;
+        const int nq0 = tid & 7, dq = (tid >> 3) % (HD / 4), nqhi = (tid >> 3) / (HD / 4);
+#pragma unroll
+        for (int b = 0; b < TBLK; ++b) {
+            const int nq = nq0 + 8 * (nqhi + b * (kThreads / 8 / (HD / 4)));
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                int m = m0 + 4 * nq + j;
+                m = m < L ? m : L - 1;
+                treg[b][j] = *(const u32x2 *)(src + ((size_t)(row0 + m) * heads + hd) * HD + 4 * dq);
+            }
+        }
+    }
+    __device__ __forceinline__ void store_transposed(uint16_t *lds) const
+    {
+        const int tid = threadIdx.x;
+        const int nq0 = tid & 7, dq = (tid >> 3) % (HD / 4), nqhi = (tid >> 3) / (HD / 4);
+#pragma unroll
+        for (int b = 0; b < TBLK; ++b) {
+            const int nq = nq0 + 8 * (nqhi + b * (kThreads / 8 / (HD / 4)));
+            const int slot = 16 * (nq >> 2) + 8 * (nq & 1) + 4 * ((nq >> 1) & 1);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
+                const uint32_t a0 = (c & 2) ? treg[b][0].y : treg[b][0].x;
+                const uint32_t a1 = (c & 2) ? treg[b][1].y : treg[b][1].x;
+                const uint32_t a2 = (c & 2) ? treg[b][2].y : treg[b][2].x;
+                const uint32_t a3 = (c & 2) ? treg[b][3].y : treg[b][3].x;
+                u32x2 w;
+                w.x = __builtin_amdgcn_perm(a1, a0, sel);
+                w.y = __builtin_amdgcn_perm(a3, a2, sel);
+                *(u32x2 *)(&lds[(4 * dq + c) * TS + slot]) = w;
+            }
+        }
+    }
+};
+
+// ---------------------------------------------------------------------------
+// dQ: query-stationary
+// ---------------------------------------------------------------------------
+template <int HD, bool CAUSAL>
+__global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(
+    const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
+    const uint16_t *__restrict__ dout, const float *__restrict__ lse, const float *__restrict__ delta,
+    uint16_t *__restrict__ dq, const int32_t *__restrict__ cu, const BwdHdr *__restrict__ hdr,
+    const int32_t *__restrict__ tile_off, int32_t batch, int32_t total_tokens, int32_t Hq, int32_t Hkv,
+    float scale, float scale_log2)
+{
+    using Stage = TileStage<HD>;
+    constexpr int RS = Stage::RS, TS = Stage::TS;
+    constexpr int NC = HD / 16, NDB = HD / 32;
+    __shared__ __attribute__((aligned(16))) uint16_t Ks[kT * RS];
+    __shared__ __attribute__((aligned(16))) uint16_t Vs[kT * RS];
+    __shared__ __attribute__((aligned(16))) uint16_t Kt[HD * TS];
+
+    const int total_tiles = hdr->total_tiles;
+    const int group = Hq / Hkv;
+    int u, h;
+    block_to_tile(blockIdx.x, Hq, Hkv, group, u, h);
+    if (u >= total_tiles) return;
+    const int g_kv = h / group;
+    int lo = 0, hi = batch - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (tile_off[mid] <= u) lo = mid; else hi = mid - 1;
+    }
+    const int row0 = cu[lo];
+    const int L = cu[lo + 1] - row0;
+    const int ntile_q = (L + kOwn - 1) / kOwn;
+    const int q0 = (ntile_q - 1 - (u - tile_off[lo])) * kOwn;  // heaviest (last) tile first
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, g = lane >> 5;
+    const int qm = q0 + 32 * wave + l32;
+    const int qm_c = qm < L ? qm : L - 1;
+
+    // stationary B operands (column = this lane's query) and the per-query scalars
+    bf16x8 qf[NC], dof[NC];
+    {
+        const uint16_t *qp = q + ((size_t)(row0 + qm_c) * Hq + h) * HD + 8 * g;
+        const uint16_t *dp = dout + ((size_t)(row0 + qm_c) * Hq + h) * HD + 8 * g;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            qf[c] = *(const bf16x8 *)(qp + 16 * c);
+            dof[c] = *(const bf16x8 *)(dp + 16 * c);
+        }
+    }
+    const float lse2 = lse[(size_t)h * total_tokens + row0 + qm_c] * kLog2e;
+    const float dlt = delta[(size_t)h * total_tokens + row0 + qm_c];
+
+    f32x16 acc[NDB];
+#pragma unroll
+    for (int b = 0; b < NDB; ++b)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[b][e] = 0.f;
+
+    const int kend = CAUSAL ? min(L, q0 + kOwn) : L;
+    const int ntile_k = (kend + kT - 1) / kT;
+
+    Stage sk, sv;
+    sk.load_rows(k, row0, L, 0, Hkv, g_kv);
+    sk.load_transposed(k, row0, L, 0, Hkv, g_kv);
+    sv.load_rows(v, row0, L, 0, Hkv, g_kv);
+    for (int it = 0; it < ntile_k; ++it) {
+        const int n0 = it * kT;
+        __syncthreads();
+        sk.store_rows(Ks);
+        sk.store_transposed(Kt);
+        sv.store_rows(Vs);
+        __syncthreads();
+        if (it + 1 < ntile_k) {
+            sk.load_rows(k, row0, L, n0 + kT, Hkv, g_kv);
+            sk.load_transposed(k, row0, L, n0 + kT, Hkv, g_kv);
+            sv.load_rows(v, row0, L, n0 + kT, Hkv, g_kv);
+        }
+        if (CAUSAL && n0 > q0 + 32 * wave + 31) continue;  // this wavefront's rows see none of the tile
+
+        // S^T = K Q^T and dP^T = V dout^T: two 32-key blocks
+        f32x16 s[2], dp[2];
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) { s[nb][e] = 0.f; dp[nb][e] = 0.f; }
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                const bf16x8 kf = *(const bf16x8 *)(&Ks[(32 * nb + l32) * RS + 16 * c + 8 * g]);
+                const bf16x8 vf = *(const bf16x8 *)(&Vs[(32 * nb + l32) * RS + 16 * c + 8 * g]);
+                s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[c], s[nb], 0, 0, 0);
+                dp[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[c], dp[nb], 0, 0, 0);
+            }
+        }
+        // dS^T = P^T (dP^T - delta), rounded to bf16 in the B-operand layout
+        const bool need_mask = (n0 + kT > L) || (CAUSAL && n0 + kT - 1 > q0 + 32 * wave);
+        bf16x8 dsf[4];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            float d8[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int idx = 8 * (kk & 1) + e;
+                const float p = __builtin_amdgcn_exp2f(s[kk >> 1][idx] * scale_log2 - lse2);
+                float val = p * (dp[kk >> 1][idx] - dlt);
+                if (need_mask) {
+                    const int n = n0 + 32 * (kk >> 1) + 8 * (idx >> 2) + 4 * g + (idx & 3);
+                    const bool vis = n < L && (!CAUSAL || n <= qm);
+                    val = vis ? val : 0.f;
+                }
+                d8[e] = val;
+            }
+            u32x4 pk;
+            pk.x = pack_bf16(d8[0], d8[1]);
+            pk.y = pack_bf16(d8[2], d8[3]);
+            pk.z = pack_bf16(d8[4], d8[5]);
+            pk.w = pack_bf16(d8[6], d8[7]);
+            dsf[kk] = __builtin_bit_cast(bf16x8, pk);
+        }
+        // dQ^T += K^T dS^T
+#pragma unroll
+        for (int b = 0; b < NDB; ++b)
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const bf16x8 ktf = *(const bf16x8 *)(&Kt[(32 * b + l32) * TS + 16 * kk + 8 * g]);
+                acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf, dsf[kk], acc[b], 0, 0, 0);
+            }
+    }
+
+    if (qm < L) {
+        uint16_t *op = dq + ((size_t)(row0 + qm) * Hq + h) * HD;
+#pragma unroll
+        for (int b = 0; b < NDB; ++b)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                u32x2 w;
+                w.x = pack_bf16(acc[b][4 * r] * scale, acc[b][4 * r + 1] * scale);
+                w.y = pack_bf16(acc[b][4 * r + 2] * scale, acc[b][4 * r + 3] * scale);
+                *(u32x2 *)(op + 32 * b + 8 * r + 4 * g) = w;
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// dK, dV: key-stationary
+// ---------------------------------------------------------------------------
+template <int HD, bool CAUSAL>
+__global__ __launch_bounds__(kThreads) void attn_bwd_dkv_kernel(
+    const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
+    const uint16_t *__restrict__ dout, const float *__restrict__ lse, const float *__restrict__ delta,
+    uint16_t *__restrict__ dk, uint16_t *__restrict__ dv, const int32_t *__restrict__ cu,
+    const BwdHdr *__restrict__ hdr, const int32_t *__restrict__ tile_off, int32_t batch,
+    int32_t total_tokens, int32_t Hq, int32_t Hkv, float scale, float scale_log2)
+{
+    using Stage = TileStage<HD>;
+    constexpr int RS = Stage::RS, TS = Stage::TS;
+    constexpr int NC = HD / 16, NDB = HD / 32;
+    __shared__ __attribute__((aligned(16))) uint16_t Qs[kT * RS];
+    __shared__ __attribute__((aligned(16))) uint16_t Os[kT * RS];   // dout, row-major
+    __shared__ __attribute__((aligned(16))) uint16_t Qt[HD * TS];
+    __shared__ __attribute__((aligned(16))) uint16_t Ot[HD * TS];   // dout, transposed
+    __shared__ __attribute__((aligned(16))) float s_lse[kT];        // lse * log2(e) of the tile's rows
+    __shared__ __attribute__((aligned(16))) float s_dlt[kT];
+
+    const int total_tiles = hdr->total_tiles;
+    const int group = Hq / Hkv;
+    int u, g_kv;
+    block_to_tile(blockIdx.x, Hkv, Hkv, 1, u, g_kv);
+    if (u >= total_tiles) return;
+    int lo = 0, hi = batch - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (tile_off[mid] <= u) lo = mid; else hi = mid - 1;
+    }
+    const int row0 = cu[lo];
+    const int L = cu[lo + 1] - row0;
+    const int k0 = (u - tile_off[lo]) * kOwn;  // under a causal mask the first key tile is the heaviest
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, g = lane >> 5;
+    const int n0w = k0 + 32 * wave;     // this wavefront's keys
+    const int kn = n0w + l32;           // this lane's key (a column of S)
+    const int kn_c = kn < L ? kn : L - 1;
+
+    bf16x8 kfs[NC], vfs[NC];
+    {
+        const uint16_t *kp = k + ((size_t)(row0 + kn_c) * Hkv + g_kv) * HD + 8 * g;
+        const uint16_t *vp = v + ((size_t)(row0 + kn_c) * Hkv + g_kv) * HD + 8 * g;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            kfs[c] = *(const bf16x8 *)(kp + 16 * c);
+            vfs[c] = *(const bf16x8 *)(vp + 16 * c);
+        }
+    }
+    f32x16 acc_k[NDB], acc_v[NDB];
+#pragma unroll
+    for (int b = 0; b < NDB; ++b)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) { acc_k[b][e] = 0.f; acc_v[b][e] = 0.f; }
+
+    const int m_begin = CAUSAL ? (k0 / kT) * kT : 0;  // rows before the first key see none of them
+    const int ntile_m = m_begin < L ? (L - m_begin + kT - 1) / kT : 0;
+    const int steps = ntile_m * group;
+
+    Stage sq, so;
+    float r_lse = 0.f, r_dlt = 0.f;
+    auto load_step = [&](int st) {
+        const int h = g_kv * group + st / ntile_m;
+        const int m0 = m_begin + (st % ntile_m) * kT;
+        sq.load_rows(q, row0, L, m0, Hq, h);
+        sq.load_transposed(q, row0, L, m0, Hq, h);
+        so.load_rows(dout, row0, L, m0, Hq, h);
+        so.load_transposed(dout, row0, L, m0, Hq, h);
+        if (tid < kT) {
+            int m = m0 + tid;
+            m = m < L ? m : L - 1;
+            r_lse = lse[(size_t)h * total_tokens + row0 + m] * kLog2e;
+            r_dlt = delta[(size_t)h * total_tokens + row0 + m];
+        }
+    };
+    if (steps > 0) load_step(0);
+    for (int st = 0; st < steps; ++st) {
+        const int m0 = m_begin + (st % ntile_m) * kT;
+        __syncthreads();
+        sq.store_rows(Qs);
+        sq.store_transposed(Qt);
+        so.store_rows(Os);
+        so.store_transposed(Ot);
+        if (tid < kT) { s_lse[tid] = r_lse; s_dlt[tid] = r_dlt; }
+        __syncthreads();
+        if (st + 1 < steps) load_step(st + 1);
+        if (CAUSAL && m0 + kT - 1 < n0w) continue;  // every row of the tile lies before this wavefront's keys
+
+        bf16x8 pf[4], dsf[4];
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) {
+            // S = Q K^T and dP = dout V^T for 32 rows x this wavefront's 32 keys
+            f32x16 s, dp;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                const bf16x8 qa = *(const bf16x8 *)(&Qs[(32 * mb + l32) * RS + 16 * c + 8 * g]);
+                const bf16x8 oa = *(const bf16x8 *)(&Os[(32 * mb + l32) * RS + 16 * c + 8 * g]);
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kfs[c], s, 0, 0, 0);
+                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(oa, vfs[c], dp, 0, 0, 0);
+            }
+            // register e of the accumulator is row 8 (e / 4) + 4 g + e % 4 of the block
+            float p16[16], d16[16];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const f32x4 l4 = *(const f32x4 *)(&s_lse[32 * mb + 8 * j + 4 * g]);
+                const f32x4 t4 = *(const f32x4 *)(&s_dlt[32 * mb + 8 * j + 4 * g]);
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    const int e = 4 * j + w;
+                    const int m = m0 + 32 * mb + 8 * j + 4 * g + w;
+                    const bool vis = m < L && kn < L && (!CAUSAL || kn <= m);
+                    const float p = vis ? __builtin_amdgcn_exp2f(s[e] * scale_log2 - l4[w]) : 0.f;
+                    p16[e] = p;
+                    d16[e] = p * (dp[e] - t4[w]);
+                }
+            }
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                u32x4 a, b;
+                a.x = pack_bf16(p16[8 * half + 0], p16[8 * half + 1]);
+                a.y = pack_bf16(p16[8 * half + 2], p16[8 * half + 3]);
+                a.z = pack_bf16(p16[8 * half + 4], p16[8 * half + 5]);
+                a.w = pack_bf16(p16[8 * half + 6], p16[8 * half + 7]);
+                b.x = pack_bf16(d16[8 * half + 0], d16[8 * half + 1]);
+                b.y = pack_bf16(d16[8 * half + 2], d16[8 * half + 3]);
+                b.z = pack_bf16(d16[8 * half + 4], d16[8 * half + 5]);
+                b.w = pack_bf16(d16[8 * half + 6], d16[8 * half + 7]);
+                pf[2 * mb + half] = __builtin_bit_cast(bf16x8, a);
+                dsf[2 * mb + half] = __builtin_bit_cast(bf16x8, b);
+            }
+        }
+        // dV^T += dout^T P and dK^T += Q^T dS over the tile's 64 rows (4 groups of 16)
+#pragma unroll
+        for (int b = 0; b < NDB; ++b)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const bf16x8 ot = *(const bf16x8 *)(&Ot[(32 * b + l32) * TS + 16 * t + 8 * g]);
+                const bf16x8 qt = *(const bf16x8 *)(&Qt[(32 * b + l32) * TS + 16 * t + 8 * g]);
+                acc_v[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ot, pf[t], acc_v[b], 0, 0, 0);
+                acc_k[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt, dsf[t], acc_k[b], 0, 0, 0);
+            }
+    }
+
+    if (kn < L) {
+        uint16_t *kp = dk + ((size_t)(row0 + kn) * Hkv + g_kv) * HD;
+        uint16_t *vp = dv + ((size_t)(row0 + kn) * Hkv + g_kv) * HD;
+#pragma unroll
+        for (int b = 0; b < NDB; ++b)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                u32x2 w;
+                w.x = pack_bf16(acc_k[b][4 * r] * scale, acc_k[b][4 * r + 1] * scale);
+                w.y = pack_bf16(acc_k[b][4 * r + 2] * scale, acc_k[b][4 * r + 3] * scale);
+                *(u32x2 *)(kp + 32 * b + 8 * r + 4 * g) = w;
+                w.x = pack_bf16(acc_v[b][4 * r], acc_v[b][4 * r + 1]);
+                w.y = pack_bf16(acc_v[b][4 * r + 2], acc_v[b][4 * r + 3]);
+                *(u32x2 *)(vp + 32 * b + 8 * r + 4 * g) = w;
+            }
+    }
+}
+
+struct BwdWs {
+    BwdHdr *hdr;
+    int32_t *tile_off;
+    float *delta;
+};
+
+size_t carve(BwdWs &w, void *ws, int32_t batch, int64_t total_tokens, int32_t Hq)
+{
+    char *p = (char *)ws;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { char *r = p ? p + off : nullptr; off += align_up(bytes, 256); return r; };
+    w.hdr = (BwdHdr *)take(sizeof(BwdHdr));
+    w.tile_off = (int32_t *)take(((size_t)(batch > 0 ? batch : 0) + 1) * 4);
+    w.delta = (float *)take((size_t)(total_tokens > 0 ? total_tokens : 0) * (size_t)Hq * 4 + 4);
+    return off;
+}
+
+}  // namespace
+
+size_t attn_bwd_ws_bytes(int32_t batch, int32_t total_tokens, int32_t Hq)
+{
+    BwdWs w;
+    return carve(w, nullptr, batch, total_tokens, Hq);
+}
+
+int launch_attn_bwd(const void *q, const void *k, const void *v, const void *out, const float *lse,
+                    const void *dout, void *dq, void *dk, void *dv, const int32_t *cu_seqlens,
+                    int32_t batch, int32_t total_tokens, int32_t Hq, int32_t Hkv, int32_t d, float scale,
+                    int32_t causal, void *ws, size_t ws_bytes, hipStream_t stream)
+{
+    BwdWs w;
+    const size_t need = carve(w, ws, batch, total_tokens, Hq);
+    if (ws_bytes < need) ORCH_FAIL(ORCH_ENOSPC, "orch_varlen_attn_bwd: workspace %zu < %zu bytes", ws_bytes, need);
+    hipLaunchKernelGGL(bwd_prep_kernel, dim3(1), dim3(kPrepThreads), 0, stream, cu_seqlens, batch, total_tokens,
+                       w.hdr, w.tile_off);
+    const int64_t max_tiles = (int64_t)total_tokens / kOwn + batch;
+    if (max_tiles * Hq > 0x7fffffffLL) ORCH_FAIL(ORCH_EUNSUPPORTED, "orch_varlen_attn_bwd: %lld workgroups", (long long)(max_tiles * Hq));
+    if (scale <= 0.f) scale = 1.0f / sqrtf((float)d);
+    const float sl2 = scale * kLog2e;
+    if (batch > 0 && total_tokens > 0) {
+        const int64_t rows = (int64_t)total_tokens * Hq * (d / 8);
+        const unsigned dgrid = (unsigned)((rows + 255) / 256);
+        const unsigned qgrid = (unsigned)(max_tiles * Hq), kgrid = (unsigned)(max_tiles * Hkv);
+#define ORCH_BWD_COMMON (const uint16_t *)q, (const uint16_t *)k, (const uint16_t *)v, (const uint16_t *)dout, lse, w.delta
+#define ORCH_BWD_TAIL cu_seqlens, w.hdr, w.tile_off, batch, total_tokens, Hq, Hkv, scale, sl2
+#define ORCH_BWD_LAUNCH(HD_, C_)                                                                                  \
+    do {                                                                                                          \
+        hipLaunchKernelGGL((attn_bwd_delta_kernel<HD_>), dim3(dgrid), dim3(256), 0, stream,                      \
+                           (const uint16_t *)dout, (const uint16_t *)out, w.delta, (int64_t)total_tokens, Hq);    \
+        hipLaunchKernelGGL((attn_bwd_dq_kernel<HD_, C_>), dim3(qgrid), dim3(kThreads), 0, stream,                 \
+                           ORCH_BWD_COMMON, (uint16_t *)dq, ORCH_BWD_TAIL);                                       \
+        hipLaunchKernelGGL((attn_bwd_dkv_kernel<HD_, C_>), dim3(kgrid), dim3(kThreads), 0, stream,                \
+                           ORCH_BWD_COMMON, (uint16_t *)dk, (uint16_t *)dv, ORCH_BWD_TAIL);                       \
+    } while (0)
+        if (d == 128 && causal) ORCH_BWD_LAUNCH(128, true);
+        else if (d == 128) ORCH_BWD_LAUNCH(128, false);
+        else if (causal) ORCH_BWD_LAUNCH(64, true);
+        else ORCH_BWD_LAUNCH(64, false);
+#undef ORCH_BWD_LAUNCH
+#undef ORCH_BWD_TAIL
+#undef ORCH_BWD_COMMON
+    }
+    ORCH_HIP_CHECK(hipGetLastError());
+    return ORCH_OK;
+}
+
+}  // namespace orch

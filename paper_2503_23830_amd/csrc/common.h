@@ -49,6 +49,11 @@ int launch_attn(const void *q, const void *k, const void *v, void *out, float *l
                 const int32_t *cu_seqlens, int32_t batch, int32_t total_tokens, int32_t Hq,
                 int32_t Hkv, int32_t d, float scale, int32_t causal, void *ws, size_t ws_bytes,
                 hipStream_t stream);
+int launch_attn_bwd(const void *q, const void *k, const void *v, const void *out, const float *lse,
+                    const void *dout, void *dq, void *dk, void *dv, const int32_t *cu_seqlens,
+                    int32_t batch, int32_t total_tokens, int32_t Hq, int32_t Hkv, int32_t d, float scale,
+                    int32_t causal, void *ws, size_t ws_bytes, hipStream_t stream);
+size_t attn_bwd_ws_bytes(int32_t batch, int32_t total_tokens, int32_t Hq);
 size_t balance_ws_bytes(int32_t n, int32_t D);
 size_t pack_ws_bytes(int32_t n, int32_t D);
 size_t pack_composed_ws_bytes(int32_t n);

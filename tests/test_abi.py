@@ -18,7 +18,8 @@ def declared_functions():
 def test_header_declares_the_boundary():
     names = declared_functions()
     for want in ("orch_balance", "orch_pack", "orch_pack_composed", "orch_pack_composed_workspace", "orch_balance_padded", "orch_balance_tolerance", "orch_comm_volume", "orch_varlen_attn_fwd", "orch_balance_workspace",
-                 "orch_pack_workspace", "orch_varlen_attn_workspace", "orch_last_error"):
+                 "orch_pack_workspace", "orch_varlen_attn_workspace", "orch_varlen_attn_bwd",
+                 "orch_varlen_attn_bwd_workspace", "orch_last_error"):
         assert want in names
 
 
@@ -95,3 +96,9 @@ def test_workspace_queries_and_host_side_errors():
     rc = lib.orch_varlen_attn_fwd(fake, fake, fake, fake, None, fake, 2, 64, 0, 8, 4, 64, 0.0, 1, fake,
                                   8, None)
     assert rc == -2
+    assert lib.orch_varlen_attn_bwd_workspace(4, 1000, 8) >= 1000 * 8 * 4
+    bwd = lambda lse, d, wsb: lib.orch_varlen_attn_bwd(fake, fake, fake, fake, lse, fake, fake, fake, fake, fake,
+                                                       2, 64, 0, 8, 4, d, 0.0, 1, fake, wsb, None)
+    assert bwd(None, 64, 1 << 20) == -1 and b"lse" in lib.orch_last_error()
+    assert bwd(fake, 96, 1 << 20) == -3
+    assert bwd(fake, 64, 8) == -2
