@@ -5,7 +5,7 @@
 //   delta_i = dout_i . out_i  (= sum_j p_ij dp_ij)      ds_ij = p_ij (dp_ij - delta_i)
 //   dq_i = scale * sum_j ds_ij k_j     dk_j = scale * sum_i ds_ij q_i     dv_j = sum_i p_ij dout_i
 //
-// Three kernels, no atomics, so the result is deterministic:
+// Four launches, no atomics, so the result is deterministic:
 //   attn_bwd_delta_kernel  delta[h, i] in fp32, one pass over dout and out (HBM-bound).
 //   attn_bwd_dq_kernel     query-stationary, shaped like the forward kernel: a workgroup of 4
 //                          wavefronts owns 128 query rows of one q-head, streams K/V tiles of
@@ -13,13 +13,13 @@
 //                          S^T = K Q^T and dP^T = V dout^T (a lane holds 16 keys of ONE query,
 //                          so lse and delta are per-lane scalars), and accumulates
 //                          dQ^T += K^T dS^T with K^T fragments read from a transposed LDS copy.
-//   attn_bwd_dkv_kernel    key-stationary: a workgroup owns 128 keys of one kv-head (32 per
-//                          wavefront, K and V fragments live in registers), loops over the
-//                          q-heads of the group and over 64-row tiles of Q and dout, computes
-//                          S = Q K^T and dP = dout V^T (a lane holds 16 queries of ONE key, which
-//                          is the B-operand layout for contractions over queries) and
-//                          accumulates dV^T += dout^T P and dK^T += Q^T dS with Q^T / dout^T
-//                          fragments read from transposed LDS copies.
+//   attn_bwd_dkv_kernel    key-stationary, launched once for dK and once for dV: a workgroup owns
+//                          128 keys of one kv-head (32 per wavefront, K and V fragments live in
+//                          registers), loops over the q-heads of the group and over 64-row tiles
+//                          of Q and dout, computes S = Q K^T and dP = dout V^T (a lane holds 16
+//                          queries of ONE key, which is the B-operand layout for contractions
+//                          over queries) and accumulates dV^T += dout^T P or dK^T += Q^T dS with
+//                          Q^T / dout^T fragments read from a transposed LDS copy.
 // Every product is v_mfma_f32_32x32x16_bf16 with fp32 accumulation; P and dS are rounded to
 // bf16 before the second products, as P is in the forward pass.
 #include "common.h"
@@ -219,7 +219,7 @@ struct TileStage {
 // dQ: query-stationary
 // ---------------------------------------------------------------------------
 template <int HD, bool CAUSAL>
-__global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(
+__global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
     const uint16_t *__restrict__ dout, const float *__restrict__ lse, const float *__restrict__ delta,
     uint16_t *__restrict__ dq, const int32_t *__restrict__ cu, const BwdHdr *__restrict__ hdr,
@@ -295,44 +295,44 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(
         }
         if (CAUSAL && n0 > q0 + 32 * wave + 31) continue;  // this wavefront's rows see none of the tile
 
-        // S^T = K Q^T and dP^T = V dout^T: two 32-key blocks
-        f32x16 s[2], dp[2];
+        // per 32-key block: S^T = K Q^T and dP^T = V dout^T, then dS^T = P^T (dP^T - delta),
+        // rounded to bf16 in the B-operand layout
+        const bool need_mask = (n0 + kT > L) || (CAUSAL && n0 + kT - 1 > q0 + 32 * wave);
+        bf16x8 dsf[4];
 #pragma unroll
         for (int nb = 0; nb < 2; ++nb) {
+            f32x16 sa, da;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) { s[nb][e] = 0.f; dp[nb][e] = 0.f; }
+            for (int e = 0; e < 16; ++e) { sa[e] = 0.f; da[e] = 0.f; }
 #pragma unroll
             for (int c = 0; c < NC; ++c) {
                 const bf16x8 kf = *(const bf16x8 *)(&Ks[(32 * nb + l32) * RS + 16 * c + 8 * g]);
                 const bf16x8 vf = *(const bf16x8 *)(&Vs[(32 * nb + l32) * RS + 16 * c + 8 * g]);
-                s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[c], s[nb], 0, 0, 0);
-                dp[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[c], dp[nb], 0, 0, 0);
+                sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[c], sa, 0, 0, 0);
+                da = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[c], da, 0, 0, 0);
             }
-        }
-        // dS^T = P^T (dP^T - delta), rounded to bf16 in the B-operand layout
-        const bool need_mask = (n0 + kT > L) || (CAUSAL && n0 + kT - 1 > q0 + 32 * wave);
-        bf16x8 dsf[4];
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            float d8[8];
+            for (int half = 0; half < 2; ++half) {
+                float d8[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int idx = 8 * (kk & 1) + e;
-                const float p = __builtin_amdgcn_exp2f(s[kk >> 1][idx] * scale_log2 - lse2);
-                float val = p * (dp[kk >> 1][idx] - dlt);
-                if (need_mask) {
-                    const int n = n0 + 32 * (kk >> 1) + 8 * (idx >> 2) + 4 * g + (idx & 3);
-                    const bool vis = n < L && (!CAUSAL || n <= qm);
-                    val = vis ? val : 0.f;
+                for (int e = 0; e < 8; ++e) {
+                    const int idx = 8 * half + e;
+                    const float p = __builtin_amdgcn_exp2f(sa[idx] * scale_log2 - lse2);
+                    float val = p * (da[idx] - dlt);
+                    if (need_mask) {
+                        const int n = n0 + 32 * nb + 8 * (idx >> 2) + 4 * g + (idx & 3);
+                        const bool vis = n < L && (!CAUSAL || n <= qm);
+                        val = vis ? val : 0.f;
+                    }
+                    d8[e] = val;
                 }
-                d8[e] = val;
+                u32x4 pk;
+                pk.x = pack_bf16(d8[0], d8[1]);
+                pk.y = pack_bf16(d8[2], d8[3]);
+                pk.z = pack_bf16(d8[4], d8[5]);
+                pk.w = pack_bf16(d8[6], d8[7]);
+                dsf[2 * nb + half] = __builtin_bit_cast(bf16x8, pk);
             }
-            u32x4 pk;
-            pk.x = pack_bf16(d8[0], d8[1]);
-            pk.y = pack_bf16(d8[2], d8[3]);
-            pk.z = pack_bf16(d8[4], d8[5]);
-            pk.w = pack_bf16(d8[6], d8[7]);
-            dsf[kk] = __builtin_bit_cast(bf16x8, pk);
         }
         // dQ^T += K^T dS^T
 #pragma unroll
@@ -359,24 +359,31 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(
 }
 
 // ---------------------------------------------------------------------------
-// dK, dV: key-stationary
+// dK, dV: key-stationary.  One kernel body, instantiated once per output (PART): holding
+// both accumulators needs more than 256 registers per lane, which leaves one wavefront per
+// SIMD and nothing to hide LDS and barrier latency behind; each half fits in 256, so two
+// workgroups share a CU, at the price of recomputing S for the second output.
+//   PART_DV: S -> P,          dV^T += dout^T P      (Q rows, dout transposed)
+//   PART_DK: S, dP -> dS,     dK^T += Q^T dS        (Q rows and transposed, dout rows)
 // ---------------------------------------------------------------------------
-template <int HD, bool CAUSAL>
-__global__ __launch_bounds__(kThreads) void attn_bwd_dkv_kernel(
+constexpr int PART_DV = 1, PART_DK = 2;
+
+template <int HD, bool CAUSAL, int PART>
+__global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
     const uint16_t *__restrict__ dout, const float *__restrict__ lse, const float *__restrict__ delta,
-    uint16_t *__restrict__ dk, uint16_t *__restrict__ dv, const int32_t *__restrict__ cu,
-    const BwdHdr *__restrict__ hdr, const int32_t *__restrict__ tile_off, int32_t batch,
-    int32_t total_tokens, int32_t Hq, int32_t Hkv, float scale, float scale_log2)
+    uint16_t *__restrict__ dkv, const int32_t *__restrict__ cu, const BwdHdr *__restrict__ hdr,
+    const int32_t *__restrict__ tile_off, int32_t batch, int32_t total_tokens, int32_t Hq, int32_t Hkv,
+    float scale, float scale_log2)
 {
+    constexpr bool DK = PART == PART_DK;
     using Stage = TileStage<HD>;
     constexpr int RS = Stage::RS, TS = Stage::TS;
     constexpr int NC = HD / 16, NDB = HD / 32;
-    __shared__ __attribute__((aligned(16))) uint16_t Qs[kT * RS];
-    __shared__ __attribute__((aligned(16))) uint16_t Os[kT * RS];   // dout, row-major
-    __shared__ __attribute__((aligned(16))) uint16_t Qt[HD * TS];
-    __shared__ __attribute__((aligned(16))) uint16_t Ot[HD * TS];   // dout, transposed
-    __shared__ __attribute__((aligned(16))) float s_lse[kT];        // lse * log2(e) of the tile's rows
+    __shared__ __attribute__((aligned(16))) uint16_t Qs[kT * RS];            // Q, row-major
+    __shared__ __attribute__((aligned(16))) uint16_t Os[DK ? kT * RS : 8];   // dout, row-major (dK)
+    __shared__ __attribute__((aligned(16))) uint16_t Xt[HD * TS];            // Q (dK) or dout (dV), transposed
+    __shared__ __attribute__((aligned(16))) float s_lse[kT];                 // lse * log2(e) of the tile's rows
     __shared__ __attribute__((aligned(16))) float s_dlt[kT];
 
     const int total_tiles = hdr->total_tiles;
@@ -399,21 +406,22 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkv_kernel(
     const int kn = n0w + l32;           // this lane's key (a column of S)
     const int kn_c = kn < L ? kn : L - 1;
 
-    bf16x8 kfs[NC], vfs[NC];
+    // stationary B operands (column = this lane's key)
+    bf16x8 kfs[NC], vfs[DK ? NC : 1];
     {
         const uint16_t *kp = k + ((size_t)(row0 + kn_c) * Hkv + g_kv) * HD + 8 * g;
         const uint16_t *vp = v + ((size_t)(row0 + kn_c) * Hkv + g_kv) * HD + 8 * g;
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
             kfs[c] = *(const bf16x8 *)(kp + 16 * c);
-            vfs[c] = *(const bf16x8 *)(vp + 16 * c);
+            if (DK) vfs[c] = *(const bf16x8 *)(vp + 16 * c);
         }
     }
-    f32x16 acc_k[NDB], acc_v[NDB];
+    f32x16 acc[NDB];
 #pragma unroll
     for (int b = 0; b < NDB; ++b)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) { acc_k[b][e] = 0.f; acc_v[b][e] = 0.f; }
+        for (int e = 0; e < 16; ++e) acc[b][e] = 0.f;
 
     const int m_begin = CAUSAL ? (k0 / kT) * kT : 0;  // rows before the first key see none of them
     const int ntile_m = m_begin < L ? (L - m_begin + kT - 1) / kT : 0;
@@ -425,14 +433,17 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkv_kernel(
         const int h = g_kv * group + st / ntile_m;
         const int m0 = m_begin + (st % ntile_m) * kT;
         sq.load_rows(q, row0, L, m0, Hq, h);
-        sq.load_transposed(q, row0, L, m0, Hq, h);
-        so.load_rows(dout, row0, L, m0, Hq, h);
-        so.load_transposed(dout, row0, L, m0, Hq, h);
+        if (DK) {
+            sq.load_transposed(q, row0, L, m0, Hq, h);
+            so.load_rows(dout, row0, L, m0, Hq, h);
+        } else {
+            so.load_transposed(dout, row0, L, m0, Hq, h);
+        }
         if (tid < kT) {
             int m = m0 + tid;
             m = m < L ? m : L - 1;
             r_lse = lse[(size_t)h * total_tokens + row0 + m] * kLog2e;
-            r_dlt = delta[(size_t)h * total_tokens + row0 + m];
+            if (DK) r_dlt = delta[(size_t)h * total_tokens + row0 + m];
         }
     };
     if (steps > 0) load_step(0);
@@ -440,85 +451,80 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkv_kernel(
         const int m0 = m_begin + (st % ntile_m) * kT;
         __syncthreads();
         sq.store_rows(Qs);
-        sq.store_transposed(Qt);
-        so.store_rows(Os);
-        so.store_transposed(Ot);
+        if (DK) {
+            sq.store_transposed(Xt);
+            so.store_rows(Os);
+        } else {
+            so.store_transposed(Xt);
+        }
         if (tid < kT) { s_lse[tid] = r_lse; s_dlt[tid] = r_dlt; }
         __syncthreads();
         if (st + 1 < steps) load_step(st + 1);
         if (CAUSAL && m0 + kT - 1 < n0w) continue;  // every row of the tile lies before this wavefront's keys
 
-        bf16x8 pf[4], dsf[4];
+        bf16x8 bf[4];  // P (dV) or dS (dK) of the tile's 64 rows, B-operand layout
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb) {
-            // S = Q K^T and dP = dout V^T for 32 rows x this wavefront's 32 keys
-            f32x16 s, dp;
+            // S = Q K^T (and dP = dout V^T) for 32 rows x this wavefront's 32 keys
+            f32x16 sa, da;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
+            for (int e = 0; e < 16; ++e) { sa[e] = 0.f; da[e] = 0.f; }
 #pragma unroll
             for (int c = 0; c < NC; ++c) {
                 const bf16x8 qa = *(const bf16x8 *)(&Qs[(32 * mb + l32) * RS + 16 * c + 8 * g]);
-                const bf16x8 oa = *(const bf16x8 *)(&Os[(32 * mb + l32) * RS + 16 * c + 8 * g]);
-                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kfs[c], s, 0, 0, 0);
-                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(oa, vfs[c], dp, 0, 0, 0);
+                sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kfs[c], sa, 0, 0, 0);
+                if (DK) {
+                    const bf16x8 oa = *(const bf16x8 *)(&Os[(32 * mb + l32) * RS + 16 * c + 8 * g]);
+                    da = __builtin_amdgcn_mfma_f32_32x32x16_bf16(oa, vfs[c], da, 0, 0, 0);
+                }
             }
             // register e of the accumulator is row 8 (e / 4) + 4 g + e % 4 of the block
-            float p16[16], d16[16];
+            float x16[16];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const f32x4 l4 = *(const f32x4 *)(&s_lse[32 * mb + 8 * j + 4 * g]);
-                const f32x4 t4 = *(const f32x4 *)(&s_dlt[32 * mb + 8 * j + 4 * g]);
+                f32x4 t4 = {0.f, 0.f, 0.f, 0.f};
+                if (DK) t4 = *(const f32x4 *)(&s_dlt[32 * mb + 8 * j + 4 * g]);
 #pragma unroll
                 for (int w = 0; w < 4; ++w) {
                     const int e = 4 * j + w;
                     const int m = m0 + 32 * mb + 8 * j + 4 * g + w;
                     const bool vis = m < L && kn < L && (!CAUSAL || kn <= m);
-                    const float p = vis ? __builtin_amdgcn_exp2f(s[e] * scale_log2 - l4[w]) : 0.f;
-                    p16[e] = p;
-                    d16[e] = p * (dp[e] - t4[w]);
+                    const float p = vis ? __builtin_amdgcn_exp2f(sa[e] * scale_log2 - l4[w]) : 0.f;
+                    x16[e] = DK ? p * (da[e] - t4[w]) : p;
                 }
             }
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
-                u32x4 a, b;
-                a.x = pack_bf16(p16[8 * half + 0], p16[8 * half + 1]);
-                a.y = pack_bf16(p16[8 * half + 2], p16[8 * half + 3]);
-                a.z = pack_bf16(p16[8 * half + 4], p16[8 * half + 5]);
-                a.w = pack_bf16(p16[8 * half + 6], p16[8 * half + 7]);
-                b.x = pack_bf16(d16[8 * half + 0], d16[8 * half + 1]);
-                b.y = pack_bf16(d16[8 * half + 2], d16[8 * half + 3]);
-                b.z = pack_bf16(d16[8 * half + 4], d16[8 * half + 5]);
-                b.w = pack_bf16(d16[8 * half + 6], d16[8 * half + 7]);
-                pf[2 * mb + half] = __builtin_bit_cast(bf16x8, a);
-                dsf[2 * mb + half] = __builtin_bit_cast(bf16x8, b);
+                u32x4 a;
+                a.x = pack_bf16(x16[8 * half + 0], x16[8 * half + 1]);
+                a.y = pack_bf16(x16[8 * half + 2], x16[8 * half + 3]);
+                a.z = pack_bf16(x16[8 * half + 4], x16[8 * half + 5]);
+                a.w = pack_bf16(x16[8 * half + 6], x16[8 * half + 7]);
+                bf[2 * mb + half] = __builtin_bit_cast(bf16x8, a);
             }
         }
-        // dV^T += dout^T P and dK^T += Q^T dS over the tile's 64 rows (4 groups of 16)
+        // dV^T += dout^T P  or  dK^T += Q^T dS  over the tile's 64 rows (4 groups of 16)
 #pragma unroll
         for (int b = 0; b < NDB; ++b)
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                const bf16x8 ot = *(const bf16x8 *)(&Ot[(32 * b + l32) * TS + 16 * t + 8 * g]);
-                const bf16x8 qt = *(const bf16x8 *)(&Qt[(32 * b + l32) * TS + 16 * t + 8 * g]);
-                acc_v[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ot, pf[t], acc_v[b], 0, 0, 0);
-                acc_k[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt, dsf[t], acc_k[b], 0, 0, 0);
+                const bf16x8 xt = *(const bf16x8 *)(&Xt[(32 * b + l32) * TS + 16 * t + 8 * g]);
+                acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xt, bf[t], acc[b], 0, 0, 0);
             }
     }
 
     if (kn < L) {
-        uint16_t *kp = dk + ((size_t)(row0 + kn) * Hkv + g_kv) * HD;
-        uint16_t *vp = dv + ((size_t)(row0 + kn) * Hkv + g_kv) * HD;
+        const float f = DK ? scale : 1.0f;
+        uint16_t *op = dkv + ((size_t)(row0 + kn) * Hkv + g_kv) * HD;
 #pragma unroll
         for (int b = 0; b < NDB; ++b)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 u32x2 w;
-                w.x = pack_bf16(acc_k[b][4 * r] * scale, acc_k[b][4 * r + 1] * scale);
-                w.y = pack_bf16(acc_k[b][4 * r + 2] * scale, acc_k[b][4 * r + 3] * scale);
-                *(u32x2 *)(kp + 32 * b + 8 * r + 4 * g) = w;
-                w.x = pack_bf16(acc_v[b][4 * r], acc_v[b][4 * r + 1]);
-                w.y = pack_bf16(acc_v[b][4 * r + 2], acc_v[b][4 * r + 3]);
-                *(u32x2 *)(vp + 32 * b + 8 * r + 4 * g) = w;
+                w.x = pack_bf16(acc[b][4 * r] * f, acc[b][4 * r + 1] * f);
+                w.y = pack_bf16(acc[b][4 * r + 2] * f, acc[b][4 * r + 3] * f);
+                *(u32x2 *)(op + 32 * b + 8 * r + 4 * g) = w;
             }
     }
 }
@@ -574,8 +580,10 @@ int launch_attn_bwd(const void *q, const void *k, const void *v, const void *out
                            (const uint16_t *)dout, (const uint16_t *)out, w.delta, (int64_t)total_tokens, Hq);    \
         hipLaunchKernelGGL((attn_bwd_dq_kernel<HD_, C_>), dim3(qgrid), dim3(kThreads), 0, stream,                 \
                            ORCH_BWD_COMMON, (uint16_t *)dq, ORCH_BWD_TAIL);                                       \
-        hipLaunchKernelGGL((attn_bwd_dkv_kernel<HD_, C_>), dim3(kgrid), dim3(kThreads), 0, stream,                \
-                           ORCH_BWD_COMMON, (uint16_t *)dk, (uint16_t *)dv, ORCH_BWD_TAIL);                       \
+        hipLaunchKernelGGL((attn_bwd_dkv_kernel<HD_, C_, PART_DK>), dim3(kgrid), dim3(kThreads), 0, stream,       \
+                           ORCH_BWD_COMMON, (uint16_t *)dk, ORCH_BWD_TAIL);                                       \
+        hipLaunchKernelGGL((attn_bwd_dkv_kernel<HD_, C_, PART_DV>), dim3(kgrid), dim3(kThreads), 0, stream,       \
+                           ORCH_BWD_COMMON, (uint16_t *)dv, ORCH_BWD_TAIL);                                       \
     } while (0)
         if (d == 128 && causal) ORCH_BWD_LAUNCH(128, true);
         else if (d == 128) ORCH_BWD_LAUNCH(128, false);

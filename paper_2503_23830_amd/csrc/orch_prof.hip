@@ -199,6 +199,35 @@ int main(int argc, char **argv)
     printf("balance %.3f ms | pack %.3f ms %.1f GB/s (%.3e B) | attn %.3f ms %.1f TFLOP/s (%.3e FLOP) [%s]\n", tb, tp,
            pbytes / tp / 1e6, pbytes, ta, flops / ta / 1e9, flops, orch_attn_variant());
 
+    // attention backward on the same instance (forward first, with lse)
+    {
+        float *lse;
+        uint16_t *dout, *dq, *dk, *dv;
+        CK(hipMalloc(&lse, std::max<size_t>((size_t)Ti * Hq, 1) * 4));
+        CK(hipMalloc(&dout, std::max<size_t>(qn, 1) * 2));
+        CK(hipMalloc(&dq, std::max<size_t>(qn, 1) * 2));
+        CK(hipMalloc(&dk, std::max<size_t>(kn, 1) * 2));
+        CK(hipMalloc(&dv, std::max<size_t>(kn, 1) * 2));
+        hipLaunchKernelGGL(fill_bf16, dim3(4096), dim3(256), 0, st, dout, qn, 44ull);
+        size_t wsw = orch_varlen_attn_bwd_workspace(batch, Ti, Hq);
+        void *ws_w;
+        CK(hipMalloc(&ws_w, wsw));
+        OK(orch_varlen_attn_fwd(q, k, v, o, lse, cu_dev, batch, Ti, 0, Hq, Hkv, d, 0.f, causal, ws_a, wsa, st));
+        double tw = 0;
+        for (int s = 0; s < steps + 1; ++s) {
+            CK(hipEventRecord(e0, st));
+            OK(orch_varlen_attn_bwd(q, k, v, o, lse, dout, dq, dk, dv, cu_dev, batch, Ti, 0, Hq, Hkv, d, 0.f, causal,
+                                    ws_w, wsw, st));
+            CK(hipEventRecord(e1, st));
+            CK(hipStreamSynchronize(st));
+            float ms;
+            if (s > 0) { CK(hipEventElapsedTime(&ms, e0, e1)); tw += ms; }
+        }
+        tw /= steps;
+        // five products of 2 * d flop per visible pair and q-head (the forward pass has two)
+        printf("attn_bwd %.3f ms %.1f TFLOP/s (%.3e FLOP)\n", tw, 2.5 * flops / tw / 1e9, 2.5 * flops);
+    }
+
     // rearrangement composition (Sec. 5.3): the same rows, now three modality buffers in
     // their encoders' packed order (text in original order), composed into the LLM batch
     if (split_path && pack_all) {
