@@ -8,8 +8,10 @@ Inputs are resident in HBM before the timed region.  Default workload: C4 (LLM
 phase with modality-composition incoherence), the configuration the targets are
 stated on.  After the timed steps the rearrangement composition (orch_pack_composed,
 three modality buffers into the same packed batch) is timed and checked on its own and
-reported under "composed_pack", and Algorithm 2 (orch_balance_padded) under "balance_padded", the appendix's third algorithm
-(orch_balance_tolerance) under "balance_tolerance"; none of them is part of `value` or `ms_per_step`.
+reported under "composed_pack"; attention backward (orch_varlen_attn_bwd) under "attn_bwd",
+Algorithm 2 (orch_balance_padded) under "balance_padded", the appendix's third algorithm
+(orch_balance_tolerance) under "balance_tolerance" and the communication-volume matrix under
+"comm_volume"; none of them is part of `value` or `ms_per_step`.
 Prints ONE JSON line.
 """
 from __future__ import annotations
@@ -165,6 +167,22 @@ def main():
     attn_before_ms = bev[0].elapsed_time(bev[1]) / 3
     flops_before = attn_flops(cu_b, w.Hq, w.d, w.causal)
     del qb, kb, vb, ob
+
+    # ---------------- attention backward on the same instance, outside the timed step ---------
+    lse_b = torch.zeros((w.Hq, T_i), dtype=torch.float32, device=dev)
+    orch.varlen_attn_fwd(q, k, v, cu_view, w.causal, out=out, lse=lse_b, ws=ws_attn)
+    dout = wl.normal_bf16_torch((T_i, w.Hq, w.d), base_seed, 7, dev)
+    dq_b, dk_b, dv_b = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    ws_bwd = torch.empty(orch.varlen_attn_bwd_workspace(batch_i, T_i, w.Hq), dtype=torch.uint8, device=dev)
+    bwd = lambda: orch.varlen_attn_bwd(q, k, v, out, lse_b, dout, cu_view, w.causal, dq=dq_b, dk=dk_b, dv=dv_b, ws=ws_bwd)
+    bwd()
+    wev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    wev[0].record()
+    for _ in range(3):
+        bwd()
+    wev[1].record()
+    torch.cuda.synchronize()
+    bwd_ms = wev[0].elapsed_time(wev[1]) / 3
 
     if args.calib_copy:
         ca = torch.zeros(1 << 29, dtype=torch.int16, device=dev)
@@ -363,6 +381,28 @@ def main():
     err = np.abs(got.float().cpu().numpy().astype(np.float64) - want)
     ok &= bool(err.max() <= 2e-2 and err.mean() <= 2e-3)
 
+    # backward parity sample: two whole (sequence, kv-head) units the oracle can afford
+    group = w.Hq // w.Hkv
+    small = nz[np.argsort(lens_i[nz], kind="stable")]
+    small = small[lens_i[small] <= 1536]
+    bwd_ok, bwd_units = True, []
+    dh = bits(dout)
+    for t_u, g_u in ((int(small[0]), 0), (int(small[-1]), w.Hkv - 1)) if len(small) else ():
+        r0, r1 = int(cu_i[t_u]), int(cu_i[t_u + 1])
+        wq, wk, wv = oracle.attn_bwd_unit(qh, kh, vh, dh, r0, r1, g_u, w.causal, nthreads=cores)
+        for got, want in ((dq_b[r0:r1, g_u * group: (g_u + 1) * group], wq), (dk_b[r0:r1, g_u], wk), (dv_b[r0:r1, g_u], wv)):
+            e = np.abs(got.float().cpu().numpy().astype(np.float64) - want)
+            rms = float(np.sqrt((want ** 2).mean()))
+            bwd_ok &= bool(e.max() <= 1e-2 + 2.0 ** -7 * np.abs(want).max() and e.mean() <= 2e-3
+                           and np.sqrt((e ** 2).mean()) <= 5e-3 * rms)
+        bwd_units.append([t_u, g_u, r1 - r0])
+    ok &= bwd_ok
+    bwd_flops = 2.5 * flops  # five products of 2*d flop per visible pair and q-head; the forward pass has two
+    attn_bwd = {"ms": bwd_ms, "tflops": bwd_flops / (bwd_ms * 1e-3) / 1e12,
+                "frac_mfma_peak": bwd_flops / (bwd_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "flop": bwd_flops,
+                "verified": bool(bwd_ok), "oracle_units_seq_kvhead_len": bwd_units,
+                "note": "delta + dq + dk + dv kernels, deterministic; executes 8 products (S three times, dP twice) for the 5 counted"}
+
     cpu_baseline = None
     if not args.no_cpu_baseline:
         tt = time.perf_counter()
@@ -428,6 +468,7 @@ def main():
                  "variant": orch.attn_variant(),
                  "straggler_before_balancing": {"instance": i_before, "tokens": T_b, "ms": attn_before_ms,
                                                 "tflops": flops_before / (attn_before_ms * 1e-3) / 1e12}},
+        "attn_bwd": attn_bwd,
         "pack": {"GBps": pack_gbps, "frac_hbm_peak": pack_gbps / HBM_PEAK_GBPS, "ms": pack_ms, "bytes": pack_bytes},
         "composed_pack": composed,
         "balance_padded": padded,
