@@ -462,6 +462,24 @@ def main():
             "dispatch_sample": "whole config, 1 core (cost, stable merge sort, linear-scan greedy, layout)",
         }
 
+    # what the matrix cores sustain on MFMAs alone on this machine (a child process; about 0.5 s)
+    ceiling = None
+    ceil_bin = os.path.join(ROOT, "paper_2503_23830_amd", "mfma_ceiling")
+    if os.path.exists(ceil_bin):
+        import subprocess
+        try:
+            txt = subprocess.run([ceil_bin, "60"], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True,
+                                 timeout=60).stdout
+            last = {}
+            for line in txt.splitlines():
+                if "TFLOP/s" in line:
+                    last[line.split()[0]] = float(line.split()[-2])
+            ceiling = {"ones_operands_tflops": last.get("ones"), "random_operands_tflops": last.get("random"),
+                       "note": "v_mfma_f32_32x32x16_bf16 only, 8 wavefronts per SIMD, about 60 ms per run; "
+                               "N(0,1) operands are power-limited well below the 2.5 PFLOP/s nominal peak"}
+        except Exception as exc:  # the microbenchmark is context, never a reason to fail the bench
+            ceiling = {"error": str(exc)}
+
     # ---------------- rooflines: the longest kernel of the step, and the other one -----
     traffic = {}
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
@@ -473,7 +491,9 @@ def main():
     roof_attn = {"kernel": "attention forward, head_dim %d, %s (%s)" % (w.d, "causal" if w.causal else "full", orch.attn_variant()),
                  "bound": "mfma", "achieved": attn_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                  "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic.get("attn"),
-                 "launch_ms": attn_ms, "flop_per_launch": flops}
+                 "launch_ms": attn_ms, "flop_per_launch": flops, "mfma_only_ceiling": ceiling,
+                 "frac_of_measured_random_operand_ceiling":
+                     (attn_tflops / ceiling["random_operands_tflops"]) if ceiling and ceiling.get("random_operands_tflops") else None}
     roof_pack = {"kernel": "pack_copy_kernel", "bound": "hbm", "achieved": pack_gbps, "peak": HBM_PEAK_GBPS,
                  "unit": "GB/s", "frac": pack_gbps / HBM_PEAK_GBPS, "traffic": traffic.get("pack"),
                  "launch_ms": pack_ms, "bytes_per_launch": pack_bytes}

@@ -9,6 +9,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB_PATH = os.path.join(PKG, "liborch.so")
 PROF_PATH = os.path.join(PKG, "orch_prof")
+CEIL_PATH = os.path.join(PKG, "mfma_ceiling")
 SOURCES = ["api.hip", "balance.hip", "pack.hip", "attn.hip", "attn_bwd.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -45,6 +46,14 @@ def build_library(verbose: bool = False) -> str:
         print(" ".join(prof), flush=True)
     _run(prof)
     os.replace(PROF_PATH + ".tmp", PROF_PATH)
+    # MFMA-only microbenchmark: the ceiling the attention rooflines are read against
+    ceil = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Wno-unused-command-line-argument",
+            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-o", CEIL_PATH + ".tmp",
+            os.path.join(CSRC, "mfma_ceiling.hip")]
+    if verbose:
+        print(" ".join(ceil), flush=True)
+    _run(ceil)
+    os.replace(CEIL_PATH + ".tmp", CEIL_PATH)
     return LIB_PATH
 
 
