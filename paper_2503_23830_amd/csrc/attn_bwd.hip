@@ -34,7 +34,35 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
 
+// A-operand fragment of X^T (row M = a column of X, contraction over 16 rows of X) read from
+// the ROW-MAJOR tile X[row][col] with two ds_read_b64_tr_b16: inside a block of 16 lanes, lane i
+// receives element i % 4 of the 8-byte words addressed by lanes i / 4, 4 + i / 4, 8 + i / 4 and
+// 12 + i / 4.  Lane (g, half, j4, a) = (lane / 32, (lane / 16) % 2, (lane % 16) / 4, lane % 4)
+// addresses row 4 g + j4 and columns 16 half + 4 a .. + 3, so it receives rows 4 g .. 4 g + 3 of
+// column 16 half + (lane % 16) = lane % 32; a second read 8 rows further completes the 8
+// contraction slots of the lane (rows 4 g + w and 8 + 4 g + w: the rows its registers 0..7 of a
+// 32x32 accumulator hold).  `base` = byte address in LDS of X[first row of the 16][first column
+// of the 32]; `stride_b` = bytes per row.
+__device__ __forceinline__ uint32_t tr_lane_offset(int lane, int stride_b)
+{
+    const int g = lane >> 5, half = (lane >> 4) & 1, j4 = (lane & 15) >> 2, a = lane & 3;
+    return (uint32_t)((4 * g + j4) * stride_b + 2 * (16 * half + 4 * a));
+}
+
+__device__ __forceinline__ bf16x8 lds_read_tr(uint32_t addr, int stride_b)
+{
+    const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(uintptr_t)addr);
+    const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) s16x4 *)(uintptr_t)(addr + 8u * (uint32_t)stride_b));
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+#ifndef ORCH_BWD_PF
+#define ORCH_BWD_PF 1
+#endif
 constexpr int kT = 64;          // rows of a streamed LDS tile (keys for dq, queries for dk/dv)
 constexpr int kOwn = 128;       // rows a workgroup owns (queries for dq, keys for dk/dv)
 constexpr int kThreads = 256;
@@ -141,21 +169,15 @@ __device__ __forceinline__ void block_to_tile(int bid, int heads, int Hkv, int g
     }
 }
 
-// Staging of one 64-row tile of a [T, heads, HD] tensor: row-major (16-byte vectors) and
-// transposed (4 x 4 blocks turned in registers).  In the transposed copy row
-// m = 16t + 8u + 4g + w sits at slot 16t + 8g + 4u + w, so that the 8 rows one lane of an
-// MFMA contracts (its registers 0..7 or 8..15 of a 32x32 accumulator) are contiguous.
+// Staging of one 64-row tile of a [T, heads, HD] tensor, row-major with a padded stride (16-byte
+// vectors through registers; the loads of the next tile are in flight during the products).
 template <int HD>
 struct TileStage {
     static constexpr int RS = HD + 8;                          // row-major stride (elements)
-    static constexpr int TS = kT + 8;                          // transposed stride
     static constexpr int ROWS_PER_PASS = kThreads / (HD / 8);
     static constexpr int PASS = kT / ROWS_PER_PASS;
-    static constexpr int TBLK = (kT / 4) * (HD / 4) / kThreads;
-    static_assert(TBLK * (kThreads / 8 / (HD / 4)) * 8 == kT / 4, "transposed staging must cover the tile");
 
     u32x4 rreg[PASS];
-    u32x2 treg[TBLK][4];
 
     // rows [m0, m0 + 64) of the sequence that starts at row0 and has L rows (clamped), head hd
     __device__ __forceinline__ void load_rows(const uint16_t *__restrict__ src, int row0, int L, int m0, int heads,
@@ -175,44 +197,6 @@ struct TileStage {
 #pragma unroll
         for (int p = 0; p < PASS; ++p) *(u32x4 *)(&lds[(p * ROWS_PER_PASS + r) * RS + col]) = rreg[p];
     }
-    __device__ __forceinline__ void load_transposed(const uint16_t *__restrict__ src, int row0, int L, int m0,
-                                                    int heads, int hd)
-    {
-        const int tid = threadIdx.x;
-        const int nq0 = tid & 7, dq = (tid >> 3) % (HD / 4), nqhi = (tid >> 3) / (HD / 4);
-#pragma unroll
-        for (int b = 0; b < TBLK; ++b) {
-            const int nq = nq0 + 8 * (nqhi + b * (kThreads / 8 / (HD / 4)));
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                int m = m0 + 4 * nq + j;
-                m = m < L ? m : L - 1;
-                treg[b][j] = *(const u32x2 *)(src + ((size_t)(row0 + m) * heads + hd) * HD + 4 * dq);
-            }
-        }
-    }
-    __device__ __forceinline__ void store_transposed(uint16_t *lds) const
-    {
-        const int tid = threadIdx.x;
-        const int nq0 = tid & 7, dq = (tid >> 3) % (HD / 4), nqhi = (tid >> 3) / (HD / 4);
-#pragma unroll
-        for (int b = 0; b < TBLK; ++b) {
-            const int nq = nq0 + 8 * (nqhi + b * (kThreads / 8 / (HD / 4)));
-            const int slot = 16 * (nq >> 2) + 8 * (nq & 1) + 4 * ((nq >> 1) & 1);
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
-                const uint32_t a0 = (c & 2) ? treg[b][0].y : treg[b][0].x;
-                const uint32_t a1 = (c & 2) ? treg[b][1].y : treg[b][1].x;
-                const uint32_t a2 = (c & 2) ? treg[b][2].y : treg[b][2].x;
-                const uint32_t a3 = (c & 2) ? treg[b][3].y : treg[b][3].x;
-                u32x2 w;
-                w.x = __builtin_amdgcn_perm(a1, a0, sel);
-                w.y = __builtin_amdgcn_perm(a3, a2, sel);
-                *(u32x2 *)(&lds[(4 * dq + c) * TS + slot]) = w;
-            }
-        }
-    }
 };
 
 // ---------------------------------------------------------------------------
@@ -227,11 +211,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
     float scale, float scale_log2)
 {
     using Stage = TileStage<HD>;
-    constexpr int RS = Stage::RS, TS = Stage::TS;
+    constexpr int RS = Stage::RS;
     constexpr int NC = HD / 16, NDB = HD / 32;
     __shared__ __attribute__((aligned(16))) uint16_t Ks[kT * RS];
     __shared__ __attribute__((aligned(16))) uint16_t Vs[kT * RS];
-    __shared__ __attribute__((aligned(16))) uint16_t Kt[HD * TS];
 
     const int total_tiles = hdr->total_tiles;
     const int group = Hq / Hkv;
@@ -277,28 +260,37 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
     const int kend = CAUSAL ? min(L, q0 + kOwn) : L;
     const int ntile_k = (kend + kT - 1) / kT;
 
+    // K^T fragments of the last product come straight from the row-major K tile
+    const uint32_t kt_base = (uint32_t)(uintptr_t)Ks + tr_lane_offset(lane, 2 * RS);
     Stage sk, sv;
     sk.load_rows(k, row0, L, 0, Hkv, g_kv);
-    sk.load_transposed(k, row0, L, 0, Hkv, g_kv);
     sv.load_rows(v, row0, L, 0, Hkv, g_kv);
     for (int it = 0; it < ntile_k; ++it) {
         const int n0 = it * kT;
         __syncthreads();
         sk.store_rows(Ks);
-        sk.store_transposed(Kt);
         sv.store_rows(Vs);
         __syncthreads();
         if (it + 1 < ntile_k) {
             sk.load_rows(k, row0, L, n0 + kT, Hkv, g_kv);
-            sk.load_transposed(k, row0, L, n0 + kT, Hkv, g_kv);
             sv.load_rows(v, row0, L, n0 + kT, Hkv, g_kv);
         }
         if (CAUSAL && n0 > q0 + 32 * wave + 31) continue;  // this wavefront's rows see none of the tile
 
         // per 32-key block: S^T = K Q^T and dP^T = V dout^T, then dS^T = P^T (dP^T - delta),
-        // rounded to bf16 in the B-operand layout
+        // rounded to bf16 in the B-operand layout.  Fragment reads run PF steps ahead of the MFMAs
+        // that use them (explicitly: left alone the compiler reuses one pair of fragment registers
+        // and every MFMA waits out a full LDS latency); the fences keep that order.
         const bool need_mask = (n0 + kT > L) || (CAUSAL && n0 + kT - 1 > q0 + 32 * wave);
+        constexpr int PF = ORCH_BWD_PF;
+        auto rd_k = [&](int nb, int c) { return *(const bf16x8 *)(&Ks[(32 * nb + l32) * RS + 16 * c + 8 * g]); };
+        auto rd_v = [&](int nb, int c) { return *(const bf16x8 *)(&Vs[(32 * nb + l32) * RS + 16 * c + 8 * g]); };
+        // step j = 4 b + kk of the last product: keys 16 kk .. + 15 of the tile, head-dim columns 32 b .. + 31
+        auto rd_t = [&](int j) { return lds_read_tr(kt_base + (uint32_t)(16 * (j & 3) * 2 * RS + 2 * 32 * (j >> 2)), 2 * RS); };
         bf16x8 dsf[4];
+        bf16x8 kq[PF + 1], vq[PF + 1], tq[PF + 1];
+#pragma unroll
+        for (int i = 0; i < PF; ++i) { kq[i] = rd_k(0, i); vq[i] = rd_v(0, i); }
 #pragma unroll
         for (int nb = 0; nb < 2; ++nb) {
             f32x16 sa, da;
@@ -306,10 +298,17 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
             for (int e = 0; e < 16; ++e) { sa[e] = 0.f; da[e] = 0.f; }
 #pragma unroll
             for (int c = 0; c < NC; ++c) {
-                const bf16x8 kf = *(const bf16x8 *)(&Ks[(32 * nb + l32) * RS + 16 * c + 8 * g]);
-                const bf16x8 vf = *(const bf16x8 *)(&Vs[(32 * nb + l32) * RS + 16 * c + 8 * g]);
-                sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[c], sa, 0, 0, 0);
-                da = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[c], da, 0, 0, 0);
+                const int sn = NC * nb + c + PF;  // the step fetched now
+                if (sn < 2 * NC) {
+                    kq[sn % (PF + 1)] = rd_k(sn / NC, sn % NC);
+                    vq[sn % (PF + 1)] = rd_v(sn / NC, sn % NC);
+                } else {
+                    tq[(sn - 2 * NC) % (PF + 1)] = rd_t(sn - 2 * NC);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kq[(NC * nb + c) % (PF + 1)], qf[c], sa, 0, 0, 0);
+                da = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vq[(NC * nb + c) % (PF + 1)], dof[c], da, 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
             }
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
@@ -336,12 +335,12 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
         }
         // dQ^T += K^T dS^T
 #pragma unroll
-        for (int b = 0; b < NDB; ++b)
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                const bf16x8 ktf = *(const bf16x8 *)(&Kt[(32 * b + l32) * TS + 16 * kk + 8 * g]);
-                acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf, dsf[kk], acc[b], 0, 0, 0);
-            }
+        for (int j = 0; j < 4 * NDB; ++j) {
+            if (j + PF < 4 * NDB) tq[(j + PF) % (PF + 1)] = rd_t(j + PF);
+            __builtin_amdgcn_sched_barrier(0);
+            acc[j >> 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq[j % (PF + 1)], dsf[j & 3], acc[j >> 2], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
 
     if (qm < L) {
@@ -378,11 +377,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(
 {
     constexpr bool DK = PART == PART_DK;
     using Stage = TileStage<HD>;
-    constexpr int RS = Stage::RS, TS = Stage::TS;
+    constexpr int RS = Stage::RS;
     constexpr int NC = HD / 16, NDB = HD / 32;
-    __shared__ __attribute__((aligned(16))) uint16_t Qs[kT * RS];            // Q, row-major
-    __shared__ __attribute__((aligned(16))) uint16_t Os[DK ? kT * RS : 8];   // dout, row-major (dK)
-    __shared__ __attribute__((aligned(16))) uint16_t Xt[HD * TS];            // Q (dK) or dout (dV), transposed
+    __shared__ __attribute__((aligned(16))) uint16_t Qs[kT * RS];   // Q, row-major
+    __shared__ __attribute__((aligned(16))) uint16_t Os[kT * RS];   // dout, row-major
     __shared__ __attribute__((aligned(16))) float s_lse[kT];                 // lse * log2(e) of the tile's rows
     __shared__ __attribute__((aligned(16))) float s_dlt[kT];
 
@@ -427,18 +425,15 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(
     const int ntile_m = m_begin < L ? (L - m_begin + kT - 1) / kT : 0;
     const int steps = ntile_m * group;
 
+    // Q^T (dK) or dout^T (dV) fragments of the last product come straight from the row-major tile
+    const uint32_t xt_base = (uint32_t)(uintptr_t)(DK ? Qs : Os) + tr_lane_offset(lane, 2 * RS);
     Stage sq, so;
     float r_lse = 0.f, r_dlt = 0.f;
     auto load_step = [&](int st) {
         const int h = g_kv * group + st / ntile_m;
         const int m0 = m_begin + (st % ntile_m) * kT;
         sq.load_rows(q, row0, L, m0, Hq, h);
-        if (DK) {
-            sq.load_transposed(q, row0, L, m0, Hq, h);
-            so.load_rows(dout, row0, L, m0, Hq, h);
-        } else {
-            so.load_transposed(dout, row0, L, m0, Hq, h);
-        }
+        so.load_rows(dout, row0, L, m0, Hq, h);
         if (tid < kT) {
             int m = m0 + tid;
             m = m < L ? m : L - 1;
@@ -451,18 +446,25 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(
         const int m0 = m_begin + (st % ntile_m) * kT;
         __syncthreads();
         sq.store_rows(Qs);
-        if (DK) {
-            sq.store_transposed(Xt);
-            so.store_rows(Os);
-        } else {
-            so.store_transposed(Xt);
-        }
+        so.store_rows(Os);
         if (tid < kT) { s_lse[tid] = r_lse; s_dlt[tid] = r_dlt; }
         __syncthreads();
         if (st + 1 < steps) load_step(st + 1);
         if (CAUSAL && m0 + kT - 1 < n0w) continue;  // every row of the tile lies before this wavefront's keys
 
+        // Fragment reads run PF steps ahead of the MFMAs that use them; the fences keep that order.
+        constexpr int PF = ORCH_BWD_PF;
+        auto rd_q = [&](int mb, int c) { return *(const bf16x8 *)(&Qs[(32 * mb + l32) * RS + 16 * c + 8 * g]); };
+        auto rd_o = [&](int mb, int c) { return *(const bf16x8 *)(&Os[(32 * mb + l32) * RS + 16 * c + 8 * g]); };
+        // step j = 4 b + t of the last product: rows 16 t .. + 15 of the tile, head-dim columns 32 b .. + 31
+        auto rd_t = [&](int j) { return lds_read_tr(xt_base + (uint32_t)(16 * (j & 3) * 2 * RS + 2 * 32 * (j >> 2)), 2 * RS); };
         bf16x8 bf[4];  // P (dV) or dS (dK) of the tile's 64 rows, B-operand layout
+        bf16x8 qq[PF + 1], oq[DK ? PF + 1 : 1], tq[PF + 1];
+#pragma unroll
+        for (int i = 0; i < PF; ++i) {
+            qq[i] = rd_q(0, i);
+            if (DK) oq[i] = rd_o(0, i);
+        }
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb) {
             // S = Q K^T (and dP = dout V^T) for 32 rows x this wavefront's 32 keys
@@ -471,12 +473,17 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(
             for (int e = 0; e < 16; ++e) { sa[e] = 0.f; da[e] = 0.f; }
 #pragma unroll
             for (int c = 0; c < NC; ++c) {
-                const bf16x8 qa = *(const bf16x8 *)(&Qs[(32 * mb + l32) * RS + 16 * c + 8 * g]);
-                sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kfs[c], sa, 0, 0, 0);
-                if (DK) {
-                    const bf16x8 oa = *(const bf16x8 *)(&Os[(32 * mb + l32) * RS + 16 * c + 8 * g]);
-                    da = __builtin_amdgcn_mfma_f32_32x32x16_bf16(oa, vfs[c], da, 0, 0, 0);
+                const int sn = NC * mb + c + PF;  // the step fetched now
+                if (sn < 2 * NC) {
+                    qq[sn % (PF + 1)] = rd_q(sn / NC, sn % NC);
+                    if (DK) oq[sn % (PF + 1)] = rd_o(sn / NC, sn % NC);
+                } else {
+                    tq[(sn - 2 * NC) % (PF + 1)] = rd_t(sn - 2 * NC);
                 }
+                __builtin_amdgcn_sched_barrier(0);
+                sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qq[(NC * mb + c) % (PF + 1)], kfs[c], sa, 0, 0, 0);
+                if (DK) da = __builtin_amdgcn_mfma_f32_32x32x16_bf16(oq[(NC * mb + c) % (PF + 1)], vfs[c], da, 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
             }
             // register e of the accumulator is row 8 (e / 4) + 4 g + e % 4 of the block
             float x16[16];
@@ -506,12 +513,12 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(
         }
         // dV^T += dout^T P  or  dK^T += Q^T dS  over the tile's 64 rows (4 groups of 16)
 #pragma unroll
-        for (int b = 0; b < NDB; ++b)
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const bf16x8 xt = *(const bf16x8 *)(&Xt[(32 * b + l32) * TS + 16 * t + 8 * g]);
-                acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xt, bf[t], acc[b], 0, 0, 0);
-            }
+        for (int j = 0; j < 4 * NDB; ++j) {
+            if (j + PF < 4 * NDB) tq[(j + PF) % (PF + 1)] = rd_t(j + PF);
+            __builtin_amdgcn_sched_barrier(0);
+            acc[j >> 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq[j % (PF + 1)], bf[j & 3], acc[j >> 2], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
 
     if (kn < L) {
