@@ -169,33 +169,175 @@ __device__ __forceinline__ void block_to_tile(int bid, int heads, int Hkv, int g
     }
 }
 
-// Staging of one 64-row tile of a [T, heads, HD] tensor, row-major with a padded stride (16-byte
-// vectors through registers; the loads of the next tile are in flight during the products).
+__device__ __forceinline__ bf16x8 lds_rd128(uint32_t addr)
+{
+    return *(const __attribute__((address_space(3))) bf16x8 *)(uintptr_t)addr;
+}
+__device__ __forceinline__ void lds_wr128(uint32_t addr, u32x4 val)
+{
+    *(__attribute__((address_space(3))) u32x4 *)(uintptr_t)addr = val;
+}
+
+// Where a pair of 64-row tiles comes from: rows [m0, m0 + 64) of the sequence that starts at
+// row0 and has L rows, head hd of two [T, heads, HD] tensors (K and V, or Q and dout).
+struct TileSrc {
+    const uint16_t *px, *py;
+    int row0, L, m0, heads, hd;
+};
+
+// The pair of streamed LDS tiles of a step (X: K or Q, Y: V or dout) and the fragment reads on
+// them.  Two forms.
+//   Register-staged (any head_dim): rows go global -> registers -> LDS with a padded stride; the
+//   loads of the next pair are in flight during the products, two barriers per step.  Row reads
+//   are conflict-free, the transpose reads two-way conflicted.
+//   LDS-DMA (head_dim 128): rows go straight from global memory into LDS (no registers, no LDS
+//   store instructions), two stages, one barrier per step.  Rows are 256 bytes without padding;
+//   row r keeps its 16-byte chunk c at slot c ^ swz(r), swz(r) = 4 (r % 4) + (r / 4) % 4, which
+//   makes BOTH read patterns conflict-free: 16 consecutive rows at one chunk hit 16 slots, and the
+//   4 rows x 4 chunks a half-wavefront transposes hit 16 slots.
+template <int HD, bool DMA>
+struct PairStage;
+
 template <int HD>
-struct TileStage {
-    static constexpr int RS = HD + 8;                          // row-major stride (elements)
+struct PairStage<HD, false> {
+    static constexpr int ROWB = (HD + 8) * 2;
+    static constexpr int TILE_B = kT * ROWB;
+    static constexpr int BYTES = 2 * TILE_B;
     static constexpr int ROWS_PER_PASS = kThreads / (HD / 8);
     static constexpr int PASS = kT / ROWS_PER_PASS;
+    uint32_t base, rlane, tlane;
+    u32x4 xr[PASS], yr[PASS];
 
-    u32x4 rreg[PASS];
-
-    // rows [m0, m0 + 64) of the sequence that starts at row0 and has L rows (clamped), head hd
-    __device__ __forceinline__ void load_rows(const uint16_t *__restrict__ src, int row0, int L, int m0, int heads,
-                                              int hd)
+    __device__ __forceinline__ void init(uint32_t lds_base, int lane, int wave)
     {
+        (void)wave;
+        base = lds_base;
+        rlane = (uint32_t)((lane & 31) * ROWB + 16 * (lane >> 5));
+        tlane = tr_lane_offset(lane, ROWB);
+    }
+    __device__ __forceinline__ uint32_t x_base(int it) const { (void)it; return base; }
+    __device__ __forceinline__ uint32_t y_base(int it) const { (void)it; return base + TILE_B; }
+    // A operand, rows 32 blk .. + 31 of the tile, contraction chunk c (16 columns)
+    __device__ __forceinline__ bf16x8 rd_row(uint32_t tile, int blk, int c) const
+    {
+        return lds_rd128(tile + rlane + (uint32_t)(blk * 32 * ROWB + 32 * c));
+    }
+    // A operand of the transposed tile, step j = 4 b + t: rows 16 t .. + 15, columns 32 b .. + 31
+    __device__ __forceinline__ bf16x8 rd_tr(uint32_t tile, int j) const
+    {
+        return lds_read_tr(tile + tlane + (uint32_t)(16 * (j & 3) * ROWB + 64 * (j >> 2)), ROWB);
+    }
+    __device__ __forceinline__ void begin(const TileSrc &s, int it)
+    {
+        (void)it;
         const int col = (threadIdx.x % (HD / 8)) * 8, r = threadIdx.x / (HD / 8);
 #pragma unroll
         for (int p = 0; p < PASS; ++p) {
-            int m = m0 + p * ROWS_PER_PASS + r;
-            m = m < L ? m : L - 1;
-            rreg[p] = *(const u32x4 *)(src + ((size_t)(row0 + m) * heads + hd) * HD + col);
+            int m = s.m0 + p * ROWS_PER_PASS + r;
+            m = m < s.L ? m : s.L - 1;
+            const size_t e = ((size_t)(s.row0 + m) * s.heads + s.hd) * HD + col;
+            xr[p] = *(const u32x4 *)(s.px + e);
+            yr[p] = *(const u32x4 *)(s.py + e);
         }
     }
-    __device__ __forceinline__ void store_rows(uint16_t *lds) const
+    __device__ __forceinline__ void publish()
     {
         const int col = (threadIdx.x % (HD / 8)) * 8, r = threadIdx.x / (HD / 8);
+        __syncthreads();
 #pragma unroll
-        for (int p = 0; p < PASS; ++p) *(u32x4 *)(&lds[(p * ROWS_PER_PASS + r) * RS + col]) = rreg[p];
+        for (int p = 0; p < PASS; ++p) {
+            const uint32_t o = (uint32_t)((p * ROWS_PER_PASS + r) * ROWB + 2 * col);
+            lds_wr128(base + o, xr[p]);
+            lds_wr128(base + TILE_B + o, yr[p]);
+        }
+        __syncthreads();
+    }
+};
+
+__device__ __forceinline__ int swz128(int r) { return 4 * (r & 3) + ((r >> 2) & 3); }
+
+template <>
+struct PairStage<128, true> {
+    static constexpr int HD = 128;
+    static constexpr int ROWB = 256;
+    static constexpr int TILE_B = kT * ROWB;
+    static constexpr int BYTES = 4 * TILE_B;  // two stages of two tiles
+    uint32_t base;
+    uint32_t raddr[HD / 16];   // row reads: l32 * 256 + 16 * ((2 c + g) ^ swz(l32))
+    uint32_t taddr[2][HD / 32];  // transpose reads, rows 8 u + 4 g + j4, columns of block b
+    uint32_t dcol[4];          // DMA: byte column this lane fetches in load p
+    int drow;                  // DMA: row of the tile this lane fetches in load 0 (load p: + 4 p)
+    uint32_t ddst;             // DMA: LDS offset of this wavefront's first load inside a tile
+
+    __device__ __forceinline__ void init(uint32_t lds_base, int lane, int wave)
+    {
+        base = lds_base;
+        const int l32 = lane & 31, g = lane >> 5;
+#pragma unroll
+        for (int c = 0; c < HD / 16; ++c) raddr[c] = (uint32_t)(l32 * ROWB + 16 * ((2 * c + g) ^ swz128(l32)));
+        const int half = (lane >> 4) & 1, j4 = (lane & 15) >> 2, a = lane & 3;
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int b = 0; b < HD / 32; ++b) {
+                const int r = 8 * u + 4 * g + j4;
+                taddr[u][b] = (uint32_t)(r * ROWB + 16 * ((4 * b + 2 * half + (a >> 1)) ^ swz128(r)) + 8 * (a & 1));
+            }
+        // a DMA load moves 64 lanes x 16 bytes = 4 rows into 1 KB of LDS in lane order; this
+        // wavefront fetches rows 16 wave .. 16 wave + 15 of the tile in four loads
+        drow = 16 * wave + (lane >> 4);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) dcol[p] = 16u * (uint32_t)((lane & 15) ^ swz128(drow + 4 * p));
+        ddst = (uint32_t)(16 * wave * ROWB);
+    }
+    __device__ __forceinline__ uint32_t x_base(int it) const { return base + (uint32_t)((it & 1) * 2 * TILE_B); }
+    __device__ __forceinline__ uint32_t y_base(int it) const { return x_base(it) + TILE_B; }
+    __device__ __forceinline__ bf16x8 rd_row(uint32_t tile, int blk, int c) const
+    {
+        return lds_rd128(tile + raddr[c] + (uint32_t)(blk * 32 * ROWB));
+    }
+    __device__ __forceinline__ bf16x8 rd_tr(uint32_t tile, int j) const
+    {
+        const uint32_t o = tile + (uint32_t)(16 * (j & 3) * ROWB);
+        const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) s16x4 *)(uintptr_t)(o + taddr[0][j >> 2]));
+        const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) s16x4 *)(uintptr_t)(o + taddr[1][j >> 2]));
+        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7));
+    }
+    // One LDS-DMA load: 64 lanes x 16 bytes from scalar base `tb` + per-lane byte offset into the
+    // 1 KB of LDS that starts at `dst` (M0; nothing else here uses M0).  Written as asm so that
+    // the compiler does not tie later LDS reads of the other stage to it; publish() waits for it.
+    static __device__ __forceinline__ void dma_issue(const char *tb, uint32_t off, uint32_t dst)
+    {
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(off), "s"(tb)
+                     : "memory");
+    }
+    static __device__ __forceinline__ const char *uniform_ptr(const void *ptr)
+    {
+        const uint64_t v = (uint64_t)(uintptr_t)ptr;
+        const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
+        const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
+        return (const char *)(uintptr_t)(((uint64_t)hi << 32) | lo);
+    }
+    __device__ __forceinline__ void begin(const TileSrc &s, int it)
+    {
+        const uint32_t rstride = (uint32_t)s.heads * HD * 2;
+        const size_t e = ((size_t)(s.row0 + s.m0) * s.heads + s.hd) * HD;
+        const char *tx = uniform_ptr(s.px + e), *ty = uniform_ptr(s.py + e);
+        const int last = s.L - 1 - s.m0;  // rows past the end of the sequence repeat its last row (masked later)
+        const uint32_t dx = (uint32_t)__builtin_amdgcn_readfirstlane((int)(x_base(it) + ddst));
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const uint32_t off = (uint32_t)min(drow + 4 * p, last) * rstride + dcol[p];
+            dma_issue(tx, off, dx + (uint32_t)(4 * p * ROWB));
+            dma_issue(ty, off, dx + (uint32_t)(TILE_B + 4 * p * ROWB));
+        }
+    }
+    __device__ __forceinline__ void publish()
+    {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
     }
 };
 
@@ -210,11 +352,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
     const int32_t *__restrict__ tile_off, int32_t batch, int32_t total_tokens, int32_t Hq, int32_t Hkv,
     float scale, float scale_log2)
 {
-    using Stage = TileStage<HD>;
-    constexpr int RS = Stage::RS;
+    using PS = PairStage<HD, HD == 128>;
     constexpr int NC = HD / 16, NDB = HD / 32;
-    __shared__ __attribute__((aligned(16))) uint16_t Ks[kT * RS];
-    __shared__ __attribute__((aligned(16))) uint16_t Vs[kT * RS];
+    __shared__ __attribute__((aligned(1024))) char lds_raw[PS::BYTES];
 
     const int total_tiles = hdr->total_tiles;
     const int group = Hq / Hkv;
@@ -232,7 +372,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
     const int ntile_q = (L + kOwn - 1) / kOwn;
     const int q0 = (ntile_q - 1 - (u - tile_off[lo])) * kOwn;  // heaviest (last) tile first
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, g = lane >> 5;
     const int qm = q0 + 32 * wave + l32;
     const int qm_c = qm < L ? qm : L - 1;
@@ -260,22 +401,19 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
     const int kend = CAUSAL ? min(L, q0 + kOwn) : L;
     const int ntile_k = (kend + kT - 1) / kT;
 
-    // K^T fragments of the last product come straight from the row-major K tile
-    const uint32_t kt_base = (uint32_t)(uintptr_t)Ks + tr_lane_offset(lane, 2 * RS);
-    Stage sk, sv;
-    sk.load_rows(k, row0, L, 0, Hkv, g_kv);
-    sv.load_rows(v, row0, L, 0, Hkv, g_kv);
+    PS ps;
+    ps.init((uint32_t)(uintptr_t)lds_raw, lane, wave);
+    TileSrc src{k, v, row0, L, 0, Hkv, g_kv};
+    ps.begin(src, 0);
     for (int it = 0; it < ntile_k; ++it) {
         const int n0 = it * kT;
-        __syncthreads();
-        sk.store_rows(Ks);
-        sv.store_rows(Vs);
-        __syncthreads();
+        ps.publish();
         if (it + 1 < ntile_k) {
-            sk.load_rows(k, row0, L, n0 + kT, Hkv, g_kv);
-            sv.load_rows(v, row0, L, n0 + kT, Hkv, g_kv);
+            src.m0 = n0 + kT;
+            ps.begin(src, it + 1);
         }
         if (CAUSAL && n0 > q0 + 32 * wave + 31) continue;  // this wavefront's rows see none of the tile
+        const uint32_t kb = ps.x_base(it), vb = ps.y_base(it);
 
         // per 32-key block: S^T = K Q^T and dP^T = V dout^T, then dS^T = P^T (dP^T - delta),
         // rounded to bf16 in the B-operand layout.  Fragment reads run PF steps ahead of the MFMAs
@@ -283,14 +421,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
         // and every MFMA waits out a full LDS latency); the fences keep that order.
         const bool need_mask = (n0 + kT > L) || (CAUSAL && n0 + kT - 1 > q0 + 32 * wave);
         constexpr int PF = ORCH_BWD_PF;
-        auto rd_k = [&](int nb, int c) { return *(const bf16x8 *)(&Ks[(32 * nb + l32) * RS + 16 * c + 8 * g]); };
-        auto rd_v = [&](int nb, int c) { return *(const bf16x8 *)(&Vs[(32 * nb + l32) * RS + 16 * c + 8 * g]); };
-        // step j = 4 b + kk of the last product: keys 16 kk .. + 15 of the tile, head-dim columns 32 b .. + 31
-        auto rd_t = [&](int j) { return lds_read_tr(kt_base + (uint32_t)(16 * (j & 3) * 2 * RS + 2 * 32 * (j >> 2)), 2 * RS); };
         bf16x8 dsf[4];
         bf16x8 kq[PF + 1], vq[PF + 1], tq[PF + 1];
 #pragma unroll
-        for (int i = 0; i < PF; ++i) { kq[i] = rd_k(0, i); vq[i] = rd_v(0, i); }
+        for (int i = 0; i < PF; ++i) { kq[i] = ps.rd_row(kb, 0, i); vq[i] = ps.rd_row(vb, 0, i); }
 #pragma unroll
         for (int nb = 0; nb < 2; ++nb) {
             f32x16 sa, da;
@@ -300,10 +434,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
             for (int c = 0; c < NC; ++c) {
                 const int sn = NC * nb + c + PF;  // the step fetched now
                 if (sn < 2 * NC) {
-                    kq[sn % (PF + 1)] = rd_k(sn / NC, sn % NC);
-                    vq[sn % (PF + 1)] = rd_v(sn / NC, sn % NC);
+                    kq[sn % (PF + 1)] = ps.rd_row(kb, sn / NC, sn % NC);
+                    vq[sn % (PF + 1)] = ps.rd_row(vb, sn / NC, sn % NC);
                 } else {
-                    tq[(sn - 2 * NC) % (PF + 1)] = rd_t(sn - 2 * NC);
+                    tq[(sn - 2 * NC) % (PF + 1)] = ps.rd_tr(kb, sn - 2 * NC);  // K^T, from the same K tile
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kq[(NC * nb + c) % (PF + 1)], qf[c], sa, 0, 0, 0);
@@ -333,10 +467,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
                 dsf[2 * nb + half] = __builtin_bit_cast(bf16x8, pk);
             }
         }
-        // dQ^T += K^T dS^T
+        // dQ^T += K^T dS^T, step j = 4 b + kk: keys 16 kk .. + 15 of the tile, head-dim columns 32 b .. + 31
 #pragma unroll
         for (int j = 0; j < 4 * NDB; ++j) {
-            if (j + PF < 4 * NDB) tq[(j + PF) % (PF + 1)] = rd_t(j + PF);
+            if (j + PF < 4 * NDB) tq[(j + PF) % (PF + 1)] = ps.rd_tr(kb, j + PF);
             __builtin_amdgcn_sched_barrier(0);
             acc[j >> 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq[j % (PF + 1)], dsf[j & 3], acc[j >> 2], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
@@ -362,8 +496,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
 // both accumulators needs more than 256 registers per lane, which leaves one wavefront per
 // SIMD and nothing to hide LDS and barrier latency behind; each half fits in 256, so two
 // workgroups share a CU, at the price of recomputing S for the second output.
-//   PART_DV: S -> P,          dV^T += dout^T P      (Q rows, dout transposed)
-//   PART_DK: S, dP -> dS,     dK^T += Q^T dS        (Q rows and transposed, dout rows)
+//   PART_DV: S -> P,          dV^T += dout^T P
+//   PART_DK: S, dP -> dS,     dK^T += Q^T dS
+// Both stream the Q and dout tiles of the group's q-heads; the transposed operand of the last
+// product is read from the same row-major tile (Q for dK, dout for dV).
 // ---------------------------------------------------------------------------
 constexpr int PART_DV = 1, PART_DK = 2;
 
@@ -376,13 +512,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(
     float scale, float scale_log2)
 {
     constexpr bool DK = PART == PART_DK;
-    using Stage = TileStage<HD>;
-    constexpr int RS = Stage::RS;
+    using PS = PairStage<HD, HD == 128>;
     constexpr int NC = HD / 16, NDB = HD / 32;
-    __shared__ __attribute__((aligned(16))) uint16_t Qs[kT * RS];   // Q, row-major
-    __shared__ __attribute__((aligned(16))) uint16_t Os[kT * RS];   // dout, row-major
-    __shared__ __attribute__((aligned(16))) float s_lse[kT];                 // lse * log2(e) of the tile's rows
-    __shared__ __attribute__((aligned(16))) float s_dlt[kT];
+    __shared__ __attribute__((aligned(1024))) char lds_raw[PS::BYTES];
+    __shared__ __attribute__((aligned(16))) float s_lse[2][kT];  // lse * log2(e) of the tile's rows, by step parity
+    __shared__ __attribute__((aligned(16))) float s_dlt[2][kT];
 
     const int total_tiles = hdr->total_tiles;
     const int group = Hq / Hkv;
@@ -398,7 +532,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(
     const int L = cu[lo + 1] - row0;
     const int k0 = (u - tile_off[lo]) * kOwn;  // under a causal mask the first key tile is the heaviest
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, g = lane >> 5;
     const int n0w = k0 + 32 * wave;     // this wavefront's keys
     const int kn = n0w + l32;           // this lane's key (a column of S)
@@ -425,100 +560,104 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(
     const int ntile_m = m_begin < L ? (L - m_begin + kT - 1) / kT : 0;
     const int steps = ntile_m * group;
 
-    // Q^T (dK) or dout^T (dV) fragments of the last product come straight from the row-major tile
-    const uint32_t xt_base = (uint32_t)(uintptr_t)(DK ? Qs : Os) + tr_lane_offset(lane, 2 * RS);
-    Stage sq, so;
+    PS ps;
+    ps.init((uint32_t)(uintptr_t)lds_raw, lane, wave);
+    TileSrc src{q, dout, row0, L, m_begin, Hq, g_kv * group};
     float r_lse = 0.f, r_dlt = 0.f;
-    auto load_step = [&](int st) {
-        const int h = g_kv * group + st / ntile_m;
-        const int m0 = m_begin + (st % ntile_m) * kT;
-        sq.load_rows(q, row0, L, m0, Hq, h);
-        so.load_rows(dout, row0, L, m0, Hq, h);
+    // step st covers head g_kv * group + st / ntile_m, rows m_begin + 64 (st % ntile_m) ..
+    auto start_step = [&](int st) {
+        src.hd = g_kv * group + st / ntile_m;
+        src.m0 = m_begin + (st % ntile_m) * kT;
+        ps.begin(src, st);
         if (tid < kT) {
-            int m = m0 + tid;
+            int m = src.m0 + tid;
             m = m < L ? m : L - 1;
-            r_lse = lse[(size_t)h * total_tokens + row0 + m] * kLog2e;
-            if (DK) r_dlt = delta[(size_t)h * total_tokens + row0 + m];
+            r_lse = lse[(size_t)src.hd * total_tokens + row0 + m] * kLog2e;
+            if (DK) r_dlt = delta[(size_t)src.hd * total_tokens + row0 + m];
         }
     };
-    if (steps > 0) load_step(0);
+    auto store_stats = [&](int st) {
+        if (tid < kT) { s_lse[st & 1][tid] = r_lse; s_dlt[st & 1][tid] = r_dlt; }
+    };
+    if (steps > 0) {
+        start_step(0);
+        store_stats(0);
+    }
     for (int st = 0; st < steps; ++st) {
         const int m0 = m_begin + (st % ntile_m) * kT;
-        __syncthreads();
-        sq.store_rows(Qs);
-        so.store_rows(Os);
-        if (tid < kT) { s_lse[tid] = r_lse; s_dlt[tid] = r_dlt; }
-        __syncthreads();
-        if (st + 1 < steps) load_step(st + 1);
-        if (CAUSAL && m0 + kT - 1 < n0w) continue;  // every row of the tile lies before this wavefront's keys
-
-        // Fragment reads run PF steps ahead of the MFMAs that use them; the fences keep that order.
-        constexpr int PF = ORCH_BWD_PF;
-        auto rd_q = [&](int mb, int c) { return *(const bf16x8 *)(&Qs[(32 * mb + l32) * RS + 16 * c + 8 * g]); };
-        auto rd_o = [&](int mb, int c) { return *(const bf16x8 *)(&Os[(32 * mb + l32) * RS + 16 * c + 8 * g]); };
-        // step j = 4 b + t of the last product: rows 16 t .. + 15 of the tile, head-dim columns 32 b .. + 31
-        auto rd_t = [&](int j) { return lds_read_tr(xt_base + (uint32_t)(16 * (j & 3) * 2 * RS + 2 * 32 * (j >> 2)), 2 * RS); };
-        bf16x8 bf[4];  // P (dV) or dS (dK) of the tile's 64 rows, B-operand layout
-        bf16x8 qq[PF + 1], oq[DK ? PF + 1 : 1], tq[PF + 1];
+        ps.publish();
+        if (st + 1 < steps) start_step(st + 1);
+        // rows of the tile that lie before this wavefront's keys see none of them
+        if (!(CAUSAL && m0 + kT - 1 < n0w)) {
+            const uint32_t qb = ps.x_base(st), ob = ps.y_base(st);
+            const uint32_t xb = DK ? qb : ob;
+            const float *lse_s = s_lse[st & 1], *dlt_s = s_dlt[st & 1];
+            // Fragment reads run PF steps ahead of the MFMAs that use them; the fences keep that order.
+            constexpr int PF = ORCH_BWD_PF;
+            bf16x8 bf[4];  // P (dV) or dS (dK) of the tile's 64 rows, B-operand layout
+            bf16x8 qq[PF + 1], oq[DK ? PF + 1 : 1], tq[PF + 1];
 #pragma unroll
-        for (int i = 0; i < PF; ++i) {
-            qq[i] = rd_q(0, i);
-            if (DK) oq[i] = rd_o(0, i);
-        }
+            for (int i = 0; i < PF; ++i) {
+                qq[i] = ps.rd_row(qb, 0, i);
+                if (DK) oq[i] = ps.rd_row(ob, 0, i);
+            }
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb) {
-            // S = Q K^T (and dP = dout V^T) for 32 rows x this wavefront's 32 keys
-            f32x16 sa, da;
+            for (int mb = 0; mb < 2; ++mb) {
+                // S = Q K^T (and dP = dout V^T) for 32 rows x this wavefront's 32 keys
+                f32x16 sa, da;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) { sa[e] = 0.f; da[e] = 0.f; }
+                for (int e = 0; e < 16; ++e) { sa[e] = 0.f; da[e] = 0.f; }
 #pragma unroll
-            for (int c = 0; c < NC; ++c) {
-                const int sn = NC * mb + c + PF;  // the step fetched now
-                if (sn < 2 * NC) {
-                    qq[sn % (PF + 1)] = rd_q(sn / NC, sn % NC);
-                    if (DK) oq[sn % (PF + 1)] = rd_o(sn / NC, sn % NC);
-                } else {
-                    tq[(sn - 2 * NC) % (PF + 1)] = rd_t(sn - 2 * NC);
+                for (int c = 0; c < NC; ++c) {
+                    const int sn = NC * mb + c + PF;  // the step fetched now
+                    if (sn < 2 * NC) {
+                        qq[sn % (PF + 1)] = ps.rd_row(qb, sn / NC, sn % NC);
+                        if (DK) oq[sn % (PF + 1)] = ps.rd_row(ob, sn / NC, sn % NC);
+                    } else {
+                        tq[(sn - 2 * NC) % (PF + 1)] = ps.rd_tr(xb, sn - 2 * NC);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qq[(NC * mb + c) % (PF + 1)], kfs[c], sa, 0, 0, 0);
+                    if (DK) da = __builtin_amdgcn_mfma_f32_32x32x16_bf16(oq[(NC * mb + c) % (PF + 1)], vfs[c], da, 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-                __builtin_amdgcn_sched_barrier(0);
-                sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qq[(NC * mb + c) % (PF + 1)], kfs[c], sa, 0, 0, 0);
-                if (DK) da = __builtin_amdgcn_mfma_f32_32x32x16_bf16(oq[(NC * mb + c) % (PF + 1)], vfs[c], da, 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            // register e of the accumulator is row 8 (e / 4) + 4 g + e % 4 of the block
-            float x16[16];
+                // register e of the accumulator is row 8 (e / 4) + 4 g + e % 4 of the block
+                float x16[16];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const f32x4 l4 = *(const f32x4 *)(&s_lse[32 * mb + 8 * j + 4 * g]);
-                f32x4 t4 = {0.f, 0.f, 0.f, 0.f};
-                if (DK) t4 = *(const f32x4 *)(&s_dlt[32 * mb + 8 * j + 4 * g]);
+                for (int j = 0; j < 4; ++j) {
+                    const f32x4 l4 = *(const f32x4 *)(&lse_s[32 * mb + 8 * j + 4 * g]);
+                    f32x4 t4 = {0.f, 0.f, 0.f, 0.f};
+                    if (DK) t4 = *(const f32x4 *)(&dlt_s[32 * mb + 8 * j + 4 * g]);
 #pragma unroll
-                for (int w = 0; w < 4; ++w) {
-                    const int e = 4 * j + w;
-                    const int m = m0 + 32 * mb + 8 * j + 4 * g + w;
-                    const bool vis = m < L && kn < L && (!CAUSAL || kn <= m);
-                    const float p = vis ? __builtin_amdgcn_exp2f(sa[e] * scale_log2 - l4[w]) : 0.f;
-                    x16[e] = DK ? p * (da[e] - t4[w]) : p;
+                    for (int w = 0; w < 4; ++w) {
+                        const int e = 4 * j + w;
+                        const int m = m0 + 32 * mb + 8 * j + 4 * g + w;
+                        const bool vis = m < L && kn < L && (!CAUSAL || kn <= m);
+                        const float p = vis ? __builtin_amdgcn_exp2f(sa[e] * scale_log2 - l4[w]) : 0.f;
+                        x16[e] = DK ? p * (da[e] - t4[w]) : p;
+                    }
+                }
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    u32x4 a;
+                    a.x = pack_bf16(x16[8 * half + 0], x16[8 * half + 1]);
+                    a.y = pack_bf16(x16[8 * half + 2], x16[8 * half + 3]);
+                    a.z = pack_bf16(x16[8 * half + 4], x16[8 * half + 5]);
+                    a.w = pack_bf16(x16[8 * half + 6], x16[8 * half + 7]);
+                    bf[2 * mb + half] = __builtin_bit_cast(bf16x8, a);
                 }
             }
+            // dV^T += dout^T P  or  dK^T += Q^T dS  over the tile's 64 rows, step j = 4 b + t
 #pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                u32x4 a;
-                a.x = pack_bf16(x16[8 * half + 0], x16[8 * half + 1]);
-                a.y = pack_bf16(x16[8 * half + 2], x16[8 * half + 3]);
-                a.z = pack_bf16(x16[8 * half + 4], x16[8 * half + 5]);
-                a.w = pack_bf16(x16[8 * half + 6], x16[8 * half + 7]);
-                bf[2 * mb + half] = __builtin_bit_cast(bf16x8, a);
+            for (int j = 0; j < 4 * NDB; ++j) {
+                if (j + PF < 4 * NDB) tq[(j + PF) % (PF + 1)] = ps.rd_tr(xb, j + PF);
+                __builtin_amdgcn_sched_barrier(0);
+                acc[j >> 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq[j % (PF + 1)], bf[j & 3], acc[j >> 2], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
-        // dV^T += dout^T P  or  dK^T += Q^T dS  over the tile's 64 rows (4 groups of 16)
-#pragma unroll
-        for (int j = 0; j < 4 * NDB; ++j) {
-            if (j + PF < 4 * NDB) tq[(j + PF) % (PF + 1)] = rd_t(j + PF);
-            __builtin_amdgcn_sched_barrier(0);
-            acc[j >> 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq[j % (PF + 1)], bf[j & 3], acc[j >> 2], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-        }
+        // the next step's row statistics: its slot was last read in the previous step
+        if (st + 1 < steps) store_stats(st + 1);
     }
 
     if (kn < L) {
