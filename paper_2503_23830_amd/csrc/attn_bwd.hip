@@ -12,14 +12,16 @@
 //                          64 keys through LDS, recomputes the transposed scores
 //                          S^T = K Q^T and dP^T = V dout^T (a lane holds 16 keys of ONE query,
 //                          so lse and delta are per-lane scalars), and accumulates
-//                          dQ^T += K^T dS^T with K^T fragments read from a transposed LDS copy.
+//                          dQ^T += K^T dS^T.
 //   attn_bwd_dkv_kernel    key-stationary, launched once for dK and once for dV: a workgroup owns
 //                          128 keys of one kv-head (32 per wavefront, K and V fragments live in
 //                          registers), loops over the q-heads of the group and over 64-row tiles
 //                          of Q and dout, computes S = Q K^T and dP = dout V^T (a lane holds 16
 //                          queries of ONE key, which is the B-operand layout for contractions
-//                          over queries) and accumulates dV^T += dout^T P or dK^T += Q^T dS with
-//                          Q^T / dout^T fragments read from a transposed LDS copy.
+//                          over queries) and accumulates dV^T += dout^T P or dK^T += Q^T dS.
+// The transposed A operands (K^T, Q^T, dout^T) are read with ds_read_b64_tr_b16 from the same
+// row-major LDS tile that serves the first products; how the tiles get into LDS is PairStage's
+// business (LDS-DMA for head_dim 128, registers for head_dim 64).
 // Every product is v_mfma_f32_32x32x16_bf16 with fp32 accumulation; P and dS are rounded to
 // bf16 before the second products, as P is in the forward pass.
 #include "common.h"
