@@ -20,8 +20,7 @@
 //                          queries of ONE key, which is the B-operand layout for contractions
 //                          over queries) and accumulates dV^T += dout^T P or dK^T += Q^T dS.
 // The transposed A operands (K^T, Q^T, dout^T) are read with ds_read_b64_tr_b16 from the same
-// row-major LDS tile that serves the first products; how the tiles get into LDS is PairStage's
-// business (LDS-DMA for head_dim 128, registers for head_dim 64).
+// row-major LDS tile that serves the first products; the tiles get into LDS by LDS-DMA (PairStage).
 // Every product is v_mfma_f32_32x32x16_bf16 with fp32 accumulation; P and dS are rounded to
 // bf16 before the second products, as P is in the forward pass.
 #include "common.h"
@@ -39,28 +38,14 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
-// A-operand fragment of X^T (row M = a column of X, contraction over 16 rows of X) read from
+// Transposed A-operand fragments (row M = a column of X, contraction over 16 rows of X) come from
 // the ROW-MAJOR tile X[row][col] with two ds_read_b64_tr_b16: inside a block of 16 lanes, lane i
 // receives element i % 4 of the 8-byte words addressed by lanes i / 4, 4 + i / 4, 8 + i / 4 and
 // 12 + i / 4.  Lane (g, half, j4, a) = (lane / 32, (lane / 16) % 2, (lane % 16) / 4, lane % 4)
 // addresses row 4 g + j4 and columns 16 half + 4 a .. + 3, so it receives rows 4 g .. 4 g + 3 of
 // column 16 half + (lane % 16) = lane % 32; a second read 8 rows further completes the 8
 // contraction slots of the lane (rows 4 g + w and 8 + 4 g + w: the rows its registers 0..7 of a
-// 32x32 accumulator hold).  `base` = byte address in LDS of X[first row of the 16][first column
-// of the 32]; `stride_b` = bytes per row.
-__device__ __forceinline__ uint32_t tr_lane_offset(int lane, int stride_b)
-{
-    const int g = lane >> 5, half = (lane >> 4) & 1, j4 = (lane & 15) >> 2, a = lane & 3;
-    return (uint32_t)((4 * g + j4) * stride_b + 2 * (16 * half + 4 * a));
-}
-
-__device__ __forceinline__ bf16x8 lds_read_tr(uint32_t addr, int stride_b)
-{
-    const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(uintptr_t)addr);
-    const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-        (__attribute__((address_space(3))) s16x4 *)(uintptr_t)(addr + 8u * (uint32_t)stride_b));
-    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7));
-}
+// 32x32 accumulator hold).  PairStage::rd_tr does this on the swizzled tile.
 
 #ifndef ORCH_BWD_PF
 #define ORCH_BWD_PF 1
@@ -175,10 +160,6 @@ __device__ __forceinline__ bf16x8 lds_rd128(uint32_t addr)
 {
     return *(const __attribute__((address_space(3))) bf16x8 *)(uintptr_t)addr;
 }
-__device__ __forceinline__ void lds_wr128(uint32_t addr, u32x4 val)
-{
-    *(__attribute__((address_space(3))) u32x4 *)(uintptr_t)addr = val;
-}
 
 // Where a pair of 64-row tiles comes from: rows [m0, m0 + 64) of the sequence that starts at
 // row0 and has L rows, head hd of two [T, heads, HD] tensors (K and V, or Q and dout).
@@ -188,108 +169,56 @@ struct TileSrc {
 };
 
 // The pair of streamed LDS tiles of a step (X: K or Q, Y: V or dout) and the fragment reads on
-// them.  Two forms.
-//   Register-staged (any head_dim): rows go global -> registers -> LDS with a padded stride; the
-//   loads of the next pair are in flight during the products, two barriers per step.  Row reads
-//   are conflict-free, the transpose reads two-way conflicted.
-//   LDS-DMA (head_dim 128): rows go straight from global memory into LDS (no registers, no LDS
-//   store instructions), two stages, one barrier per step.  Rows are 256 bytes without padding;
-//   row r keeps its 16-byte chunk c at slot c ^ swz(r), swz(r) = 4 (r % 4) + (r / 4) % 4, which
-//   makes BOTH read patterns conflict-free: 16 consecutive rows at one chunk hit 16 slots, and the
-//   4 rows x 4 chunks a half-wavefront transposes hit 16 slots.
-template <int HD, bool DMA>
-struct PairStage;
+// them.  Rows go straight from global memory into LDS by LDS-DMA (no staging registers, no LDS
+// store instructions); two stages, one barrier per step.  Rows are unpadded; a slot swizzle keeps
+// both read patterns (16-byte row reads for the first products, 8-byte transpose reads for the
+// last one) free of bank conflicts.
+// Slot swizzle of the LDS-DMA layout: row r keeps its 16-byte chunk c at slot c ^ swz(r).
+// 256-byte rows (head_dim 128, 16 chunks, one row per 64 banks): swz = 4 (r % 4) + (r / 4) % 4.
+// 128-byte rows (head_dim 64, 8 chunks, two rows per 64 banks): swz = 4 r1 + 2 r3 + r2 (bits of r).
+// In both, 16 consecutive rows at one chunk land in 16 distinct 16-byte bank groups, and so do the
+// 4 rows x 4 chunks that a half-wavefront reads in one transpose read.
+template <int HD>
+__device__ __forceinline__ int dma_swz(int r)
+{
+    if (HD == 128) return 4 * (r & 3) + ((r >> 2) & 3);
+    return 4 * ((r >> 1) & 1) + 2 * ((r >> 3) & 1) + ((r >> 2) & 1);
+}
 
 template <int HD>
-struct PairStage<HD, false> {
-    static constexpr int ROWB = (HD + 8) * 2;
+struct PairStage {
+    static constexpr int ROWB = 2 * HD;
     static constexpr int TILE_B = kT * ROWB;
-    static constexpr int BYTES = 2 * TILE_B;
-    static constexpr int ROWS_PER_PASS = kThreads / (HD / 8);
-    static constexpr int PASS = kT / ROWS_PER_PASS;
-    uint32_t base, rlane, tlane;
-    u32x4 xr[PASS], yr[PASS];
-
-    __device__ __forceinline__ void init(uint32_t lds_base, int lane, int wave)
-    {
-        (void)wave;
-        base = lds_base;
-        rlane = (uint32_t)((lane & 31) * ROWB + 16 * (lane >> 5));
-        tlane = tr_lane_offset(lane, ROWB);
-    }
-    __device__ __forceinline__ uint32_t x_base(int it) const { (void)it; return base; }
-    __device__ __forceinline__ uint32_t y_base(int it) const { (void)it; return base + TILE_B; }
-    // A operand, rows 32 blk .. + 31 of the tile, contraction chunk c (16 columns)
-    __device__ __forceinline__ bf16x8 rd_row(uint32_t tile, int blk, int c) const
-    {
-        return lds_rd128(tile + rlane + (uint32_t)(blk * 32 * ROWB + 32 * c));
-    }
-    // A operand of the transposed tile, step j = 4 b + t: rows 16 t .. + 15, columns 32 b .. + 31
-    __device__ __forceinline__ bf16x8 rd_tr(uint32_t tile, int j) const
-    {
-        return lds_read_tr(tile + tlane + (uint32_t)(16 * (j & 3) * ROWB + 64 * (j >> 2)), ROWB);
-    }
-    __device__ __forceinline__ void begin(const TileSrc &s, int it)
-    {
-        (void)it;
-        const int col = (threadIdx.x % (HD / 8)) * 8, r = threadIdx.x / (HD / 8);
-#pragma unroll
-        for (int p = 0; p < PASS; ++p) {
-            int m = s.m0 + p * ROWS_PER_PASS + r;
-            m = m < s.L ? m : s.L - 1;
-            const size_t e = ((size_t)(s.row0 + m) * s.heads + s.hd) * HD + col;
-            xr[p] = *(const u32x4 *)(s.px + e);
-            yr[p] = *(const u32x4 *)(s.py + e);
-        }
-    }
-    __device__ __forceinline__ void publish()
-    {
-        const int col = (threadIdx.x % (HD / 8)) * 8, r = threadIdx.x / (HD / 8);
-        __syncthreads();
-#pragma unroll
-        for (int p = 0; p < PASS; ++p) {
-            const uint32_t o = (uint32_t)((p * ROWS_PER_PASS + r) * ROWB + 2 * col);
-            lds_wr128(base + o, xr[p]);
-            lds_wr128(base + TILE_B + o, yr[p]);
-        }
-        __syncthreads();
-    }
-};
-
-__device__ __forceinline__ int swz128(int r) { return 4 * (r & 3) + ((r >> 2) & 3); }
-
-template <>
-struct PairStage<128, true> {
-    static constexpr int HD = 128;
-    static constexpr int ROWB = 256;
-    static constexpr int TILE_B = kT * ROWB;
-    static constexpr int BYTES = 4 * TILE_B;  // two stages of two tiles
+    static constexpr int BYTES = 4 * TILE_B;      // two stages of two tiles
+    static constexpr int CH = ROWB / 16;          // 16-byte chunks per row
+    static constexpr int RPI = 1024 / ROWB;       // rows one DMA load moves (64 lanes x 16 bytes)
+    static constexpr int NP = 16 / RPI;           // loads per wavefront and tile (it fetches 16 rows)
     uint32_t base;
-    uint32_t raddr[HD / 16];   // row reads: l32 * 256 + 16 * ((2 c + g) ^ swz(l32))
+    uint32_t raddr[HD / 16];     // row reads: l32 * ROWB + 16 * ((2 c + g) ^ swz(l32))
     uint32_t taddr[2][HD / 32];  // transpose reads, rows 8 u + 4 g + j4, columns of block b
-    uint32_t dcol[4];          // DMA: byte column this lane fetches in load p
-    int drow;                  // DMA: row of the tile this lane fetches in load 0 (load p: + 4 p)
-    uint32_t ddst;             // DMA: LDS offset of this wavefront's first load inside a tile
+    uint32_t dcol[NP];           // DMA: byte column this lane fetches in load p
+    int drow;                    // DMA: row of the tile this lane fetches in load 0 (load p: + RPI p)
+    uint32_t ddst;               // DMA: LDS offset of this wavefront's first load inside a tile
 
     __device__ __forceinline__ void init(uint32_t lds_base, int lane, int wave)
     {
         base = lds_base;
         const int l32 = lane & 31, g = lane >> 5;
 #pragma unroll
-        for (int c = 0; c < HD / 16; ++c) raddr[c] = (uint32_t)(l32 * ROWB + 16 * ((2 * c + g) ^ swz128(l32)));
+        for (int c = 0; c < HD / 16; ++c) raddr[c] = (uint32_t)(l32 * ROWB + 16 * ((2 * c + g) ^ dma_swz<HD>(l32)));
         const int half = (lane >> 4) & 1, j4 = (lane & 15) >> 2, a = lane & 3;
 #pragma unroll
         for (int u = 0; u < 2; ++u)
 #pragma unroll
             for (int b = 0; b < HD / 32; ++b) {
                 const int r = 8 * u + 4 * g + j4;
-                taddr[u][b] = (uint32_t)(r * ROWB + 16 * ((4 * b + 2 * half + (a >> 1)) ^ swz128(r)) + 8 * (a & 1));
+                taddr[u][b] = (uint32_t)(r * ROWB + 16 * ((4 * b + 2 * half + (a >> 1)) ^ dma_swz<HD>(r)) + 8 * (a & 1));
             }
-        // a DMA load moves 64 lanes x 16 bytes = 4 rows into 1 KB of LDS in lane order; this
-        // wavefront fetches rows 16 wave .. 16 wave + 15 of the tile in four loads
-        drow = 16 * wave + (lane >> 4);
+        // a DMA load moves 64 lanes x 16 bytes = RPI rows into 1 KB of LDS in lane order; this
+        // wavefront fetches rows 16 wave .. 16 wave + 15 of the tile in NP loads
+        drow = 16 * wave + lane / CH;
 #pragma unroll
-        for (int p = 0; p < 4; ++p) dcol[p] = 16u * (uint32_t)((lane & 15) ^ swz128(drow + 4 * p));
+        for (int p = 0; p < NP; ++p) dcol[p] = 16u * (uint32_t)((lane % CH) ^ dma_swz<HD>(drow + RPI * p));
         ddst = (uint32_t)(16 * wave * ROWB);
     }
     __device__ __forceinline__ uint32_t x_base(int it) const { return base + (uint32_t)((it & 1) * 2 * TILE_B); }
@@ -330,10 +259,10 @@ struct PairStage<128, true> {
         const int last = s.L - 1 - s.m0;  // rows past the end of the sequence repeat its last row (masked later)
         const uint32_t dx = (uint32_t)__builtin_amdgcn_readfirstlane((int)(x_base(it) + ddst));
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const uint32_t off = (uint32_t)min(drow + 4 * p, last) * rstride + dcol[p];
-            dma_issue(tx, off, dx + (uint32_t)(4 * p * ROWB));
-            dma_issue(ty, off, dx + (uint32_t)(TILE_B + 4 * p * ROWB));
+        for (int p = 0; p < NP; ++p) {
+            const uint32_t off = (uint32_t)min(drow + RPI * p, last) * rstride + dcol[p];
+            dma_issue(tx, off, dx + (uint32_t)(RPI * p * ROWB));
+            dma_issue(ty, off, dx + (uint32_t)(TILE_B + RPI * p * ROWB));
         }
     }
     __device__ __forceinline__ void publish()
@@ -354,7 +283,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
     const int32_t *__restrict__ tile_off, int32_t batch, int32_t total_tokens, int32_t Hq, int32_t Hkv,
     float scale, float scale_log2)
 {
-    using PS = PairStage<HD, HD == 128>;
+    using PS = PairStage<HD>;
     constexpr int NC = HD / 16, NDB = HD / 32;
     __shared__ __attribute__((aligned(1024))) char lds_raw[PS::BYTES];
 
@@ -514,7 +443,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(
     float scale, float scale_log2)
 {
     constexpr bool DK = PART == PART_DK;
-    using PS = PairStage<HD, HD == 128>;
+    using PS = PairStage<HD>;
     constexpr int NC = HD / 16, NDB = HD / 32;
     __shared__ __attribute__((aligned(1024))) char lds_raw[PS::BYTES];
     __shared__ __attribute__((aligned(16))) float s_lse[2][kT];  // lse * log2(e) of the tile's rows, by step parity
