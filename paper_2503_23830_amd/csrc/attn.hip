@@ -8,9 +8,10 @@
 //
 // attn_fwd_kernel: one workgroup (4 wavefronts) owns 128*MB consecutive query rows
 // of one sequence and one q-head; each wavefront owns MB blocks of 32 rows.  K/V tiles
-// of BN = 64 keys are staged through LDS (V transposed on the way in) and shared
-// by the four wavefronts; with MB = 2 every K/V fragment read from LDS feeds two
-// MFMAs, which halves LDS traffic per FLOP.  The scores are computed transposed,
+// of BN = 64 keys go from global memory into LDS by LDS-DMA (row-major, swizzled; two
+// stages, one barrier per tile) and are shared by the four wavefronts; the V^T operand
+// of the second product is read from the row-major V tile with transpose reads.  With
+// MB = 2 every K/V fragment read from LDS feeds two MFMAs, which halves LDS traffic per FLOP.  The scores are computed transposed,
 // S^T = K Q^T, with v_mfma_f32_32x32x16_bf16: in the accumulator layout every
 // lane then holds 16 keys of ONE query, so the online-softmax statistics are
 // per-lane scalars (one cross-lane exchange per tile), the probabilities are
@@ -20,20 +21,13 @@
 // the final division), so O is rarely rescaled after the first tile.
 #include <type_traits>
 
+#include "attn_tiles.h"
 #include "common.h"
 
 namespace orch {
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-
 constexpr int BN = 64;   // keys per LDS tile
-constexpr int kThreads = 256;
 constexpr int kPrepThreads = 1024;
 
 struct AttnHdr {
@@ -101,12 +95,11 @@ __global__ __launch_bounds__(kThreads, (MB * HD > 128 ? 1 : 2)) void attn_fwd_ke
 {
     constexpr int BM = 128 * MB;  // query rows per workgroup
     constexpr int NBLK = 4 * MB;  // 32-row blocks per workgroup
-    constexpr int KS = HD + 8;    // K tile row stride (elements): 16-byte rows land on distinct banks
-    constexpr int VS = BN + 8;    // V^T tile row stride
     constexpr int NC = HD / 16;   // 16-wide chunks of the head dimension
     constexpr int NDB = HD / 32;  // 32-row blocks of O^T
-    __shared__ __attribute__((aligned(16))) uint16_t Ks[BN * KS];
-    __shared__ __attribute__((aligned(16))) uint16_t Vt[HD * VS];
+    using PS = PairStage<HD>;
+    static_assert(BN == kT, "the staged tile pair is 64 keys deep");
+    __shared__ __attribute__((aligned(1024))) char lds_raw[PS::BYTES];
 
     const int total_tiles = hdr->total_tiles;
     const int group = Hq / Hkv;
@@ -143,8 +136,11 @@ __global__ __launch_bounds__(kThreads, (MB * HD > 128 ? 1 : 2)) void attn_fwd_ke
     const int qt = ntile_q - 1 - (u - tile_off[seq]);  // heaviest (last) tile first
     const int q0 = qt * BM;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, g = lane >> 5;
+    PS ps;
+    ps.init((uint32_t)(uintptr_t)lds_raw, lane, wave);
 
     // 32-row blocks of this wavefront.  Under a causal mask block b needs b+1
     // units of work near the diagonal, so wave w takes blocks w and NBLK-1-w:
@@ -183,65 +179,9 @@ __global__ __launch_bounds__(kThreads, (MB * HD > 128 ? 1 : 2)) void attn_fwd_ke
     const int kend = CAUSAL ? min(L, q0 + BM) : L;
     const int ntile_k = (kend + BN - 1) / BN;
 
-    // ---- global -> register staging of one K/V tile
-    constexpr int KROWS_PER_PASS = kThreads / (HD / 8);  // rows covered by 256 16-byte loads
-    constexpr int KPASS = BN / KROWS_PER_PASS;
-    constexpr int VBLK = (BN / 4) * (HD / 4) / kThreads;  // 4(key) x 4(dim) blocks per thread
-    u32x4 kreg[KPASS];
-    u32x2 vreg[VBLK][4];
-    const int k_col = (tid % (HD / 8)) * 8, k_row = tid / (HD / 8);
-    // V blocks: 8 adjacent lanes take 8 different key quads (so their transposed
-    // 8-byte LDS writes fall on different banks), the next lane bits walk the
-    // head dimension
-    const int v_nq0 = tid & 7, v_dq = (tid >> 3) % (HD / 4), v_nqhi = (tid >> 3) / (HD / 4);
-    static_assert(VBLK * (kThreads / 8 / (HD / 4)) * 8 == BN / 4, "V staging must cover the tile");
-
-    auto load_tile = [&](int n0) {
-#pragma unroll
-        for (int p = 0; p < KPASS; ++p) {
-            int n = n0 + p * KROWS_PER_PASS + k_row;
-            n = n < L ? n : L - 1;
-            kreg[p] = *(const u32x4 *)(k + ((size_t)(row0 + n) * Hkv + g_kv) * HD + k_col);
-        }
-#pragma unroll
-        for (int b = 0; b < VBLK; ++b) {
-            const int nq = v_nq0 + 8 * (v_nqhi + b * (kThreads / 8 / (HD / 4)));
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                int n = n0 + 4 * nq + j;
-                n = n < L ? n : L - 1;
-                vreg[b][j] = *(const u32x2 *)(v + ((size_t)(row0 + n) * Hkv + g_kv) * HD + 4 * v_dq);
-            }
-        }
-    };
-    auto store_tile = [&]() {
-#pragma unroll
-        for (int p = 0; p < KPASS; ++p)
-            *(u32x4 *)(&Ks[(p * KROWS_PER_PASS + k_row) * KS + k_col]) = kreg[p];
-#pragma unroll
-        for (int b = 0; b < VBLK; ++b) {
-            const int nq = v_nq0 + 8 * (v_nqhi + b * (kThreads / 8 / (HD / 4)));
-            // key n = 16t + 8u + 4g + w is stored at slot 16t + 8g + 4u + w, so the 8
-            // keys a lane contracts in one MFMA are contiguous
-            const int slot = 16 * (nq >> 2) + 8 * (nq & 1) + 4 * ((nq >> 1) & 1);
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
-                const uint32_t a0 = (c & 2) ? vreg[b][0].y : vreg[b][0].x;
-                const uint32_t a1 = (c & 2) ? vreg[b][1].y : vreg[b][1].x;
-                const uint32_t a2 = (c & 2) ? vreg[b][2].y : vreg[b][2].x;
-                const uint32_t a3 = (c & 2) ? vreg[b][3].y : vreg[b][3].x;
-                u32x2 w;
-                w.x = __builtin_amdgcn_perm(a1, a0, sel);
-                w.y = __builtin_amdgcn_perm(a3, a2, sel);
-                *(u32x2 *)(&Vt[(4 * v_dq + c) * VS + slot]) = w;
-            }
-        }
-    };
-
     // One K/V tile for the row blocks mb >= MB0 of this wavefront (blocks below
     // MB0 lie entirely above the causal diagonal for this tile).
-    auto compute_tile = [&](auto mb0_tag, int n0) {
+    auto compute_tile = [&](auto mb0_tag, int n0, uint32_t kb, uint32_t vb) {
         constexpr int MB0 = decltype(mb0_tag)::value;
         // ---- S^T = K Q^T : two 32-key blocks
         f32x16 acc_s[MB][2];
@@ -253,7 +193,7 @@ __global__ __launch_bounds__(kThreads, (MB * HD > 128 ? 1 : 2)) void attn_fwd_ke
                 for (int e = 0; e < 16; ++e) acc_s[mb][nb][e] = 0.f;
 #pragma unroll
             for (int c = 0; c < NC; ++c) {
-                const bf16x8 kf = *(const bf16x8 *)(&Ks[(32 * nb + l32) * KS + 16 * c + 8 * g]);
+                const bf16x8 kf = ps.rd_row(kb, nb, c);
 #pragma unroll
                 for (int mb = MB0; mb < MB; ++mb)
                     acc_s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[mb][c], acc_s[mb][nb], 0, 0, 0);
@@ -323,20 +263,22 @@ __global__ __launch_bounds__(kThreads, (MB * HD > 128 ? 1 : 2)) void attn_fwd_ke
         for (int b = 0; b < NDB; ++b)
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk) {
-                const bf16x8 vf = *(const bf16x8 *)(&Vt[(32 * b + l32) * VS + 16 * kk + 8 * g]);
+                const bf16x8 vf = ps.rd_tr(vb, 4 * b + kk);  // V^T: head-dim columns 32 b .. + 31, keys 16 kk .. + 15
 #pragma unroll
                 for (int mb = MB0; mb < MB; ++mb)
                     acc_o[mb][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[mb][kk], acc_o[mb][b], 0, 0, 0);
             }
     };
 
-    load_tile(0);
+    TileSrc src{k, v, row0, L, 0, Hkv, g_kv};
+    ps.begin(src, 0);
     for (int it = 0; it < ntile_k; ++it) {
         const int n0 = it * BN;
-        __syncthreads();
-        store_tile();
-        __syncthreads();
-        if (it + 1 < ntile_k) load_tile(n0 + BN);
+        ps.publish();
+        if (it + 1 < ntile_k) {
+            src.m0 = n0 + BN;
+            ps.begin(src, it + 1);
+        }
 
         // row blocks entirely above the diagonal have nothing to do in this tile;
         // blk[] ascends with mb, so the active ones are a suffix
@@ -346,8 +288,8 @@ __global__ __launch_bounds__(kThreads, (MB * HD > 128 ? 1 : 2)) void attn_fwd_ke
             for (int mb = 0; mb < MB; ++mb)
                 if (n0 > q0 + 32 * blk[mb] + 31) first = mb + 1;
         }
-        if (first == 0) compute_tile(std::integral_constant<int, 0>{}, n0);
-        else if (MB > 1 && first == 1) compute_tile(std::integral_constant<int, (MB > 1 ? 1 : 0)>{}, n0);
+        if (first == 0) compute_tile(std::integral_constant<int, 0>{}, n0, ps.x_base(it), ps.y_base(it));
+        else if (MB > 1 && first == 1) compute_tile(std::integral_constant<int, (MB > 1 ? 1 : 0)>{}, n0, ps.x_base(it), ps.y_base(it));
     }
 
     // ---- epilogue
@@ -410,8 +352,6 @@ __global__ __launch_bounds__(kThreads, (MB * HD > 128 ? 1 : 2)) void attn_fwd_ke
 // in half 2 of iteration b: O has received P(b-1) V(b-1) and not yet P(b) V(b).
 // ---------------------------------------------------------------------------
 constexpr int kILThreads = 512;
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x8 __attribute__((ext_vector_type(8)));
 
 #define ORCH_SB() __builtin_amdgcn_sched_barrier(0)
 
@@ -884,7 +824,7 @@ int launch_attn(const void *q, const void *k, const void *v, void *out, float *l
             hipLaunchKernelGGL((attn_fwd_kernel<64, false, 2>), dim3((unsigned)grid), dim3(kThreads), 0, stream, ORCH_ATTN_ARGS);
 #undef ORCH_ATTN_ARGS
     }
-    set_attn_variant(il ? "mfma32x32x16_bm256_8wave_ldsdma_interleaved" : "mfma32x32x16_bm256_4wave");
+    set_attn_variant(il ? "mfma32x32x16_bm256_8wave_ldsdma_interleaved" : "mfma32x32x16_bm256_4wave_ldsdma");
     ORCH_HIP_CHECK(hipGetLastError());
     return ORCH_OK;
 }
