@@ -5,7 +5,7 @@
 //   delta_i = dout_i . out_i  (= sum_j p_ij dp_ij)      ds_ij = p_ij (dp_ij - delta_i)
 //   dq_i = scale * sum_j ds_ij k_j     dk_j = scale * sum_i ds_ij q_i     dv_j = sum_i p_ij dout_i
 //
-// Four launches, no atomics, so the result is deterministic:
+// Three or four launches, no atomics, so the result is deterministic:
 //   attn_bwd_delta_kernel  delta[h, i] in fp32, one pass over dout and out (HBM-bound).
 //   attn_bwd_dq_kernel     query-stationary, shaped like the forward kernel: a workgroup of 4
 //                          wavefronts owns 128 query rows of one q-head, streams K/V tiles of
@@ -13,16 +13,21 @@
 //                          S^T = K Q^T and dP^T = V dout^T (a lane holds 16 keys of ONE query,
 //                          so lse and delta are per-lane scalars), and accumulates
 //                          dQ^T += K^T dS^T.
-//   attn_bwd_dkv_kernel    key-stationary, launched once for dK and once for dV: a workgroup owns
-//                          128 keys of one kv-head (32 per wavefront, K and V fragments live in
-//                          registers), loops over the q-heads of the group and over 64-row tiles
-//                          of Q and dout, computes S = Q K^T and dP = dout V^T (a lane holds 16
-//                          queries of ONE key, which is the B-operand layout for contractions
-//                          over queries) and accumulates dV^T += dout^T P or dK^T += Q^T dS.
+//   dK, dV                 key-stationary: a workgroup owns 128 keys of one kv-head (32 per
+//                          wavefront, K or V fragments live in registers), loops over the q-heads
+//                          of the group and over 64-row tiles of Q and dout, computes S = Q K^T
+//                          and dP = dout V^T (a lane holds 16 queries of ONE key, which is the
+//                          B-operand layout for contractions over queries) and accumulates
+//                          dV^T += dout^T P and dK^T += Q^T dS.
+//                          head_dim 128: attn_bwd_dkv_fused_kernel, 8 wavefronts, S computed once:
+//                          four wavefronts make P and dV, four take P through LDS and make dK.
+//                          head_dim 64: attn_bwd_dkv_kernel, launched once for dK and once for dV.
 // The transposed A operands (K^T, Q^T, dout^T) are read with ds_read_b64_tr_b16 from the same
 // row-major LDS tile that serves the first products; the tiles get into LDS by LDS-DMA (PairStage).
 // Every product is v_mfma_f32_32x32x16_bf16 with fp32 accumulation; P and dS are rounded to
 // bf16 before the second products, as P is in the forward pass.
+#include <type_traits>
+
 #include "attn_tiles.h"
 #include "common.h"
 
@@ -387,6 +392,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(
             const uint32_t qb = ps.x_base(st), ob = ps.y_base(st);
             const uint32_t xb = DK ? qb : ob;
             const float *lse_s = s_lse[st & 1], *dlt_s = s_dlt[st & 1];
+            // only tiles that touch the end of the sequence or the diagonal have masked elements
+            const bool need_mask = m0 + kT > L || n0w + 32 > L || (CAUSAL && n0w + 31 > m0);
             // Fragment reads run PF steps ahead of the MFMAs that use them; the fences keep that order.
             constexpr int PF = ORCH_BWD_PF;
             bf16x8 bf[4];  // P (dV) or dS (dK) of the tile's 64 rows, B-operand layout
@@ -426,10 +433,16 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(
 #pragma unroll
                     for (int w = 0; w < 4; ++w) {
                         const int e = 4 * j + w;
-                        const int m = m0 + 32 * mb + 8 * j + 4 * g + w;
-                        const bool vis = m < L && kn < L && (!CAUSAL || kn <= m);
-                        const float p = vis ? __builtin_amdgcn_exp2f(sa[e] * scale_log2 - l4[w]) : 0.f;
+                        const float p = __builtin_amdgcn_exp2f(sa[e] * scale_log2 - l4[w]);
                         x16[e] = DK ? p * (da[e] - t4[w]) : p;
+                    }
+                }
+                if (need_mask) {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const int m = m0 + 32 * mb + 8 * (e >> 2) + 4 * g + (e & 3);
+                        const bool vis = m < L && kn < L && (!CAUSAL || kn <= m);
+                        x16[e] = vis ? x16[e] : 0.f;
                     }
                 }
 #pragma unroll
@@ -458,6 +471,247 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(
     if (kn < L) {
         const float f = DK ? scale : 1.0f;
         uint16_t *op = dkv + ((size_t)(row0 + kn) * Hkv + g_kv) * HD;
+#pragma unroll
+        for (int b = 0; b < NDB; ++b)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                u32x2 w;
+                w.x = pack_bf16(acc[b][4 * r] * f, acc[b][4 * r + 1] * f);
+                w.y = pack_bf16(acc[b][4 * r + 2] * f, acc[b][4 * r + 3] * f);
+                *(u32x2 *)(op + 32 * b + 8 * r + 4 * g) = w;
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// dK and dV in one pass: 8 wavefronts, two per 32-key block of the workgroup's 128 keys.
+//   producer (wavefronts 0..3), tile t in step t:      S = Q K^T -> P (to LDS, bf16),  dV^T += dout^T P
+//   consumer (wavefronts 4..7), tile t in step t + 1:  dP = dout V^T, dS = P (dP - delta),  dK^T += Q^T dS
+// Each role holds one 64-register accumulator and one stationary operand, so both fit the 256
+// registers that two wavefronts per SIMD allow (a SIMD runs one producer and one consumer), and S
+// is computed once for both outputs: four products per (query, key) pair instead of five.  P
+// crosses in the B-operand layout it is consumed in (16 bytes per lane and 16 rows); tiles, P and
+// the row statistics live in three stages because the consumer runs one step behind.
+// One workgroup barrier per step orders all of it.
+// ---------------------------------------------------------------------------
+template <int HD, bool CAUSAL>
+__global__ __launch_bounds__(2 * kThreads, 1) void attn_bwd_dkv_fused_kernel(
+    const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
+    const uint16_t *__restrict__ dout, const float *__restrict__ lse, const float *__restrict__ delta,
+    uint16_t *__restrict__ dk, uint16_t *__restrict__ dv, const int32_t *__restrict__ cu,
+    const BwdHdr *__restrict__ hdr, const int32_t *__restrict__ tile_off, int32_t batch, int32_t total_tokens,
+    int32_t Hq, int32_t Hkv, float scale, float scale_log2)
+{
+    using PS = PairStage<HD, 3, 8>;
+    constexpr int NC = HD / 16, NDB = HD / 32;
+    __shared__ __attribute__((aligned(1024))) char lds_raw[PS::BYTES];
+    // P and the row statistics live in a slot per stage, like the tiles they belong to
+    __shared__ __attribute__((aligned(16))) bf16x8 s_p[3][4][4][64];  // P: stage, key block, fragment, lane
+    __shared__ __attribute__((aligned(16))) float s_lse[3][kT];        // lse * log2(e) of a tile's rows (read in its step)
+    __shared__ __attribute__((aligned(16))) float s_dlt[3][kT];        // delta of a tile's rows (read one step later)
+
+    const int total_tiles = hdr->total_tiles;
+    const int group = Hq / Hkv;
+    int u, g_kv;
+    block_to_tile(blockIdx.x, Hkv, Hkv, 1, u, g_kv);
+    if (u >= total_tiles) return;
+    int lo = 0, hi = batch - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (tile_off[mid] <= u) lo = mid; else hi = mid - 1;
+    }
+    const int row0 = cu[lo];
+    const int L = cu[lo + 1] - row0;
+    const int k0 = (u - tile_off[lo]) * kOwn;  // under a causal mask the first key tile is the heaviest
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int kbw = wave & 3;            // 32-key block of this wavefront
+    const bool consumer = wave >= 4;
+    const int l32 = lane & 31, g = lane >> 5;
+    const int n0w = k0 + 32 * kbw;
+    const int kn = n0w + l32;            // this lane's key (a column of S and dP)
+    const int kn_c = kn < L ? kn : L - 1;
+
+    // stationary B operand (column = this lane's key): K for the producer, V for the consumer
+    bf16x8 sf[NC];
+    {
+        const uint16_t *sp = (consumer ? v : k) + ((size_t)(row0 + kn_c) * Hkv + g_kv) * HD + 8 * g;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) sf[c] = *(const bf16x8 *)(sp + 16 * c);
+    }
+    f32x16 acc[NDB];
+#pragma unroll
+    for (int b = 0; b < NDB; ++b)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[b][e] = 0.f;
+
+    const int m_begin = CAUSAL ? (k0 / kT) * kT : 0;  // rows before the first key see none of them
+    const int ntile_m = m_begin < L ? (L - m_begin + kT - 1) / kT : 0;
+    const int steps = ntile_m * group;
+
+    PS ps;
+    ps.init((uint32_t)(uintptr_t)lds_raw, lane, wave);
+    TileSrc src{q, dout, row0, L, m_begin, Hq, g_kv * group};
+    float r_lse = 0.f, r_dlt = 0.f;
+    // Steps walk the group's q-heads, and inside a head the 64-row tiles from m_begin on.  The
+    // loop is unrolled by the three stages, so a step's stage is a constant and every fragment
+    // read is a fixed lane address plus an immediate offset.
+    int f_tile = 0;                 // tile index (inside its head) of the step fetched next
+    auto start_step = [&](auto stage_c) {
+        constexpr int STG = decltype(stage_c)::value;
+        src.m0 = m_begin + f_tile * kT;
+        ps.begin_at(src, STG);
+        if (tid < kT) {
+            int m = src.m0 + tid;
+            m = m < L ? m : L - 1;
+            r_lse = lse[(size_t)src.hd * total_tokens + row0 + m] * kLog2e;
+            r_dlt = delta[(size_t)src.hd * total_tokens + row0 + m];
+        }
+        if (++f_tile == ntile_m) { f_tile = 0; ++src.hd; }
+    };
+    auto store_stats = [&](auto stage_c) {
+        constexpr int STG = decltype(stage_c)::value;
+        if (tid < kT) { s_lse[STG][tid] = r_lse; s_dlt[STG][tid] = r_dlt; }
+    };
+    if (steps > 0) {
+        start_step(std::integral_constant<int, 0>{});
+        store_stats(std::integral_constant<int, 0>{});
+    }
+    constexpr int PF = ORCH_BWD_PF;
+    const int nloop = steps > 0 ? steps + 1 : 0;   // the consumer's last tile is done in one more step
+    int w_tile = consumer ? -1 : 0;                // tile index (inside its head) this wavefront works on
+
+    // dV^T += dout^T P (producer) or dK^T += Q^T dS (consumer) over the tile's 64 rows, step j = 4 b + t
+    auto accumulate = [&](uint32_t xb, const bf16x8 (&bf)[4], bf16x8 (&tq)[PF + 1]) {
+#pragma unroll
+        for (int j = 0; j < 4 * NDB; ++j) {
+            if (j + PF < 4 * NDB) tq[(j + PF) % (PF + 1)] = ps.rd_tr(xb, j + PF);
+            __builtin_amdgcn_sched_barrier(0);
+            acc[j >> 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq[j % (PF + 1)], bf[j & 3], acc[j >> 2], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    auto step = [&](auto stage_c, int st) {
+        constexpr int SA = decltype(stage_c)::value;   // stage of the tile fetched for step st (the producer's)
+        constexpr int SB = (SA + 2) % 3;               // stage of the tile of step st - 1 (the consumer's)
+        ps.publish();
+        if (st + 1 < steps) start_step(std::integral_constant<int, (SA + 1) % 3>{});
+        const int m0 = m_begin + w_tile * kT;
+        const bool live = consumer ? st >= 1 : st < steps;
+        // rows of the tile that lie before this wavefront's keys see none of them (both roles skip alike)
+        if (live && !(CAUSAL && m0 + kT - 1 < n0w)) {
+            bf16x8 bf[4];  // P (producer) or dS (consumer) of the tile's 64 rows, B-operand layout
+            bf16x8 rq[PF + 1], tq[PF + 1];
+            if (!consumer) {
+                const uint32_t qb = ps.x_at(SA), ob = ps.y_at(SA);
+                const float *lse_s = s_lse[SA];
+                // only tiles that touch the end of the sequence or the diagonal have masked elements
+                const bool need_mask = m0 + kT > L || n0w + 32 > L || (CAUSAL && n0w + 31 > m0);
+#pragma unroll
+                for (int i = 0; i < PF; ++i) rq[i] = ps.rd_row(qb, 0, i);
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb) {
+                    f32x16 sa;
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) sa[e] = 0.f;
+#pragma unroll
+                    for (int c = 0; c < NC; ++c) {
+                        const int sn = NC * mb + c + PF;
+                        if (sn < 2 * NC) rq[sn % (PF + 1)] = ps.rd_row(qb, sn / NC, sn % NC);
+                        else tq[(sn - 2 * NC) % (PF + 1)] = ps.rd_tr(ob, sn - 2 * NC);
+                        __builtin_amdgcn_sched_barrier(0);
+                        sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rq[(NC * mb + c) % (PF + 1)], sf[c], sa, 0, 0, 0);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    // register e of the accumulator is row 8 (e / 4) + 4 g + e % 4 of the block
+                    float x16[16];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const f32x4 l4 = *(const f32x4 *)(&lse_s[32 * mb + 8 * j + 4 * g]);
+#pragma unroll
+                        for (int w = 0; w < 4; ++w)
+                            x16[4 * j + w] = __builtin_amdgcn_exp2f(sa[4 * j + w] * scale_log2 - l4[w]);
+                    }
+                    if (need_mask) {
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) {
+                            const int m = m0 + 32 * mb + 8 * (e >> 2) + 4 * g + (e & 3);
+                            const bool vis = m < L && kn < L && (!CAUSAL || kn <= m);
+                            x16[e] = vis ? x16[e] : 0.f;
+                        }
+                    }
+#pragma unroll
+                    for (int half = 0; half < 2; ++half) {
+                        u32x4 a;
+                        a.x = pack_bf16(x16[8 * half + 0], x16[8 * half + 1]);
+                        a.y = pack_bf16(x16[8 * half + 2], x16[8 * half + 3]);
+                        a.z = pack_bf16(x16[8 * half + 4], x16[8 * half + 5]);
+                        a.w = pack_bf16(x16[8 * half + 6], x16[8 * half + 7]);
+                        bf[2 * mb + half] = __builtin_bit_cast(bf16x8, a);
+                        s_p[SA][kbw][2 * mb + half][lane] = bf[2 * mb + half];
+                    }
+                }
+                accumulate(ob, bf, tq);
+            } else {
+                const uint32_t qb = ps.x_at(SB), ob = ps.y_at(SB);
+                const float *dlt_s = s_dlt[SB];
+#pragma unroll
+                for (int i = 0; i < PF; ++i) rq[i] = ps.rd_row(ob, 0, i);
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb) {
+                    f32x16 da;
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) da[e] = 0.f;
+#pragma unroll
+                    for (int c = 0; c < NC; ++c) {
+                        const int sn = NC * mb + c + PF;
+                        if (sn < 2 * NC) rq[sn % (PF + 1)] = ps.rd_row(ob, sn / NC, sn % NC);
+                        else tq[(sn - 2 * NC) % (PF + 1)] = ps.rd_tr(qb, sn - 2 * NC);
+                        __builtin_amdgcn_sched_barrier(0);
+                        da = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rq[(NC * mb + c) % (PF + 1)], sf[c], da, 0, 0, 0);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+#pragma unroll
+                    for (int half = 0; half < 2; ++half) {
+                        const u32x4 pw = __builtin_bit_cast(u32x4, s_p[SB][kbw][2 * mb + half][lane]);
+                        float d8[8];
+#pragma unroll
+                        for (int jj = 0; jj < 2; ++jj) {
+                            const f32x4 t4 = *(const f32x4 *)(&dlt_s[32 * mb + 8 * (2 * half + jj) + 4 * g]);
+#pragma unroll
+                            for (int w = 0; w < 4; ++w) {
+                                const int i = 4 * jj + w;                      // element of the fragment
+                                const uint32_t pr = pw[i >> 1];
+                                const float p = __uint_as_float((i & 1) ? (pr & 0xffff0000u) : (pr << 16));
+                                d8[i] = p * (da[8 * half + i] - t4[w]);
+                            }
+                        }
+                        u32x4 a;
+                        a.x = pack_bf16(d8[0], d8[1]);
+                        a.y = pack_bf16(d8[2], d8[3]);
+                        a.z = pack_bf16(d8[4], d8[5]);
+                        a.w = pack_bf16(d8[6], d8[7]);
+                        bf[2 * mb + half] = __builtin_bit_cast(bf16x8, a);
+                    }
+                }
+                accumulate(qb, bf, tq);
+            }
+        }
+        if (++w_tile == ntile_m) w_tile = 0;
+        // the next step's row statistics: their slots were last read before this step's barrier
+        if (st + 1 < steps) store_stats(std::integral_constant<int, (SA + 1) % 3>{});
+    };
+    for (int st = 0; st < nloop; st += 3) {
+        step(std::integral_constant<int, 0>{}, st);
+        if (st + 1 < nloop) step(std::integral_constant<int, 1>{}, st + 1);
+        if (st + 2 < nloop) step(std::integral_constant<int, 2>{}, st + 2);
+    }
+
+    if (kn < L) {
+        const float f = consumer ? scale : 1.0f;
+        uint16_t *op = (consumer ? dk : dv) + ((size_t)(row0 + kn) * Hkv + g_kv) * HD;
 #pragma unroll
         for (int b = 0; b < NDB; ++b)
 #pragma unroll
@@ -515,16 +769,24 @@ int launch_attn_bwd(const void *q, const void *k, const void *v, const void *out
         const unsigned qgrid = (unsigned)(max_tiles * Hq), kgrid = (unsigned)(max_tiles * Hkv);
 #define ORCH_BWD_COMMON (const uint16_t *)q, (const uint16_t *)k, (const uint16_t *)v, (const uint16_t *)dout, lse, w.delta
 #define ORCH_BWD_TAIL cu_seqlens, w.hdr, w.tile_off, batch, total_tokens, Hq, Hkv, scale, sl2
+// head_dim 128 (long LLM-phase sequences): dK and dV from the fused producer/consumer kernel.
+// head_dim 64 (encoder phases, sequences of a few hundred rows): one kernel per output; the fused
+// kernel's extra step per (key tile, head) costs more there than the second S product.
 #define ORCH_BWD_LAUNCH(HD_, C_)                                                                                  \
     do {                                                                                                          \
         hipLaunchKernelGGL((attn_bwd_delta_kernel<HD_>), dim3(dgrid), dim3(256), 0, stream,                      \
                            (const uint16_t *)dout, (const uint16_t *)out, w.delta, (int64_t)total_tokens, Hq);    \
         hipLaunchKernelGGL((attn_bwd_dq_kernel<HD_, C_>), dim3(qgrid), dim3(kThreads), 0, stream,                 \
                            ORCH_BWD_COMMON, (uint16_t *)dq, ORCH_BWD_TAIL);                                       \
-        hipLaunchKernelGGL((attn_bwd_dkv_kernel<HD_, C_, PART_DK>), dim3(kgrid), dim3(kThreads), 0, stream,       \
-                           ORCH_BWD_COMMON, (uint16_t *)dk, ORCH_BWD_TAIL);                                       \
-        hipLaunchKernelGGL((attn_bwd_dkv_kernel<HD_, C_, PART_DV>), dim3(kgrid), dim3(kThreads), 0, stream,       \
-                           ORCH_BWD_COMMON, (uint16_t *)dv, ORCH_BWD_TAIL);                                       \
+        if (HD_ == 128) {                                                                                         \
+            hipLaunchKernelGGL((attn_bwd_dkv_fused_kernel<128, C_>), dim3(kgrid), dim3(2 * kThreads), 0, stream,  \
+                               ORCH_BWD_COMMON, (uint16_t *)dk, (uint16_t *)dv, ORCH_BWD_TAIL);                   \
+        } else {                                                                                                  \
+            hipLaunchKernelGGL((attn_bwd_dkv_kernel<64, C_, PART_DK>), dim3(kgrid), dim3(kThreads), 0, stream,    \
+                               ORCH_BWD_COMMON, (uint16_t *)dk, ORCH_BWD_TAIL);                                   \
+            hipLaunchKernelGGL((attn_bwd_dkv_kernel<64, C_, PART_DV>), dim3(kgrid), dim3(kThreads), 0, stream,    \
+                               ORCH_BWD_COMMON, (uint16_t *)dv, ORCH_BWD_TAIL);                                   \
+        }                                                                                                         \
     } while (0)
         if (d == 128 && causal) ORCH_BWD_LAUNCH(128, true);
         else if (d == 128) ORCH_BWD_LAUNCH(128, false);

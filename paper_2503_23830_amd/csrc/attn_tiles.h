@@ -57,14 +57,18 @@ __device__ __forceinline__ int dma_swz(int r)
     return 4 * ((r >> 1) & 1) + 2 * ((r >> 3) & 1) + ((r >> 2) & 1);
 }
 
-template <int HD>
+// NST stages (a tile pair stays readable for NST - 1 steps after the one that fetched it);
+// NWAVE wavefronts share the staging, each fetching kT / NWAVE rows of both tiles.
+template <int HD, int NST = 2, int NWAVE = 4>
 struct PairStage {
     static constexpr int ROWB = 2 * HD;
     static constexpr int TILE_B = kT * ROWB;
-    static constexpr int BYTES = 4 * TILE_B;      // two stages of two tiles
+    static constexpr int BYTES = NST * 2 * TILE_B;
     static constexpr int CH = ROWB / 16;          // 16-byte chunks per row
     static constexpr int RPI = 1024 / ROWB;       // rows one DMA load moves (64 lanes x 16 bytes)
-    static constexpr int NP = 16 / RPI;           // loads per wavefront and tile (it fetches 16 rows)
+    static constexpr int WROWS = kT / NWAVE;      // rows of a tile one wavefront fetches
+    static constexpr int NP = WROWS / RPI;        // loads per wavefront and tile
+    static_assert(NP >= 1 && NP * RPI * NWAVE == kT, "the wavefronts' loads must tile the 64 rows");
     uint32_t base;
     uint32_t raddr[HD / 16];     // row reads: l32 * ROWB + 16 * ((2 c + g) ^ swz(l32))
     uint32_t taddr[2][HD / 32];  // transpose reads, rows 8 u + 4 g + j4, columns of block b
@@ -87,14 +91,20 @@ struct PairStage {
                 taddr[u][b] = (uint32_t)(r * ROWB + 16 * ((4 * b + 2 * half + (a >> 1)) ^ dma_swz<HD>(r)) + 8 * (a & 1));
             }
         // a DMA load moves 64 lanes x 16 bytes = RPI rows into 1 KB of LDS in lane order; this
-        // wavefront fetches rows 16 wave .. 16 wave + 15 of the tile in NP loads
-        drow = 16 * wave + lane / CH;
+        // wavefront fetches rows WROWS wave .. + WROWS - 1 of the tile in NP loads
+        drow = WROWS * wave + lane / CH;
 #pragma unroll
         for (int p = 0; p < NP; ++p) dcol[p] = 16u * (uint32_t)((lane % CH) ^ dma_swz<HD>(drow + RPI * p));
-        ddst = (uint32_t)(16 * wave * ROWB);
+        ddst = (uint32_t)(WROWS * wave * ROWB);
     }
-    __device__ __forceinline__ uint32_t x_base(int it) const { return base + (uint32_t)((it & 1) * 2 * TILE_B); }
+    __device__ __forceinline__ uint32_t x_base(int it) const
+    {
+        return base + (uint32_t)((NST == 2 ? (it & 1) : (it % NST)) * 2 * TILE_B);
+    }
     __device__ __forceinline__ uint32_t y_base(int it) const { return x_base(it) + TILE_B; }
+    // the same by stage number (a constant in loops unrolled by NST)
+    __device__ __forceinline__ uint32_t x_at(int stage) const { return base + (uint32_t)(stage * 2 * TILE_B); }
+    __device__ __forceinline__ uint32_t y_at(int stage) const { return x_at(stage) + TILE_B; }
     __device__ __forceinline__ bf16x8 rd_row(uint32_t tile, int blk, int c) const
     {
         return lds_rd128(tile + raddr[c] + (uint32_t)(blk * 32 * ROWB));
@@ -123,13 +133,14 @@ struct PairStage {
         const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
         return (const char *)(uintptr_t)(((uint64_t)hi << 32) | lo);
     }
-    __device__ __forceinline__ void begin(const TileSrc &s, int it)
+    __device__ __forceinline__ void begin(const TileSrc &s, int it) { begin_at(s, NST == 2 ? (it & 1) : (it % NST)); }
+    __device__ __forceinline__ void begin_at(const TileSrc &s, int stage)
     {
         const uint32_t rstride = (uint32_t)s.heads * HD * 2;
         const size_t e = ((size_t)(s.row0 + s.m0) * s.heads + s.hd) * HD;
         const char *tx = uniform_ptr(s.px + e), *ty = uniform_ptr(s.py + e);
         const int last = s.L - 1 - s.m0;  // rows past the end of the sequence repeat its last row (masked later)
-        const uint32_t dx = (uint32_t)__builtin_amdgcn_readfirstlane((int)(x_base(it) + ddst));
+        const uint32_t dx = (uint32_t)__builtin_amdgcn_readfirstlane((int)(x_at(stage) + ddst));
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
             const uint32_t off = (uint32_t)min(drow + RPI * p, last) * rstride + dcol[p];
