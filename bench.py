@@ -426,7 +426,7 @@ def main():
     attn_bwd = {"ms": bwd_ms, "tflops": bwd_flops / (bwd_ms * 1e-3) / 1e12,
                 "frac_mfma_peak": bwd_flops / (bwd_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "flop": bwd_flops,
                 "verified": bool(bwd_ok), "oracle_units_seq_kvhead_len": bwd_units,
-                "note": "delta + dq + dk + dv kernels, deterministic; executes 8 products (S three times, dP twice) for the 5 counted"}
+                "note": "delta + dq + fused dk/dv kernels at head_dim 128 (dk and dv separately at 64), deterministic; executes 7 products at head_dim 128 (S and dP twice), 8 at 64, for the 5 counted"}
 
     cpu_baseline = None
     if not args.no_cpu_baseline:
