@@ -244,26 +244,24 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
                 da = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vq[(NC * nb + c) % (PF + 1)], dof[c], da, 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
+            float d16[16];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) d16[e] = __builtin_amdgcn_exp2f(sa[e] * scale_log2 - lse2) * (da[e] - dlt);
+            if (need_mask) {   // one wave-uniform branch around all the selects
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int n = n0 + 32 * nb + 8 * (e >> 2) + 4 * g + (e & 3);
+                    const bool vis = n < L && (!CAUSAL || n <= qm);
+                    d16[e] = vis ? d16[e] : 0.f;
+                }
+            }
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
-                float d8[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int idx = 8 * half + e;
-                    const float p = __builtin_amdgcn_exp2f(sa[idx] * scale_log2 - lse2);
-                    float val = p * (da[idx] - dlt);
-                    if (need_mask) {
-                        const int n = n0 + 32 * nb + 8 * (idx >> 2) + 4 * g + (idx & 3);
-                        const bool vis = n < L && (!CAUSAL || n <= qm);
-                        val = vis ? val : 0.f;
-                    }
-                    d8[e] = val;
-                }
                 u32x4 pk;
-                pk.x = pack_bf16(d8[0], d8[1]);
-                pk.y = pack_bf16(d8[2], d8[3]);
-                pk.z = pack_bf16(d8[4], d8[5]);
-                pk.w = pack_bf16(d8[6], d8[7]);
+                pk.x = pack_bf16(d16[8 * half + 0], d16[8 * half + 1]);
+                pk.y = pack_bf16(d16[8 * half + 2], d16[8 * half + 3]);
+                pk.z = pack_bf16(d16[8 * half + 4], d16[8 * half + 5]);
+                pk.w = pack_bf16(d16[8 * half + 6], d16[8 * half + 7]);
                 dsf[2 * nb + half] = __builtin_bit_cast(bf16x8, pk);
             }
         }
