@@ -205,14 +205,28 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
     ps.init((uint32_t)(uintptr_t)lds_raw, lane, wave);
     TileSrc src{k, v, row0, L, 0, Hkv, g_kv};
     ps.begin(src, 0);
+    // the next tile's loads go out between this tile's MFMAs, one every kSlots / NLOAD slots (a slot
+    // is a pair of first-product MFMAs or one MFMA of the last product)
+    using Plan = typename PS::Plan;
+    constexpr int kSlots = 4 * NC;
+    bool has_next = false;
+    auto dma_slot = [&](const Plan &pl, int i) {
+        constexpr int every = kSlots / PS::NLOAD;
+        if (i % every == 1 && has_next) PS::issue(pl, i / every);
+    };
     for (int it = 0; it < ntile_k; ++it) {
         const int n0 = it * kT;
         ps.publish();
-        if (it + 1 < ntile_k) {
-            src.m0 = n0 + kT;
-            ps.begin(src, it + 1);
+        has_next = it + 1 < ntile_k;
+        if (has_next) src.m0 = n0 + kT;
+        const Plan pl = ps.plan(src, (it + 1) & 1);
+        if (CAUSAL && n0 > q0 + 32 * wave + 31) {  // this wavefront's rows see none of the tile
+            if (has_next) {
+#pragma unroll
+                for (int kq_ = 0; kq_ < PS::NLOAD; ++kq_) PS::issue(pl, kq_);
+            }
+            continue;
         }
-        if (CAUSAL && n0 > q0 + 32 * wave + 31) continue;  // this wavefront's rows see none of the tile
         const uint32_t kb = ps.x_base(it), vb = ps.y_base(it);
 
         // per 32-key block: S^T = K Q^T and dP^T = V dout^T, then dS^T = P^T (dP^T - delta),
@@ -242,6 +256,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
                 __builtin_amdgcn_sched_barrier(0);
                 sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kq[(NC * nb + c) % (PF + 1)], qf[c], sa, 0, 0, 0);
                 da = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vq[(NC * nb + c) % (PF + 1)], dof[c], da, 0, 0, 0);
+                dma_slot(pl, NC * nb + c);
                 __builtin_amdgcn_sched_barrier(0);
             }
             float d16[16];
@@ -271,6 +286,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
             if (j + PF < 4 * NDB) tq[(j + PF) % (PF + 1)] = ps.rd_tr(kb, j + PF);
             __builtin_amdgcn_sched_barrier(0);
             acc[j >> 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq[j % (PF + 1)], dsf[j & 3], acc[j >> 2], 0, 0, 0);
+            dma_slot(pl, 2 * NC + j);
             __builtin_amdgcn_sched_barrier(0);
         }
     }
@@ -556,24 +572,39 @@ __global__ __launch_bounds__(2 * kThreads, 1) void attn_bwd_dkv_fused_kernel(
     // loop is unrolled by the three stages, so a step's stage is a constant and every fragment
     // read is a fixed lane address plus an immediate offset.
     int f_tile = 0;                 // tile index (inside its head) of the step fetched next
-    auto start_step = [&](auto stage_c) {
+    // Moves on to the next step's tile (when there is one) and returns its loads; the caller
+    // spreads them over its MFMAs.
+    using Plan = typename PS::Plan;
+    auto start_step = [&](auto stage_c, bool more) {
         constexpr int STG = decltype(stage_c)::value;
-        src.m0 = m_begin + f_tile * kT;
-        ps.begin_at(src, STG);
+        if (more) {
+            if (f_tile == ntile_m) { f_tile = 0; ++src.hd; }
+            src.m0 = m_begin + f_tile * kT;
+            ++f_tile;
+        }
         if (tid < kT) {
             int m = src.m0 + tid;
             m = m < L ? m : L - 1;
             r_lse = lse[(size_t)src.hd * total_tokens + row0 + m] * kLog2e;
             r_dlt = delta[(size_t)src.hd * total_tokens + row0 + m];
         }
-        if (++f_tile == ntile_m) { f_tile = 0; ++src.hd; }
+        return ps.plan(src, STG);
+    };
+    // load k of the plan goes out after MFMA 1 + k * (MFMAs per step / loads per step) of the step
+    constexpr int kMfmaPerStep = 4 * NC;
+    bool has_next = false;
+    auto dma_slot = [&](const Plan &pl, int i) {
+        constexpr int every = kMfmaPerStep / PS::NLOAD;
+        if (i % every == 1 && has_next) PS::issue(pl, i / every);
     };
     auto store_stats = [&](auto stage_c) {
         constexpr int STG = decltype(stage_c)::value;
         if (tid < kT) { s_lse[STG][tid] = r_lse; s_dlt[STG][tid] = r_dlt; }
     };
     if (steps > 0) {
-        start_step(std::integral_constant<int, 0>{});
+        const Plan pl = start_step(std::integral_constant<int, 0>{}, true);
+#pragma unroll
+        for (int k = 0; k < PS::NLOAD; ++k) PS::issue(pl, k);
         store_stats(std::integral_constant<int, 0>{});
     }
     constexpr int PF = ORCH_BWD_PF;
@@ -581,12 +612,13 @@ __global__ __launch_bounds__(2 * kThreads, 1) void attn_bwd_dkv_fused_kernel(
     int w_tile = consumer ? -1 : 0;                // tile index (inside its head) this wavefront works on
 
     // dV^T += dout^T P (producer) or dK^T += Q^T dS (consumer) over the tile's 64 rows, step j = 4 b + t
-    auto accumulate = [&](uint32_t xb, const bf16x8 (&bf)[4], bf16x8 (&tq)[PF + 1]) {
+    auto accumulate = [&](uint32_t xb, const bf16x8 (&bf)[4], bf16x8 (&tq)[PF + 1], const Plan &pl) {
 #pragma unroll
         for (int j = 0; j < 4 * NDB; ++j) {
             if (j + PF < 4 * NDB) tq[(j + PF) % (PF + 1)] = ps.rd_tr(xb, j + PF);
             __builtin_amdgcn_sched_barrier(0);
             acc[j >> 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq[j % (PF + 1)], bf[j & 3], acc[j >> 2], 0, 0, 0);
+            dma_slot(pl, 2 * NC + j);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -595,20 +627,23 @@ __global__ __launch_bounds__(2 * kThreads, 1) void attn_bwd_dkv_fused_kernel(
         constexpr int SA = decltype(stage_c)::value;   // stage of the tile fetched for step st (the producer's)
         constexpr int SB = (SA + 2) % 3;               // stage of the tile of step st - 1 (the consumer's)
         ps.publish();
-        if (st + 1 < steps) start_step(std::integral_constant<int, (SA + 1) % 3>{});
+        has_next = st + 1 < steps;
+        const Plan pl = start_step(std::integral_constant<int, (SA + 1) % 3>{}, has_next);
         const int m0 = m_begin + w_tile * kT;
         const bool live = consumer ? st >= 1 : st < steps;
         // rows of the tile that lie before this wavefront's keys see none of them (both roles skip alike)
         if (live && !(CAUSAL && m0 + kT - 1 < n0w)) {
             bf16x8 bf[4];  // P (producer) or dS (consumer) of the tile's 64 rows, B-operand layout
-            bf16x8 rq[PF + 1], tq[PF + 1];
+            // one ring for row and transposed fragments: every run of MFMAs has an even length
+            static_assert(PF == 1 && NC % 2 == 0, "the fragment ring alternates between two registers");
+            bf16x8 fq[2];
             if (!consumer) {
                 const uint32_t qb = ps.x_at(SA), ob = ps.y_at(SA);
                 const float *lse_s = s_lse[SA];
                 // only tiles that touch the end of the sequence or the diagonal have masked elements
                 const bool need_mask = m0 + kT > L || n0w + 32 > L || (CAUSAL && n0w + 31 > m0);
 #pragma unroll
-                for (int i = 0; i < PF; ++i) rq[i] = ps.rd_row(qb, 0, i);
+                for (int i = 0; i < PF; ++i) fq[i] = ps.rd_row(qb, 0, i);
 #pragma unroll
                 for (int mb = 0; mb < 2; ++mb) {
                     f32x16 sa;
@@ -617,10 +652,11 @@ __global__ __launch_bounds__(2 * kThreads, 1) void attn_bwd_dkv_fused_kernel(
 #pragma unroll
                     for (int c = 0; c < NC; ++c) {
                         const int sn = NC * mb + c + PF;
-                        if (sn < 2 * NC) rq[sn % (PF + 1)] = ps.rd_row(qb, sn / NC, sn % NC);
-                        else tq[(sn - 2 * NC) % (PF + 1)] = ps.rd_tr(ob, sn - 2 * NC);
+                        if (sn < 2 * NC) fq[sn % (PF + 1)] = ps.rd_row(qb, sn / NC, sn % NC);
+                        else fq[(sn - 2 * NC) % (PF + 1)] = ps.rd_tr(ob, sn - 2 * NC);
                         __builtin_amdgcn_sched_barrier(0);
-                        sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rq[(NC * mb + c) % (PF + 1)], sf[c], sa, 0, 0, 0);
+                        sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[(NC * mb + c) % (PF + 1)], sf[c], sa, 0, 0, 0);
+                        dma_slot(pl, NC * mb + c);
                         __builtin_amdgcn_sched_barrier(0);
                     }
                     // register e of the accumulator is row 8 (e / 4) + 4 g + e % 4 of the block
@@ -651,12 +687,12 @@ __global__ __launch_bounds__(2 * kThreads, 1) void attn_bwd_dkv_fused_kernel(
                         s_p[SA][kbw][2 * mb + half][lane] = bf[2 * mb + half];
                     }
                 }
-                accumulate(ob, bf, tq);
+                accumulate(ob, bf, fq, pl);
             } else {
                 const uint32_t qb = ps.x_at(SB), ob = ps.y_at(SB);
                 const float *dlt_s = s_dlt[SB];
 #pragma unroll
-                for (int i = 0; i < PF; ++i) rq[i] = ps.rd_row(ob, 0, i);
+                for (int i = 0; i < PF; ++i) fq[i] = ps.rd_row(ob, 0, i);
 #pragma unroll
                 for (int mb = 0; mb < 2; ++mb) {
                     f32x16 da;
@@ -665,10 +701,11 @@ __global__ __launch_bounds__(2 * kThreads, 1) void attn_bwd_dkv_fused_kernel(
 #pragma unroll
                     for (int c = 0; c < NC; ++c) {
                         const int sn = NC * mb + c + PF;
-                        if (sn < 2 * NC) rq[sn % (PF + 1)] = ps.rd_row(ob, sn / NC, sn % NC);
-                        else tq[(sn - 2 * NC) % (PF + 1)] = ps.rd_tr(qb, sn - 2 * NC);
+                        if (sn < 2 * NC) fq[sn % (PF + 1)] = ps.rd_row(ob, sn / NC, sn % NC);
+                        else fq[(sn - 2 * NC) % (PF + 1)] = ps.rd_tr(qb, sn - 2 * NC);
                         __builtin_amdgcn_sched_barrier(0);
-                        da = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rq[(NC * mb + c) % (PF + 1)], sf[c], da, 0, 0, 0);
+                        da = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[(NC * mb + c) % (PF + 1)], sf[c], da, 0, 0, 0);
+                        dma_slot(pl, NC * mb + c);
                         __builtin_amdgcn_sched_barrier(0);
                     }
 #pragma unroll
@@ -694,8 +731,11 @@ __global__ __launch_bounds__(2 * kThreads, 1) void attn_bwd_dkv_fused_kernel(
                         bf[2 * mb + half] = __builtin_bit_cast(bf16x8, a);
                     }
                 }
-                accumulate(qb, bf, tq);
+                accumulate(qb, bf, fq, pl);
             }
+        } else if (has_next) {   // nothing to compute in this step: the loads still go out
+#pragma unroll
+            for (int k = 0; k < PS::NLOAD; ++k) PS::issue(pl, k);
         }
         if (++w_tile == ntile_m) w_tile = 0;
         // the next step's row statistics: their slots were last read before this step's barrier

@@ -133,20 +133,40 @@ struct PairStage {
         const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
         return (const char *)(uintptr_t)(((uint64_t)hi << 32) | lo);
     }
+    // The loads of one tile pair, ready to issue: 2 NP per wavefront.  The LDS-DMA unit is shared
+    // by the workgroup and a wavefront stalls at issue while it is busy, so callers that can
+    // spread issue(plan, k), k = 0 .. 2 NP - 1, over their MFMAs instead of issuing all at once.
+    struct Plan {
+        const char *tx, *ty;   // first row of the tiles (scalar)
+        uint32_t dx;           // LDS address of this wavefront's first load in the X tile (scalar)
+        uint32_t off[NP];      // this lane's byte offsets from tx / ty
+    };
+    static constexpr int NLOAD = 2 * NP;
+    __device__ __forceinline__ Plan plan(const TileSrc &s, int stage) const
+    {
+        Plan p;
+        const uint32_t rstride = (uint32_t)s.heads * HD * 2;
+        const size_t e = ((size_t)(s.row0 + s.m0) * s.heads + s.hd) * HD;
+        p.tx = uniform_ptr(s.px + e);
+        p.ty = uniform_ptr(s.py + e);
+        const int last = s.L - 1 - s.m0;  // rows past the end of the sequence repeat its last row (masked later)
+        p.dx = (uint32_t)__builtin_amdgcn_readfirstlane((int)(x_at(stage) + ddst));
+#pragma unroll
+        for (int i = 0; i < NP; ++i) p.off[i] = (uint32_t)min(drow + RPI * i, last) * rstride + dcol[i];
+        return p;
+    }
+    static __device__ __forceinline__ void issue(const Plan &p, int k)
+    {
+        const int i = k >> 1;
+        if (k & 1) dma_issue(p.ty, p.off[i], p.dx + (uint32_t)(TILE_B + RPI * i * ROWB));
+        else dma_issue(p.tx, p.off[i], p.dx + (uint32_t)(RPI * i * ROWB));
+    }
     __device__ __forceinline__ void begin(const TileSrc &s, int it) { begin_at(s, NST == 2 ? (it & 1) : (it % NST)); }
     __device__ __forceinline__ void begin_at(const TileSrc &s, int stage)
     {
-        const uint32_t rstride = (uint32_t)s.heads * HD * 2;
-        const size_t e = ((size_t)(s.row0 + s.m0) * s.heads + s.hd) * HD;
-        const char *tx = uniform_ptr(s.px + e), *ty = uniform_ptr(s.py + e);
-        const int last = s.L - 1 - s.m0;  // rows past the end of the sequence repeat its last row (masked later)
-        const uint32_t dx = (uint32_t)__builtin_amdgcn_readfirstlane((int)(x_at(stage) + ddst));
+        const Plan p = plan(s, stage);
 #pragma unroll
-        for (int p = 0; p < NP; ++p) {
-            const uint32_t off = (uint32_t)min(drow + RPI * p, last) * rstride + dcol[p];
-            dma_issue(tx, off, dx + (uint32_t)(RPI * p * ROWB));
-            dma_issue(ty, off, dx + (uint32_t)(TILE_B + RPI * p * ROWB));
-        }
+        for (int k = 0; k < NLOAD; ++k) issue(p, k);
     }
     __device__ __forceinline__ void publish()
     {
