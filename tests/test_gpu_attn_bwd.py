@@ -1,7 +1,8 @@
 """HIP orch_varlen_attn_bwd vs the fp64 CPU oracle.
 
 Tolerance (derived, not from the paper): every term of a gradient passes bf16 roundings (P or dS
-before the second product, the output), each at most 2^-9 relative to the TERM; a gradient
+before the second product, at head_dim 128 both of them for dk, and the output), each at most 2^-9
+relative to the TERM; a gradient
 element is a sum of many such terms that partly cancel, so its error scales with the size of the
 gradients of the tensor, not with the element: max |got - want| <= 1e-2 + 2^-7 max|want| over the
 compared tensor, mean-abs <= 2e-3, and the rms error is at most 5e-3 of the rms gradient (the
