@@ -80,6 +80,13 @@ def test_tile_boundaries(gpu_device, causal, Hq, Hkv, d):
     run_full(np.concatenate([[0], np.cumsum(L)]), Hq, Hkv, d, causal, gpu_device, seed=7)
 
 
+@pytest.mark.parametrize("causal", [True, False])
+def test_long_rows_wide_group(gpu_device, causal):
+    """Eight q-heads per kv-head and sequences of many 64-row tiles: the key-stationary kernels walk
+    heads x tiles through their LDS stages many times over."""
+    run_full(np.array([0, 1500, 1500 + 257]), 16, 2, 128, causal, gpu_device, seed=11)
+
+
 def test_explicit_scale_and_padding_rows(gpu_device):
     cu = np.array([0, 200, 200, 431], dtype=np.int32)
     run_full(cu, 4, 2, 128, True, gpu_device, scale=0.05, total=500)
