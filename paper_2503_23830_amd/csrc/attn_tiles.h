@@ -26,7 +26,7 @@ typedef short s16x8 __attribute__((ext_vector_type(8)));
 // 32x32 accumulator hold).  PairStage::rd_tr does this on the swizzled tile.
 
 constexpr int kT = 64;        // rows of a streamed LDS tile
-constexpr int kThreads = 256; // 4 wavefronts stage a tile pair together
+constexpr int kThreads = 256; // 4 wavefronts: the workgroup of every kernel here but the fused dK/dV one (8)
 
 __device__ __forceinline__ bf16x8 lds_rd128(uint32_t addr)
 {
@@ -42,7 +42,7 @@ struct TileSrc {
 
 // The pair of streamed LDS tiles of a step (X: K or Q, Y: V or dout) and the fragment reads on
 // them.  Rows go straight from global memory into LDS by LDS-DMA (no staging registers, no LDS
-// store instructions); two stages, one barrier per step.  Rows are unpadded; a slot swizzle keeps
+// store instructions); NST stages, one barrier per step.  Rows are unpadded; a slot swizzle keeps
 // both read patterns (16-byte row reads for the first products, 8-byte transpose reads for the
 // last one) free of bank conflicts.
 // Slot swizzle of the LDS-DMA layout: row r keeps its 16-byte chunk c at slot c ^ swz(r).
