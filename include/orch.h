@@ -194,14 +194,19 @@ size_t orch_varlen_attn_workspace(int32_t batch);
  *   q, out  [total_tokens, Hq, d] bf16      k, v  [total_tokens, Hkv, d] bf16
  *   lse     [Hq, total_tokens] fp32 natural-log-sum-exp, or NULL
  *   cu_seqlens [batch+1] int32, non-decreasing, cu_seqlens[batch] <= total_tokens
- *   max_seqlen  an upper bound on any sequence length (<= total_tokens), or 0
+ *   max_seqlen  an upper bound on any sequence length (<= total_tokens), or 0 = not known;
+ *               a nonzero bound caps the number of workgroups launched, and a sequence
+ *               longer than it is a data error
  *   d in {64, 128}; Hq % Hkv == 0; scale <= 0 means 1/sqrt(d)
+ *   dev_status  [1] device, may be NULL: receives ORCH_OK, or ORCH_EDATA when cu_seqlens is
+ *               not non-decreasing inside [0, total_tokens] or a sequence exceeds a nonzero
+ *               max_seqlen; on a data error nothing is written to out and lse
  * bf16 inputs, fp32 accumulation, bf16 output (round to nearest even).
  * Empty sequences write nothing. */
 int orch_varlen_attn_fwd(const void *q, const void *k, const void *v, void *out, float *lse,
                          const int32_t *cu_seqlens, int32_t batch, int32_t total_tokens,
                          int32_t max_seqlen, int32_t Hq, int32_t Hkv, int32_t d, float scale,
-                         int32_t causal, void *ws, size_t ws_bytes, void *stream);
+                         int32_t causal, int32_t *dev_status, void *ws, size_t ws_bytes, void *stream);
 
 /* Message for the last non-OK status returned on this thread; never NULL. */
 const char *orch_last_error(void);
@@ -222,12 +227,14 @@ size_t orch_varlen_attn_bwd_workspace(int32_t batch, int32_t total_tokens, int32
  *   dv[j,g,:] =         sum_{h in the group of g} sum_i p_ij dout[i,h,:]
  *   q, out, dout, dq  [total_tokens, Hq, d] bf16     k, v, dk, dv  [total_tokens, Hkv, d] bf16
  *   lse   [Hq, total_tokens] fp32 as written by the forward pass (required)
- * Same cu_seqlens, scale, causal and head-dim rules as the forward pass.  Rows outside every
- * sequence are not written.  No atomics: results are bit-reproducible. */
+ * Same cu_seqlens, max_seqlen, scale, causal, head-dim and dev_status rules as the forward
+ * pass (on a data error no gradient is written).  Rows outside every sequence are not
+ * written.  No atomics: results are bit-reproducible. */
 int orch_varlen_attn_bwd(const void *q, const void *k, const void *v, const void *out, const float *lse,
                          const void *dout, void *dq, void *dk, void *dv, const int32_t *cu_seqlens,
                          int32_t batch, int32_t total_tokens, int32_t max_seqlen, int32_t Hq, int32_t Hkv,
-                         int32_t d, float scale, int32_t causal, void *ws, size_t ws_bytes, void *stream);
+                         int32_t d, float scale, int32_t causal, int32_t *dev_status, void *ws, size_t ws_bytes,
+                         void *stream);
 
 #ifdef __cplusplus
 }

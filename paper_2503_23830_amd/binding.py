@@ -84,13 +84,13 @@ def load_library():
     lib.orch_varlen_attn_fwd.restype = C.c_int
     lib.orch_varlen_attn_fwd.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                          C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
-                                         C.c_int32, C.c_int32, C.c_float, C.c_int32, C.c_void_p,
+                                         C.c_int32, C.c_int32, C.c_float, C.c_int32, C.c_void_p, C.c_void_p,
                                          C.c_size_t, C.c_void_p]
     lib.orch_varlen_attn_bwd_workspace.restype = C.c_size_t
     lib.orch_varlen_attn_bwd_workspace.argtypes = [C.c_int32, C.c_int32, C.c_int32]
     lib.orch_varlen_attn_bwd.restype = C.c_int
     lib.orch_varlen_attn_bwd.argtypes = [C.c_void_p] * 10 + [C.c_int32] * 6 + [C.c_float, C.c_int32, C.c_void_p,
-                                                                                C.c_size_t, C.c_void_p]
+                                                                                C.c_void_p, C.c_size_t, C.c_void_p]
     lib.orch_last_error.restype = C.c_char_p
     lib.orch_attn_variant.restype = C.c_char_p
     _lib = lib
@@ -268,8 +268,10 @@ def comm_volume(lengths: torch.Tensor, asg: Assignment, D_src: int, src_inst: to
 
 def varlen_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cu_seqlens: torch.Tensor,
                     causal: bool, scale: float = 0.0, max_seqlen: int = 0, out: torch.Tensor | None = None,
-                    lse: torch.Tensor | None = None, ws: torch.Tensor | None = None) -> torch.Tensor:
-    """orch_varlen_attn_fwd: q [T,Hq,d], k,v [T,Hkv,d] bf16, cu_seqlens int32[batch+1]."""
+                    lse: torch.Tensor | None = None, ws: torch.Tensor | None = None,
+                    dev_status: torch.Tensor | None = None) -> torch.Tensor:
+    """orch_varlen_attn_fwd: q [T,Hq,d], k,v [T,Hkv,d] bf16, cu_seqlens int32[batch+1];
+    dev_status, if given, is an int32 device tensor of one element."""
     lib = load_library()
     for t in (q, k, v):
         assert t.is_cuda and t.is_contiguous() and t.dtype == torch.bfloat16 and t.dim() == 3
@@ -287,7 +289,7 @@ def varlen_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cu_seqlen
         ws = _workspace(lib.orch_varlen_attn_workspace(batch), dev)
     _check(lib.orch_varlen_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(cu_seqlens),
                                     batch, T, max_seqlen, Hq, Hkv, d, float(scale), 1 if causal else 0,
-                                    _ptr(ws), ws.numel(), C.c_void_p(_stream(dev))))
+                                    _ptr(dev_status), _ptr(ws), ws.numel(), C.c_void_p(_stream(dev))))
     return out
 
 
@@ -298,7 +300,8 @@ def varlen_attn_bwd_workspace(batch: int, total_tokens: int, Hq: int) -> int:
 def varlen_attn_bwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, out: torch.Tensor, lse: torch.Tensor,
                     dout: torch.Tensor, cu_seqlens: torch.Tensor, causal: bool, scale: float = 0.0,
                     max_seqlen: int = 0, dq: torch.Tensor | None = None, dk: torch.Tensor | None = None,
-                    dv: torch.Tensor | None = None, ws: torch.Tensor | None = None):
+                    dv: torch.Tensor | None = None, ws: torch.Tensor | None = None,
+                    dev_status: torch.Tensor | None = None):
     """orch_varlen_attn_bwd: (dq, dk, dv) from the forward pass's inputs, out and lse, and dout."""
     lib = load_library()
     for t in (q, k, v, out, dout):
@@ -319,7 +322,8 @@ def varlen_attn_bwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, out: torc
         ws = _workspace(lib.orch_varlen_attn_bwd_workspace(batch, T, Hq), dev)
     _check(lib.orch_varlen_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(dout), _ptr(dq), _ptr(dk),
                                     _ptr(dv), _ptr(cu_seqlens), batch, T, max_seqlen, Hq, Hkv, d, float(scale),
-                                    1 if causal else 0, _ptr(ws), ws.numel(), C.c_void_p(_stream(dev))))
+                                    1 if causal else 0, _ptr(dev_status), _ptr(ws), ws.numel(),
+                                    C.c_void_p(_stream(dev))))
     return dq, dk, dv
 
 

@@ -140,7 +140,7 @@ int orch_comm_volume(const int32_t *lengths, int32_t n, int32_t D_src, const int
 int orch_varlen_attn_fwd(const void *q, const void *k, const void *v, void *out, float *lse,
                          const int32_t *cu_seqlens, int32_t batch, int32_t total_tokens,
                          int32_t max_seqlen, int32_t Hq, int32_t Hkv, int32_t d, float scale,
-                         int32_t causal, void *ws, size_t ws_bytes, void *stream)
+                         int32_t causal, int32_t *dev_status, void *ws, size_t ws_bytes, void *stream)
 {
     if (batch < 0 || total_tokens < 0) ORCH_FAIL(ORCH_EINVAL, "orch_varlen_attn_fwd: batch = %d, total_tokens = %d", batch, total_tokens);
     if (max_seqlen < 0 || max_seqlen > total_tokens) ORCH_FAIL(ORCH_EINVAL, "orch_varlen_attn_fwd: max_seqlen = %d outside [0, %d]", max_seqlen, total_tokens);
@@ -152,14 +152,15 @@ int orch_varlen_attn_fwd(const void *q, const void *k, const void *v, void *out,
         ORCH_FAIL(ORCH_EINVAL, "orch_varlen_attn_fwd: q, k, v, out must be 16-byte aligned");
     if (!ws) ORCH_FAIL(ORCH_EINVAL, "orch_varlen_attn_fwd: workspace is NULL");
     if ((uintptr_t)ws & 255) ORCH_FAIL(ORCH_EINVAL, "orch_varlen_attn_fwd: workspace not 256-byte aligned");
-    return launch_attn(q, k, v, out, lse, cu_seqlens, batch, total_tokens, Hq, Hkv, d, scale, causal, ws,
-                       ws_bytes, (hipStream_t)stream);
+    return launch_attn(q, k, v, out, lse, cu_seqlens, batch, total_tokens, max_seqlen, Hq, Hkv, d, scale, causal,
+                       dev_status, ws, ws_bytes, (hipStream_t)stream);
 }
 
 int orch_varlen_attn_bwd(const void *q, const void *k, const void *v, const void *out, const float *lse,
                          const void *dout, void *dq, void *dk, void *dv, const int32_t *cu_seqlens,
                          int32_t batch, int32_t total_tokens, int32_t max_seqlen, int32_t Hq, int32_t Hkv,
-                         int32_t d, float scale, int32_t causal, void *ws, size_t ws_bytes, void *stream)
+                         int32_t d, float scale, int32_t causal, int32_t *dev_status, void *ws, size_t ws_bytes,
+                         void *stream)
 {
     if (batch < 0 || total_tokens < 0) ORCH_FAIL(ORCH_EINVAL, "orch_varlen_attn_bwd: batch = %d, total_tokens = %d", batch, total_tokens);
     if (max_seqlen < 0 || max_seqlen > total_tokens) ORCH_FAIL(ORCH_EINVAL, "orch_varlen_attn_bwd: max_seqlen = %d outside [0, %d]", max_seqlen, total_tokens);
@@ -172,8 +173,8 @@ int orch_varlen_attn_bwd(const void *q, const void *k, const void *v, const void
         ORCH_FAIL(ORCH_EINVAL, "orch_varlen_attn_bwd: tensors must be 16-byte aligned");
     if (!ws) ORCH_FAIL(ORCH_EINVAL, "orch_varlen_attn_bwd: workspace is NULL");
     if ((uintptr_t)ws & 255) ORCH_FAIL(ORCH_EINVAL, "orch_varlen_attn_bwd: workspace not 256-byte aligned");
-    return launch_attn_bwd(q, k, v, out, lse, dout, dq, dk, dv, cu_seqlens, batch, total_tokens, Hq, Hkv, d, scale,
-                           causal, ws, ws_bytes, (hipStream_t)stream);
+    return launch_attn_bwd(q, k, v, out, lse, dout, dq, dk, dv, cu_seqlens, batch, total_tokens, max_seqlen, Hq, Hkv,
+                           d, scale, causal, dev_status, ws, ws_bytes, (hipStream_t)stream);
 }
 
 }  // extern "C"

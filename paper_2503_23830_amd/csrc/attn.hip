@@ -19,6 +19,7 @@
 // rescaling O is a per-lane multiply.  The running maximum is only moved when a
 // row's maximum grows by more than 2^8 (exact: the stale reference cancels in
 // the final division), so O is rarely rescaled after the first tile.
+#include <algorithm>
 #include <type_traits>
 
 #include "attn_tiles.h"
@@ -36,9 +37,12 @@ struct AttnHdr {
 };
 
 // tile_off[t] = number of BM-row query tiles in sequences before t.
+// A cu_seqlens that is not non-decreasing inside [0, total_tokens], or a sequence longer than a
+// nonzero max_seqlen (the launch was sized for that bound), is a data error: no tile is
+// scheduled and dev_status, if given, receives ORCH_EDATA.
 __global__ __launch_bounds__(kPrepThreads) void attn_prep_kernel(const int32_t *__restrict__ cu,
                                                                 int32_t batch, int32_t total_tokens,
-                                                                int32_t BM, AttnHdr *hdr,
+                                                                int32_t max_seqlen, int32_t BM, AttnHdr *hdr,
                                                                 int32_t *tile_off, int32_t *dev_status)
 {
     __shared__ int32_t part[kPrepThreads];
@@ -52,7 +56,7 @@ __global__ __launch_bounds__(kPrepThreads) void attn_prep_kernel(const int32_t *
     int bad = 0;
     for (int t = b0; t < b1; ++t) {
         const int32_t lo = cu[t], hi = cu[t + 1];
-        if (lo < 0 || hi < lo || hi > total_tokens) { bad = 1; continue; }
+        if (lo < 0 || hi < lo || hi > total_tokens || (max_seqlen > 0 && hi - lo > max_seqlen)) { bad = 1; continue; }
         sum += (hi - lo + BM - 1) / BM;
     }
     if (bad) atomicOr(&s_bad, 1);
@@ -442,12 +446,14 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
     // One LDS-DMA load: 64 lanes x 16 bytes from tile base `tb` (scalar) + per-lane offset into
     // 1 KB of LDS at `dst`.  Written as asm so that the compiler does not tie later LDS reads
     // (of other stages) to this load with a vmcnt(0); completion is waited for explicitly
-    // before the tile barrier.  M0 = LDS destination of lane 0; nothing else in this kernel
-    // uses M0.
+    // before the tile barrier.  M0 = LDS destination of lane 0 (declared as clobbered).
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"   // M0 is reserved; the clobber is deliberate
     auto dma_issue = [&](const char *tb, uint32_t off, uint32_t dst) {
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                     :: "s"(dst), "v"(off), "s"(tb) : "memory");
+                     :: "s"(dst), "v"(off), "s"(tb) : "memory", "m0");
     };
+#pragma clang diagnostic pop
     struct DmaJob {
         const char *tb;     // first row of the tile
         uint32_t off[2];    // this lane's offsets for the wavefront's two loads
@@ -789,9 +795,9 @@ size_t attn_ws_bytes(int32_t batch)
 }
 
 int launch_attn(const void *q, const void *k, const void *v, void *out, float *lse,
-                const int32_t *cu_seqlens, int32_t batch, int32_t total_tokens, int32_t Hq,
-                int32_t Hkv, int32_t d, float scale, int32_t causal, void *ws, size_t ws_bytes,
-                hipStream_t stream)
+                const int32_t *cu_seqlens, int32_t batch, int32_t total_tokens, int32_t max_seqlen,
+                int32_t Hq, int32_t Hkv, int32_t d, float scale, int32_t causal, int32_t *dev_status,
+                void *ws, size_t ws_bytes, hipStream_t stream)
 {
     const size_t need = attn_ws_bytes(batch);
     if (ws_bytes < need) ORCH_FAIL(ORCH_ENOSPC, "orch_varlen_attn_fwd: workspace %zu < %zu bytes", ws_bytes, need);
@@ -804,8 +810,10 @@ int launch_attn(const void *q, const void *k, const void *v, void *out, float *l
     const bool il = d == 128;
     const int BM = 256;   // both kernels own 256 query rows per workgroup
     hipLaunchKernelGGL(attn_prep_kernel, dim3(1), dim3(kPrepThreads), 0, stream, cu_seqlens, batch,
-                       total_tokens, BM, hdr, tile_off, (int32_t *)nullptr);
-    const int64_t max_tiles = (int64_t)total_tokens / BM + batch;
+                       total_tokens, max_seqlen, BM, hdr, tile_off, dev_status);
+    // sum over sequences of ceil(L / BM) <= total / BM + batch, and <= batch * ceil(max_seqlen / BM)
+    int64_t max_tiles = (int64_t)total_tokens / BM + batch;
+    if (max_seqlen > 0) max_tiles = std::min<int64_t>(max_tiles, (int64_t)batch * ((max_seqlen + BM - 1) / BM));
     const int64_t grid = max_tiles * Hq;
     if (grid > 0x7fffffffLL) ORCH_FAIL(ORCH_EUNSUPPORTED, "orch_varlen_attn_fwd: %lld workgroups", (long long)grid);
     if (scale <= 0.f) scale = 1.0f / sqrtf((float)d);

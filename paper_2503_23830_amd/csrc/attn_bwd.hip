@@ -26,6 +26,7 @@
 // row-major LDS tile that serves the first products; the tiles get into LDS by LDS-DMA (PairStage).
 // Every product is v_mfma_f32_32x32x16_bf16 with fp32 accumulation; P and dS are rounded to
 // bf16 before the second products, as P is in the forward pass.
+#include <algorithm>
 #include <type_traits>
 
 #include "attn_tiles.h"
@@ -34,9 +35,7 @@
 namespace orch {
 namespace {
 
-#ifndef ORCH_BWD_PF
-#define ORCH_BWD_PF 1
-#endif
+constexpr int kFragAhead = 1;   // LDS fragment reads run this many MFMAs ahead of their use
 constexpr int kOwn = 128;       // rows a workgroup owns (queries for dq, keys for dk/dv)
 constexpr int kPrepThreads = 1024;
 constexpr float kLog2e = 1.4426950408889634f;
@@ -46,10 +45,12 @@ struct BwdHdr {
     int32_t ok;
 };
 
-// tile_off[t] = number of 128-row tiles in sequences before t; validates cu_seqlens.
+// tile_off[t] = number of 128-row tiles in sequences before t; validates cu_seqlens (not
+// non-decreasing inside [0, total_tokens], or a sequence longer than a nonzero max_seqlen: no
+// tile is scheduled and dev_status, if given, receives ORCH_EDATA).
 __global__ __launch_bounds__(kPrepThreads) void bwd_prep_kernel(const int32_t *__restrict__ cu, int32_t batch,
-                                                               int32_t total_tokens, BwdHdr *hdr,
-                                                               int32_t *tile_off)
+                                                               int32_t total_tokens, int32_t max_seqlen,
+                                                               BwdHdr *hdr, int32_t *tile_off, int32_t *dev_status)
 {
     __shared__ int32_t part[kPrepThreads];
     __shared__ int s_bad;
@@ -62,7 +63,7 @@ __global__ __launch_bounds__(kPrepThreads) void bwd_prep_kernel(const int32_t *_
     int bad = 0;
     for (int t = b0; t < b1; ++t) {
         const int32_t lo = cu[t], hi = cu[t + 1];
-        if (lo < 0 || hi < lo || hi > total_tokens) { bad = 1; continue; }
+        if (lo < 0 || hi < lo || hi > total_tokens || (max_seqlen > 0 && hi - lo > max_seqlen)) { bad = 1; continue; }
         sum += (hi - lo + kOwn - 1) / kOwn;
     }
     if (bad) atomicOr(&s_bad, 1);
@@ -85,6 +86,7 @@ __global__ __launch_bounds__(kPrepThreads) void bwd_prep_kernel(const int32_t *_
         hdr->ok = ok;
         hdr->total_tiles = ok ? part[kPrepThreads - 1] : 0;
         if (ok) tile_off[batch] = part[kPrepThreads - 1];
+        if (dev_status) dev_status[0] = ok ? (int32_t)ORCH_OK : (int32_t)ORCH_EDATA;
     }
 }
 
@@ -234,7 +236,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
         // that use them (explicitly: left alone the compiler reuses one pair of fragment registers
         // and every MFMA waits out a full LDS latency); the fences keep that order.
         const bool need_mask = (n0 + kT > L) || (CAUSAL && n0 + kT - 1 > q0 + 32 * wave);
-        constexpr int PF = ORCH_BWD_PF;
+        constexpr int PF = kFragAhead;
         bf16x8 dsf[4];
         bf16x8 kq[PF + 1], vq[PF + 1], tq[PF + 1];
 #pragma unroll
@@ -409,7 +411,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(
             // only tiles that touch the end of the sequence or the diagonal have masked elements
             const bool need_mask = m0 + kT > L || n0w + 32 > L || (CAUSAL && n0w + 31 > m0);
             // Fragment reads run PF steps ahead of the MFMAs that use them; the fences keep that order.
-            constexpr int PF = ORCH_BWD_PF;
+            constexpr int PF = kFragAhead;
             bf16x8 bf[4];  // P (dV) or dS (dK) of the tile's 64 rows, B-operand layout
             bf16x8 qq[PF + 1], oq[DK ? PF + 1 : 1], tq[PF + 1];
 #pragma unroll
@@ -607,7 +609,7 @@ __global__ __launch_bounds__(2 * kThreads, 1) void attn_bwd_dkv_fused_kernel(
         for (int k = 0; k < PS::NLOAD; ++k) PS::issue(pl, k);
         store_stats(std::integral_constant<int, 0>{});
     }
-    constexpr int PF = ORCH_BWD_PF;
+    constexpr int PF = kFragAhead;
     const int nloop = steps > 0 ? steps + 1 : 0;   // the consumer's last tile is done in one more step
     int w_tile = consumer ? -1 : 0;                // tile index (inside its head) this wavefront works on
 
@@ -789,15 +791,17 @@ size_t attn_bwd_ws_bytes(int32_t batch, int32_t total_tokens, int32_t Hq)
 
 int launch_attn_bwd(const void *q, const void *k, const void *v, const void *out, const float *lse,
                     const void *dout, void *dq, void *dk, void *dv, const int32_t *cu_seqlens,
-                    int32_t batch, int32_t total_tokens, int32_t Hq, int32_t Hkv, int32_t d, float scale,
-                    int32_t causal, void *ws, size_t ws_bytes, hipStream_t stream)
+                    int32_t batch, int32_t total_tokens, int32_t max_seqlen, int32_t Hq, int32_t Hkv, int32_t d,
+                    float scale, int32_t causal, int32_t *dev_status, void *ws, size_t ws_bytes,
+                    hipStream_t stream)
 {
     BwdWs w;
     const size_t need = carve(w, ws, batch, total_tokens, Hq);
     if (ws_bytes < need) ORCH_FAIL(ORCH_ENOSPC, "orch_varlen_attn_bwd: workspace %zu < %zu bytes", ws_bytes, need);
     hipLaunchKernelGGL(bwd_prep_kernel, dim3(1), dim3(kPrepThreads), 0, stream, cu_seqlens, batch, total_tokens,
-                       w.hdr, w.tile_off);
-    const int64_t max_tiles = (int64_t)total_tokens / kOwn + batch;
+                       max_seqlen, w.hdr, w.tile_off, dev_status);
+    int64_t max_tiles = (int64_t)total_tokens / kOwn + batch;
+    if (max_seqlen > 0) max_tiles = std::min<int64_t>(max_tiles, (int64_t)batch * ((max_seqlen + kOwn - 1) / kOwn));
     if (max_tiles * Hq > 0x7fffffffLL) ORCH_FAIL(ORCH_EUNSUPPORTED, "orch_varlen_attn_bwd: %lld workgroups", (long long)(max_tiles * Hq));
     if (scale <= 0.f) scale = 1.0f / sqrtf((float)d);
     const float sl2 = scale * kLog2e;

@@ -119,13 +119,18 @@ struct PairStage {
         return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7));
     }
     // One LDS-DMA load: 64 lanes x 16 bytes from scalar base `tb` + per-lane byte offset into the
-    // 1 KB of LDS that starts at `dst` (M0; nothing else here uses M0).  Written as asm so that
-    // the compiler does not tie later LDS reads of the other stage to it; publish() waits for it.
+    // 1 KB of LDS that starts at `dst` (M0, declared as clobbered).  Written as asm so that the
+    // compiler does not tie later LDS reads of the other stage to it; publish() waits for it.
+    // (the compiler reserves M0 for its own LDS-DMA / indexed-register sequences and warns about
+    // the clobber; declaring it is what makes it re-materialise M0 after this statement)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
     static __device__ __forceinline__ void dma_issue(const char *tb, uint32_t off, uint32_t dst)
     {
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(off), "s"(tb)
-                     : "memory");
+                     : "memory", "m0");
     }
+#pragma clang diagnostic pop
     static __device__ __forceinline__ const char *uniform_ptr(const void *ptr)
     {
         const uint64_t v = (uint64_t)(uintptr_t)ptr;

@@ -9,12 +9,13 @@
 //   cost_sort_kernel   one 1024-thread workgroup: cost keys, then a stable LSD
 //                      radix sort (8-bit digits, only as many passes as the
 //                      largest key needs) of (~cost, index) pairs
-//   greedy_*_kernel    two wavefronts.  Wave 0 runs the n-step serial loop and
-//                      does nothing but choose the receiving instance; every 64
-//                      steps it publishes the 64 choices.  Wave 1 trails it and
-//                      turns the choices into (instance, rank within instance,
-//                      first token) per sequence, so that bookkeeping never
-//                      sits on the dependent chain.
+//   greedy_*_kernel    one workgroup of four wavefronts.  Wave 0 runs the serial
+//                      loop (in rounds of up to D items where the loads allow) and
+//                      does nothing but choose the receiving instance; it publishes
+//                      the choices per sorted position.  Waves 1-3 trail it, taking
+//                      64-position chunks in turn, and make (instance, rank within
+//                      instance, first token) per sequence, so that bookkeeping
+//                      never sits on the dependent chain.
 //   layout_kernel      n threads: scatter sequence ids and segment starts
 // n <= 32768 keys is latency-bound work, so everything is arranged to keep the
 // dependent chain short rather than to stream memory.
@@ -404,12 +405,9 @@ __device__ void bookkeep_wave(const int32_t *ipos, const int32_t *__restrict__ s
 // instance index among equal loads.  A step is a 64-lane min-reduction.
 // ---------------------------------------------------------------------------
 template <int K>
-__global__ __launch_bounds__(kGreedyThreads) void greedy_reg_kernel(ORCH_GREEDY_PARAMS)
+__device__ __forceinline__ void greedy_reg_body(ORCH_GREEDY_PARAMS, uint32_t *s_cnt, unsigned long long *s_tok,
+                                                int &s_progress, int &s_booked)
 {
-    __shared__ uint32_t s_cnt[64 * K];
-    __shared__ unsigned long long s_tok[64 * K];
-    __shared__ int s_progress, s_booked;
-    if (flags[0] != 0) return;  // the packed-key kernel handles this call
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     for (int i = threadIdx.x; i < 64 * K; i += kGreedyThreads) { s_cnt[i] = 0; s_tok[i] = 0; }
@@ -520,14 +518,11 @@ constexpr int kRing = 4096;         // LDS window over the sorted costs, entries
 constexpr int kRefillChunks = 16;   // 64-entry chunks fetched per refill
 
 template <int K>
-__global__ __launch_bounds__(kGreedyThreads) void greedy_sorted_kernel(ORCH_GREEDY_PARAMS)
+__device__ __forceinline__ void greedy_sorted_body(ORCH_GREEDY_PARAMS, uint32_t *s_cnt, unsigned long long *s_tok,
+                                                   int &s_progress, int &s_booked)
 {
-    __shared__ uint32_t s_cnt[64 * K];
-    __shared__ unsigned long long s_tok[64 * K];
     __shared__ uint64_t s_perm[64 * K];   // rank-sort scatter, then loads by instance
     __shared__ uint64_t s_ring[kRing];    // (cost << 12) of sorted positions [.., filled)
-    __shared__ int s_progress, s_booked;
-    if (flags[0] != 1) return;  // loads too wide for the packed key: the general kernel runs
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     for (int i = threadIdx.x; i < 64 * K; i += kGreedyThreads) { s_cnt[i] = 0; s_tok[i] = 0; }
@@ -670,6 +665,21 @@ __global__ __launch_bounds__(kGreedyThreads) void greedy_sorted_kernel(ORCH_GREE
         for (int i = lane; i < D; i += 64) loads[i] = s_perm[i];
         finish_layout(s_cnt, s_tok, D, seq_off, tok_off, cu_seqlens, dev_status);
     }
+}
+
+// One entry for both register forms: the sort kernel's flag (every load fits the packed
+// (load << 12 | instance) key) picks the body on the device, so a call enqueues one launch.
+#define ORCH_GREEDY_NAMES                                                                           \
+    csorted, sorted, lengths, n, D, ipos, inst, rank, start, loads, seq_off, tok_off, cu_seqlens,   \
+        flags, dev_status
+template <int K>
+__global__ __launch_bounds__(kGreedyThreads) void greedy_kernel(ORCH_GREEDY_PARAMS)
+{
+    __shared__ uint32_t s_cnt[64 * K];
+    __shared__ unsigned long long s_tok[64 * K];
+    __shared__ int s_progress, s_booked;
+    if (flags[0] == 1) greedy_sorted_body<K>(ORCH_GREEDY_NAMES, s_cnt, s_tok, s_progress, s_booked);
+    else greedy_reg_body<K>(ORCH_GREEDY_NAMES, s_cnt, s_tok, s_progress, s_booked);
 }
 
 // Same loop for D beyond what registers hold: per-instance loads in LDS,
@@ -1124,13 +1134,9 @@ int launch_balance(const int32_t *lengths, int32_t n, int32_t D, orch_phase phas
 #define ORCH_GREEDY_ARGS                                                                        \
     w.csorted, w.sorted, lengths, n, D, w.ipos, out.inst, w.rank, w.start, out.loads,           \
         out.seq_off, out.tok_off, out.cu_seqlens, w.flags, out.dev_status
-    // both forms are enqueued; the flag written by the sort kernel decides on the
-    // device which of them does the work (the other returns at once)
-#define ORCH_GREEDY_BOTH(K_)                                                                    \
-    do {                                                                                        \
-        hipLaunchKernelGGL(greedy_sorted_kernel<K_>, dim3(1), dim3(kGreedyThreads), 0, stream, ORCH_GREEDY_ARGS); \
-        hipLaunchKernelGGL(greedy_reg_kernel<K_>, dim3(1), dim3(kGreedyThreads), 0, stream, ORCH_GREEDY_ARGS);    \
-    } while (0)
+    // the flag written by the sort kernel decides on the device which form of the greedy runs
+#define ORCH_GREEDY_BOTH(K_) \
+    hipLaunchKernelGGL(greedy_kernel<K_>, dim3(1), dim3(kGreedyThreads), 0, stream, ORCH_GREEDY_ARGS)
     if (D <= 64) ORCH_GREEDY_BOTH(1);
     else if (D <= 128) ORCH_GREEDY_BOTH(2);
     else if (D <= 256) ORCH_GREEDY_BOTH(4);

@@ -46,13 +46,14 @@ int launch_pack_composed(const void *enc_rows, void *packed, const int32_t *sub_
 int launch_comm_volume(const int32_t *lengths, int32_t n, int32_t D_src, const int32_t *from, int32_t D_dst,
                        orch_assignment dst, uint64_t *V, int32_t node, uint64_t *inter, hipStream_t stream);
 int launch_attn(const void *q, const void *k, const void *v, void *out, float *lse,
-                const int32_t *cu_seqlens, int32_t batch, int32_t total_tokens, int32_t Hq,
-                int32_t Hkv, int32_t d, float scale, int32_t causal, void *ws, size_t ws_bytes,
-                hipStream_t stream);
+                const int32_t *cu_seqlens, int32_t batch, int32_t total_tokens, int32_t max_seqlen,
+                int32_t Hq, int32_t Hkv, int32_t d, float scale, int32_t causal, int32_t *dev_status,
+                void *ws, size_t ws_bytes, hipStream_t stream);
 int launch_attn_bwd(const void *q, const void *k, const void *v, const void *out, const float *lse,
                     const void *dout, void *dq, void *dk, void *dv, const int32_t *cu_seqlens,
-                    int32_t batch, int32_t total_tokens, int32_t Hq, int32_t Hkv, int32_t d, float scale,
-                    int32_t causal, void *ws, size_t ws_bytes, hipStream_t stream);
+                    int32_t batch, int32_t total_tokens, int32_t max_seqlen, int32_t Hq, int32_t Hkv, int32_t d,
+                    float scale, int32_t causal, int32_t *dev_status, void *ws, size_t ws_bytes,
+                    hipStream_t stream);
 size_t attn_bwd_ws_bytes(int32_t batch, int32_t total_tokens, int32_t Hq);
 size_t balance_ws_bytes(int32_t n, int32_t D);
 size_t pack_ws_bytes(int32_t n, int32_t D);

@@ -182,7 +182,7 @@ int main(int argc, char **argv)
         CK(hipEventRecord(e1b, st));
         OK(orch_pack(tokens, packed, dLp, n, D, Tp, H, prow, ap, ib, ie, ws_p, wsp, st));
         CK(hipEventRecord(e2, st));
-        OK(orch_varlen_attn_fwd(q, k, v, o, nullptr, cu_dev, batch, Ti, 0, Hq, Hkv, d, 0.f, causal, ws_a, wsa, st));
+        OK(orch_varlen_attn_fwd(q, k, v, o, nullptr, cu_dev, batch, Ti, 0, Hq, Hkv, d, 0.f, causal, nullptr, ws_a, wsa, st));
         CK(hipEventRecord(e3, st));
         CK(hipStreamSynchronize(st));
         float m;
@@ -212,12 +212,12 @@ int main(int argc, char **argv)
         size_t wsw = orch_varlen_attn_bwd_workspace(batch, Ti, Hq);
         void *ws_w;
         CK(hipMalloc(&ws_w, wsw));
-        OK(orch_varlen_attn_fwd(q, k, v, o, lse, cu_dev, batch, Ti, 0, Hq, Hkv, d, 0.f, causal, ws_a, wsa, st));
+        OK(orch_varlen_attn_fwd(q, k, v, o, lse, cu_dev, batch, Ti, 0, Hq, Hkv, d, 0.f, causal, nullptr, ws_a, wsa, st));
         double tw = 0;
         for (int s = 0; s < steps + 1; ++s) {
             CK(hipEventRecord(e0, st));
             OK(orch_varlen_attn_bwd(q, k, v, o, lse, dout, dq, dk, dv, cu_dev, batch, Ti, 0, Hq, Hkv, d, 0.f, causal,
-                                    ws_w, wsw, st));
+                                    nullptr, ws_w, wsw, st));
             CK(hipEventRecord(e1, st));
             CK(hipStreamSynchronize(st));
             float ms;

@@ -87,18 +87,18 @@ def test_workspace_queries_and_host_side_errors():
     assert rc == -1 and b"sub_off" in lib.orch_last_error()
     rc = lib.orch_pack_composed(fake, fake, fake, fake, 8, 0, None, 4, asg, 10, 64, 10, 0, 4, fake, 64, None)
     assert rc == -2 and b"workspace" in lib.orch_last_error()
-    rc = lib.orch_varlen_attn_fwd(fake, fake, fake, fake, None, fake, 2, 64, 0, 8, 3, 64, 0.0, 1, fake,
+    rc = lib.orch_varlen_attn_fwd(fake, fake, fake, fake, None, fake, 2, 64, 0, 8, 3, 64, 0.0, 1, None, fake,
                                   1 << 20, None)
     assert rc == -1
-    rc = lib.orch_varlen_attn_fwd(fake, fake, fake, fake, None, fake, 2, 64, 0, 8, 4, 96, 0.0, 1, fake,
+    rc = lib.orch_varlen_attn_fwd(fake, fake, fake, fake, None, fake, 2, 64, 0, 8, 4, 96, 0.0, 1, None, fake,
                                   1 << 20, None)
     assert rc == -3 and b"head_dim" in lib.orch_last_error()
-    rc = lib.orch_varlen_attn_fwd(fake, fake, fake, fake, None, fake, 2, 64, 0, 8, 4, 64, 0.0, 1, fake,
+    rc = lib.orch_varlen_attn_fwd(fake, fake, fake, fake, None, fake, 2, 64, 0, 8, 4, 64, 0.0, 1, None, fake,
                                   8, None)
     assert rc == -2
     assert lib.orch_varlen_attn_bwd_workspace(4, 1000, 8) >= 1000 * 8 * 4
     bwd = lambda lse, d, wsb: lib.orch_varlen_attn_bwd(fake, fake, fake, fake, lse, fake, fake, fake, fake, fake,
-                                                       2, 64, 0, 8, 4, d, 0.0, 1, fake, wsb, None)
+                                                       2, 64, 0, 8, 4, d, 0.0, 1, None, fake, wsb, None)
     assert bwd(None, 64, 1 << 20) == -1 and b"lse" in lib.orch_last_error()
     assert bwd(fake, 96, 1 << 20) == -3
     assert bwd(fake, 64, 8) == -2

@@ -150,13 +150,58 @@ def test_config_row_sampled(gpu_device, cid):
     T = int(cu[-1])
     dev = gpu_device
     q, k, v = make_qkv(100 + cid, T, w.Hq, w.Hkv, w.d, dev)
-    out = orch.varlen_attn_fwd(q, k, v, torch.from_numpy(cu).to(dev), w.causal)
+    lse = torch.full((w.Hq, T), float("nan"), dtype=torch.float32, device=dev)
+    status = torch.full((1,), 77, dtype=torch.int32, device=dev)
+    out = orch.varlen_attn_fwd(q, k, v, torch.from_numpy(cu).to(dev), w.causal, lse=lse,
+                               max_seqlen=int(np.diff(cu).max()), dev_status=status)
     torch.cuda.synchronize()
+    assert int(status.item()) == 0
     count = 4096 if cid < 5 else 1024
     seq, head, row = sample_triples(cu, w.Hq, w.Hq // w.Hkv, count, cid)
-    want = oracle.attn_rows(bits(q), bits(k), bits(v), cu, w.causal, seq, head, row, nthreads=NT)
+    want, wlse = oracle.attn_rows(bits(q), bits(k), bits(v), cu, w.causal, seq, head, row, nthreads=NT,
+                                  want_lse=True)
     rt = torch.from_numpy(row.astype(np.int64)).to(dev)
     ht = torch.from_numpy(head.astype(np.int64)).to(dev)
     got = out[rt, ht].float().cpu().numpy()
     attn_tolerance_check(got, want)
+    assert np.max(np.abs(lse[ht, rt].cpu().numpy().astype(np.float64) - wlse)) <= 1e-3
     assert torch.isfinite(out.float()).all()
+    assert torch.isfinite(lse).all()   # every row of the instance belongs to a sequence
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_invalid_cu_seqlens_is_reported_and_writes_nothing(gpu_device, d):
+    """Data errors only the device can see: dev_status = ORCH_EDATA and out / lse untouched."""
+    dev = gpu_device
+    Hq, Hkv, T = 4, 2, 600
+    q, k, v = make_qkv(3, T, Hq, Hkv, d, dev)
+    good = np.array([0, 100, 100, 600], dtype=np.int32)
+    cases = {
+        "decreasing": (np.array([0, 300, 200, 600], dtype=np.int32), 0),
+        "beyond total_tokens": (np.array([0, 100, 300, 601], dtype=np.int32), 0),
+        "negative": (np.array([-1, 100, 300, 600], dtype=np.int32), 0),
+        "longer than max_seqlen": (good, 499),
+    }
+    for name, (cu, max_seqlen) in cases.items():
+        out = torch.full((T, Hq, d), float("nan"), dtype=torch.bfloat16, device=dev)
+        lse = torch.full((Hq, T), float("nan"), dtype=torch.float32, device=dev)
+        status = torch.zeros(1, dtype=torch.int32, device=dev)
+        orch.varlen_attn_fwd(q, k, v, torch.from_numpy(cu).to(dev), True, out=out, lse=lse,
+                             max_seqlen=max_seqlen, dev_status=status)
+        torch.cuda.synchronize()
+        assert int(status.item()) == -5, name
+        assert torch.isnan(out.float()).all() and torch.isnan(lse).all(), name
+        dq, dk, dv = (torch.full_like(t, float("nan")) for t in (q, k, v))
+        status.zero_()
+        orch.varlen_attn_bwd(q, k, v, q, torch.zeros((Hq, T), dtype=torch.float32, device=dev), q,
+                             torch.from_numpy(cu).to(dev), True, max_seqlen=max_seqlen, dq=dq, dk=dk, dv=dv,
+                             dev_status=status)
+        torch.cuda.synchronize()
+        assert int(status.item()) == -5, name
+        assert all(torch.isnan(t.float()).all() for t in (dq, dk, dv)), name
+    # a valid call with the exact bound: status OK, same result as without the bound
+    status = torch.full((1,), 77, dtype=torch.int32, device=dev)
+    a = orch.varlen_attn_fwd(q, k, v, torch.from_numpy(good).to(dev), True, max_seqlen=500, dev_status=status)
+    b = orch.varlen_attn_fwd(q, k, v, torch.from_numpy(good).to(dev), True)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0 and torch.equal(a, b)

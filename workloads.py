@@ -229,6 +229,18 @@ def token_tag_torch(row_begin: int, row_end: int, H: int, device, out=None):
     return out
 
 
+def token_tag_rows_torch(rows, H: int):
+    """Same words as token_tag_np for an arbitrary list of global source rows: `rows` is an
+    int64 tensor on the target device; returns int16 [len(rows), H].  The caller bounds the
+    chunk (8 * len(rows) * H bytes of temporaries)."""
+    import torch
+
+    c = torch.arange(H, dtype=torch.int64, device=rows.device)[None, :]
+    x = (rows.to(torch.int64)[:, None] * H + c) * _s64(_GOLD)
+    x = (x ^ ((x >> 29) & ((1 << 35) - 1))) * _s64(_MIX1)
+    return ((x >> 40) & 0xFFFF).to(torch.int16)
+
+
 def normal_bf16_torch(shape, seed: int, stream: int, device):
     """bf16 tensor ~ N(0,1) of `shape`, counter-based (hash of the flat index),
     generated with torch ops on `device` in bounded chunks."""
