@@ -86,6 +86,20 @@ size_t orch_balance_workspace(int32_t n, int32_t D);
 int orch_balance(const int32_t *lengths, int32_t n, int32_t D, orch_phase phase,
                  orch_assignment out, void *ws, size_t ws_bytes, void *stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): orch_balance with its workspace inside
+ * the library, in a device array of fixed size (about 3 MB, held on every GPU the library
+ * runs on until the process ends).  Same inputs, outputs, ties and device-side errors as
+ * orch_balance; n above orch_balance_static_max_n() returns ORCH_EUNSUPPORTED before any
+ * launch.  The call allocates nothing.  All calls on one GPU share the array: calls that
+ * overlap on one GPU (different streams, or threads) race and must be serialised by the
+ * caller; calls in stream order on one stream are safe. */
+int orch_balance_static(const int32_t *lengths, int32_t n, int32_t D, orch_phase phase,
+                        orch_assignment out, void *stream);
+
+/* Largest n orch_balance_static accepts. */
+int32_t orch_balance_static_max_n(void);
+
 /* Sec. 5.1, Algorithm 2 ("Post-Balancing Algorithm with Paddings"): for phases that batch
  * with paddings (the auditory encoder, Sec. 7), where a batch of cnt sequences costs
  * cnt * (its longest sequence) rows (Eq. 1, padding branch).  Sorts ascending by length

@@ -6,6 +6,8 @@ from .binding import (  # noqa: F401
     attn_variant,
     balance,
     balance_padded,
+    balance_static,
+    balance_static_max_n,
     balance_tolerance,
     comm_volume,
     balance_workspace,

@@ -18,7 +18,7 @@ _LIB_PATH = os.path.join(_PKG, "liborch.so")
 _lib = None
 
 EXPORTS = ("orch_balance_workspace", "orch_balance", "orch_pack_workspace", "orch_pack",
-           "orch_balance_padded", "orch_balance_tolerance",
+           "orch_balance_padded", "orch_balance_tolerance", "orch_balance_static", "orch_balance_static_max_n",
            "orch_pack_composed_workspace", "orch_pack_composed", "orch_comm_volume",
            "orch_varlen_attn_workspace", "orch_varlen_attn_fwd", "orch_varlen_attn_bwd_workspace",
            "orch_varlen_attn_bwd", "orch_last_error",
@@ -62,6 +62,10 @@ def load_library():
     lib.orch_balance.restype = C.c_int
     lib.orch_balance.argtypes = [C.c_void_p, C.c_int32, C.c_int32, _Phase, _Assignment, C.c_void_p,
                                  C.c_size_t, C.c_void_p]
+    lib.orch_balance_static.restype = C.c_int
+    lib.orch_balance_static.argtypes = [C.c_void_p, C.c_int32, C.c_int32, _Phase, _Assignment, C.c_void_p]
+    lib.orch_balance_static_max_n.restype = C.c_int32
+    lib.orch_balance_static_max_n.argtypes = []
     lib.orch_balance_padded.restype = C.c_int
     lib.orch_balance_padded.argtypes = [C.c_void_p, C.c_int32, C.c_int32, _Phase, _Assignment, C.c_void_p,
                                         C.c_void_p, C.c_size_t, C.c_void_p]
@@ -170,6 +174,20 @@ def balance(lengths: torch.Tensor, D: int, a: int, b: int, out: Assignment | Non
     _check(lib.orch_balance(_ptr(lengths), n, D, _Phase(a, b), out._c(), _ptr(ws), ws.numel(),
                             C.c_void_p(_stream(dev))))
     return out
+
+
+def balance_static(lengths: torch.Tensor, D: int, a: int, b: int, out: Assignment) -> Assignment:
+    """orch_balance_static: orch_balance on the library's built-in scratch; allocates nothing, so
+    `out` must be given."""
+    lib = load_library()
+    assert lengths.dtype == torch.int32 and lengths.is_cuda and lengths.is_contiguous()
+    _check(lib.orch_balance_static(_ptr(lengths), lengths.numel(), D, _Phase(a, b), out._c(),
+                                   C.c_void_p(_stream(lengths.device))))
+    return out
+
+
+def balance_static_max_n() -> int:
+    return load_library().orch_balance_static_max_n()
 
 
 def balance_padded(lengths: torch.Tensor, D: int, a: int, b: int, out: Assignment | None = None,

@@ -58,6 +58,19 @@ int orch_balance(const int32_t *lengths, int32_t n, int32_t D, orch_phase phase,
     return launch_balance(lengths, n, D, phase, out, ws, ws_bytes, (hipStream_t)stream);
 }
 
+int32_t orch_balance_static_max_n(void) { return balance_static_max_n(); }
+
+int orch_balance_static(const int32_t *lengths, int32_t n, int32_t D, orch_phase phase, orch_assignment out,
+                        void *stream)
+{
+    if (n < 0) ORCH_FAIL(ORCH_EINVAL, "orch_balance_static: n = %d < 0", n);
+    if (D < 1) ORCH_FAIL(ORCH_EINVAL, "orch_balance_static: D = %d < 1", D);
+    if (D > 4096) ORCH_FAIL(ORCH_EUNSUPPORTED, "orch_balance_static: D = %d > 4096", D);
+    if (n > 0 && !lengths) ORCH_FAIL(ORCH_EINVAL, "orch_balance_static: lengths is NULL");
+    if (!assignment_complete(out)) ORCH_FAIL(ORCH_EINVAL, "orch_balance_static: an output pointer is NULL");
+    return launch_balance_static(lengths, n, D, phase, out, (hipStream_t)stream);
+}
+
 int orch_balance_padded(const int32_t *lengths, int32_t n, int32_t D, orch_phase phase, orch_assignment out,
                         uint64_t *bound, void *ws, size_t ws_bytes, void *stream)
 {

@@ -19,6 +19,8 @@
 //   layout_kernel      n threads: scatter sequence ids and segment starts
 // n <= 32768 keys is latency-bound work, so everything is arranged to keep the
 // dependent chain short rather than to stream memory.
+#include <mutex>
+
 #include "common.h"
 
 namespace orch {
@@ -1150,6 +1152,52 @@ int launch_balance(const int32_t *lengths, int32_t n, int32_t D, orch_phase phas
                            w.start, out.seq_off, n, out.order, out.cu_seqlens);
     ORCH_HIP_CHECK(hipGetLastError());
     return ORCH_OK;
+}
+
+// ---------------------------------------------------------------------------
+// orch_balance_static: orch_balance with its workspace in a file-scope device
+// array, for callers that cannot allocate (HIP graph capture, tight serving
+// loops).  The array's name is only a host-side handle; its device address is
+// looked up once per device and that address is what the kernels receive.
+// ---------------------------------------------------------------------------
+constexpr int32_t kStaticMaxN = 65536;
+constexpr size_t kStaticBytes = (size_t)kStaticMaxN * 48 + 16 * 256;   // carve(kStaticMaxN) fits
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+constexpr int kStaticMaxDevices = 64;
+static void *g_scratch_ptr[kStaticMaxDevices];   // device address of `scratch`, per device
+static std::mutex g_scratch_mutex;
+
+int32_t balance_static_max_n() { return kStaticMaxN; }
+
+int launch_balance_static(const int32_t *lengths, int32_t n, int32_t D, orch_phase phase,
+                          orch_assignment out, hipStream_t stream)
+{
+    if (n > kStaticMaxN)
+        ORCH_FAIL(ORCH_EUNSUPPORTED, "orch_balance_static: n = %d exceeds the built-in scratch (%d sequences)", n,
+                  kStaticMaxN);
+    int dev = -1;
+    ORCH_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kStaticMaxDevices)
+        ORCH_FAIL(ORCH_EUNSUPPORTED, "orch_balance_static: device %d outside [0, %d)", dev, kStaticMaxDevices);
+    void *ptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[dev]) {
+            void *p = nullptr;
+            ORCH_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+            if (!p) ORCH_FAIL(ORCH_EHIP, "orch_balance_static: no device address for the scratch array");
+            g_scratch_ptr[dev] = p;
+        }
+        ptr = g_scratch_ptr[dev];
+    }
+    BalanceWs w;
+    if (carve(w, nullptr, n) > kStaticBytes)
+        ORCH_FAIL(ORCH_EUNSUPPORTED, "orch_balance_static: n = %d needs more than %zu bytes", n, kStaticBytes);
+    // every word of the workspace that a kernel reads was written earlier in the same call
+    // (the sort kernel writes flags, keys and order; the greedy writes ipos, rank and start
+    // before the layout kernel reads them), so nothing has to be cleared between calls
+    return launch_balance(lengths, n, D, phase, out, ptr, kStaticBytes, stream);
 }
 
 int launch_balance_padded(const int32_t *lengths, int32_t n, int32_t D, orch_phase phase,
