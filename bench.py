@@ -116,7 +116,7 @@ def main():
     k = wl.normal_bf16_torch((T_i, w.Hkv, w.d), base_seed, 2, dev)
     v = wl.normal_bf16_torch((T_i, w.Hkv, w.d), base_seed, 3, dev)
     out = torch.empty_like(q)
-    ws_attn = torch.empty(orch.varlen_attn_workspace(batch_i), dtype=torch.uint8, device=dev)
+    ws_attn = torch.empty(orch.varlen_attn_workspace(batch_i, T_i, w.Hq), dtype=torch.uint8, device=dev)
     cu_view = asg.cu_seqlens[cu_lo: cu_lo + batch_i + 1]  # device slice written by balance each step
 
     def step(ev=None):
@@ -181,7 +181,7 @@ def main():
     vb = wl.normal_bf16_torch((T_b, w.Hkv, w.d), base_seed, 6, dev)
     ob = torch.empty_like(qb)
     cu_bd = torch.from_numpy(cu_b).to(dev)
-    ws_b = torch.empty(orch.varlen_attn_workspace(len(cu_b) - 1), dtype=torch.uint8, device=dev)
+    ws_b = torch.empty(orch.varlen_attn_workspace(len(cu_b) - 1, T_b, w.Hq), dtype=torch.uint8, device=dev)
     orch.varlen_attn_fwd(qb, kb, vb, cu_bd, w.causal, out=ob, ws=ws_b)
     bev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
     bev[0].record()

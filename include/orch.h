@@ -198,8 +198,9 @@ int orch_pack_composed(const void *enc_rows, void *packed, const int32_t *sub_le
 int orch_comm_volume(const int32_t *lengths, int32_t n, int32_t D_src, const int32_t *from, int32_t D_dst,
                      orch_assignment dst, uint64_t *V, int32_t node, uint64_t *inter, void *stream);
 
-/* Bytes of workspace orch_varlen_attn_fwd needs. */
-size_t orch_varlen_attn_workspace(int32_t batch);
+/* Bytes of workspace orch_varlen_attn_fwd needs (4 bytes per sequence and per
+ * (256-row query tile, q-head) pair). */
+size_t orch_varlen_attn_workspace(int32_t batch, int32_t total_tokens, int32_t Hq);
 
 /* Padding-free attention forward over `batch` sequences stored back to back.
  * For sequence t (rows cu_seqlens[t] .. cu_seqlens[t+1]), q-head h, kv-head

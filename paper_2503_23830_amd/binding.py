@@ -58,7 +58,7 @@ def load_library():
     lib.orch_pack_workspace.restype = C.c_size_t
     lib.orch_pack_workspace.argtypes = [C.c_int32, C.c_int32]
     lib.orch_varlen_attn_workspace.restype = C.c_size_t
-    lib.orch_varlen_attn_workspace.argtypes = [C.c_int32]
+    lib.orch_varlen_attn_workspace.argtypes = [C.c_int32, C.c_int32, C.c_int32]
     lib.orch_balance.restype = C.c_int
     lib.orch_balance.argtypes = [C.c_void_p, C.c_int32, C.c_int32, _Phase, _Assignment, C.c_void_p,
                                  C.c_size_t, C.c_void_p]
@@ -156,8 +156,8 @@ def pack_composed_workspace(n: int) -> int:
     return load_library().orch_pack_composed_workspace(n)
 
 
-def varlen_attn_workspace(batch: int) -> int:
-    return load_library().orch_varlen_attn_workspace(batch)
+def varlen_attn_workspace(batch: int, total_tokens: int, Hq: int) -> int:
+    return load_library().orch_varlen_attn_workspace(batch, total_tokens, Hq)
 
 
 def balance(lengths: torch.Tensor, D: int, a: int, b: int, out: Assignment | None = None,
@@ -304,7 +304,7 @@ def varlen_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cu_seqlen
     if lse is not None:
         assert lse.dtype == torch.float32 and lse.is_contiguous() and lse.numel() == Hq * T
     if ws is None:
-        ws = _workspace(lib.orch_varlen_attn_workspace(batch), dev)
+        ws = _workspace(lib.orch_varlen_attn_workspace(batch, T, Hq), dev)
     _check(lib.orch_varlen_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(cu_seqlens),
                                     batch, T, max_seqlen, Hq, Hkv, d, float(scale), 1 if causal else 0,
                                     _ptr(dev_status), _ptr(ws), ws.numel(), C.c_void_p(_stream(dev))))

@@ -39,7 +39,10 @@ const char *orch_attn_variant(void) { return g_variant; }
 size_t orch_balance_workspace(int32_t n, int32_t D) { return balance_ws_bytes(n, D); }
 size_t orch_pack_workspace(int32_t n, int32_t D) { return pack_ws_bytes(n, D); }
 size_t orch_pack_composed_workspace(int32_t n) { return pack_composed_ws_bytes(n); }
-size_t orch_varlen_attn_workspace(int32_t batch) { return attn_ws_bytes(batch); }
+size_t orch_varlen_attn_workspace(int32_t batch, int32_t total_tokens, int32_t Hq)
+{
+    return attn_ws_bytes(batch, total_tokens, Hq);
+}
 size_t orch_varlen_attn_bwd_workspace(int32_t batch, int32_t total_tokens, int32_t Hq)
 {
     return attn_bwd_ws_bytes(batch, total_tokens, Hq);

@@ -61,6 +61,6 @@ size_t attn_bwd_ws_bytes(int32_t batch, int32_t total_tokens, int32_t Hq);
 size_t balance_ws_bytes(int32_t n, int32_t D);
 size_t pack_ws_bytes(int32_t n, int32_t D);
 size_t pack_composed_ws_bytes(int32_t n);
-size_t attn_ws_bytes(int32_t batch);
+size_t attn_ws_bytes(int32_t batch, int32_t total_tokens, int32_t Hq);
 
 }  // namespace orch

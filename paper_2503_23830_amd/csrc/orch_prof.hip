@@ -166,7 +166,7 @@ int main(int argc, char **argv)
     hipLaunchKernelGGL(fill_bf16, dim3(4096), dim3(256), 0, st, q, qn, 11ull);
     hipLaunchKernelGGL(fill_bf16, dim3(4096), dim3(256), 0, st, k, kn, 22ull);
     hipLaunchKernelGGL(fill_bf16, dim3(4096), dim3(256), 0, st, v, kn, 33ull);
-    size_t wsa = orch_varlen_attn_workspace(batch);
+    size_t wsa = orch_varlen_attn_workspace(batch, Ti, Hq);
     void *ws_a;
     CK(hipMalloc(&ws_a, wsa));
     CK(hipStreamSynchronize(st));

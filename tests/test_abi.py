@@ -45,7 +45,7 @@ def test_workspace_queries_and_host_side_errors():
     lib = orch.load_library()
     assert lib.orch_balance_workspace(32768, 256) >= 32768 * 40
     assert lib.orch_pack_workspace(32768, 256) >= 32768 * 24
-    assert lib.orch_varlen_attn_workspace(128) >= 129 * 4
+    assert lib.orch_varlen_attn_workspace(128, 352000, 32) >= 129 * 4 + (352000 // 256 + 128) * 32 * 4
     fake = ctypes.c_void_p(256)
     asg = B._Assignment(256, 256, 256, 256, 256, 256, 256)
     rc = lib.orch_balance(fake, -1, 4, B._Phase(1, 1), asg, fake, 1 << 20, None)

@@ -205,3 +205,31 @@ def test_invalid_cu_seqlens_is_reported_and_writes_nothing(gpu_device, d):
     b = orch.varlen_attn_fwd(q, k, v, torch.from_numpy(good).to(dev), True)
     torch.cuda.synchronize()
     assert int(status.item()) == 0 and torch.equal(a, b)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_head_dim_128_reference_far_above_the_first_block(gpu_device, causal):
+    """The head_dim-128 kernel takes every probability against the row maximum of the FIRST
+    32-key block.  Here later keys score thousands of units above it (the exponentials would
+    overflow), so the marked tiles must come from the moving-reference pass; other sequences of
+    the same call (ordinary data) keep the fast pass.  Both against the fp64 oracle."""
+    dev = gpu_device
+    Hq, Hkv, d = 4, 2, 128
+    L = [300, 700, 40, 513]
+    cu = np.concatenate([[0], np.cumsum(L)]).astype(np.int32)
+    T = int(cu[-1])
+    q, k, v = make_qkv(21, T, Hq, Hkv, d, dev)
+    # sequence 1 (rows 300..999): queries all +4, keys 0..31 all -4, keys from 320 on all +4 scaled up
+    q[300:1000] = 4.0
+    k[300:332] = -4.0
+    k[620:1000] = 4.0 + 0.25 * k[620:1000].sign()
+    # sequence 3: one huge late key for half of the heads only
+    k[1040 + 400, 0] = 24.0 * q[1040 + 400, 0].sign()
+    lse = torch.full((Hq, T), float("nan"), dtype=torch.float32, device=dev)
+    out = torch.full((T, Hq, d), float("nan"), dtype=torch.bfloat16, device=dev)
+    orch.varlen_attn_fwd(q, k, v, torch.from_numpy(cu).to(dev), causal, out=out, lse=lse)
+    torch.cuda.synchronize()
+    want, wlse = oracle.attn_fwd(bits(q), bits(k), bits(v), cu, causal, nthreads=NT, want_lse=True)
+    attn_tolerance_check(out.float().cpu().numpy(), want)
+    gl, wl_ = lse.cpu().numpy().astype(np.float64), wlse
+    assert np.max(np.abs(gl - wl_) / np.maximum(1.0, np.abs(wl_))) <= 1e-3

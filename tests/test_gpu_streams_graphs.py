@@ -39,7 +39,7 @@ class Path:
         self.out = torch.zeros_like(self.q)
         self.lse = torch.zeros((Hq, Ti), dtype=torch.float32, device=dev)
         self.dq, self.dk, self.dv = torch.zeros_like(self.q), torch.zeros_like(self.k), torch.zeros_like(self.v)
-        self.ws_attn = torch.empty(orch.varlen_attn_workspace(batch), dtype=torch.uint8, device=dev)
+        self.ws_attn = torch.empty(orch.varlen_attn_workspace(batch, Ti, Hq), dtype=torch.uint8, device=dev)
         self.ws_bwd = torch.empty(orch.varlen_attn_bwd_workspace(batch, Ti, Hq), dtype=torch.uint8, device=dev)
         self.ref = ref
 
