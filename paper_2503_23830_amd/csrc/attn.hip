@@ -19,8 +19,6 @@
 // rescaling O is a per-lane multiply.  The running maximum is only moved when a
 // row's maximum grows by more than 2^8 (exact: the stale reference cancels in
 // the final division), so O is rarely rescaled after the first tile.
-#include <stdlib.h>
-
 #include <algorithm>
 #include <type_traits>
 
@@ -37,6 +35,16 @@ struct AttnHdr {
     int32_t total_tiles;
     int32_t ok;
 };
+
+// Fixed softmax reference (the form of both kernels that normally runs): every probability of
+// a row is taken against the row's maximum over its FIRST 32-key block, which never moves, so
+// later blocks compute no maximum and O is never rescaled (the result is the same: the
+// reference cancels in the final division, and fp32 carries probabilities up to 2^64 times the
+// reference with the same relative precision).  A row whose sum of probabilities does not stay
+// below 2^64 marks its (query tile, head) in `redo`; the moving-reference form of the same
+// kernel, launched right after on the same grid, recomputes exactly the marked tiles and
+// returns at once on the others.
+constexpr float kRedoSum = 1.8446744e19f;   // 2^64
 
 // tile_off[t] = number of BM-row query tiles in sequences before t.
 // A cu_seqlens that is not non-decreasing inside [0, total_tokens], or a sequence longer than a
@@ -98,12 +106,12 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b)
 }
 
 
-template <int HD, bool CAUSAL, int MB>
+template <int HD, bool CAUSAL, int MB, bool FIXED>
 __global__ __launch_bounds__(kThreads, (MB * HD > 128 ? 1 : 2)) void attn_fwd_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
     uint16_t *__restrict__ out, float *__restrict__ lse, const int32_t *__restrict__ cu,
-    const AttnHdr *__restrict__ hdr, const int32_t *__restrict__ tile_off, int32_t batch,
-    int32_t total_tokens, int32_t Hq, int32_t Hkv, float scale, float scale_log2)
+    const AttnHdr *__restrict__ hdr, const int32_t *__restrict__ tile_off, int32_t *__restrict__ redo,
+    int32_t batch, int32_t total_tokens, int32_t Hq, int32_t Hkv, float scale, float scale_log2)
 {
     constexpr int BM = 128 * MB;  // query rows per workgroup
     constexpr int NBLK = 4 * MB;  // 32-row blocks per workgroup
@@ -133,6 +141,7 @@ __global__ __launch_bounds__(kThreads, (MB * HD > 128 ? 1 : 2)) void attn_fwd_ke
         }
     }
     if (u >= total_tiles) return;
+    if (!FIXED && redo[u * Hq + h] == 0) return;   // the fixed-reference pass was good enough
     const int g_kv = h / group;
 
     // sequence t with tile_off[t] <= u < tile_off[t+1]
@@ -195,6 +204,7 @@ __global__ __launch_bounds__(kThreads, (MB * HD > 128 ? 1 : 2)) void attn_fwd_ke
     // MB0 lie entirely above the causal diagonal for this tile).
     auto compute_tile = [&](auto mb0_tag, int n0, uint32_t kb, uint32_t vb) {
         constexpr int MB0 = decltype(mb0_tag)::value;
+        const bool first = n0 == 0;   // fixed reference: taken here, from the first 32 keys
         // ---- S^T = K Q^T : two 32-key blocks
         f32x16 acc_s[MB][2];
 #pragma unroll
@@ -230,19 +240,31 @@ __global__ __launch_bounds__(kThreads, (MB * HD > 128 ? 1 : 2)) void attn_fwd_ke
                     }
             }
             // ---- online softmax, one query per lane (shared by lanes l and l^32)
-            float tmax = acc_s[mb][0][0];
+            float mbias;
+            if (FIXED) {
+                if (first) {   // key 0 is visible to every row, so the maximum is finite
+                    float tmax = acc_s[mb][0][0];
 #pragma unroll
-            for (int nb = 0; nb < 2; ++nb)
+                    for (int e = 1; e < 16; ++e) tmax = fmaxf(tmax, acc_s[mb][0][e]);
+                    m_run[mb] = fmaxf(tmax, __shfl_xor(tmax, 32));
+                }
+                alpha[mb] = 1.0f;
+                mbias = m_run[mb] * scale_log2;
+            } else {
+                float tmax = acc_s[mb][0][0];
 #pragma unroll
-                for (int e = 0; e < 16; ++e) tmax = fmaxf(tmax, acc_s[mb][nb][e]);
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-            const bool upd = tmax > m_run[mb] + lazy_thr;
-            const float m_new = upd ? tmax : m_run[mb];
-            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-            alpha[mb] = upd ? __builtin_amdgcn_exp2f((m_run[mb] - m_use) * scale_log2) : 1.0f;
-            any_upd |= upd;
-            m_run[mb] = m_new;
-            const float mbias = m_use * scale_log2;
+                for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) tmax = fmaxf(tmax, acc_s[mb][nb][e]);
+                tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+                const bool upd = tmax > m_run[mb] + lazy_thr;
+                const float m_new = upd ? tmax : m_run[mb];
+                const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+                alpha[mb] = upd ? __builtin_amdgcn_exp2f((m_run[mb] - m_use) * scale_log2) : 1.0f;
+                any_upd |= upd;
+                m_run[mb] = m_new;
+                mbias = m_use * scale_log2;
+            }
             float psum = 0.f;
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk) {
@@ -259,9 +281,9 @@ __global__ __launch_bounds__(kThreads, (MB * HD > 128 ? 1 : 2)) void attn_fwd_ke
                 pk.w = pack_bf16(p[6], p[7]);
                 pf[mb][kk] = __builtin_bit_cast(bf16x8, pk);
             }
-            l_run[mb] = l_run[mb] * alpha[mb] + psum;
+            l_run[mb] = FIXED ? l_run[mb] + psum : l_run[mb] * alpha[mb] + psum;
         }
-        if (__any(any_upd)) {
+        if (!FIXED && __any(any_upd)) {
 #pragma unroll
             for (int mb = MB0; mb < MB; ++mb)
 #pragma unroll
@@ -305,10 +327,12 @@ __global__ __launch_bounds__(kThreads, (MB * HD > 128 ? 1 : 2)) void attn_fwd_ke
     }
 
     // ---- epilogue
+    bool bad = false;
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
         const float l_tot = l_run[mb] + __shfl_xor(l_run[mb], 32);
         const float inv = 1.f / l_tot;
+        if (FIXED) bad |= !(l_tot < kRedoSum);   // rows past the end were computed on the clamped last row
         if (qm[mb] < L) {
             uint16_t *op = out + ((size_t)(row0 + qm[mb]) * Hq + h) * HD;
 #pragma unroll
@@ -324,6 +348,8 @@ __global__ __launch_bounds__(kThreads, (MB * HD > 128 ? 1 : 2)) void attn_fwd_ke
                 lse[(size_t)h * total_tokens + row0 + qm[mb]] = m_run[mb] * scale + __logf(l_tot);
         }
     }
+    // a sum that did not stay below 2^64 (or is not a number): the moving-reference pass redoes the tile
+    if (FIXED && __any(bad) && lane == 0) redo[u * Hq + h] = 1;
 }
 
 
@@ -367,15 +393,8 @@ constexpr int kILThreads = 512;
 
 #define ORCH_SB() __builtin_amdgcn_sched_barrier(0)
 
-// FIXED = true is the form that normally runs: the reference every probability of a row is taken
-// against is the row's maximum over its FIRST 32-key block and never moves, so blocks after the
-// first compute no maximum and O is never rescaled (the result is the same: the reference
-// cancels in the final division; fp32 carries probabilities up to 2^64 times the reference with
-// the same relative precision).  A row whose sum of probabilities does not stay below 2^64 marks
-// its (query tile, head) in `redo`; the FIXED = false form (moving reference, launched right
-// after on the same grid) recomputes exactly the marked tiles and returns at once on the others.
-constexpr float kRedoSum = 1.8446744e19f;   // 2^64
-
+// FIXED: fixed softmax reference (see kRedoSum above); its row maximum over block 0 is taken in
+// the prologue, so every block of the tile loop runs the same code without maxima.
 template <int HD, bool CAUSAL, bool FIXED>
 __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
@@ -831,497 +850,6 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
     }
 }
 
-// ---------------------------------------------------------------------------
-// Two row blocks per wavefront (head_dim 128): 4 free-running wavefronts, one per SIMD, own
-// 64 query rows each (row blocks w and 7 - w of the 256-row query tile, so that under a causal
-// mask every wavefront carries the same number of blocks).  Staging, swizzles, rings, the
-// transposed score product and the in-stream MFMA / vector-ALU interleave are those of
-// attn_fwd_il_kernel; the difference is that every K and V fragment read from LDS, every LDS-DMA
-// load and every tile barrier now feeds two MFMAs instead of one (LDS reads per FLOP halved), at
-// the price of one wavefront per SIMD: all latency hiding is inside the one instruction stream.
-// The wavefront needs about 400 registers: the O accumulators and Q fragments of both row
-// blocks (192), two generations of scores (64), P, the K/V fragments and the softmax pipeline.
-// A row block whose rows end before the other's (past the end of the sequence, or above the
-// causal diagonal) leaves the pipeline early: its last P V product is issued on its own (drain)
-// and the remaining iterations run the one-block form of the body.
-// ---------------------------------------------------------------------------
-constexpr int kW64Threads = 256;
-
-template <bool CAUSAL>
-__global__ __launch_bounds__(kW64Threads) void attn_fwd_w64_kernel(
-    const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
-    uint16_t *__restrict__ out, float *__restrict__ lse, const int32_t *__restrict__ cu,
-    const AttnHdr *__restrict__ hdr, const int32_t *__restrict__ tile_off, int32_t batch,
-    int32_t total_tokens, int32_t Hq, int32_t Hkv, float scale, float scale_log2)
-{
-    constexpr int HD = 128;
-    constexpr int BM = 256;
-    constexpr int NC = HD / 16;    // k-chunks of Q K^T
-    constexpr int NDB = HD / 32;   // 32-row blocks of O^T
-    constexpr int ROWB = HD * 2;   // bytes per key row
-    constexpr int TILE_B = BN * ROWB;
-    constexpr int KST = 4, VST = 4;
-    constexpr int NLD = 4;         // LDS-DMA loads per wavefront per tile and tensor (16 rows)
-    __shared__ __attribute__((aligned(1024))) char lds_raw[(KST + VST) * TILE_B];
-    const uint32_t lds_k = (uint32_t)(uintptr_t)lds_raw;
-    const uint32_t lds_v = lds_k + KST * TILE_B;
-
-    const int total_tiles = hdr->total_tiles;
-    const int group = Hq / Hkv;
-    int u, h;
-    {
-        const int bid = blockIdx.x;
-        if ((Hkv & 7) == 0) {   // kv-head chosen by XCD: blocks sharing K/V share an L2
-            const int kvh = (bid & 7) + 8 * ((bid >> 3) % (Hkv >> 3));
-            const int rest = bid / Hkv;
-            h = kvh * group + rest % group;
-            u = rest / group;
-        } else {
-            h = bid % Hq;
-            u = bid / Hq;
-        }
-    }
-    if (u >= total_tiles) return;
-    const int g_kv = h / group;
-    int lo = 0, hi = batch - 1;
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (tile_off[mid] <= u) lo = mid; else hi = mid - 1;
-    }
-    const int seq = lo;
-    const int row0 = cu[seq];
-    const int L = cu[seq + 1] - row0;
-    const int ntile_q = (L + BM - 1) / BM;
-    const int qt = ntile_q - 1 - (u - tile_off[seq]);  // heaviest (last) tile first
-    const int q0 = qt * BM;
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int l32 = lane & 31, g = lane >> 5;
-    int qrow0[2], qm[2], nblk[2];
-#pragma unroll
-    for (int r = 0; r < 2; ++r) {
-        const int rblk = r == 0 ? wave : 7 - wave;
-        qrow0[r] = q0 + 32 * rblk;
-        qm[r] = qrow0[r] + l32;
-        const int kend_r = CAUSAL ? min(L, qrow0[r] + 32) : L;
-        nblk[r] = qrow0[r] < L ? (kend_r + 31) / 32 : 0;   // 32-key blocks this row block computes
-    }
-    const int kend = CAUSAL ? min(L, q0 + BM) : L;
-    const int ntile_k = (kend + BN - 1) / BN;               // tiles the workgroup stages
-
-    // ---- LDS-DMA: per tile this wavefront fetches rows 16w..16w+15 of K and of V (four loads of
-    // four rows each); lane -> (row, slot), slot -> chunk by the swizzle
-    const uint32_t rstride_b = (uint32_t)Hkv * HD * 2;
-    const char *kseq = (const char *)(k + ((size_t)row0 * Hkv + g_kv) * HD);
-    const char *vseq = (const char *)(v + ((size_t)row0 * Hkv + g_kv) * HD);
-    const int lrem_last = L - 1 - (ntile_k - 1) * BN;   // last row of the sequence inside the last staged tile
-    auto dma_lane_off = [&](int is_v, int p, bool clamp) {
-        const int r = 4 * (NLD * wave + p) + (lane >> 4);
-        const int slot = lane & 15;
-        const int swz = is_v ? 4 * (r & 3) + 2 * ((r >> 2) & 1) : (r & 15);
-        const uint32_t col = 16u * (uint32_t)(slot ^ swz);
-        return __umul24((uint32_t)(clamp ? min(r, lrem_last) : r), rstride_b) + col;
-    };
-    uint32_t dma_off[2][NLD];   // tiles inside the sequence; the last staged tile recomputes with the clamp
-#pragma unroll
-    for (int is_v = 0; is_v < 2; ++is_v)
-#pragma unroll
-        for (int p = 0; p < NLD; ++p) dma_off[is_v][p] = dma_lane_off(is_v, p, false);
-#pragma clang diagnostic push
-#pragma clang diagnostic ignored "-Winline-asm"   // M0 is reserved; the clobber is deliberate
-    auto dma_issue = [&](const char *tb, uint32_t off, uint32_t dst) {
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                     :: "s"(dst), "v"(off), "s"(tb) : "memory", "m0");
-    };
-#pragma clang diagnostic pop
-    struct DmaJob {
-        const char *tb;     // first row of the tile
-        uint32_t dst;       // LDS stage
-        int is_v;
-        bool last;
-    };
-    auto dma_job = [&](int t, int is_v, uint32_t lds_stage) {
-        const int tc = t < ntile_k ? t : ntile_k - 1;   // past the end: repeat the last tile
-        DmaJob j;
-        j.tb = (is_v ? vseq : kseq) + (size_t)tc * BN * rstride_b;
-        j.dst = lds_stage + (uint32_t)(NLD * wave) * 1024u;
-        j.is_v = is_v;
-        j.last = tc == ntile_k - 1;
-        return j;
-    };
-    auto dma_run = [&](const DmaJob &j, int p) {
-        // rows of the last staged tile past the end of the sequence repeat row L-1 (masked later)
-        const uint32_t off = j.last ? dma_lane_off(j.is_v, p, true) : (j.is_v ? dma_off[1][p] : dma_off[0][p]);
-        dma_issue(j.tb, off, j.dst + (uint32_t)p * 1024u);
-    };
-    auto dma_tile = [&](int t, int is_v, uint32_t lds_stage) {
-        const DmaJob j = dma_job(t, is_v, lds_stage);
-#pragma unroll
-        for (int p = 0; p < NLD; ++p) dma_run(j, p);
-    };
-
-    // ---- per-lane LDS addresses of the fragments (stage 0, first 32-key block); as in
-    // attn_fwd_il_kernel
-    uint32_t kaddr[NC];
-#pragma unroll
-    for (int j = 0; j < NC; ++j) kaddr[j] = lds_k + (uint32_t)(l32 * ROWB + 16 * ((2 * j + g) ^ (l32 & 15)));
-    uint32_t vaddr[NDB];
-    {
-        const int j4 = (lane & 15) >> 2, a = lane & 3, half = (lane >> 4) & 1;
-#pragma unroll
-        for (int db = 0; db < NDB; ++db) {
-            const int c = (4 * db + 2 * half + (a >> 1)) ^ (4 * j4 + 2 * g);
-            vaddr[db] = lds_v + (uint32_t)((4 * g + j4) * ROWB + 16 * c + 8 * (a & 1));
-        }
-    }
-
-    // ---- Q fragments of both row blocks: B operand, column m = lane%32, k = 16c + 8g + [0..7]
-    bf16x8 qf[2][NC];
-#pragma unroll
-    for (int r = 0; r < 2; ++r) {
-        const int qm_c = qm[r] < L ? qm[r] : L - 1;
-        const uint16_t *qp = q + ((size_t)(row0 + qm_c) * Hq + h) * HD + 8 * g;
-#pragma unroll
-        for (int c = 0; c < NC; ++c) {
-            qf[r][c] = *(const bf16x8 *)(qp + 16 * c);
-        }
-    }
-    f32x16 acc_o[2][NDB];
-#pragma unroll
-    for (int r = 0; r < 2; ++r)
-#pragma unroll
-        for (int d = 0; d < NDB; ++d)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc_o[r][d][e] = 0.f;
-    float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
-    const float lazy_thr = 8.0f / scale_log2;
-
-    // Register plan (one wavefront per SIMD: 256 vector registers and 256 accumulation registers).
-    // With more than 256 registers in play the compiler gives every MFMA it knows an accumulation-
-    // register destination, which is where O belongs (128; only MFMAs touch it on the common path).
-    // The scores are read by the vector ALU, so their product is written as an asm statement with
-    // a vector-register destination (two generations of two row blocks: 64); beside them live the
-    // Q fragments (64), a ring of four K / V fragments (16), P (16) and the softmax pipeline.
-    f32x16 S[2][2];  // [parity of the block][row block]: scores of blocks b (current) and b+1 (next)
-    bf16x8 P[2][2];  // [row block][16-key chunk]: block b-1 until rewritten for block b
-    // K / V fragments in consumption order (per iteration: V(b-1) fragments 0..7 for half 1, then
-    // K(b+1) fragments 0..7 for half 2) pass through a ring of four; a fragment is requested three
-    // MFMA pairs before its use, into the slot whose last reader has just been issued
-    bf16x8 fr[4];
-    float alpha[2] = {1.f, 1.f}, mbias[2] = {0.f, 0.f}, psum[2] = {0.f, 0.f};
-    bool moved[2] = {false, false};
-
-    auto lds_rd128 = [](uint32_t addr, int off) {
-        return *(const __attribute__((address_space(3))) bf16x8 *)(uintptr_t)(addr + (uint32_t)off);
-    };
-    auto lds_rd_tr = [](uint32_t addr, int off) {
-        return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (__attribute__((address_space(3))) s16x4 *)(uintptr_t)(addr + (uint32_t)off));
-    };
-    auto read_kfrag = [&](int j, int off) { return lds_rd128(kaddr[j], off); };
-    // V fragment j: O block db = j % 4, key chunk kk = j / 4
-    auto read_vfrag = [&](int j, int off) {
-        const int db = j % NDB, kk = j / NDB;
-        const s16x4 lo4 = lds_rd_tr(vaddr[db], off + (16 * kk) * ROWB);
-        const s16x4 hi4 = lds_rd_tr(vaddr[db], off + (16 * kk + 8) * ROWB);
-        const s16x8 both = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
-        return __builtin_bit_cast(bf16x8, both);
-    };
-    auto mask_block = [&](f32x16 &Sx, int b, int r) {
-        const bool masked = (32 * b + 32 > L) || (CAUSAL && 32 * b + 31 > qrow0[r]);
-        if (masked) {
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int n = 32 * b + 8 * (e >> 2) + 4 * g + (e & 3);
-                const bool vis = n < L && (!CAUSAL || n <= qm[r]);
-                if (!vis) Sx[e] = -INFINITY;
-            }
-        }
-    };
-    auto vmax3 = [](float a, float b, float c) {
-        float r;
-        asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
-        return r;
-    };
-    auto vmax2 = [](float a, float b) {
-        float r;
-        asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
-        return r;
-    };
-    float tm[2][5];
-    auto max_a = [&](const f32x16 &Sx, int r) {
-#pragma unroll
-        for (int i = 0; i < 5; ++i) tm[r][i] = vmax3(Sx[3 * i], Sx[3 * i + 1], Sx[3 * i + 2]);
-        asm volatile("" : "+v"(tm[r][0]), "+v"(tm[r][1]), "+v"(tm[r][2]), "+v"(tm[r][3]), "+v"(tm[r][4]));
-    };
-    auto max_b = [&](const f32x16 &Sx, int r) {
-        const float u0 = vmax3(tm[r][0], tm[r][1], tm[r][2]);
-        const float u1 = vmax3(tm[r][3], tm[r][4], Sx[15]);
-        float tmax = vmax2(u0, u1);
-        {   // the other half of the row lives in lane ^ 32
-            const uint32_t tb = __float_as_uint(tmax);
-            const auto sw = __builtin_amdgcn_permlane32_swap(tb, tb, false, false);
-            tmax = vmax2(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-        }
-        asm volatile("" : "+v"(tmax));
-        tm[r][0] = tmax;
-    };
-    auto max_c = [&](int r) {
-        const float tmax = tm[r][0];
-        const bool upd = tmax > m_run[r] + lazy_thr;
-        const float m_new = upd ? tmax : m_run[r];
-        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-        alpha[r] = upd ? __builtin_amdgcn_exp2f((m_run[r] - m_use) * scale_log2) : 1.0f;
-        moved[r] = __any(upd);
-        m_run[r] = m_new;
-        mbias[r] = m_use * scale_log2;
-        asm volatile("" : "+v"(mbias[r]), "+v"(alpha[r]));
-    };
-    // the 16 exponentials of a block as a four-stage pipeline over ticks (see attn_fwd_il_kernel)
-    float xs[2][16], ps[2][16];
-    auto tick_of = [](int e) { return e < 8 ? e / 2 : e - 4; };
-    auto exp_tick = [&](const f32x16 &Sc, int r, int t) {
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int te = tick_of(e);
-            if (te == t) {   // A
-                xs[r][e] = Sc[e] * scale_log2 - mbias[r];
-                asm volatile("" : "+v"(xs[r][e]));
-            }
-            if (te + 1 == t) {   // B
-                ps[r][e] = __builtin_amdgcn_exp2f(xs[r][e]);
-                asm volatile("" : "+v"(ps[r][e]));
-            }
-            if (te + 2 == t) {   // C, and D for a completed pair
-                psum[r] += ps[r][e];
-                if (e & 1) {
-                    uint32_t pk = pack_bf16(ps[r][e - 1], ps[r][e]);
-                    asm volatile("" : "+v"(pk), "+v"(psum[r]));
-                    u32x4 w = __builtin_bit_cast(u32x4, P[r][e >> 3]);
-                    w[(e & 7) >> 1] = pk;
-                    P[r][e >> 3] = __builtin_bit_cast(bf16x8, w);
-                }
-            }
-        }
-    };
-    auto mfma = [](const bf16x8 &a, const bf16x8 &b, const f32x16 &c) {
-        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
-    };
-    // The score product with a vector-register destination.  The compiler does not know these are
-    // MFMAs, so what it would insert is guaranteed by construction: the operands are LDS fragments
-    // and Q (never vector-ALU results), consecutive products of a chain use the same destination,
-    // and the first vector-ALU read of a finished chain comes more than 20 instructions later (the
-    // prologue adds explicit s_nop).
-    auto mfma_s_first = [](f32x16 &d, const bf16x8 &a, const bf16x8 &b) {
-        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "v"(b));
-    };
-    auto mfma_s_next = [](f32x16 &d, const bf16x8 &a, const bf16x8 &b) {
-        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "v"(b));
-    };
-
-    // One pipeline iteration for block b of parity PAR with the row blocks A0 / A1 taking part:
-    // S[PAR][r] holds S(b), P[r] holds P(b-1), the ring holds fragments 0..2 of V(b-1).  A slot is one
-    // MFMA followed by one piece of that row block's softmax; the ring is refilled after the last
-    // MFMA of a pair.  FIRST: block 0, where there is no P(b-1) V(b-1) product to issue.
-    auto body = [&](auto par_c, auto st_c, auto a0_c, auto a1_c, auto first_c, int b, const DmaJob &dj) {
-        constexpr int PAR = decltype(par_c)::value;
-        constexpr int ST = decltype(st_c)::value;
-        constexpr bool ACT[2] = {decltype(a0_c)::value, decltype(a1_c)::value};
-        constexpr bool FIRST = decltype(first_c)::value;
-        constexpr int RLAST = ACT[1] ? 1 : 0;     // the row block whose MFMA comes last in a pair
-        // K(b+1): odd half of this tile, or even half of the next one; V(b): this tile; V(b-1): the
-        // even half of this tile, or the odd half of the previous one (its stage is replaced only
-        // after the next barrier)
-        constexpr int K_OFF = PAR == 0 ? ST * TILE_B + 32 * ROWB : ((ST + 1) % KST) * TILE_B;
-        constexpr int V_OFF = ST * TILE_B + (PAR == 0 ? 0 : 32 * ROWB);
-        constexpr int VP_OFF = PAR == 1 ? ST * TILE_B : ((ST + VST - 1) % VST) * TILE_B + 32 * ROWB;
-        // request fragment u of this iteration's consumption order (16, 17, 18: the first three of
-        // the next iteration)
-        auto prefetch = [&](int u) {
-            if (u < 8) {
-                if (!FIRST) fr[u % 4] = read_vfrag(u, VP_OFF);
-            } else if (u < 16) {
-                fr[u % 4] = read_kfrag(u - 8, K_OFF);
-            } else {
-                fr[u % 4] = read_vfrag(u - 16, V_OFF);
-            }
-        };
-#pragma unroll
-        for (int r = 0; r < 2; ++r)
-            if (ACT[r]) psum[r] = 0.f;
-        // ---- half 1: O^T += V(b-1)^T P(b-1); maxima of S(b); exp of keys 0..15
-#pragma unroll
-        for (int j = 0; j < 2 * NDB; ++j) {
-            const int db = j % NDB, kk = j / NDB;
-#pragma unroll
-            for (int r = 0; r < 2; ++r) {
-                if (!ACT[r]) continue;
-                if (!FIRST) {
-                    acc_o[r][db] = mfma(fr[j % 4], P[r][kk], acc_o[r][db]);
-                    ORCH_SB();
-                }
-                if (r == RLAST) {
-                    prefetch(j + 3);
-                    ORCH_SB();
-                }
-                f32x16 &Sc = S[PAR][r];
-                if (j == 0) mask_block(Sc, b, r);
-                if (j == 1) max_a(Sc, r);
-                if (j == 2) max_b(Sc, r);
-                if (j == 3) max_c(r);
-                if (j >= 4) exp_tick(Sc, r, j - 4);   // chunk 0 of P[r] is rewritten from tick 2 on
-                if (r == RLAST && (j & 3) == 2) dma_run(dj, j >> 2);
-                ORCH_SB();
-            }
-        }
-        // ---- half 2: S(b+1) = K(b+1) Q^T; exp of keys 16..31
-#pragma unroll
-        for (int j = 0; j < NC; ++j) {
-#pragma unroll
-            for (int r = 0; r < 2; ++r) {
-                if (!ACT[r]) continue;
-                if (j == 0) mfma_s_first(S[PAR ^ 1][r], fr[(8 + j) % 4], qf[r][0]);
-                else mfma_s_next(S[PAR ^ 1][r], fr[(8 + j) % 4], qf[r][j]);
-                ORCH_SB();
-                if (r == RLAST) {
-                    prefetch(8 + j + 3);
-                    ORCH_SB();
-                }
-                exp_tick(S[PAR][r], r, 4 + j);
-                if (r == RLAST && (j & 3) == 2) dma_run(dj, 2 + (j >> 2));
-                ORCH_SB();
-            }
-        }
-#pragma unroll
-        for (int r = 0; r < 2; ++r) {
-            if (!ACT[r]) continue;
-            exp_tick(S[PAR][r], r, 12);
-            exp_tick(S[PAR][r], r, 13);
-        }
-        // ---- carry O and l to the reference of block b (rarely != 1), add this block's sum
-#pragma unroll
-        for (int r = 0; r < 2; ++r) {
-            if (!ACT[r]) continue;
-            if (moved[r]) {
-#pragma unroll
-                for (int d = 0; d < NDB; ++d)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) acc_o[r][d][e] *= alpha[r];
-            }
-            l_run[r] = l_run[r] * alpha[r] + psum[r];
-        }
-    };
-    // the last P V product of a row block that leaves the pipeline; `voff` = where V of its last
-    // block lies in the V ring (that stage is not replaced before the next barrier)
-    auto drain = [&](int r, int voff) {
-#pragma unroll
-        for (int j = 0; j < 2 * NDB; ++j) {
-            const int db = j % NDB, kk = j / NDB;
-            const bf16x8 vfrag = read_vfrag(j, voff);
-            acc_o[r][db] = mfma(vfrag, P[r][kk], acc_o[r][db]);
-        }
-    };
-
-    // ---- prologue: K tiles 0..2 and V tiles 0..1 on their way; S(0); V(0) fragments meet P = 0
-    dma_tile(0, 0, lds_k);
-    dma_tile(0, 1, lds_v);
-    dma_tile(1, 0, lds_k + TILE_B);
-    dma_tile(1, 1, lds_v + TILE_B);
-    dma_tile(2, 0, lds_k + 2 * TILE_B);
-    __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): this wavefront's DMA has landed
-    __builtin_amdgcn_s_barrier();
-#pragma unroll
-    for (int r = 0; r < 2; ++r)
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk) P[r][kk] = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
-    if (nblk[0] > 0 || nblk[1] > 0) {
-#pragma unroll
-        for (int j = 0; j < NC; ++j) {
-            fr[j % 4] = read_kfrag(j, 0);
-#pragma unroll
-            for (int r = 0; r < 2; ++r) {
-                if (j == 0) mfma_s_first(S[0][r], fr[0], qf[r][0]);
-                else mfma_s_next(S[0][r], fr[j % 4], qf[r][j]);
-            }
-        }
-        // the first iteration reads S(0) at once: let the last product retire
-        asm volatile("s_nop 15\n\ts_nop 15");
-    }
-
-    // one 32-key block: leave-the-pipeline drains first, then the form of the body that matches
-    // the row blocks still at work; a wavefront with nothing left still feeds the ring
-    auto block = [&](auto par_c, auto st_c, auto first_c, int b, const DmaJob &dj) {
-        constexpr int PAR = decltype(par_c)::value;
-        constexpr int ST = decltype(st_c)::value;
-        constexpr int VP_OFF = PAR == 1 ? ST * TILE_B : ((ST + VST - 1) % VST) * TILE_B + 32 * ROWB;
-#pragma unroll
-        for (int r = 0; r < 2; ++r)
-            if (b == nblk[r] && b > 0) drain(r, VP_OFF);
-        const bool a0 = b < nblk[0], a1 = b < nblk[1];
-        using T = std::true_type;
-        using F = std::false_type;
-        if (a0 && a1) body(par_c, st_c, T{}, T{}, first_c, b, dj);
-        else if (a1) body(par_c, st_c, F{}, T{}, first_c, b, dj);
-        else if (a0) body(par_c, st_c, T{}, F{}, first_c, b, dj);
-        else {
-#pragma unroll
-            for (int p = 0; p < NLD; ++p) dma_run(dj, p);
-        }
-    };
-    // one 64-key tile (two blocks) whose ring stage ST = i % 4 is a compile-time constant
-    auto step = [&](auto st_c, int i) {
-        constexpr int ST = decltype(st_c)::value;
-        if (i > 0) {
-            // K(i+1) and V(i) were requested two steps ago; the eight loads of the last step
-            // (K(i+2), V(i+1)) may stay in flight: vmcnt(8)
-            __builtin_amdgcn_s_waitcnt(0x0f78);
-            __builtin_amdgcn_s_barrier();
-        }
-        // K(i+3) replaces K(i-1), V(i+2) replaces V(i-2): nobody reads those any more
-        const DmaJob kj = dma_job(i + 3, 0, lds_k + (uint32_t)(((ST + 3) % KST) * TILE_B));
-        const DmaJob vj = dma_job(i + 2, 1, lds_v + (uint32_t)(((ST + 2) % VST) * TILE_B));
-        if (ST == 0 && i == 0) block(std::integral_constant<int, 0>{}, st_c, std::true_type{}, 0, kj);
-        else block(std::integral_constant<int, 0>{}, st_c, std::false_type{}, 2 * i, kj);
-        block(std::integral_constant<int, 1>{}, st_c, std::false_type{}, 2 * i + 1, vj);
-    };
-    for (int i0 = 0; i0 < ntile_k; i0 += 4) {
-        step(std::integral_constant<int, 0>{}, i0);
-        if (i0 + 1 < ntile_k) step(std::integral_constant<int, 1>{}, i0 + 1);
-        if (i0 + 2 < ntile_k) step(std::integral_constant<int, 2>{}, i0 + 2);
-        if (i0 + 3 < ntile_k) step(std::integral_constant<int, 3>{}, i0 + 3);
-    }
-    // a row block that computed every staged block has its last P V product still to do
-#pragma unroll
-    for (int r = 0; r < 2; ++r)
-        if (nblk[r] == 2 * ntile_k && nblk[r] > 0) drain(r, ((ntile_k - 1) % VST) * TILE_B + 32 * ROWB);
-
-    // ---- epilogue
-#pragma unroll
-    for (int r = 0; r < 2; ++r) {
-        float l_tot;
-        {
-            const uint32_t lb = __float_as_uint(l_run[r]);
-            const auto sw = __builtin_amdgcn_permlane32_swap(lb, lb, false, false);
-            l_tot = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
-        }
-        const float inv = 1.f / l_tot;
-        if (qm[r] < L) {
-            uint16_t *op = out + ((size_t)(row0 + qm[r]) * Hq + h) * HD;
-#pragma unroll
-            for (int d = 0; d < NDB; ++d)
-#pragma unroll
-                for (int rr = 0; rr < 4; ++rr) {
-                    u32x2 w;
-                    w.x = pack_bf16(acc_o[r][d][4 * rr] * inv, acc_o[r][d][4 * rr + 1] * inv);
-                    w.y = pack_bf16(acc_o[r][d][4 * rr + 2] * inv, acc_o[r][d][4 * rr + 3] * inv);
-                    *(u32x2 *)(op + 32 * d + 8 * rr + 4 * g) = w;
-                }
-            if (lse != nullptr && g == 0)
-                lse[(size_t)h * total_tokens + row0 + qm[r]] = m_run[r] * scale + __logf(l_tot);
-        }
-    }
-}
 #undef ORCH_SB
 
 }  // namespace
@@ -1356,7 +884,7 @@ int launch_attn(const void *q, const void *k, const void *v, void *out, float *l
     const bool il = d == 128;
     const int BM = 256;   // both kernels own 256 query rows per workgroup
     hipLaunchKernelGGL(attn_prep_kernel, dim3(1), dim3(kPrepThreads), 0, stream, cu_seqlens, batch,
-                       total_tokens, max_seqlen, BM, hdr, tile_off, dev_status, il ? redo : (int32_t *)nullptr, Hq);
+                       total_tokens, max_seqlen, BM, hdr, tile_off, dev_status, redo, Hq);
     // sum over sequences of ceil(L / BM) <= total / BM + batch, and <= batch * ceil(max_seqlen / BM)
     int64_t max_tiles = (int64_t)attn_max_tiles(batch, total_tokens);
     if (max_seqlen > 0) max_tiles = std::min<int64_t>(max_tiles, (int64_t)batch * ((max_seqlen + BM - 1) / BM));
@@ -1367,27 +895,24 @@ int launch_attn(const void *q, const void *k, const void *v, void *out, float *l
     if (grid > 0 && batch > 0) {
 #define ORCH_ATTN_HEAD (const uint16_t *)q, (const uint16_t *)k, (const uint16_t *)v, (uint16_t *)out, lse, cu_seqlens, hdr, tile_off
 #define ORCH_ATTN_TAIL batch, total_tokens, Hq, Hkv, scale, sl2
-        static const int w64 = getenv("ORCH_ATTN_W64") ? atoi(getenv("ORCH_ATTN_W64")) : 0;
-        static const int safe_only = getenv("ORCH_ATTN_SAFE") ? atoi(getenv("ORCH_ATTN_SAFE")) : 0;
         const dim3 g((unsigned)grid);
-        if (il && w64 && causal)
-            hipLaunchKernelGGL((attn_fwd_w64_kernel<true>), g, dim3(kW64Threads), 0, stream, ORCH_ATTN_HEAD, ORCH_ATTN_TAIL);
-        else if (il && w64)
-            hipLaunchKernelGGL((attn_fwd_w64_kernel<false>), g, dim3(kW64Threads), 0, stream, ORCH_ATTN_HEAD, ORCH_ATTN_TAIL);
-        else if (il && causal) {
-            if (!safe_only) hipLaunchKernelGGL((attn_fwd_il_kernel<128, true, true>), g, dim3(kILThreads), 0, stream, ORCH_ATTN_HEAD, redo, ORCH_ATTN_TAIL);
+        if (il && causal) {
+            hipLaunchKernelGGL((attn_fwd_il_kernel<128, true, true>), g, dim3(kILThreads), 0, stream, ORCH_ATTN_HEAD, redo, ORCH_ATTN_TAIL);
             hipLaunchKernelGGL((attn_fwd_il_kernel<128, true, false>), g, dim3(kILThreads), 0, stream, ORCH_ATTN_HEAD, redo, ORCH_ATTN_TAIL);
         } else if (il) {
-            if (!safe_only) hipLaunchKernelGGL((attn_fwd_il_kernel<128, false, true>), g, dim3(kILThreads), 0, stream, ORCH_ATTN_HEAD, redo, ORCH_ATTN_TAIL);
+            hipLaunchKernelGGL((attn_fwd_il_kernel<128, false, true>), g, dim3(kILThreads), 0, stream, ORCH_ATTN_HEAD, redo, ORCH_ATTN_TAIL);
             hipLaunchKernelGGL((attn_fwd_il_kernel<128, false, false>), g, dim3(kILThreads), 0, stream, ORCH_ATTN_HEAD, redo, ORCH_ATTN_TAIL);
-        } else if (causal)
-            hipLaunchKernelGGL((attn_fwd_kernel<64, true, 2>), g, dim3(kThreads), 0, stream, ORCH_ATTN_HEAD, ORCH_ATTN_TAIL);
-        else
-            hipLaunchKernelGGL((attn_fwd_kernel<64, false, 2>), g, dim3(kThreads), 0, stream, ORCH_ATTN_HEAD, ORCH_ATTN_TAIL);
+        } else if (causal) {
+            hipLaunchKernelGGL((attn_fwd_kernel<64, true, 2, true>), g, dim3(kThreads), 0, stream, ORCH_ATTN_HEAD, redo, ORCH_ATTN_TAIL);
+            hipLaunchKernelGGL((attn_fwd_kernel<64, true, 2, false>), g, dim3(kThreads), 0, stream, ORCH_ATTN_HEAD, redo, ORCH_ATTN_TAIL);
+        } else {
+            hipLaunchKernelGGL((attn_fwd_kernel<64, false, 2, true>), g, dim3(kThreads), 0, stream, ORCH_ATTN_HEAD, redo, ORCH_ATTN_TAIL);
+            hipLaunchKernelGGL((attn_fwd_kernel<64, false, 2, false>), g, dim3(kThreads), 0, stream, ORCH_ATTN_HEAD, redo, ORCH_ATTN_TAIL);
+        }
 #undef ORCH_ATTN_HEAD
 #undef ORCH_ATTN_TAIL
     }
-    set_attn_variant(il ? "mfma32x32x16_bm256_8wave_ldsdma_interleaved_fixedref" : "mfma32x32x16_bm256_4wave_ldsdma");
+    set_attn_variant(il ? "mfma32x32x16_bm256_8wave_ldsdma_interleaved_fixedref" : "mfma32x32x16_bm256_4wave_ldsdma_fixedref");
     ORCH_HIP_CHECK(hipGetLastError());
     return ORCH_OK;
 }

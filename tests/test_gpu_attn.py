@@ -208,13 +208,14 @@ def test_invalid_cu_seqlens_is_reported_and_writes_nothing(gpu_device, d):
 
 
 @pytest.mark.parametrize("causal", [True, False])
-def test_head_dim_128_reference_far_above_the_first_block(gpu_device, causal):
-    """The head_dim-128 kernel takes every probability against the row maximum of the FIRST
-    32-key block.  Here later keys score thousands of units above it (the exponentials would
-    overflow), so the marked tiles must come from the moving-reference pass; other sequences of
-    the same call (ordinary data) keep the fast pass.  Both against the fp64 oracle."""
+@pytest.mark.parametrize("d", [64, 128])
+def test_reference_far_above_the_first_block(gpu_device, causal, d):
+    """The kernels take every probability against the row maximum of the FIRST 32-key block.
+    Here later keys score hundreds of units above it (the exponentials would overflow), so the
+    marked tiles must come from the moving-reference pass; other sequences of the same call
+    (ordinary data) keep the fast pass.  Both against the fp64 oracle."""
     dev = gpu_device
-    Hq, Hkv, d = 4, 2, 128
+    Hq, Hkv = 4, 2
     L = [300, 700, 40, 513]
     cu = np.concatenate([[0], np.cumsum(L)]).astype(np.int32)
     T = int(cu[-1])
