@@ -34,6 +34,7 @@ constexpr int kPrepThreads = 1024;
 struct AttnHdr {
     int32_t total_tiles;
     int32_t ok;
+    int32_t bm;   // query rows per tile the table was built for; a kernel built for another size does nothing
 };
 
 // Fixed softmax reference (the form of both kernels that normally runs): every probability of
@@ -88,6 +89,7 @@ __global__ __launch_bounds__(kPrepThreads) void attn_prep_kernel(const int32_t *
     if (tid == 0) {
         const int ok = !s_bad;
         hdr->ok = ok;
+        hdr->bm = BM;
         hdr->total_tiles = ok ? part[kPrepThreads - 1] : 0;
         if (ok) tile_off[batch] = part[kPrepThreads - 1];
         if (dev_status) dev_status[0] = ok ? (int32_t)ORCH_OK : (int32_t)ORCH_EDATA;
@@ -107,7 +109,7 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b)
 
 
 template <int HD, bool CAUSAL, int MB, bool FIXED>
-__global__ __launch_bounds__(kThreads, (MB * HD > 128 ? 1 : 2)) void attn_fwd_kernel(
+__global__ __launch_bounds__(kThreads, (MB * HD > 128 ? 1 : (MB * HD > 64 ? 2 : 4))) void attn_fwd_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
     uint16_t *__restrict__ out, float *__restrict__ lse, const int32_t *__restrict__ cu,
     const AttnHdr *__restrict__ hdr, const int32_t *__restrict__ tile_off, int32_t *__restrict__ redo,
@@ -121,7 +123,7 @@ __global__ __launch_bounds__(kThreads, (MB * HD > 128 ? 1 : 2)) void attn_fwd_ke
     static_assert(BN == kT, "the staged tile pair is 64 keys deep");
     __shared__ __attribute__((aligned(1024))) char lds_raw[PS::BYTES];
 
-    const int total_tiles = hdr->total_tiles;
+    const int total_tiles = hdr->bm == BM ? hdr->total_tiles : 0;
     const int group = Hq / Hkv;
 
     // block -> (query tile u, head h).  With Hkv a multiple of 8 the kv-head is
@@ -414,7 +416,7 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
     const uint32_t lds_k = (uint32_t)(uintptr_t)lds_raw;
     const uint32_t lds_v = lds_k + KST * TILE_B;
 
-    const int total_tiles = hdr->total_tiles;
+    const int total_tiles = hdr->bm == BM ? hdr->total_tiles : 0;
     const int group = Hq / Hkv;
     int u, h;
     {
@@ -857,7 +859,7 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
 // workspace: header, tile_off[batch + 1], redo[(query tiles) * Hq] (one mark per workgroup)
 static size_t attn_max_tiles(int32_t batch, int32_t total_tokens)
 {
-    return (size_t)(total_tokens > 0 ? total_tokens : 0) / 256 + (size_t)(batch > 0 ? batch : 0);
+    return (size_t)(total_tokens > 0 ? total_tokens : 0) / 128 + (size_t)(batch > 0 ? batch : 0);
 }
 
 size_t attn_ws_bytes(int32_t batch, int32_t total_tokens, int32_t Hq)
@@ -880,13 +882,20 @@ int launch_attn(const void *q, const void *k, const void *v, void *out, float *l
     // interleaved in one instruction stream, first with a fixed softmax reference, then (same
     // grid; returns at once unless a tile was marked) with a moving one.  head_dim 64: half the
     // MFMA work per softmax, so the vector ALU dominates and the simpler 4-wavefront kernel with
-    // two row blocks per wavefront is used.
+    // one or two row blocks per wavefront is used.
     const bool il = d == 128;
-    const int BM = 256;   // both kernels own 256 query rows per workgroup
+    // Row blocks per wavefront of the head_dim-64 kernel launched below (the tile table the prep
+    // kernel builds and the grid use the same rows per workgroup; a kernel built for another
+    // size finds the mismatch in the header and does nothing).  Bidirectional (the encoder
+    // phases: sequences of a few hundred rows): one block, 128-row tiles, four workgroups per CU,
+    // whose phases overlap; measured 810 against 720-750 TFLOP/s (C2) and 616 against 543 (C3) for
+    // two blocks.  Causal keeps two blocks (the diagonal balances over block pairs).
+    const int mb64 = (!il && !causal) ? 1 : 2;
+    const int BM = il ? 256 : 128 * mb64;   // query rows per workgroup
     hipLaunchKernelGGL(attn_prep_kernel, dim3(1), dim3(kPrepThreads), 0, stream, cu_seqlens, batch,
                        total_tokens, max_seqlen, BM, hdr, tile_off, dev_status, redo, Hq);
     // sum over sequences of ceil(L / BM) <= total / BM + batch, and <= batch * ceil(max_seqlen / BM)
-    int64_t max_tiles = (int64_t)attn_max_tiles(batch, total_tokens);
+    int64_t max_tiles = (int64_t)total_tokens / BM + batch;
     if (max_seqlen > 0) max_tiles = std::min<int64_t>(max_tiles, (int64_t)batch * ((max_seqlen + BM - 1) / BM));
     const int64_t grid = max_tiles * Hq;
     if (grid > 0x7fffffffLL) ORCH_FAIL(ORCH_EUNSUPPORTED, "orch_varlen_attn_fwd: %lld workgroups", (long long)grid);
@@ -902,6 +911,9 @@ int launch_attn(const void *q, const void *k, const void *v, void *out, float *l
         } else if (il) {
             hipLaunchKernelGGL((attn_fwd_il_kernel<128, false, true>), g, dim3(kILThreads), 0, stream, ORCH_ATTN_HEAD, redo, ORCH_ATTN_TAIL);
             hipLaunchKernelGGL((attn_fwd_il_kernel<128, false, false>), g, dim3(kILThreads), 0, stream, ORCH_ATTN_HEAD, redo, ORCH_ATTN_TAIL);
+        } else if (mb64 == 1) {
+            hipLaunchKernelGGL((attn_fwd_kernel<64, false, 1, true>), g, dim3(kThreads), 0, stream, ORCH_ATTN_HEAD, redo, ORCH_ATTN_TAIL);
+            hipLaunchKernelGGL((attn_fwd_kernel<64, false, 1, false>), g, dim3(kThreads), 0, stream, ORCH_ATTN_HEAD, redo, ORCH_ATTN_TAIL);
         } else if (causal) {
             hipLaunchKernelGGL((attn_fwd_kernel<64, true, 2, true>), g, dim3(kThreads), 0, stream, ORCH_ATTN_HEAD, redo, ORCH_ATTN_TAIL);
             hipLaunchKernelGGL((attn_fwd_kernel<64, true, 2, false>), g, dim3(kThreads), 0, stream, ORCH_ATTN_HEAD, redo, ORCH_ATTN_TAIL);
@@ -912,7 +924,8 @@ int launch_attn(const void *q, const void *k, const void *v, void *out, float *l
 #undef ORCH_ATTN_HEAD
 #undef ORCH_ATTN_TAIL
     }
-    set_attn_variant(il ? "mfma32x32x16_bm256_8wave_ldsdma_interleaved_fixedref" : "mfma32x32x16_bm256_4wave_ldsdma_fixedref");
+    set_attn_variant(il ? "mfma32x32x16_bm256_8wave_ldsdma_interleaved_fixedref"
+                        : (mb64 == 1 ? "mfma32x32x16_bm128_4wave_ldsdma_fixedref" : "mfma32x32x16_bm256_4wave_ldsdma_fixedref"));
     ORCH_HIP_CHECK(hipGetLastError());
     return ORCH_OK;
 }
