@@ -148,6 +148,33 @@ def main():
                            "min": float(np.min([e[a].elapsed_time(e[b]) for e in events]))}
     bal_sp, pack_sp, attn_sp = spread(0, 1), spread(1, 2), spread(2, 3)
 
+    # ---------------- the stages of orch_balance (untimed part of the run; own events) ---------
+    # sort: 12 bytes per key and radix pass (8-byte key and 4-byte index, read once and written
+    # once per pass is 24; the kernel's passes run out of L2, so 12 B is the algorithmic figure
+    # the roofline section states); greedy: one D-wide reduction per sequence.  Both are
+    # latency-bound (n <= 32768 keys, one workgroup): the figures are reported, not held against
+    # the HBM peak.
+    sev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    for e in sev:
+        e.record()
+    st_ms = np.zeros(3)
+    reps = 10
+    for _ in range(reps + 1):
+        orch.balance_stages(Ld, D, w.a, w.b, asg, ws_bal, sev)
+        torch.cuda.synchronize()
+        if _ > 0:
+            st_ms += [sev[0].elapsed_time(sev[1]), sev[1].elapsed_time(sev[2]), sev[2].elapsed_time(sev[3])]
+    st_ms /= reps
+    max_cost = int(w.a) * int(L.max(initial=0)) ** 2 + int(w.b) * int(L.max(initial=0))
+    sort_passes = max(1, (max_cost.bit_length() + 7) // 8)
+    dispatch_stages = {
+        "sort_ms": float(st_ms[0]), "greedy_ms": float(st_ms[1]), "layout_ms": float(st_ms[2]),
+        "sort_passes": sort_passes,
+        "sort_GBps": 12.0 * n * sort_passes / (st_ms[0] * 1e-3) / 1e9 if st_ms[0] > 0 else None,
+        "greedy_ns_per_item": float(st_ms[1]) * 1e6 / max(n, 1),
+        "bound": "latency (one workgroup, n dependent keys); not a bandwidth or ALU roofline",
+    }
+
     # C5 names "about 64k tokens" for one instance's share while its length law gives about 390k;
     # the law is followed above, and the named size is reported too: whole sequences of the same
     # instance up to 65536 tokens
@@ -451,8 +478,32 @@ def main():
         tt = time.perf_counter()
         oracle.pack(host_tok, Ls, ra)
         t_pack = time.perf_counter() - tt
+        # the same oracle on one core (a tenth of the sample)
+        M1 = max(64, M // 10)
+        tt = time.perf_counter()
+        oracle.attn_rows(qh, kh, vh, cu_i, w.causal, bt[:M1], bh[:M1], br[:M1], nthreads=1)
+        t_attn1 = time.perf_counter() - tt
+        # the pack oracle on all cores: instance ranges of the same slice in parallel (threads over
+        # instances; the C routine releases the interpreter lock)
+        from concurrent.futures import ThreadPoolExecutor
+        cuts = np.linspace(0, Dh, min(cores, Dh) + 1).astype(int)
+        tt = time.perf_counter()
+        with ThreadPoolExecutor(max_workers=cores) as ex:
+            list(ex.map(lambda ab: oracle.pack(host_tok, Ls, ra, int(ab[0]), int(ab[1])), zip(cuts[:-1], cuts[1:])))
+        t_pack_all = time.perf_counter() - tt
+        cpu_model = "unknown"
+        try:
+            for line in open("/proc/cpuinfo"):
+                if line.startswith("model name"):
+                    cpu_model = line.split(":", 1)[1].strip()
+                    break
+        except OSError:
+            pass
         cpu_baseline = {
-            "value": cpu_tflops, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "value": cpu_tflops, "unit": "TFLOP/s", "cores": cores, "kind": "oracle", "cpu_model": cpu_model,
+            "host_cpus": os.cpu_count(),
+            "attention_one_core_TFLOPs": rows_flops(bt[:M1], br[:M1]) / t_attn1 / 1e12,
+            "pack_all_cores_GBps": 2.0 * host_tok.nbytes / t_pack_all / 1e9,
             "sample": "naive fp64 attention oracle on %d seeded (sequence, head, row) samples of the same "
                       "instance (%.2f GFLOP counted, %.1f s); extrapolated whole-instance time %.0f s"
                       % (M, rows_flops(bt, br) / 1e9, t_attn, flops / (cpu_tflops * 1e12)),
@@ -481,23 +532,34 @@ def main():
             ceiling = {"error": str(exc)}
 
     # ---------------- rooflines: the longest kernel of the step, and the other one -----
-    traffic = {}
+    # `traffic` is not measured in this run: it is the HBM byte count per launch that the committed
+    # rocprofv3 --pmc runs recorded for this workload (profiles/traffic.json names the profile),
+    # or null when no profile covers the workload
+    traffic, traffic_src = {}, None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get("C%d" % w.cid, {})
+            tj = json.load(open(tpath))
+            traffic = tj.get("C%d" % w.cid, {})
+            traffic_src = tj.get("_source")
         except Exception:
             traffic = {}
     roof_attn = {"kernel": "attention forward, head_dim %d, %s (%s)" % (w.d, "causal" if w.causal else "full", orch.attn_variant()),
                  "bound": "mfma", "achieved": attn_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                  "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic.get("attn"),
+                 "traffic_source": traffic_src if traffic.get("attn") else None,
                  "launch_ms": attn_ms, "flop_per_launch": flops, "mfma_only_ceiling": ceiling,
                  "frac_of_measured_random_operand_ceiling":
                      (attn_tflops / ceiling["random_operands_tflops"]) if ceiling and ceiling.get("random_operands_tflops") else None}
     roof_pack = {"kernel": "pack_copy_kernel", "bound": "hbm", "achieved": pack_gbps, "peak": HBM_PEAK_GBPS,
                  "unit": "GB/s", "frac": pack_gbps / HBM_PEAK_GBPS, "traffic": traffic.get("pack"),
+                 "traffic_source": traffic_src if traffic.get("pack") else None,
                  "launch_ms": pack_ms, "bytes_per_launch": pack_bytes}
-    roofline, roofline_other = (roof_attn, roof_pack) if attn_ms >= pack_ms else (roof_pack, roof_attn)
+    # top-level fields: the kernel `value` is about (attention); `kernels` holds both long kernels
+    # of the step, `longest_kernel` names the one with the longer launch
+    roofline = dict(roof_attn)
+    roofline["kernels"] = [roof_attn, roof_pack]
+    roofline["longest_kernel"] = roof_attn["kernel"] if attn_ms >= pack_ms else roof_pack["kernel"]
 
     result = {
         "metric": "varlen attn TFLOP/s + pack GB/s (% peak); max/mean instance load, 1 GPU",
@@ -522,11 +584,10 @@ def main():
         "balance_tolerance": tolerance,
         "comm_volume": comm,
         "dispatch": {"ms": bal_ms, "ms_median": bal_sp["median"], "ms_min": bal_sp["min"],
-                     "calls_per_step": 1 if whole else 2},
+                     "calls_per_step": 1 if whole else 2, **dispatch_stages},
         "load_max_over_mean": {"before": before, "after": after},
         "verified": bool(ok), "attn_err": {"max_abs": float(err.max()), "mean_abs": float(err.mean())},
         "roofline": roofline,
-        "roofline_other": roofline_other,
         "cpu_baseline": cpu_baseline,
     }
     print(json.dumps(result), flush=True)

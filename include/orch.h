@@ -86,6 +86,14 @@ size_t orch_balance_workspace(int32_t n, int32_t D);
 int orch_balance(const int32_t *lengths, int32_t n, int32_t D, orch_phase phase,
                  orch_assignment out, void *ws, size_t ws_bytes, void *stream);
 
+/* orch_balance with the caller's events between its stages, for measurement: host_events is a
+ * HOST array of four hipEvent_t handles (any of them may be NULL), recorded on `stream` before
+ * the cost / sort kernel, after it, after the greedy kernel and after the layout kernel.
+ * Everything else as orch_balance (Sec. 5.1, Algorithm 1). */
+int orch_balance_stages(const int32_t *lengths, int32_t n, int32_t D, orch_phase phase,
+                        orch_assignment out, void *ws, size_t ws_bytes, void *stream,
+                        void *const *host_events);
+
 /* For callers that cannot allocate device memory (code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc): orch_balance with its workspace inside
  * the library, in a device array of fixed size (about 3 MB, held on every GPU the library

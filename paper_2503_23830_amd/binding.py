@@ -18,7 +18,7 @@ _LIB_PATH = os.path.join(_PKG, "liborch.so")
 _lib = None
 
 EXPORTS = ("orch_balance_workspace", "orch_balance", "orch_pack_workspace", "orch_pack",
-           "orch_balance_padded", "orch_balance_tolerance", "orch_balance_static", "orch_balance_static_max_n",
+           "orch_balance_padded", "orch_balance_tolerance", "orch_balance_static", "orch_balance_static_max_n", "orch_balance_stages",
            "orch_pack_composed_workspace", "orch_pack_composed", "orch_comm_volume",
            "orch_varlen_attn_workspace", "orch_varlen_attn_fwd", "orch_varlen_attn_bwd_workspace",
            "orch_varlen_attn_bwd", "orch_last_error",
@@ -62,6 +62,9 @@ def load_library():
     lib.orch_balance.restype = C.c_int
     lib.orch_balance.argtypes = [C.c_void_p, C.c_int32, C.c_int32, _Phase, _Assignment, C.c_void_p,
                                  C.c_size_t, C.c_void_p]
+    lib.orch_balance_stages.restype = C.c_int
+    lib.orch_balance_stages.argtypes = [C.c_void_p, C.c_int32, C.c_int32, _Phase, _Assignment, C.c_void_p,
+                                        C.c_size_t, C.c_void_p, C.POINTER(C.c_void_p)]
     lib.orch_balance_static.restype = C.c_int
     lib.orch_balance_static.argtypes = [C.c_void_p, C.c_int32, C.c_int32, _Phase, _Assignment, C.c_void_p]
     lib.orch_balance_static_max_n.restype = C.c_int32
@@ -173,6 +176,18 @@ def balance(lengths: torch.Tensor, D: int, a: int, b: int, out: Assignment | Non
         ws = _workspace(lib.orch_balance_workspace(n, max(D, 1)), dev)
     _check(lib.orch_balance(_ptr(lengths), n, D, _Phase(a, b), out._c(), _ptr(ws), ws.numel(),
                             C.c_void_p(_stream(dev))))
+    return out
+
+
+def balance_stages(lengths: torch.Tensor, D: int, a: int, b: int, out: Assignment, ws: torch.Tensor, events):
+    """orch_balance_stages: orch_balance that records the caller's four torch.cuda.Event objects
+    (created with enable_timing=True and recorded once before, so that their handles exist)
+    before the sort, after it, after the greedy and after the layout kernel."""
+    lib = load_library()
+    assert lengths.dtype == torch.int32 and lengths.is_cuda and lengths.is_contiguous() and len(events) == 4
+    arr = (C.c_void_p * 4)(*[C.c_void_p(e.cuda_event) for e in events])
+    _check(lib.orch_balance_stages(_ptr(lengths), lengths.numel(), D, _Phase(a, b), out._c(), _ptr(ws), ws.numel(),
+                                   C.c_void_p(_stream(lengths.device)), arr))
     return out
 
 

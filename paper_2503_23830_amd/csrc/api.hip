@@ -58,7 +58,21 @@ int orch_balance(const int32_t *lengths, int32_t n, int32_t D, orch_phase phase,
     if (!assignment_complete(out)) ORCH_FAIL(ORCH_EINVAL, "orch_balance: an output pointer is NULL");
     if (!ws) ORCH_FAIL(ORCH_EINVAL, "orch_balance: workspace is NULL");
     if ((uintptr_t)ws & 255) ORCH_FAIL(ORCH_EINVAL, "orch_balance: workspace not 256-byte aligned");
-    return launch_balance(lengths, n, D, phase, out, ws, ws_bytes, (hipStream_t)stream);
+    return launch_balance(lengths, n, D, phase, out, ws, ws_bytes, (hipStream_t)stream, nullptr);
+}
+
+int orch_balance_stages(const int32_t *lengths, int32_t n, int32_t D, orch_phase phase, orch_assignment out,
+                        void *ws, size_t ws_bytes, void *stream, void *const *host_events)
+{
+    if (!host_events) ORCH_FAIL(ORCH_EINVAL, "orch_balance_stages: host_events is NULL");
+    if (n < 0) ORCH_FAIL(ORCH_EINVAL, "orch_balance_stages: n = %d < 0", n);
+    if (D < 1) ORCH_FAIL(ORCH_EINVAL, "orch_balance_stages: D = %d < 1", D);
+    if (D > 4096) ORCH_FAIL(ORCH_EUNSUPPORTED, "orch_balance_stages: D = %d > 4096", D);
+    if (n > 0 && !lengths) ORCH_FAIL(ORCH_EINVAL, "orch_balance_stages: lengths is NULL");
+    if (!assignment_complete(out)) ORCH_FAIL(ORCH_EINVAL, "orch_balance_stages: an output pointer is NULL");
+    if (!ws) ORCH_FAIL(ORCH_EINVAL, "orch_balance_stages: workspace is NULL");
+    if ((uintptr_t)ws & 255) ORCH_FAIL(ORCH_EINVAL, "orch_balance_stages: workspace not 256-byte aligned");
+    return launch_balance(lengths, n, D, phase, out, ws, ws_bytes, (hipStream_t)stream, host_events);
 }
 
 int32_t orch_balance_static_max_n(void) { return balance_static_max_n(); }

@@ -1125,14 +1125,21 @@ size_t balance_ws_bytes(int32_t n, int32_t D)
 }
 
 int launch_balance(const int32_t *lengths, int32_t n, int32_t D, orch_phase phase,
-                   orch_assignment out, void *ws, size_t ws_bytes, hipStream_t stream)
+                   orch_assignment out, void *ws, size_t ws_bytes, hipStream_t stream, void *const *stage_events)
 {
     BalanceWs w;
     size_t need = carve(w, ws, n);
     if (ws_bytes < need) ORCH_FAIL(ORCH_ENOSPC, "orch_balance: workspace %zu < %zu bytes", ws_bytes, need);
+    // optional: the caller's events, recorded before the sort, after it, after the greedy and
+    // after the layout kernel (how the bench splits the call into its stages)
+    auto mark = [&](int i) {
+        if (stage_events && stage_events[i]) (void)hipEventRecord((hipEvent_t)stage_events[i], stream);
+    };
 
+    mark(0);
     hipLaunchKernelGGL(cost_sort_kernel, dim3(1), dim3(kSortThreads), 0, stream, lengths, n, phase.a,
                        phase.b, 0, w.csorted, w.keyA, w.keyB, w.idxA, w.idxB, w.sorted, w.flags, out.dev_status);
+    mark(1);
 #define ORCH_GREEDY_ARGS                                                                        \
     w.csorted, w.sorted, lengths, n, D, w.ipos, out.inst, w.rank, w.start, out.loads,           \
         out.seq_off, out.tok_off, out.cu_seqlens, w.flags, out.dev_status
@@ -1147,9 +1154,11 @@ int launch_balance(const int32_t *lengths, int32_t n, int32_t D, orch_phase phas
     else hipLaunchKernelGGL(greedy_lds_kernel, dim3(1), dim3(kGreedyThreads), 0, stream, ORCH_GREEDY_ARGS);
 #undef ORCH_GREEDY_BOTH
 #undef ORCH_GREEDY_ARGS
+    mark(2);
     if (n > 0)
         hipLaunchKernelGGL(layout_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, out.inst, w.rank,
                            w.start, out.seq_off, n, out.order, out.cu_seqlens);
+    mark(3);
     ORCH_HIP_CHECK(hipGetLastError());
     return ORCH_OK;
 }
@@ -1197,7 +1206,7 @@ int launch_balance_static(const int32_t *lengths, int32_t n, int32_t D, orch_pha
     // every word of the workspace that a kernel reads was written earlier in the same call
     // (the sort kernel writes flags, keys and order; the greedy writes ipos, rank and start
     // before the layout kernel reads them), so nothing has to be cleared between calls
-    return launch_balance(lengths, n, D, phase, out, ptr, kStaticBytes, stream);
+    return launch_balance(lengths, n, D, phase, out, ptr, kStaticBytes, stream, nullptr);
 }
 
 int launch_balance_padded(const int32_t *lengths, int32_t n, int32_t D, orch_phase phase,

@@ -29,7 +29,7 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // Launchers implemented per translation unit (host side).
 int launch_balance(const int32_t *lengths, int32_t n, int32_t D, orch_phase phase,
-                   orch_assignment out, void *ws, size_t ws_bytes, hipStream_t stream);
+                   orch_assignment out, void *ws, size_t ws_bytes, hipStream_t stream, void *const *stage_events);
 int launch_balance_static(const int32_t *lengths, int32_t n, int32_t D, orch_phase phase,
                           orch_assignment out, hipStream_t stream);
 int32_t balance_static_max_n();
