@@ -455,37 +455,39 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
     const int qm = qrow0 + l32;
 
     const int kend = CAUSAL ? min(L, q0 + BM) : L;
-    const int ntile_k = (kend + BN - 1) / BN;               // tiles the workgroup stages
+    const int nblk_wg = (kend + 31) / 32;                   // 32-key blocks the workgroup stages
     const int kend_w = CAUSAL ? min(L, qrow0 + 32) : L;
     const int nblk_w = qrow0 < L ? (kend_w + 31) / 32 : 0;  // 32-key blocks this wavefront computes
 
-    // ---- LDS-DMA: per tile this wavefront fetches rows 8w..8w+7 of K and of V
-    // (two loads of 4 rows each); lane -> (row, slot), slot -> chunk by the swizzle
+    // ---- LDS-DMA: per 32-key block this wavefront fetches rows 4w..4w+3 of K and of V (one load
+    // each); lane -> (row, slot), slot -> chunk by the swizzle.  Block b of either tensor lives in
+    // ring stage b % 8 (8 KB per stage).
+    constexpr int BLK_B = 32 * ROWB;
+    constexpr int NSTG = 8;
+    static_assert(KST * TILE_B == NSTG * BLK_B && VST * TILE_B == NSTG * BLK_B, "ring size");
     const uint32_t rstride_b = (uint32_t)Hkv * HD * 2;
     const char *kseq = (const char *)(k + ((size_t)row0 * Hkv + g_kv) * HD);
     const char *vseq = (const char *)(v + ((size_t)row0 * Hkv + g_kv) * HD);
-    // per-lane byte offset of the 16 bytes this lane fetches, relative to the tile's first row:
-    // [0] for tiles inside the sequence, [1] for the last tile this workgroup stages, whose rows
+    // per-lane byte offset of the 16 bytes this lane fetches, relative to the block's first row:
+    // [0] for blocks inside the sequence, [1] for the last block this workgroup stages, whose rows
     // past the end repeat row L-1 (they are masked later)
-    uint32_t dma_off[2][2][2];
+    uint32_t dma_off[2][2];
     {
-        const int lrem_last = L - 1 - (ntile_k - 1) * BN;
+        const int lrem_last = L - 1 - (nblk_wg - 1) * 32;
+        const int r = 4 * wave + (lane >> 4);
+        const int slot = lane & 15;
 #pragma unroll
-        for (int is_v = 0; is_v < 2; ++is_v)
-#pragma unroll
-            for (int p = 0; p < 2; ++p) {
-                const int r = 4 * (2 * wave + p) + (lane >> 4);
-                const int slot = lane & 15;
-                const int swz = is_v ? 4 * (r & 3) + 2 * ((r >> 2) & 1) : (r & 15);
-                const uint32_t col = 16u * (uint32_t)(slot ^ swz);
-                dma_off[0][is_v][p] = __umul24((uint32_t)r, rstride_b) + col;
-                dma_off[1][is_v][p] = __umul24((uint32_t)min(r, lrem_last), rstride_b) + col;
-            }
+        for (int is_v = 0; is_v < 2; ++is_v) {
+            const int swz = is_v ? 4 * (r & 3) + 2 * ((r >> 2) & 1) : (r & 15);
+            const uint32_t col = 16u * (uint32_t)(slot ^ swz);
+            dma_off[0][is_v] = __umul24((uint32_t)r, rstride_b) + col;
+            dma_off[1][is_v] = __umul24((uint32_t)min(r, lrem_last), rstride_b) + col;
+        }
     }
-    // One LDS-DMA load: 64 lanes x 16 bytes from tile base `tb` (scalar) + per-lane offset into
+    // One LDS-DMA load: 64 lanes x 16 bytes from block base `tb` (scalar) + per-lane offset into
     // 1 KB of LDS at `dst`.  Written as asm so that the compiler does not tie later LDS reads
     // (of other stages) to this load with a vmcnt(0); completion is waited for explicitly
-    // before the tile barrier.  M0 = LDS destination of lane 0 (declared as clobbered).
+    // before the barrier.  M0 = LDS destination of lane 0 (declared as clobbered).
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Winline-asm"   // M0 is reserved; the clobber is deliberate
     auto dma_issue = [&](const char *tb, uint32_t off, uint32_t dst) {
@@ -494,25 +496,37 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
     };
 #pragma clang diagnostic pop
     struct DmaJob {
-        const char *tb;     // first row of the tile
-        uint32_t off[2];    // this lane's offsets for the wavefront's two loads
-        uint32_t dst;       // LDS stage
+        const char *tb;     // first row of the block
+        uint32_t off;       // this lane's offset
+        uint32_t dst;       // this wavefront's 1 KB of the block's ring stage
     };
-    auto dma_job = [&](int t, bool is_v, uint32_t lds_stage) {
-        const int tc = t < ntile_k ? t : ntile_k - 1;   // past the end: repeat the last tile
-        const bool last = tc == ntile_k - 1;
+    auto dma_job = [&](int blk, bool is_v) {
+        const int bc = blk < nblk_wg ? blk : nblk_wg - 1;   // past the end: repeat the last block
+        const bool last = bc == nblk_wg - 1;
         DmaJob j;
-        j.tb = (is_v ? vseq : kseq) + (size_t)tc * BN * rstride_b;
-        j.off[0] = last ? dma_off[1][is_v][0] : dma_off[0][is_v][0];
-        j.off[1] = last ? dma_off[1][is_v][1] : dma_off[0][is_v][1];
-        j.dst = lds_stage + (uint32_t)(2 * wave) * 1024u;
+        j.tb = (is_v ? vseq : kseq) + (size_t)bc * 32 * rstride_b;
+        j.off = last ? dma_off[1][is_v] : dma_off[0][is_v];
+        j.dst = (is_v ? lds_v : lds_k) + (uint32_t)(blk & (NSTG - 1)) * BLK_B + (uint32_t)wave * 1024u;
         return j;
     };
-    auto dma_run = [&](const DmaJob &j, int p) { dma_issue(j.tb, j.off[p], j.dst + (uint32_t)p * 1024u); };
-    auto dma_tile = [&](int t, bool is_v, uint32_t lds_stage) {
-        const DmaJob j = dma_job(t, is_v, lds_stage);
-        dma_run(j, 0);
-        dma_run(j, 1);
+    auto dma_run = [&](const DmaJob &j) { dma_issue(j.tb, j.off, j.dst); };
+    auto dma_block = [&](int blk, bool is_v) { dma_run(dma_job(blk, is_v)); };
+    // the loads a wavefront issues during block b of an interval of four blocks (between two
+    // workgroup barriers): everything the NEXT interval reads, requested in its first two blocks
+    struct DmaSet {
+        DmaJob j[4];
+        bool on;   // the next interval exists
+    };
+    auto dma_set = [&](int b) {
+        const int q = b & 3, i4 = b - q;   // block q of the interval that starts at block i4
+        DmaSet s;
+        s.on = i4 + 4 < nblk_wg;
+        // interval I reads K blocks 4I+1 .. 4I+4 and V blocks 4I .. 4I+3
+        s.j[0] = dma_job(i4 + 5 + 2 * q, false);
+        s.j[1] = dma_job(i4 + 6 + 2 * q, false);
+        s.j[2] = dma_job(i4 + 4 + 2 * q, true);
+        s.j[3] = dma_job(i4 + 5 + 2 * q, true);
+        return s;
     };
 
     // ---- per-lane LDS addresses of the fragments (stage 0, first 32-key block)
@@ -677,19 +691,20 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
     // one pipeline iteration for block b of parity PAR: S[PAR] holds S(b), P holds P(b-1),
     // vf holds V(b-1)
     // The LDS-DMA unit is shared by the workgroup and a wavefront stalls at issue while it is
-    // busy, so a wavefront's four loads per step are spread over the step: one in the middle
-    // of each half of its two iterations (K in the even block, V in the odd one).
-    auto body = [&](auto par_c, auto st_c, int b, const DmaJob &dj) {
-        constexpr int PAR = decltype(par_c)::value;
-        constexpr int ST = decltype(st_c)::value;   // ring stage of the tile block b lies in
+    // busy, so the four loads of a block (blocks 0 and 1 of an interval have them) are spread
+    // over the iteration: two in each half.
+    auto body = [&](auto bs_c, int b, const DmaSet &ds) {
+        constexpr int BS = decltype(bs_c)::value;   // ring stage of block b (= b % 8)
+        constexpr int PAR = BS & 1;
+        constexpr bool LOADS = (BS & 3) < 2;
         // A block's maximum is computed only with a moving reference (the fixed one comes from
         // block 0 in the prologue).  Without it the exponentials start two slots into half 1 (chunk
         // 0 of P is rewritten from tick 2 on, after MFMAs 0..3 have read it) and end with half 2.
         constexpr bool WITH_MAX = !FIXED;
         constexpr int T0 = WITH_MAX ? 4 : 2;        // half-1 slot of tick 0
-        // K(b+1): odd half of this tile, or even half of the next one; V(b): this tile
-        constexpr int K_OFF = PAR == 0 ? ST * TILE_B + 32 * ROWB : ((ST + 1) % KST) * TILE_B;
-        constexpr int V_OFF = ST * TILE_B + (PAR == 0 ? 0 : 32 * ROWB);
+        // ring stages of K(b+1) and V(b)
+        constexpr int K_OFF = ((BS + 1) % NSTG) * BLK_B;
+        constexpr int V_OFF = BS * BLK_B;
         f32x16 &Sc = S[PAR];
         f32x16 &Sn = S[PAR ^ 1];
         psum = 0.f;
@@ -709,7 +724,8 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
             if (WITH_MAX && j == 3) max_c();
             // chunk 0 of P is rewritten from tick 2 on: MFMAs 0..3 have read it by then
             if (j >= T0) exp_tick(Sc, j - T0);
-            if (j == 4) dma_run(dj, 0);
+            if (LOADS && j == 2 && ds.on) dma_run(ds.j[0]);
+            if (LOADS && j == 6 && ds.on) dma_run(ds.j[1]);
             ORCH_SB();
         }
         // ---- half 2: S(b+1) = K(b+1) Q^T; exp of keys 16..31
@@ -728,7 +744,8 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
             read_v1(j % NDB, j / NDB, V_OFF);
             ORCH_SB();
             exp_tick(Sc, 8 - T0 + j);
-            if (j == 4) dma_run(dj, 1);
+            if (LOADS && j == 2 && ds.on) dma_run(ds.j[2]);
+            if (LOADS && j == 6 && ds.on) dma_run(ds.j[3]);
             ORCH_SB();
         }
         if (WITH_MAX) {
@@ -749,14 +766,13 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
         l_run = l_run * alpha + psum;
     };
 
-    // ---- prologue: K tiles 0 and 1, V tile 0 on their way; S(0); V(0) fragments meet P = 0
-    // (tile indices past the end are clamped: the copy lands in a stage nobody reads, and every
-    // step issues the same number of loads, which the vmcnt arithmetic below relies on)
-    dma_tile(0, false, lds_k);
-    dma_tile(0, true, lds_v);
-    dma_tile(1, false, lds_k + TILE_B);
-    dma_tile(1, true, lds_v + TILE_B);
-    dma_tile(2, false, lds_k + 2 * TILE_B);
+    // ---- prologue: what interval 0 reads (K blocks 0..4, V blocks 0..3); S(0); V(0) fragments
+    // meet P = 0.  (Block indices past the end are clamped: the copy lands in a stage whose
+    // contents are masked or never read.)
+#pragma unroll
+    for (int blk = 0; blk < 5; ++blk) dma_block(blk, false);
+#pragma unroll
+    for (int blk = 0; blk < 4; ++blk) dma_block(blk, true);
     __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): this wavefront's DMA has landed
     __builtin_amdgcn_s_barrier();
 #pragma unroll
@@ -784,36 +800,35 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
         }
     }
 
-    // one 64-key tile (two blocks) whose ring stage ST = i % 4 is a compile-time constant
-    auto step = [&](auto st_c, int i) {
-        constexpr int ST = decltype(st_c)::value;
-        if (i > 0) {
-            // K(i+1) and V(i) were requested two steps ago; the four loads of the last step
-            // (K(i+2), V(i+1)) may stay in flight: vmcnt(4)
-            __builtin_amdgcn_s_waitcnt(0x0f74);
+    // One 32-key block whose ring stage BS = b % 8 is a compile-time constant.  The workgroup
+    // meets at a barrier every FOUR blocks: interval I (blocks 4I .. 4I+3) reads K blocks 4I+1 ..
+    // 4I+4 (the scores run one block ahead) and V blocks 4I .. 4I+3, all requested during interval
+    // I-1 and waited for (vmcnt(0)) before its barrier; its own requests, K blocks 4I+5 .. 4I+8
+    // and V blocks 4I+4 .. 4I+7, replace K blocks 4I-3 .. 4I and V blocks 4I-4 .. 4I-1, which nobody
+    // reads any more once everybody has passed that barrier.
+    auto block = [&](auto bs_c, int b) {
+        constexpr int BS = decltype(bs_c)::value;
+        if ((BS & 3) == 0 && b > 0) {
+            __builtin_amdgcn_s_waitcnt(0x0f70);
             __builtin_amdgcn_s_barrier();
         }
-        // K(i+3) replaces K(i-1), V(i+2) replaces V(i-2): nobody reads those any more
-        const DmaJob kj = dma_job(i + 3, false, lds_k + (uint32_t)(((ST + 3) % KST) * TILE_B));
-        const DmaJob vj = dma_job(i + 2, true, lds_v + (uint32_t)(((ST + 2) % VST) * TILE_B));
-        if (2 * i < nblk_w) {
-            body(std::integral_constant<int, 0>{}, st_c, 2 * i, kj);
-        } else {   // a wavefront past its causal range still feeds the ring
-            dma_run(kj, 0);
-            dma_run(kj, 1);
-        }
-        if (2 * i + 1 < nblk_w) {
-            body(std::integral_constant<int, 1>{}, st_c, 2 * i + 1, vj);
-        } else {
-            dma_run(vj, 0);
-            dma_run(vj, 1);
+        const DmaSet ds = dma_set(b);
+        if (b < nblk_w) {
+            body(bs_c, b, ds);
+        } else if ((BS & 3) < 2 && ds.on) {   // a wavefront past its causal range still feeds the ring
+#pragma unroll
+            for (int i = 0; i < 4; ++i) dma_run(ds.j[i]);
         }
     };
-    for (int i0 = 0; i0 < ntile_k; i0 += 4) {
-        step(std::integral_constant<int, 0>{}, i0);
-        if (i0 + 1 < ntile_k) step(std::integral_constant<int, 1>{}, i0 + 1);
-        if (i0 + 2 < ntile_k) step(std::integral_constant<int, 2>{}, i0 + 2);
-        if (i0 + 3 < ntile_k) step(std::integral_constant<int, 3>{}, i0 + 3);
+    for (int b0 = 0; b0 < nblk_wg; b0 += NSTG) {
+        block(std::integral_constant<int, 0>{}, b0);
+        if (b0 + 1 < nblk_wg) block(std::integral_constant<int, 1>{}, b0 + 1);
+        if (b0 + 2 < nblk_wg) block(std::integral_constant<int, 2>{}, b0 + 2);
+        if (b0 + 3 < nblk_wg) block(std::integral_constant<int, 3>{}, b0 + 3);
+        if (b0 + 4 < nblk_wg) block(std::integral_constant<int, 4>{}, b0 + 4);
+        if (b0 + 5 < nblk_wg) block(std::integral_constant<int, 5>{}, b0 + 5);
+        if (b0 + 6 < nblk_wg) block(std::integral_constant<int, 6>{}, b0 + 6);
+        if (b0 + 7 < nblk_wg) block(std::integral_constant<int, 7>{}, b0 + 7);
     }
     // ---- drain: O^T += V(B-1)^T P(B-1) for the wavefront's last block; both are in registers
     if (nblk_w > 0) {
