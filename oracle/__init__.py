@@ -213,6 +213,31 @@ def pack_composed(enc_rows: np.ndarray, packed: np.ndarray, sub_len, sub_off, en
     return packed
 
 
+def pack_composed_pieces(enc_rows: np.ndarray, packed: np.ndarray, piece_ptr, piece_off, piece_len, enc_asg,
+                         llm_asg: Assignment, inst_begin: int = 0, inst_end: int | None = None) -> np.ndarray:
+    """Rearrangement composition with several sub-sequences per example (Sec. 6): example s's rows of
+    this modality (one run in the encoder's packed order `enc_asg`, or in original order when None) are
+    cut into the pieces piece_ptr[s] .. piece_ptr[s+1]-1; piece p goes to row piece_off[p] of the
+    example's interleaved sequence.  Writes into `packed` in place and returns it."""
+    pp, po, pl = _i32(piece_ptr), _i32(piece_off), _i32(piece_len)
+    n = len(pp) - 1
+    Dm = len(llm_asg.loads)
+    if inst_end is None:
+        inst_end = Dm
+    enc_rows = np.ascontiguousarray(enc_rows)
+    assert packed.flags.c_contiguous and packed.dtype == enc_rows.dtype
+    rb = enc_rows.shape[1] * enc_rows.dtype.itemsize
+    if enc_asg is None:
+        e = (0, None, None, None, None)
+    else:
+        e = (len(enc_asg.loads), _p(enc_asg.order), _p(enc_asg.seq_off), _p(enc_asg.tok_off), _p(enc_asg.cu_seqlens))
+    _check(lib().orc_pack_composed_pieces(_p(enc_rows), _p(packed), _p(pp), _p(po), _p(pl), C.c_int32(n),
+                                          C.c_int64(rb), C.c_int32(e[0]), e[1], e[2], e[3], e[4], C.c_int32(Dm),
+                                          _p(llm_asg.order), _p(llm_asg.seq_off), _p(llm_asg.tok_off),
+                                          _p(llm_asg.cu_seqlens), C.c_int32(inst_begin), C.c_int32(inst_end)))
+    return packed
+
+
 def row_map(lengths, asg: Assignment) -> np.ndarray:
     L = _i32(lengths)
     D = len(asg.loads)

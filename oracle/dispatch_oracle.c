@@ -263,6 +263,83 @@ int orc_pack_composed(const void *enc_rows, void *packed, const int32_t *sub_len
     return rc;
 }
 
+/* Rearrangement composition with several sub-sequences per example (Sec. 6, subsequence
+ * assembly: an example's subsequences of the different modalities are interleaved in a
+ * predefined order, and one modality may contribute more than one of them, e.g. several
+ * images between pieces of text).  The encoder still hands back example s's rows of this
+ * modality as ONE run (its segment of the encoder assignment, or its place in original
+ * order); that run is cut into the pieces piece_ptr[s] .. piece_ptr[s+1]-1, taken in that order:
+ * piece p has piece_len[p] rows and goes to row piece_off[p] of the example's interleaved
+ * sequence.  Same two steps as orc_pack_composed: reset to original example order, then place.
+ * Pieces of one example must ascend without overlap (piece_off[p] >= end of the piece before);
+ * returns -5 otherwise, or if a piece leaves its sequence, or an encoder segment is too short. */
+int orc_pack_composed_pieces(const void *enc_rows, void *packed, const int32_t *piece_ptr,
+                             const int32_t *piece_off, const int32_t *piece_len, int32_t n,
+                             int64_t row_bytes, int32_t De, const int32_t *e_order,
+                             const int32_t *e_seq_off, const int64_t *e_tok_off, const int32_t *e_cu,
+                             int32_t Dm, const int32_t *m_order, const int32_t *m_seq_off,
+                             const int64_t *m_tok_off, const int32_t *m_cu, int32_t inst_begin,
+                             int32_t inst_end)
+{
+    if (n < 0 || Dm < 1 || inst_begin < 0 || inst_end > Dm || inst_begin > inst_end || row_bytes < 1)
+        return -1;
+    if (e_order && De < 1) return -1;
+    if (piece_ptr[0] != 0) return -5;
+    /* rows of this modality per example, and where each example starts in original order */
+    int64_t *sub_cu = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n + 1));
+    if (!sub_cu) return -1;
+    sub_cu[0] = 0;
+    for (int32_t s = 0; s < n; ++s) {
+        if (piece_ptr[s + 1] < piece_ptr[s]) { free(sub_cu); return -5; }
+        int64_t rows = 0;
+        for (int32_t p = piece_ptr[s]; p < piece_ptr[s + 1]; ++p) {
+            if (piece_len[p] < 0 || piece_off[p] < 0) { free(sub_cu); return -5; }
+            rows += piece_len[p];
+        }
+        sub_cu[s + 1] = sub_cu[s] + rows;
+    }
+    const char *src = (const char *)enc_rows;
+    char *tmp = NULL;
+    /* step 1: reset to original example order */
+    if (e_order) {
+        tmp = (char *)malloc((size_t)(sub_cu[n] > 0 ? sub_cu[n] : 1) * (size_t)row_bytes);
+        if (!tmp) { free(sub_cu); return -1; }
+        for (int32_t i = 0; i < De; ++i) {
+            const int32_t *cu = e_cu + e_seq_off[i] + i;
+            for (int32_t j = 0; j < e_seq_off[i + 1] - e_seq_off[i]; ++j) {
+                int32_t s = e_order[e_seq_off[i] + j];
+                int64_t rows = sub_cu[s + 1] - sub_cu[s];
+                if (cu[j + 1] - cu[j] < rows) { free(tmp); free(sub_cu); return -5; }
+                memcpy(tmp + sub_cu[s] * row_bytes, src + (e_tok_off[i] + cu[j]) * row_bytes,
+                       (size_t)rows * (size_t)row_bytes);
+            }
+        }
+        src = tmp;
+    }
+    /* step 2: place the pieces inside the interleaved sequences of the destination instances */
+    char *dst = (char *)packed;
+    int rc = 0;
+    for (int32_t i = inst_begin; i < inst_end && rc == 0; ++i) {
+        const int32_t *cu = m_cu + m_seq_off[i] + i;
+        for (int32_t j = 0; j < m_seq_off[i + 1] - m_seq_off[i] && rc == 0; ++j) {
+            int32_t s = m_order[m_seq_off[i] + j];
+            int64_t seq_rows = (int64_t)cu[j + 1] - cu[j];
+            int64_t drow = m_tok_off[i] - m_tok_off[inst_begin] + cu[j];
+            int64_t taken = 0, prev_end = 0;
+            for (int32_t p = piece_ptr[s]; p < piece_ptr[s + 1]; ++p) {
+                if (piece_off[p] < prev_end || (int64_t)piece_off[p] + piece_len[p] > seq_rows) { rc = -5; break; }
+                memcpy(dst + (drow + piece_off[p]) * row_bytes, src + (sub_cu[s] + taken) * row_bytes,
+                       (size_t)piece_len[p] * (size_t)row_bytes);
+                taken += piece_len[p];
+                prev_end = (int64_t)piece_off[p] + piece_len[p];
+            }
+        }
+    }
+    free(tmp);
+    free(sub_cu);
+    return rc;
+}
+
 /* ---------------------------------------------------------------------------
  * Algorithm 2, "Post-Balancing Algorithm with Paddings" (Sec. 5.1).  A padded
  * batch of k sequences costs k * (its longest sequence) rows (Eq. 1, padding

@@ -181,6 +181,46 @@ def draw_interleave_offsets(split: np.ndarray, seed: int) -> np.ndarray:
     return off
 
 
+def draw_piece_layout(split: np.ndarray, seed: int, max_pieces: int = 4):
+    """Several sub-sequences per (example, modality) (Sec. 6: an example's subsequences are interleaved
+    in a predefined order; e.g. several images between pieces of text).  Every modality's token count
+    of an example is cut into 1..max_pieces pieces (0 pieces when the count is 0) at seeded cut points,
+    and the pieces of the three modalities are laid out back to back in a seeded order that keeps each
+    modality's own pieces in sequence.  Returns one (piece_ptr int32[n+1], piece_off int32[P],
+    piece_len int32[P]) triple per modality; offsets are rows inside the example's interleaved
+    sequence."""
+    n, M = split.shape
+    ptr = [np.zeros(n + 1, dtype=np.int64) for _ in range(M)]
+    offs = [[] for _ in range(M)]
+    lens = [[] for _ in range(M)]
+    u_cnt = uniform01(seed, 31, n * M).reshape(n, M)
+    u_cut = uniform01(seed, 32, n * M * max_pieces).reshape(n, M, max_pieces)
+    u_ord = uniform01(seed, 33, n * M * max_pieces).reshape(n, M, max_pieces)
+    for s in range(n):
+        pieces = []   # (order key, modality, index within modality, length)
+        for m in range(M):
+            tot = int(split[s, m])
+            k = 0 if tot == 0 else min(tot, 1 + int(u_cnt[s, m] * max_pieces))
+            cuts = np.sort((u_cut[s, m, : max(k - 1, 0)] * (tot + 1)).astype(np.int64)) if k > 1 else np.zeros(0, np.int64)
+            edges = np.concatenate([[0], cuts, [tot]])
+            keys = np.sort(u_ord[s, m, :k])   # ascending keys keep the modality's pieces in order
+            for t in range(k):
+                pieces.append((float(keys[t]), m, t, int(edges[t + 1] - edges[t])))
+            ptr[m][s + 1] = ptr[m][s] + k
+        pieces.sort(key=lambda x: (x[0], x[1], x[2]))
+        row = 0
+        place = {}
+        for _, m, t, ln in pieces:
+            place[(m, t)] = (row, ln)
+            row += ln
+        for m in range(M):
+            for t in range(int(ptr[m][s + 1] - ptr[m][s])):
+                offs[m].append(place[(m, t)][0])
+                lens[m].append(place[(m, t)][1])
+    return [(ptr[m].astype(np.int32), np.array(offs[m], dtype=np.int32), np.array(lens[m], dtype=np.int32))
+            for m in range(M)]
+
+
 def random_lengths(seed: int, n: int, lo: int, hi: int, zero_frac: float = 0.0) -> np.ndarray:
     """Generic test helper: uniform ints in [lo, hi], a fraction forced to 0."""
     u = uniform01(seed, 11, n)
