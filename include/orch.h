@@ -15,6 +15,8 @@
  *   orch_pack_composed    Sec. 5.3 (rearrangement composition): rows in an encoder
  *                         phase's packed order go straight into the LLM phase's
  *                         packed, interleaved sequences: one row pass, not two.
+ *   orch_pack_composed_pieces  the same with several sub-sequences per example and modality
+ *                         (Sec. 6, subsequence assembly).
  *   orch_comm_volume      Sec. 5.2.2: the communication-volume matrix V of a rearrangement.
  *   orch_varlen_attn_bwd  its backward (dq, dk, dv from dout, out and lse).
  *   orch_varlen_attn_fwd  the padding-free ("batched along the sequence
@@ -191,6 +193,29 @@ int orch_pack_composed(const void *enc_rows, void *packed, const int32_t *sub_le
                        int32_t D_dst, orch_assignment dst, int64_t src_rows, int32_t H,
                        int64_t packed_rows, int32_t inst_begin, int32_t inst_end, void *ws,
                        size_t ws_bytes, void *stream);
+
+/* Bytes of workspace orch_pack_composed_pieces needs for n examples and n_pieces pieces. */
+size_t orch_pack_composed_pieces_workspace(int32_t n, int32_t n_pieces);
+
+/* Sec. 6 (subsequence assembly) on top of Sec. 5.3: the composition when one modality
+ * contributes SEVERAL sub-sequences to an example's interleaved sequence (several images
+ * between pieces of text).  The encoder's output still holds example s's rows of the modality
+ * as one run (located through `src` exactly as in orch_pack_composed; its length is the sum of
+ * the example's piece lengths); the run is cut into the pieces piece_ptr[s] .. piece_ptr[s+1]-1,
+ * in that order:
+ *   piece_ptr [n+1]      int32, piece_ptr[0] = 0, non-decreasing, piece_ptr[n] = n_pieces
+ *   piece_off [n_pieces] row of the example's interleaved sequence where the piece starts
+ *   piece_len [n_pieces] rows of the piece (0 is allowed)
+ * The pieces of one example must ascend without overlap and stay inside its sequence.
+ * Result: packed[dst.tok_off[i] - dst.tok_off[inst_begin] + cu_i[j] + piece_off[p] + r, :]
+ * = enc_rows[start_src(s) + (rows of s's earlier pieces) + r, :], 0 <= r < piece_len[p].
+ * One piece per example with piece_off = sub_off, piece_len = sub_len is orch_pack_composed.
+ * Inconsistent data sets dst.dev_status = ORCH_EDATA and copies nothing. */
+int orch_pack_composed_pieces(const void *enc_rows, void *packed, const int32_t *piece_ptr,
+                              const int32_t *piece_off, const int32_t *piece_len, int32_t n,
+                              int32_t n_pieces, int32_t D_src, const orch_assignment *src, int32_t D_dst,
+                              orch_assignment dst, int64_t src_rows, int32_t H, int64_t packed_rows,
+                              int32_t inst_begin, int32_t inst_end, void *ws, size_t ws_bytes, void *stream);
 
 /* Sec. 5.2.2, first loop of the node-wise rearrangement algorithm: the communication-volume
  * matrix of a rearrangement, V[from][to] = tokens that move from the instance they were

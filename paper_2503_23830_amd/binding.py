@@ -20,6 +20,7 @@ _lib = None
 EXPORTS = ("orch_balance_workspace", "orch_balance", "orch_pack_workspace", "orch_pack",
            "orch_balance_padded", "orch_balance_tolerance", "orch_balance_static", "orch_balance_static_max_n", "orch_balance_stages",
            "orch_pack_composed_workspace", "orch_pack_composed", "orch_comm_volume",
+           "orch_pack_composed_pieces_workspace", "orch_pack_composed_pieces",
            "orch_varlen_attn_workspace", "orch_varlen_attn_fwd", "orch_varlen_attn_bwd_workspace",
            "orch_varlen_attn_bwd", "orch_last_error",
            "orch_attn_variant")
@@ -85,6 +86,13 @@ def load_library():
     lib.orch_pack_composed.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                        C.POINTER(_Assignment), C.c_int32, _Assignment, C.c_int64, C.c_int32,
                                        C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.orch_pack_composed_pieces_workspace.restype = C.c_size_t
+    lib.orch_pack_composed_pieces_workspace.argtypes = [C.c_int32, C.c_int32]
+    lib.orch_pack_composed_pieces.restype = C.c_int
+    lib.orch_pack_composed_pieces.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                              C.c_int32, C.c_int32, C.POINTER(_Assignment), C.c_int32, _Assignment,
+                                              C.c_int64, C.c_int32, C.c_int64, C.c_int32, C.c_int32, C.c_void_p,
+                                              C.c_size_t, C.c_void_p]
     lib.orch_comm_volume.restype = C.c_int
     lib.orch_comm_volume.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, _Assignment,
                                      C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
@@ -283,6 +291,37 @@ def pack_composed(enc_rows: torch.Tensor, out: torch.Tensor, sub_len: torch.Tens
                                   dst.D, dst._c(), enc_rows.shape[0], enc_rows.shape[1], out.shape[0],
                                   inst_begin, inst_end, _ptr(ws), ws.numel(), C.c_void_p(_stream(dev))))
     return out
+
+
+def pack_composed_pieces(enc_rows: torch.Tensor, out: torch.Tensor, piece_ptr: torch.Tensor, piece_off: torch.Tensor,
+                         piece_len: torch.Tensor, src: Assignment | None, dst: Assignment, inst_begin: int = 0,
+                         inst_end: int | None = None, ws: torch.Tensor | None = None) -> torch.Tensor:
+    """orch_pack_composed_pieces (Sec. 6 on Sec. 5.3): as pack_composed, with example s's run of rows cut
+    into the pieces piece_ptr[s] .. piece_ptr[s+1]-1 placed at rows piece_off of its sequence."""
+    lib = load_library()
+    assert enc_rows.is_cuda and enc_rows.is_contiguous() and enc_rows.element_size() == 2 and enc_rows.dim() == 2
+    assert out.is_contiguous() and out.dtype == enc_rows.dtype and out.dim() == 2 and out.shape[1] == enc_rows.shape[1]
+    for t in (piece_ptr, piece_off, piece_len):
+        assert t.dtype == torch.int32 and t.is_cuda and t.is_contiguous()
+    assert piece_ptr.numel() == dst.n + 1 and piece_off.numel() == piece_len.numel()
+    assert src is None or src.n == dst.n
+    dev = enc_rows.device
+    P = piece_off.numel()
+    if inst_end is None:
+        inst_end = dst.D
+    if ws is None:
+        ws = _workspace(lib.orch_pack_composed_pieces_workspace(dst.n, P), dev)
+    src_c = src._c() if src is not None else None
+    _check(lib.orch_pack_composed_pieces(_ptr(enc_rows), _ptr(out), _ptr(piece_ptr), _ptr(piece_off), _ptr(piece_len),
+                                         dst.n, P, src.D if src is not None else 0,
+                                         C.byref(src_c) if src_c is not None else None, dst.D, dst._c(),
+                                         enc_rows.shape[0], enc_rows.shape[1], out.shape[0], inst_begin, inst_end,
+                                         _ptr(ws), ws.numel(), C.c_void_p(_stream(dev))))
+    return out
+
+
+def pack_composed_pieces_workspace(n: int, n_pieces: int) -> int:
+    return load_library().orch_pack_composed_pieces_workspace(n, n_pieces)
 
 
 def comm_volume(lengths: torch.Tensor, asg: Assignment, D_src: int, src_inst: torch.Tensor | None = None,

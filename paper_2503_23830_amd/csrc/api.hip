@@ -39,6 +39,7 @@ const char *orch_attn_variant(void) { return g_variant; }
 size_t orch_balance_workspace(int32_t n, int32_t D) { return balance_ws_bytes(n, D); }
 size_t orch_pack_workspace(int32_t n, int32_t D) { return pack_ws_bytes(n, D); }
 size_t orch_pack_composed_workspace(int32_t n) { return pack_composed_ws_bytes(n); }
+size_t orch_pack_composed_pieces_workspace(int32_t n, int32_t n_pieces) { return pack_composed_pieces_ws_bytes(n, n_pieces); }
 size_t orch_varlen_attn_workspace(int32_t batch, int32_t total_tokens, int32_t Hq)
 {
     return attn_ws_bytes(batch, total_tokens, Hq);
@@ -154,6 +155,33 @@ int orch_pack_composed(const void *enc_rows, void *packed, const int32_t *sub_le
     if ((uintptr_t)ws & 255) ORCH_FAIL(ORCH_EINVAL, "orch_pack_composed: workspace not 256-byte aligned");
     return launch_pack_composed(enc_rows, packed, sub_len, sub_off, n, D_src, src, D_dst, dst, src_rows, H,
                                 packed_rows, inst_begin, inst_end, ws, ws_bytes, (hipStream_t)stream);
+}
+
+int orch_pack_composed_pieces(const void *enc_rows, void *packed, const int32_t *piece_ptr, const int32_t *piece_off,
+                              const int32_t *piece_len, int32_t n, int32_t n_pieces, int32_t D_src,
+                              const orch_assignment *src, int32_t D_dst, orch_assignment dst, int64_t src_rows,
+                              int32_t H, int64_t packed_rows, int32_t inst_begin, int32_t inst_end, void *ws,
+                              size_t ws_bytes, void *stream)
+{
+    if (n < 0 || n_pieces < 0 || D_dst < 1)
+        ORCH_FAIL(ORCH_EINVAL, "orch_pack_composed_pieces: n = %d, n_pieces = %d, D_dst = %d", n, n_pieces, D_dst);
+    if (src && D_src < 1) ORCH_FAIL(ORCH_EINVAL, "orch_pack_composed_pieces: D_src = %d < 1", D_src);
+    if (src_rows < 0 || packed_rows < 0)
+        ORCH_FAIL(ORCH_EINVAL, "orch_pack_composed_pieces: src_rows = %lld, packed_rows = %lld", (long long)src_rows, (long long)packed_rows);
+    if (H < 1) ORCH_FAIL(ORCH_EINVAL, "orch_pack_composed_pieces: H = %d < 1", H);
+    if (inst_begin < 0 || inst_end > D_dst || inst_begin > inst_end)
+        ORCH_FAIL(ORCH_EINVAL, "orch_pack_composed_pieces: instance range [%d, %d) outside [0, %d]", inst_begin, inst_end, D_dst);
+    if (!piece_ptr) ORCH_FAIL(ORCH_EINVAL, "orch_pack_composed_pieces: piece_ptr is NULL");
+    if (n_pieces > 0 && (!piece_off || !piece_len)) ORCH_FAIL(ORCH_EINVAL, "orch_pack_composed_pieces: piece_off or piece_len is NULL");
+    if ((src_rows > 0 && !enc_rows) || (packed_rows > 0 && !packed)) ORCH_FAIL(ORCH_EINVAL, "orch_pack_composed_pieces: a row buffer is NULL");
+    if (((uintptr_t)enc_rows | (uintptr_t)packed) & 1) ORCH_FAIL(ORCH_EINVAL, "orch_pack_composed_pieces: row buffers must be 2-byte aligned");
+    if (!assignment_complete(dst) || (src && !assignment_complete(*src)))
+        ORCH_FAIL(ORCH_EINVAL, "orch_pack_composed_pieces: an assignment pointer is NULL");
+    if (!ws) ORCH_FAIL(ORCH_EINVAL, "orch_pack_composed_pieces: workspace is NULL");
+    if ((uintptr_t)ws & 255) ORCH_FAIL(ORCH_EINVAL, "orch_pack_composed_pieces: workspace not 256-byte aligned");
+    return launch_pack_composed_pieces(enc_rows, packed, piece_ptr, piece_off, piece_len, n, n_pieces, D_src, src,
+                                       D_dst, dst, src_rows, H, packed_rows, inst_begin, inst_end, ws, ws_bytes,
+                                       (hipStream_t)stream);
 }
 
 int orch_comm_volume(const int32_t *lengths, int32_t n, int32_t D_src, const int32_t *from, int32_t D_dst,

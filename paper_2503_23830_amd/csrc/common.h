@@ -46,6 +46,12 @@ int launch_pack_composed(const void *enc_rows, void *packed, const int32_t *sub_
                          int32_t D_dst, orch_assignment dst, int64_t src_rows, int32_t H,
                          int64_t packed_rows, int32_t inst_begin, int32_t inst_end, void *ws,
                          size_t ws_bytes, hipStream_t stream);
+int launch_pack_composed_pieces(const void *enc_rows, void *packed, const int32_t *piece_ptr,
+                                const int32_t *piece_off, const int32_t *piece_len, int32_t n, int32_t P,
+                                int32_t D_src, const orch_assignment *src, int32_t D_dst, orch_assignment dst,
+                                int64_t src_rows, int32_t H, int64_t packed_rows, int32_t inst_begin,
+                                int32_t inst_end, void *ws, size_t ws_bytes, hipStream_t stream);
+size_t pack_composed_pieces_ws_bytes(int32_t n, int32_t P);
 int launch_comm_volume(const int32_t *lengths, int32_t n, int32_t D_src, const int32_t *from, int32_t D_dst,
                        orch_assignment dst, uint64_t *V, int32_t node, uint64_t *inter, hipStream_t stream);
 int launch_attn(const void *q, const void *k, const void *v, void *out, float *lse,

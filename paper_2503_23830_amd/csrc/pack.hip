@@ -68,6 +68,33 @@ size_t carve(ComposeWs &w, void *ws, int32_t n)
     return off;
 }
 
+// orch_pack_composed_pieces: several segments per example (P pieces in all)
+struct PiecesWs {
+    PackHdr *hdr;
+    int64_t *src_start;  // [n]     first source row of example s
+    int64_t *piece_pre;  // [P+1]   exclusive prefix of piece lengths (rows), piece order
+    int64_t *seg_base;   // [n+1]   first segment of the q-th chosen destination position
+    int64_t *seg_pos;    // [P+1]   exclusive prefix of segment lengths (rows), [nseg] = total
+    int64_t *seg_dst;    // [P]     destination row of segment (relative)
+    int64_t *seg_src;    // [P]     source row of segment
+};
+
+size_t carve(PiecesWs &w, void *ws, int32_t n, int32_t P)
+{
+    size_t nn = (size_t)(n > 0 ? n : 0) + 1, pp = (size_t)(P > 0 ? P : 0) + 1;
+    char *p = (char *)ws;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { char *r = p ? p + off : nullptr; off += align_up(bytes, 256); return r; };
+    w.hdr = (PackHdr *)take(sizeof(PackHdr));
+    w.src_start = (int64_t *)take(nn * 8);
+    w.piece_pre = (int64_t *)take(pp * 8);
+    w.seg_base = (int64_t *)take(nn * 8);
+    w.seg_pos = (int64_t *)take(pp * 8);
+    w.seg_dst = (int64_t *)take(pp * 8);
+    w.seg_src = (int64_t *)take(pp * 8);
+    return off;
+}
+
 constexpr int kPrepThreads = 1024;
 
 // Inclusive scan of one value per thread over the workgroup; returns this thread's
@@ -259,6 +286,161 @@ __global__ __launch_bounds__(kPrepThreads) void compose_prep_kernel(
     }
 }
 
+// One workgroup, the composition with several pieces per example (Sec. 6, subsequence assembly).
+// (1) running sum of the piece lengths, which gives every example's row count of this modality
+// and the place of every piece inside the example's run; (2) first source row of every example,
+// from the encoder assignment or, for an original-order source, from that running sum; (3) one
+// segment per piece of the examples on the chosen destination instances, in destination order,
+// validated against both buffers, the interleaved sequence and the piece before it; (4) the
+// running sum of segment lengths the copy kernel chunks over.
+__global__ __launch_bounds__(kPrepThreads) void compose_pieces_prep_kernel(
+    const int32_t *__restrict__ piece_ptr, const int32_t *__restrict__ piece_off,
+    const int32_t *__restrict__ piece_len, int32_t n, int32_t P, int64_t src_rows, int64_t packed_rows,
+    int has_src, ComposeSide e, ComposeSide m, int32_t *dev_status, int32_t inst_begin, int32_t inst_end,
+    PackHdr *hdr, int64_t *src_start, int64_t *piece_pre, int64_t *seg_base, int64_t *seg_pos,
+    int64_t *seg_dst, int64_t *seg_src)
+{
+    __shared__ int64_t part[kPrepThreads];
+    __shared__ int s_bad;
+    const int tid = threadIdx.x;
+    if (tid == 0) s_bad = (m.status[0] != 0) || (has_src && e.status[0] != 0);
+    int bad = 0;
+    if (piece_ptr[0] != 0 || piece_ptr[n] != P) bad = 1;
+
+    // (1) piece_pre
+    {
+        const int64_t per = ((int64_t)P + kPrepThreads - 1) / kPrepThreads;
+        const int64_t b0 = min((int64_t)P, per * tid), b1 = min((int64_t)P, b0 + per);
+        int64_t sum = 0;
+        for (int64_t p = b0; p < b1; ++p) {
+            const int32_t L = piece_len[p];
+            if (L < 0 || piece_off[p] < 0) { bad = 1; continue; }
+            sum += L;
+        }
+        int64_t run = block_scan(part, tid, sum) - sum;
+        for (int64_t p = b0; p < b1; ++p) {
+            piece_pre[p] = run;
+            run += piece_len[p] > 0 ? piece_len[p] : 0;
+        }
+        if (tid == kPrepThreads - 1) piece_pre[P] = part[tid];
+        if (part[kPrepThreads - 1] > src_rows) bad = 1;
+    }
+    __syncthreads();
+    // a usable piece_ptr: non-decreasing inside [0, P]
+    for (int64_t s = tid; s < n; s += kPrepThreads) {
+        const int32_t a = piece_ptr[s], b = piece_ptr[s + 1];
+        if (a < 0 || b < a || b > P) bad = 1;
+    }
+    if (bad) atomicOr(&s_bad, 1);
+    __syncthreads();
+    if (s_bad) {   // nothing below may index with a broken piece_ptr
+        if (tid == 0) {
+            hdr->nseg = 0;
+            hdr->total_rows = 0;
+            hdr->ok = 0;
+            dev_status[0] = (int32_t)ORCH_EDATA;
+        }
+        return;
+    }
+
+    // (2) src_start
+    if (has_src) {
+        for (int64_t s = tid; s < n; s += kPrepThreads) src_start[s] = -1;
+        __syncthreads();
+        const int32_t pe = e.seq_off[e.D];
+        if (pe != n) bad = 1;
+        else
+            for (int64_t p = tid; p < n; p += kPrepThreads) {
+                const int32_t s = e.order[p];
+                if (s < 0 || s >= n) { bad = 1; continue; }
+                const int32_t i = e.inst[s];
+                if (i < 0 || i >= e.D) { bad = 1; continue; }
+                if (p < e.seq_off[i] || p >= e.seq_off[i + 1]) { bad = 1; continue; }
+                const int64_t c0 = e.cu[p + i], c1 = e.cu[p + i + 1];
+                const int64_t start = e.tok_off[i] + c0;
+                const int64_t rows = piece_pre[piece_ptr[s + 1]] - piece_pre[piece_ptr[s]];
+                if (c1 - c0 < rows || c0 < 0 || start < 0) { bad = 1; continue; }
+                src_start[s] = start;
+            }
+    } else {
+        for (int64_t s = tid; s < n; s += kPrepThreads) src_start[s] = piece_pre[piece_ptr[s]];
+    }
+    __syncthreads();
+
+    // (3) segments of the chosen destination positions
+    const int32_t p0 = m.seq_off[inst_begin], p1 = m.seq_off[inst_end];
+    const int64_t row0 = m.tok_off[inst_begin], rows = m.tok_off[inst_end] - row0;
+    if (p0 < 0 || p1 < p0 || p1 > n || rows < 0 || rows > packed_rows) bad = 1;
+    const int64_t npos = bad ? 0 : p1 - p0;
+    const int64_t per = (npos + kPrepThreads - 1) / kPrepThreads;
+    const int64_t b0 = min(npos, per * tid), b1 = min(npos, b0 + per);
+    int64_t cnt = 0;
+    for (int64_t q = b0; q < b1; ++q) {
+        const int32_t s = m.order[p0 + q];
+        if (s < 0 || s >= n) { bad = 1; continue; }
+        cnt += piece_ptr[s + 1] - piece_ptr[s];
+    }
+    if (bad) atomicOr(&s_bad, 1);
+    int64_t base = block_scan(part, tid, cnt) - cnt;
+    const int64_t nseg = part[kPrepThreads - 1];
+    __syncthreads();   // part[] is reused below
+    if (s_bad || nseg > P) bad = 1;
+    if (!bad) {
+        for (int64_t q = b0; q < b1; ++q) {
+            const int64_t p = p0 + q;
+            const int32_t s = m.order[p];
+            const int32_t i = m.inst[s];
+            const int32_t t0 = piece_ptr[s], t1 = piece_ptr[s + 1];
+            seg_base[q] = base;
+            if (i < inst_begin || i >= inst_end || p < m.seq_off[i] || p >= m.seq_off[i + 1]) {
+                bad = 1;
+                for (int32_t t = t0; t < t1; ++t) { seg_pos[base + (t - t0)] = 0; seg_dst[base + (t - t0)] = 0; seg_src[base + (t - t0)] = 0; }
+                base += t1 - t0;
+                continue;
+            }
+            const int64_t c0 = m.cu[p + i], seq_len = (int64_t)m.cu[p + i + 1] - c0;
+            const int64_t dst0 = m.tok_off[i] - row0 + c0, src0 = src_start[s] - piece_pre[t0];
+            int64_t prev_end = 0;
+            for (int32_t t = t0; t < t1; ++t) {
+                const int64_t L = piece_len[t], off = piece_off[t];
+                const int64_t dst = dst0 + off, src = src0 + piece_pre[t];
+                // pieces of an example ascend without overlap and stay inside its sequence
+                if (off < prev_end || off + L > seq_len || c0 < 0 || dst < 0 || dst + L > rows || src < 0 ||
+                    src + L > src_rows) bad = 1;
+                prev_end = off + L;
+                seg_pos[base] = L;   // length for now; the running sum follows
+                seg_dst[base] = dst;
+                seg_src[base] = src;
+                ++base;
+            }
+        }
+    }
+    if (bad) atomicOr(&s_bad, 1);
+    __syncthreads();
+    const int ok = !s_bad;
+    // (4) running sum of segment lengths, in place
+    {
+        const int64_t ns = ok ? nseg : 0;
+        const int64_t per2 = (ns + kPrepThreads - 1) / kPrepThreads;
+        const int64_t c0 = min(ns, per2 * tid), c1 = min(ns, c0 + per2);
+        int64_t sum = 0;
+        for (int64_t x = c0; x < c1; ++x) sum += seg_pos[x];
+        int64_t run = block_scan(part, tid, sum) - sum;
+        for (int64_t x = c0; x < c1; ++x) {
+            const int64_t L = seg_pos[x];
+            seg_pos[x] = run;
+            run += L;
+        }
+        if (tid == 0) {
+            hdr->nseg = ns;
+            hdr->total_rows = ok ? part[kPrepThreads - 1] : 0;
+            hdr->ok = ok;
+            if (ok) seg_pos[ns] = part[kPrepThreads - 1];
+            else dev_status[0] = (int32_t)ORCH_EDATA;
+        }
+    }
+}
+
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
@@ -427,6 +609,33 @@ int launch_pack_composed(const void *enc_rows, void *packed, const int32_t *sub_
     hipLaunchKernelGGL(compose_prep_kernel, dim3(1), dim3(kPrepThreads), 0, stream, sub_len, sub_off, n,
                        src_rows, packed_rows, src ? 1 : 0, e, m, dst.dev_status, inst_begin, inst_end, w.hdr,
                        w.src_start, w.seg_pos, w.seg_dst, w.seg_src);
+    launch_copy(enc_rows, packed, (packed_rows < src_rows ? packed_rows : src_rows) * row_bytes, row_bytes,
+                w.hdr, w.seg_pos, w.seg_dst, w.seg_src, stream);
+    ORCH_HIP_CHECK(hipGetLastError());
+    return ORCH_OK;
+}
+
+size_t pack_composed_pieces_ws_bytes(int32_t n, int32_t P)
+{
+    PiecesWs w;
+    return carve(w, nullptr, n, P);
+}
+
+int launch_pack_composed_pieces(const void *enc_rows, void *packed, const int32_t *piece_ptr,
+                                const int32_t *piece_off, const int32_t *piece_len, int32_t n, int32_t P,
+                                int32_t D_src, const orch_assignment *src, int32_t D_dst, orch_assignment dst,
+                                int64_t src_rows, int32_t H, int64_t packed_rows, int32_t inst_begin,
+                                int32_t inst_end, void *ws, size_t ws_bytes, hipStream_t stream)
+{
+    PiecesWs w;
+    size_t need = carve(w, ws, n, P);
+    if (ws_bytes < need) ORCH_FAIL(ORCH_ENOSPC, "orch_pack_composed_pieces: workspace %zu < %zu bytes", ws_bytes, need);
+    const int64_t row_bytes = (int64_t)H * 2;
+    ComposeSide e{}, m{dst.inst, dst.order, dst.seq_off, dst.cu_seqlens, dst.tok_off, dst.dev_status, D_dst};
+    if (src) e = ComposeSide{src->inst, src->order, src->seq_off, src->cu_seqlens, src->tok_off, src->dev_status, D_src};
+    hipLaunchKernelGGL(compose_pieces_prep_kernel, dim3(1), dim3(kPrepThreads), 0, stream, piece_ptr, piece_off,
+                       piece_len, n, P, src_rows, packed_rows, src ? 1 : 0, e, m, dst.dev_status, inst_begin,
+                       inst_end, w.hdr, w.src_start, w.piece_pre, w.seg_base, w.seg_pos, w.seg_dst, w.seg_src);
     launch_copy(enc_rows, packed, (packed_rows < src_rows ? packed_rows : src_rows) * row_bytes, row_bytes,
                 w.hdr, w.seg_pos, w.seg_dst, w.seg_src, stream);
     ORCH_HIP_CHECK(hipGetLastError());

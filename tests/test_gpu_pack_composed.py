@@ -245,3 +245,107 @@ def test_c4_full_size_every_row(gpu_device):
         del want
     del packed
     torch.cuda.empty_cache()
+
+
+# ----------------------------------------------------------------------------
+# several sub-sequences per example and modality (Sec. 6, subsequence assembly)
+# ----------------------------------------------------------------------------
+def compose_pieces_all(L, split, lay, Dm, phase_m, enc, H, dev, lo=0, hi=None, pad=64):
+    hi = Dm if hi is None else hi
+    mref = oracle.balance(L, Dm, *phase_m)
+    _, masg = run_balance(L, Dm, *phase_m, dev)
+    rows = int(mref.tok_off[hi] - mref.tok_off[lo])
+    buf = torch.full((rows + 2 * pad, H), GUARD, dtype=torch.int16, device=dev)
+    out = buf[pad: pad + rows]
+    want = np.full((rows, H), GUARD, dtype=np.uint16)
+    for m in range(3):
+        sub = np.ascontiguousarray(split[:, m])
+        pp, po, pl = lay[m]
+        De, phase_e = enc[m]
+        rows_m, eref, easg = encoder_side(sub, De, phase_e, m, H, dev)
+        oracle.pack_composed_pieces(rows_m, want, pp, po, pl, eref, mref, lo, hi)
+        src_d = host_rows(rows_m, dev)
+        before = src_d.clone()
+        orch.pack_composed_pieces(src_d, out, to_dev(pp, dev), to_dev(po, dev), to_dev(pl, dev), easg, masg, lo, hi)
+        torch.cuda.synchronize()
+        assert torch.equal(src_d, before)
+    assert int(masg.dev_status.item()) == 0
+    guards = bool((buf[:pad] == GUARD).all()) and bool((buf[pad + rows:] == GUARD).all())
+    return out, guards, want, mref, masg
+
+
+@pytest.mark.parametrize("cid,shrink,keep,H,max_pieces", [(4, 4, 1500, 64, 4), (4, 1, 300, 256, 3), (1, 1, None, 24, 4),
+                                                          (3, 1, None, 40, 2)])
+def test_pieces_three_modalities(gpu_device, cid, shrink, keep, H, max_pieces):
+    w = wl.WORKLOADS[cid]
+    L = wl.draw_lengths(w)
+    if keep is not None:
+        L = L[:keep]
+    L = (L // shrink).astype(np.int32)
+    split = wl.draw_modality_split(w, L)
+    lay = wl.draw_piece_layout(split, 40 + cid, max_pieces)
+    enc = {0: (None, None), 1: (max(2, w.D // 2), (1, 6144)), 2: (w.D, (1, 7680))}
+    out, guards, want, mref, _ = compose_pieces_all(L, split, lay, w.D, (w.a, w.b), enc, H, gpu_device)
+    assert guards
+    assert np.array_equal(bits(out), want)
+    assert not (want == GUARD).all(axis=1).any()  # the three modalities' pieces cover every row
+    # an instance sub-range
+    lo, hi = 1, max(2, w.D // 2)
+    out2, guards2, want2, _, _ = compose_pieces_all(L, split, lay, w.D, (w.a, w.b), enc, H, gpu_device, lo, hi)
+    assert guards2 and np.array_equal(bits(out2), want2)
+
+
+def test_pieces_one_per_example_equals_pack_composed(gpu_device):
+    dev = gpu_device
+    w = wl.WORKLOADS[4]
+    L = (wl.draw_lengths(w)[:800] // 4).astype(np.int32)
+    split = wl.draw_modality_split(w, L)
+    sub_off = wl.draw_interleave_offsets(split, 4)
+    H = 128
+    Ld, masg = run_balance(L, w.D, w.a, w.b, dev)
+    T = int(L.sum())
+    for m in (1, 2):
+        sub = np.ascontiguousarray(split[:, m])
+        rows_m, _, easg = encoder_side(sub, 8, (1, 5), m, H, dev)
+        src_d = host_rows(rows_m, dev)
+        a = torch.full((T, H), GUARD, dtype=torch.int16, device=dev)
+        b = a.clone()
+        orch.pack_composed(src_d, a, to_dev(sub, dev), to_dev(sub_off[:, m], dev), easg, masg)
+        pp = np.arange(len(L) + 1, dtype=np.int32)
+        orch.pack_composed_pieces(src_d, b, to_dev(pp, dev), to_dev(sub_off[:, m], dev), to_dev(sub, dev), easg, masg)
+        torch.cuda.synchronize()
+        assert int(masg.dev_status.item()) == 0 and torch.equal(a, b)
+
+
+def test_pieces_refused_on_device(gpu_device):
+    dev = gpu_device
+    L = np.array([10, 6, 8], dtype=np.int32)
+    _, asg = run_balance(L, 2, 0, 1, dev)
+    rows = host_rows(wl.token_tag_np(np.arange(12), 8), dev)
+    pp = to_dev(np.array([0, 2, 3, 4], np.int32), dev)
+    good = (np.array([0, 5, 1, 2], np.int32), np.array([3, 5, 2, 2], np.int32))
+    out = torch.full((24, 8), GUARD, dtype=torch.int16, device=dev)
+    orch.pack_composed_pieces(rows, out, pp, to_dev(good[0], dev), to_dev(good[1], dev), None, asg)
+    torch.cuda.synchronize()
+    assert int(asg.dev_status.item()) == 0 and int((out != GUARD).all(dim=1).sum().item()) == 12
+    bad_cases = [([0, 2, 1, 2], [3, 5, 2, 2], pp),          # overlap inside an example
+                 ([5, 0, 1, 2], [5, 3, 2, 2], pp),          # descending pieces
+                 ([0, 6, 1, 2], [3, 5, 2, 2], pp),          # past the end of the sequence
+                 ([0, 5, 1, -1], [3, 5, 2, 2], pp),         # negative offset
+                 ([0, 5, 1, 2], [3, -5, 2, 2], pp),         # negative length
+                 ([0, 5, 1, 2], [3, 5, 2, 2], to_dev(np.array([0, 3, 2, 4], np.int32), dev)),   # piece_ptr not monotone
+                 ([0, 5, 1, 2], [3, 5, 2, 2], to_dev(np.array([0, 2, 3, 3], np.int32), dev))]   # piece_ptr[n] != n_pieces
+    for off, ln, ptr in bad_cases:
+        asg.dev_status.zero_()
+        out.fill_(GUARD)
+        orch.pack_composed_pieces(rows, out, ptr, to_dev(np.array(off, np.int32), dev), to_dev(np.array(ln, np.int32), dev),
+                                  None, asg)
+        torch.cuda.synchronize()
+        assert int(asg.dev_status.item()) == -5, (off, ln)
+        assert bool((out == GUARD).all())
+    # no pieces at all: nothing is written, no error
+    asg.dev_status.zero_()
+    empty = torch.zeros(0, dtype=torch.int32, device=dev)
+    orch.pack_composed_pieces(rows[:0], out, to_dev(np.zeros(4, np.int32), dev), empty, empty, None, asg)
+    torch.cuda.synchronize()
+    assert int(asg.dev_status.item()) == 0 and bool((out == GUARD).all())
