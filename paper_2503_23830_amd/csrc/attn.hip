@@ -55,7 +55,7 @@ __global__ __launch_bounds__(kPrepThreads) void attn_prep_kernel(const int32_t *
                                                                 int32_t batch, int32_t total_tokens,
                                                                 int32_t max_seqlen, int32_t BM, AttnHdr *hdr,
                                                                 int32_t *tile_off, int32_t *dev_status,
-                                                                int32_t *redo, int32_t Hq)
+                                                                int32_t *redo, int32_t *redo_list, int32_t Hq)
 {
     __shared__ int32_t part[kPrepThreads];
     __shared__ int s_bad;
@@ -99,6 +99,7 @@ __global__ __launch_bounds__(kPrepThreads) void attn_prep_kernel(const int32_t *
         const int64_t marks = (int64_t)part[kPrepThreads - 1] * Hq;
         for (int64_t i = tid; i < marks; i += kPrepThreads) redo[i] = 0;
     }
+    if (redo_list != nullptr && tid == 0) redo_list[0] = 0;   // number of listed tiles
 }
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b)
@@ -397,12 +398,15 @@ constexpr int kILThreads = 512;
 
 // FIXED: fixed softmax reference (see kRedoSum above); its row maximum over block 0 is taken in
 // the prologue, so every block of the tile loop runs the same code without maxima.
+// One (query tile, head) of the grid, named by the workgroup number `bid` it has in the
+// fixed-reference launch.  The moving-reference form is driven by the list of marked tiles.
 template <int HD, bool CAUSAL, bool FIXED>
-__global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
+__device__ __forceinline__ void attn_il_tile(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
     uint16_t *__restrict__ out, float *__restrict__ lse, const int32_t *__restrict__ cu,
     const AttnHdr *__restrict__ hdr, const int32_t *__restrict__ tile_off, int32_t *__restrict__ redo,
-    int32_t batch, int32_t total_tokens, int32_t Hq, int32_t Hkv, float scale, float scale_log2)
+    int32_t *__restrict__ redo_list, int32_t batch, int32_t total_tokens, int32_t Hq, int32_t Hkv, float scale,
+    float scale_log2, const int bid)
 {
     static_assert(HD == 128, "layout constants below assume 256-byte rows");
     constexpr int BM = 256;
@@ -420,7 +424,6 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
     const int group = Hq / Hkv;
     int u, h;
     {
-        const int bid = blockIdx.x;
         if ((Hkv & 7) == 0) {   // kv-head chosen by XCD: blocks sharing K/V share an L2
             const int kvh = (bid & 7) + 8 * ((bid >> 3) % (Hkv >> 3));
             const int rest = bid / Hkv;
@@ -432,7 +435,6 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
         }
     }
     if (u >= total_tiles) return;
-    if (!FIXED && redo[u * Hq + h] == 0) return;   // the fixed-reference pass was good enough
     const int g_kv = h / group;
     int lo = 0, hi = batch - 1;
     while (lo < hi) {
@@ -849,7 +851,9 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
     const float inv = 1.f / l_tot;
     if (FIXED) {
         // a sum that did not stay below 2^64 (or is not a number): the moving-reference pass redoes the tile
-        if (__any(!(l_tot < kRedoSum)) && lane == 0) redo[u * Hq + h] = 1;
+        // (the first wavefront of the workgroup to find one appends the tile to the list)
+        if (__any(!(l_tot < kRedoSum)) && lane == 0 && atomicExch(&redo[u * Hq + h], 1) == 0)
+            redo_list[1 + atomicAdd(&redo_list[0], 1)] = bid;
     }
     if (qm < L) {
         uint16_t *op = out + ((size_t)(row0 + qm) * Hq + h) * HD;
@@ -869,9 +873,40 @@ __global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
 
 #undef ORCH_SB
 
+// the launch every call makes: fixed reference, one workgroup per (query tile, head)
+template <int HD, bool CAUSAL>
+__global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
+    const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
+    uint16_t *__restrict__ out, float *__restrict__ lse, const int32_t *__restrict__ cu,
+    const AttnHdr *__restrict__ hdr, const int32_t *__restrict__ tile_off, int32_t *__restrict__ redo,
+    int32_t *__restrict__ redo_list, int32_t batch, int32_t total_tokens, int32_t Hq, int32_t Hkv, float scale,
+    float scale_log2)
+{
+    attn_il_tile<HD, CAUSAL, true>(q, k, v, out, lse, cu, hdr, tile_off, redo, redo_list, batch, total_tokens, Hq, Hkv,
+                                   scale, scale_log2, (int)blockIdx.x);
+}
+
+// the moving-reference pass: a small grid walks the list of marked tiles (normally empty)
+template <int HD, bool CAUSAL>
+__global__ __launch_bounds__(kILThreads) void attn_fwd_il_redo_kernel(
+    const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
+    uint16_t *__restrict__ out, float *__restrict__ lse, const int32_t *__restrict__ cu,
+    const AttnHdr *__restrict__ hdr, const int32_t *__restrict__ tile_off, int32_t *__restrict__ redo,
+    int32_t *__restrict__ redo_list, int32_t batch, int32_t total_tokens, int32_t Hq, int32_t Hkv, float scale,
+    float scale_log2)
+{
+    const int count = redo_list[0];
+    for (int item = blockIdx.x; item < count; item += gridDim.x) {
+        attn_il_tile<HD, CAUSAL, false>(q, k, v, out, lse, cu, hdr, tile_off, redo, redo_list, batch, total_tokens,
+                                        Hq, Hkv, scale, scale_log2, redo_list[1 + item]);
+        __syncthreads();   // the LDS rings are reused by the next tile
+    }
+}
+
 }  // namespace
 
-// workspace: header, tile_off[batch + 1], redo[(query tiles) * Hq] (one mark per workgroup)
+// workspace: header, tile_off[batch + 1], redo[(query tiles) * Hq] (one mark per workgroup),
+// redo_list[1 + marks] (count, then the marked workgroup numbers)
 static size_t attn_max_tiles(int32_t batch, int32_t total_tokens)
 {
     return (size_t)(total_tokens > 0 ? total_tokens : 0) / 128 + (size_t)(batch > 0 ? batch : 0);
@@ -879,8 +914,9 @@ static size_t attn_max_tiles(int32_t batch, int32_t total_tokens)
 
 size_t attn_ws_bytes(int32_t batch, int32_t total_tokens, int32_t Hq)
 {
+    const size_t marks = attn_max_tiles(batch, total_tokens) * (size_t)(Hq > 0 ? Hq : 0);
     return align_up(sizeof(AttnHdr), 256) + align_up(((size_t)(batch > 0 ? batch : 0) + 1) * 4, 256) +
-           align_up(attn_max_tiles(batch, total_tokens) * (size_t)(Hq > 0 ? Hq : 0) * 4, 256);
+           align_up(marks * 4, 256) + align_up((marks + 1) * 4, 256);
 }
 
 int launch_attn(const void *q, const void *k, const void *v, void *out, float *lse,
@@ -893,6 +929,7 @@ int launch_attn(const void *q, const void *k, const void *v, void *out, float *l
     AttnHdr *hdr = (AttnHdr *)ws;
     int32_t *tile_off = (int32_t *)((char *)ws + align_up(sizeof(AttnHdr), 256));
     int32_t *redo = (int32_t *)((char *)tile_off + align_up(((size_t)(batch > 0 ? batch : 0) + 1) * 4, 256));
+    int32_t *redo_list = (int32_t *)((char *)redo + align_up(attn_max_tiles(batch, total_tokens) * (size_t)Hq * 4, 256));
     // head_dim 128: the 8-wavefront kernel with LDS-DMA staging and MFMA / vector-ALU work
     // interleaved in one instruction stream, first with a fixed softmax reference, then (same
     // grid; returns at once unless a tile was marked) with a moving one.  head_dim 64: half the
@@ -908,7 +945,7 @@ int launch_attn(const void *q, const void *k, const void *v, void *out, float *l
     const int mb64 = (!il && !causal) ? 1 : 2;
     const int BM = il ? 256 : 128 * mb64;   // query rows per workgroup
     hipLaunchKernelGGL(attn_prep_kernel, dim3(1), dim3(kPrepThreads), 0, stream, cu_seqlens, batch,
-                       total_tokens, max_seqlen, BM, hdr, tile_off, dev_status, redo, Hq);
+                       total_tokens, max_seqlen, BM, hdr, tile_off, dev_status, redo, redo_list, Hq);
     // sum over sequences of ceil(L / BM) <= total / BM + batch, and <= batch * ceil(max_seqlen / BM)
     int64_t max_tiles = (int64_t)total_tokens / BM + batch;
     if (max_seqlen > 0) max_tiles = std::min<int64_t>(max_tiles, (int64_t)batch * ((max_seqlen + BM - 1) / BM));
@@ -920,12 +957,15 @@ int launch_attn(const void *q, const void *k, const void *v, void *out, float *l
 #define ORCH_ATTN_HEAD (const uint16_t *)q, (const uint16_t *)k, (const uint16_t *)v, (uint16_t *)out, lse, cu_seqlens, hdr, tile_off
 #define ORCH_ATTN_TAIL batch, total_tokens, Hq, Hkv, scale, sl2
         const dim3 g((unsigned)grid);
+        // the redo pass of the head_dim-128 kernel: one workgroup per CU walks the list (launching
+        // the full grid of 128 KB workgroups only to find it empty cost 130 us on C4)
+        const dim3 gr((unsigned)std::min<int64_t>(grid, 256));
         if (il && causal) {
-            hipLaunchKernelGGL((attn_fwd_il_kernel<128, true, true>), g, dim3(kILThreads), 0, stream, ORCH_ATTN_HEAD, redo, ORCH_ATTN_TAIL);
-            hipLaunchKernelGGL((attn_fwd_il_kernel<128, true, false>), g, dim3(kILThreads), 0, stream, ORCH_ATTN_HEAD, redo, ORCH_ATTN_TAIL);
+            hipLaunchKernelGGL((attn_fwd_il_kernel<128, true>), g, dim3(kILThreads), 0, stream, ORCH_ATTN_HEAD, redo, redo_list, ORCH_ATTN_TAIL);
+            hipLaunchKernelGGL((attn_fwd_il_redo_kernel<128, true>), gr, dim3(kILThreads), 0, stream, ORCH_ATTN_HEAD, redo, redo_list, ORCH_ATTN_TAIL);
         } else if (il) {
-            hipLaunchKernelGGL((attn_fwd_il_kernel<128, false, true>), g, dim3(kILThreads), 0, stream, ORCH_ATTN_HEAD, redo, ORCH_ATTN_TAIL);
-            hipLaunchKernelGGL((attn_fwd_il_kernel<128, false, false>), g, dim3(kILThreads), 0, stream, ORCH_ATTN_HEAD, redo, ORCH_ATTN_TAIL);
+            hipLaunchKernelGGL((attn_fwd_il_kernel<128, false>), g, dim3(kILThreads), 0, stream, ORCH_ATTN_HEAD, redo, redo_list, ORCH_ATTN_TAIL);
+            hipLaunchKernelGGL((attn_fwd_il_redo_kernel<128, false>), gr, dim3(kILThreads), 0, stream, ORCH_ATTN_HEAD, redo, redo_list, ORCH_ATTN_TAIL);
         } else if (mb64 == 1) {
             hipLaunchKernelGGL((attn_fwd_kernel<64, false, 1, true>), g, dim3(kThreads), 0, stream, ORCH_ATTN_HEAD, redo, ORCH_ATTN_TAIL);
             hipLaunchKernelGGL((attn_fwd_kernel<64, false, 1, false>), g, dim3(kThreads), 0, stream, ORCH_ATTN_HEAD, redo, ORCH_ATTN_TAIL);
