@@ -109,12 +109,15 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b)
 }
 
 
+// One (query tile, head) of the grid, named by the workgroup number `bid` it has in the
+// fixed-reference launch.  The moving-reference form is driven by the list of marked tiles.
 template <int HD, bool CAUSAL, int MB, bool FIXED>
-__global__ __launch_bounds__(kThreads, (MB * HD > 128 ? 1 : (MB * HD > 64 ? 2 : 4))) void attn_fwd_kernel(
+__device__ __forceinline__ void attn_tile(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
     uint16_t *__restrict__ out, float *__restrict__ lse, const int32_t *__restrict__ cu,
     const AttnHdr *__restrict__ hdr, const int32_t *__restrict__ tile_off, int32_t *__restrict__ redo,
-    int32_t batch, int32_t total_tokens, int32_t Hq, int32_t Hkv, float scale, float scale_log2)
+    int32_t *__restrict__ redo_list, int32_t batch, int32_t total_tokens, int32_t Hq, int32_t Hkv, float scale,
+    float scale_log2, const int bid)
 {
     constexpr int BM = 128 * MB;  // query rows per workgroup
     constexpr int NBLK = 4 * MB;  // 32-row blocks per workgroup
@@ -132,7 +135,6 @@ __global__ __launch_bounds__(kThreads, (MB * HD > 128 ? 1 : (MB * HD > 64 ? 2 : 
     // share an L2.
     int u, h;
     {
-        const int bid = blockIdx.x;
         if ((Hkv & 7) == 0) {
             const int kvh = (bid & 7) + 8 * ((bid >> 3) % (Hkv >> 3));
             const int rest = bid / Hkv;
@@ -144,7 +146,6 @@ __global__ __launch_bounds__(kThreads, (MB * HD > 128 ? 1 : (MB * HD > 64 ? 2 : 
         }
     }
     if (u >= total_tiles) return;
-    if (!FIXED && redo[u * Hq + h] == 0) return;   // the fixed-reference pass was good enough
     const int g_kv = h / group;
 
     // sequence t with tile_off[t] <= u < tile_off[t+1]
@@ -352,7 +353,35 @@ __global__ __launch_bounds__(kThreads, (MB * HD > 128 ? 1 : (MB * HD > 64 ? 2 : 
         }
     }
     // a sum that did not stay below 2^64 (or is not a number): the moving-reference pass redoes the tile
-    if (FIXED && __any(bad) && lane == 0) redo[u * Hq + h] = 1;
+    // (the first wavefront of the workgroup to find one appends the tile to the list)
+    if (FIXED && __any(bad) && lane == 0 && atomicExch(&redo[u * Hq + h], 1) == 0)
+        redo_list[1 + atomicAdd(&redo_list[0], 1)] = bid;
+}
+
+#define ORCH_ATTN_PARAMS                                                                                       \
+    const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,            \
+        uint16_t *__restrict__ out, float *__restrict__ lse, const int32_t *__restrict__ cu,                   \
+        const AttnHdr *__restrict__ hdr, const int32_t *__restrict__ tile_off, int32_t *__restrict__ redo,     \
+        int32_t *__restrict__ redo_list, int32_t batch, int32_t total_tokens, int32_t Hq, int32_t Hkv,         \
+        float scale, float scale_log2
+#define ORCH_ATTN_NAMES q, k, v, out, lse, cu, hdr, tile_off, redo, redo_list, batch, total_tokens, Hq, Hkv, scale, scale_log2
+
+// the launch every call makes: fixed reference, one workgroup per (query tile, head)
+template <int HD, bool CAUSAL, int MB>
+__global__ __launch_bounds__(kThreads, (MB * HD > 128 ? 1 : (MB * HD > 64 ? 2 : 4))) void attn_fwd_kernel(ORCH_ATTN_PARAMS)
+{
+    attn_tile<HD, CAUSAL, MB, true>(ORCH_ATTN_NAMES, (int)blockIdx.x);
+}
+
+// the moving-reference pass: a small grid walks the list of marked tiles (normally empty)
+template <int HD, bool CAUSAL, int MB>
+__global__ __launch_bounds__(kThreads, (MB * HD > 128 ? 1 : (MB * HD > 64 ? 2 : 4))) void attn_fwd_redo_kernel(ORCH_ATTN_PARAMS)
+{
+    const int count = redo_list[0];
+    for (int item = blockIdx.x; item < count; item += gridDim.x) {
+        attn_tile<HD, CAUSAL, MB, false>(ORCH_ATTN_NAMES, redo_list[1 + item]);
+        __syncthreads();   // the LDS stages are reused by the next tile
+    }
 }
 
 
@@ -875,33 +904,23 @@ __device__ __forceinline__ void attn_il_tile(
 
 // the launch every call makes: fixed reference, one workgroup per (query tile, head)
 template <int HD, bool CAUSAL>
-__global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(
-    const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
-    uint16_t *__restrict__ out, float *__restrict__ lse, const int32_t *__restrict__ cu,
-    const AttnHdr *__restrict__ hdr, const int32_t *__restrict__ tile_off, int32_t *__restrict__ redo,
-    int32_t *__restrict__ redo_list, int32_t batch, int32_t total_tokens, int32_t Hq, int32_t Hkv, float scale,
-    float scale_log2)
+__global__ __launch_bounds__(kILThreads) void attn_fwd_il_kernel(ORCH_ATTN_PARAMS)
 {
-    attn_il_tile<HD, CAUSAL, true>(q, k, v, out, lse, cu, hdr, tile_off, redo, redo_list, batch, total_tokens, Hq, Hkv,
-                                   scale, scale_log2, (int)blockIdx.x);
+    attn_il_tile<HD, CAUSAL, true>(ORCH_ATTN_NAMES, (int)blockIdx.x);
 }
 
 // the moving-reference pass: a small grid walks the list of marked tiles (normally empty)
 template <int HD, bool CAUSAL>
-__global__ __launch_bounds__(kILThreads) void attn_fwd_il_redo_kernel(
-    const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
-    uint16_t *__restrict__ out, float *__restrict__ lse, const int32_t *__restrict__ cu,
-    const AttnHdr *__restrict__ hdr, const int32_t *__restrict__ tile_off, int32_t *__restrict__ redo,
-    int32_t *__restrict__ redo_list, int32_t batch, int32_t total_tokens, int32_t Hq, int32_t Hkv, float scale,
-    float scale_log2)
+__global__ __launch_bounds__(kILThreads) void attn_fwd_il_redo_kernel(ORCH_ATTN_PARAMS)
 {
     const int count = redo_list[0];
     for (int item = blockIdx.x; item < count; item += gridDim.x) {
-        attn_il_tile<HD, CAUSAL, false>(q, k, v, out, lse, cu, hdr, tile_off, redo, redo_list, batch, total_tokens,
-                                        Hq, Hkv, scale, scale_log2, redo_list[1 + item]);
+        attn_il_tile<HD, CAUSAL, false>(ORCH_ATTN_NAMES, redo_list[1 + item]);
         __syncthreads();   // the LDS rings are reused by the next tile
     }
 }
+#undef ORCH_ATTN_PARAMS
+#undef ORCH_ATTN_NAMES
 
 }  // namespace
 
@@ -957,25 +976,20 @@ int launch_attn(const void *q, const void *k, const void *v, void *out, float *l
 #define ORCH_ATTN_HEAD (const uint16_t *)q, (const uint16_t *)k, (const uint16_t *)v, (uint16_t *)out, lse, cu_seqlens, hdr, tile_off
 #define ORCH_ATTN_TAIL batch, total_tokens, Hq, Hkv, scale, sl2
         const dim3 g((unsigned)grid);
-        // the redo pass of the head_dim-128 kernel: one workgroup per CU walks the list (launching
-        // the full grid of 128 KB workgroups only to find it empty cost 130 us on C4)
-        const dim3 gr((unsigned)std::min<int64_t>(grid, 256));
-        if (il && causal) {
-            hipLaunchKernelGGL((attn_fwd_il_kernel<128, true>), g, dim3(kILThreads), 0, stream, ORCH_ATTN_HEAD, redo, redo_list, ORCH_ATTN_TAIL);
-            hipLaunchKernelGGL((attn_fwd_il_redo_kernel<128, true>), gr, dim3(kILThreads), 0, stream, ORCH_ATTN_HEAD, redo, redo_list, ORCH_ATTN_TAIL);
-        } else if (il) {
-            hipLaunchKernelGGL((attn_fwd_il_kernel<128, false>), g, dim3(kILThreads), 0, stream, ORCH_ATTN_HEAD, redo, redo_list, ORCH_ATTN_TAIL);
-            hipLaunchKernelGGL((attn_fwd_il_redo_kernel<128, false>), gr, dim3(kILThreads), 0, stream, ORCH_ATTN_HEAD, redo, redo_list, ORCH_ATTN_TAIL);
-        } else if (mb64 == 1) {
-            hipLaunchKernelGGL((attn_fwd_kernel<64, false, 1, true>), g, dim3(kThreads), 0, stream, ORCH_ATTN_HEAD, redo, ORCH_ATTN_TAIL);
-            hipLaunchKernelGGL((attn_fwd_kernel<64, false, 1, false>), g, dim3(kThreads), 0, stream, ORCH_ATTN_HEAD, redo, ORCH_ATTN_TAIL);
-        } else if (causal) {
-            hipLaunchKernelGGL((attn_fwd_kernel<64, true, 2, true>), g, dim3(kThreads), 0, stream, ORCH_ATTN_HEAD, redo, ORCH_ATTN_TAIL);
-            hipLaunchKernelGGL((attn_fwd_kernel<64, true, 2, false>), g, dim3(kThreads), 0, stream, ORCH_ATTN_HEAD, redo, ORCH_ATTN_TAIL);
-        } else {
-            hipLaunchKernelGGL((attn_fwd_kernel<64, false, 2, true>), g, dim3(kThreads), 0, stream, ORCH_ATTN_HEAD, redo, ORCH_ATTN_TAIL);
-            hipLaunchKernelGGL((attn_fwd_kernel<64, false, 2, false>), g, dim3(kThreads), 0, stream, ORCH_ATTN_HEAD, redo, ORCH_ATTN_TAIL);
-        }
+        // the redo pass: a small grid walks the list of marked tiles (launching the full grid of
+        // 128 KB workgroups only to find nothing marked cost 130 us on C4)
+        const dim3 gr((unsigned)std::min<int64_t>(grid, il ? 256 : 1024));
+#define ORCH_ATTN_LAUNCH(FAST_, REDO_, THREADS_)                                                                      \
+    do {                                                                                                              \
+        hipLaunchKernelGGL((FAST_), g, dim3(THREADS_), 0, stream, ORCH_ATTN_HEAD, redo, redo_list, ORCH_ATTN_TAIL);  \
+        hipLaunchKernelGGL((REDO_), gr, dim3(THREADS_), 0, stream, ORCH_ATTN_HEAD, redo, redo_list, ORCH_ATTN_TAIL); \
+    } while (0)
+        if (il && causal) ORCH_ATTN_LAUNCH((attn_fwd_il_kernel<128, true>), (attn_fwd_il_redo_kernel<128, true>), kILThreads);
+        else if (il) ORCH_ATTN_LAUNCH((attn_fwd_il_kernel<128, false>), (attn_fwd_il_redo_kernel<128, false>), kILThreads);
+        else if (mb64 == 1) ORCH_ATTN_LAUNCH((attn_fwd_kernel<64, false, 1>), (attn_fwd_redo_kernel<64, false, 1>), kThreads);
+        else if (causal) ORCH_ATTN_LAUNCH((attn_fwd_kernel<64, true, 2>), (attn_fwd_redo_kernel<64, true, 2>), kThreads);
+        else ORCH_ATTN_LAUNCH((attn_fwd_kernel<64, false, 2>), (attn_fwd_redo_kernel<64, false, 2>), kThreads);
+#undef ORCH_ATTN_LAUNCH
 #undef ORCH_ATTN_HEAD
 #undef ORCH_ATTN_TAIL
     }
