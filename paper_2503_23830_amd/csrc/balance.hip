@@ -746,171 +746,277 @@ __global__ __launch_bounds__(kGreedyThreads) void greedy_lds_kernel(ORCH_GREEDY_
 // batches with a length sum less than (smallest length sum) + max(v, 1), the one with
 // the smallest sum of squared lengths (lowest index on ties).  Same workgroup shape as
 // greedy_reg_kernel: wave 0 chooses, the other waves turn choices into the layout.
-// A step is three 64-lane reductions: smallest sum, smallest squares inside the
-// window, lowest lane holding it.
+// The n steps depend on one another and one wavefront issues about one instruction per
+// 5 clocks, so a step costs what its instruction count says.  Two forms:
+//   * general (64-bit length sums): three 64-lane reductions per step: smallest sum,
+//     smallest squares inside the window, lowest lane holding it;
+//   * all lengths together < 2^32 and the longest < 2^30 (so the squares of all sequences
+//     together stay below 2^62): 32-bit sums; the smallest sum is kept from step to step
+//     and recomputed only when the instance that held it wins; the squares are compared by
+//     their leading 31 bits (one 32-bit reduction whose result lands in every lane, no
+//     scalar round trip), and only when two candidates agree in those bits does the step
+//     fall back to the exact 64-bit comparison.
 // ---------------------------------------------------------------------------
-template <int K>
-__global__ __launch_bounds__(kGreedyThreads) void greedy_tolerance_kernel(
-    const uint64_t *__restrict__ csorted, const int32_t *__restrict__ sorted,
-    const int32_t *__restrict__ lengths, int32_t n, int32_t D, uint64_t window, uint64_t a, uint64_t b,
-    int32_t *ipos, int32_t *inst, int32_t *rank, int32_t *start, uint64_t *loads, int32_t *seq_off,
-    int64_t *tok_off, int32_t *cu_seqlens, const int32_t *flags, int32_t *dev_status)
+
+// Smallest x over the wavefront (HALF: over lanes 0..31), delivered to every one of those
+// lanes: four butterfly stages inside the rows of 16 lanes (each one v_min_u32 with a DPP
+// operand; a VALU result needs two wait states before a DPP read of it), then the rows are
+// combined by the row / half swaps.
+template <bool HALF>
+__device__ __forceinline__ uint32_t lanes_min_u32(uint32_t x)
 {
-    __shared__ uint32_t s_cnt[64 * K];
-    __shared__ unsigned long long s_tok[64 * K];
-    __shared__ int s_progress, s_booked;
-    if (flags[1] != 0) return;  // the 32-bit kernel handles this call
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    for (int i = threadIdx.x; i < 64 * K; i += kGreedyThreads) { s_cnt[i] = 0; s_tok[i] = 0; }
-    if (threadIdx.x == 0) { s_progress = 0; s_booked = 0; }
-    __syncthreads();
-    if (wave >= 1) {
-        bookkeep_wave(ipos, sorted, lengths, n, D, lane, wave - 1, BookState{&s_progress, &s_booked, s_cnt, s_tok},
-                      inst, rank, start, dev_status);
-    } else {
-        // lane l owns instances l*K .. l*K+K-1; slots past D never enter a window
-        uint64_t sum[K], sq[K];
-#pragma unroll
-        for (int k = 0; k < K; ++k) { sum[k] = (lane * K + k < D) ? 0ull : ~0ull; sq[k] = 0; }
-        int err = 0;
-        ChoiceLog log{ipos, &s_progress, 0};
-        uint64_t c_cur = lane < n ? csorted[lane] : 0;
-        int chunk = 0;
-        for (int64_t t0 = 0; t0 < n; t0 += 64, ++chunk) {
-            const uint64_t c_nxt = (t0 + 64 + lane < n) ? csorted[t0 + 64 + lane] : 0;
-            const int m = (int)min((int64_t)64, (int64_t)n - t0);
-            for (int j = 0; j < m; ++j) {
-                const uint64_t c = readlane_u64(c_cur, j);  // the length
-                uint64_t lm = sum[0];
-#pragma unroll
-                for (int k = 1; k < K; ++k) lm = sum[k] < lm ? sum[k] : lm;
-                const uint64_t least = wave_min_u64(lm);
-                uint64_t lq = ~0ull;
-#pragma unroll
-                for (int k = 0; k < K; ++k) {
-                    const bool in = sum[k] != ~0ull && sum[k] - least < window;
-                    lq = (in && sq[k] < lq) ? sq[k] : lq;
-                }
-                const uint64_t q = wave_min_u64(lq);  // < 2^63: some real instance holds `least`
-                const uint64_t ball = __ballot(lq == q);
-                const int win = __ffsll((unsigned long long)ball) - 1;
-                int kk = K - 1;
-#pragma unroll
-                for (int k = K - 2; k >= 0; --k)
-                    kk = (sum[k] != ~0ull && sum[k] - least < window && sq[k] == q) ? k : kk;
-                if (lane == win) {
-#pragma unroll
-                    for (int k = 0; k < K; ++k)
-                        if (k == kk) {
-                            sum[k] += c;
-                            sq[k] += c * c;
-                            if (sq[k] >> 63) { err = 1; sq[k] = 0; }
-                        }
-                }
-                log_choice(log, lane, j, __builtin_amdgcn_readlane(lane * K + kk, win));
-            }
-            publish_chunk(log, t0, n, lane, chunk);
-            c_cur = c_nxt;
-        }
-        // Eq. 2, no-padding branch per instance: a * sum of squares + b * length sum
-#pragma unroll
-        for (int k = 0; k < K; ++k)
-            if (lane * K + k < D) {
-                const uint64_t t1 = a * sq[k], t2 = b * sum[k], load = t1 + t2;
-                if (__umul64hi(a, sq[k]) != 0 || __umul64hi(b, sum[k]) != 0 || load < t1 || (load >> 63)) err = 1;
-                loads[lane * K + k] = load;
-            }
-        if (__any(err) && lane == 0) dev_status[0] = (int32_t)ORCH_EDATA;
-    }
-    __syncthreads();
-    if (wave == 0) finish_layout(s_cnt, s_tok, D, seq_off, tok_off, cu_seqlens, dev_status);
+    uint32_t r, t;   // every lane of a quad has a partner, so the first stage may write a fresh register
+    if (HALF)
+        asm volatile(
+            "s_nop 1\n\t"
+            "v_min_u32_dpp %0, %2, %2 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\ts_nop 1\n\t"
+            "v_min_u32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\ts_nop 1\n\t"
+            "v_min_u32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\ts_nop 1\n\t"
+            "v_min_u32_dpp %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf\n\t"
+            "v_mov_b32_e32 %1, %0\n\ts_nop 1\n\t"
+            "v_permlane16_swap_b32_e32 %0, %1\n\t"   // rows 0|1 (and 2|3)
+            "v_min_u32_e32 %0, %0, %1"
+            : "=&v"(r), "=&v"(t)
+            : "v"(x));
+    else
+        asm volatile(
+            "s_nop 1\n\t"
+            "v_min_u32_dpp %0, %2, %2 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\ts_nop 1\n\t"
+            "v_min_u32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\ts_nop 1\n\t"
+            "v_min_u32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\ts_nop 1\n\t"
+            "v_min_u32_dpp %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf\n\t"
+            "v_mov_b32_e32 %1, %0\n\ts_nop 1\n\t"
+            "v_permlane16_swap_b32_e32 %0, %1\n\t"   // rows 0|1 and 2|3
+            "v_min_u32_e32 %0, %0, %1\n\t"
+            "v_mov_b32_e32 %1, %0\n\ts_nop 1\n\t"
+            "v_permlane32_swap_b32_e32 %0, %1\n\t"   // lanes 0..31 | 32..63
+            "v_min_u32_e32 %0, %0, %1"
+            : "=&v"(r), "=&v"(t)
+            : "v"(x));
+    return r;
 }
 
-// The same algorithm when all lengths together stay below 2^32 tokens (flags[1]): length sums
-// are 32-bit, and the smallest sum of squares is found in two 32-bit reductions (high words,
-// then low words among the lanes that hold the smallest high word), so a step is three
-// single-instruction-per-stage DPP reductions instead of two 64-bit ones.
+#define ORCH_TOL_PARAMS                                                                                           \
+    const uint64_t *__restrict__ csorted, const int32_t *__restrict__ sorted, const int32_t *__restrict__ lengths, \
+        int32_t n, int32_t D, uint64_t window, uint64_t a, uint64_t b, int32_t *ipos, int32_t *inst,              \
+        int32_t *rank, int32_t *start, uint64_t *loads, int32_t *seq_off, int64_t *tok_off,                       \
+        int32_t *cu_seqlens, const int32_t *flags, int32_t *dev_status
+
+// the choosing wavefront, general form
 template <int K>
-__global__ __launch_bounds__(kGreedyThreads) void greedy_tolerance32_kernel(
-    const uint64_t *__restrict__ csorted, const int32_t *__restrict__ sorted,
-    const int32_t *__restrict__ lengths, int32_t n, int32_t D, uint64_t window, uint64_t a, uint64_t b,
-    int32_t *ipos, int32_t *inst, int32_t *rank, int32_t *start, uint64_t *loads, int32_t *seq_off,
-    int64_t *tok_off, int32_t *cu_seqlens, const int32_t *flags, int32_t *dev_status)
+__device__ __forceinline__ void tolerance_choose64(const uint64_t *__restrict__ csorted, int32_t n, int32_t D,
+                                                   uint64_t window, uint64_t a, uint64_t b, int32_t *ipos,
+                                                   uint64_t *loads, int32_t *dev_status, int *progress, int lane)
 {
-    __shared__ uint32_t s_cnt[64 * K];
-    __shared__ unsigned long long s_tok[64 * K];
-    __shared__ int s_progress, s_booked;
-    if (flags[1] == 0) return;  // the 64-bit kernel handles this call
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    for (int i = threadIdx.x; i < 64 * K; i += kGreedyThreads) { s_cnt[i] = 0; s_tok[i] = 0; }
-    if (threadIdx.x == 0) { s_progress = 0; s_booked = 0; }
-    __syncthreads();
-    if (wave >= 1) {
-        bookkeep_wave(ipos, sorted, lengths, n, D, lane, wave - 1, BookState{&s_progress, &s_booked, s_cnt, s_tok},
-                      inst, rank, start, dev_status);
-    } else {
-        const uint32_t win32 = window > 0xffffffffull ? 0xffffffffu : (uint32_t)window;
-        uint32_t sum[K];  // slots past D hold 2^32 - 1 and are masked out explicitly
-        uint64_t sq[K];
-        bool real[K];
+    // lane l owns instances l*K .. l*K+K-1; slots past D never enter a window
+    uint64_t sum[K], sq[K];
 #pragma unroll
-        for (int k = 0; k < K; ++k) { real[k] = lane * K + k < D; sum[k] = real[k] ? 0u : 0xffffffffu; sq[k] = 0; }
-        int err = 0;
-        ChoiceLog log{ipos, &s_progress, 0};
-        uint32_t c_cur = lane < n ? (uint32_t)csorted[lane] : 0;
-        int chunk = 0;
-        for (int64_t t0 = 0; t0 < n; t0 += 64, ++chunk) {
-            const uint32_t c_nxt = (t0 + 64 + lane < n) ? (uint32_t)csorted[t0 + 64 + lane] : 0;
-            const int m = (int)min((int64_t)64, (int64_t)n - t0);
-            for (int j = 0; j < m; ++j) {
-                const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)c_cur, j);  // the length
+    for (int k = 0; k < K; ++k) { sum[k] = (lane * K + k < D) ? 0ull : ~0ull; sq[k] = 0; }
+    int err = 0;
+    ChoiceLog log{ipos, progress, 0};
+    uint64_t c_cur = lane < n ? csorted[lane] : 0;
+    int chunk = 0;
+    for (int64_t t0 = 0; t0 < n; t0 += 64, ++chunk) {
+        const uint64_t c_nxt = (t0 + 64 + lane < n) ? csorted[t0 + 64 + lane] : 0;
+        const int m = (int)min((int64_t)64, (int64_t)n - t0);
+        for (int j = 0; j < m; ++j) {
+            const uint64_t c = readlane_u64(c_cur, j);  // the length
+            uint64_t lm = sum[0];
+#pragma unroll
+            for (int k = 1; k < K; ++k) lm = sum[k] < lm ? sum[k] : lm;
+            const uint64_t least = wave_min_u64(lm);
+            uint64_t lq = ~0ull;
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                const bool in = sum[k] != ~0ull && sum[k] - least < window;
+                lq = (in && sq[k] < lq) ? sq[k] : lq;
+            }
+            const uint64_t q = wave_min_u64(lq);  // < 2^63: some real instance holds `least`
+            const uint64_t ball = __ballot(lq == q);
+            const int win = __ffsll((unsigned long long)ball) - 1;
+            int kk = K - 1;
+#pragma unroll
+            for (int k = K - 2; k >= 0; --k)
+                kk = (sum[k] != ~0ull && sum[k] - least < window && sq[k] == q) ? k : kk;
+            if (lane == win) {
+#pragma unroll
+                for (int k = 0; k < K; ++k)
+                    if (k == kk) {
+                        sum[k] += c;
+                        sq[k] += c * c;
+                        if (sq[k] >> 63) { err = 1; sq[k] = 0; }
+                    }
+            }
+            log_choice(log, lane, j, __builtin_amdgcn_readlane(lane * K + kk, win));
+        }
+        publish_chunk(log, t0, n, lane, chunk);
+        c_cur = c_nxt;
+    }
+    // Eq. 2, no-padding branch per instance: a * sum of squares + b * length sum
+#pragma unroll
+    for (int k = 0; k < K; ++k)
+        if (lane * K + k < D) {
+            const uint64_t t1 = a * sq[k], t2 = b * sum[k], load = t1 + t2;
+            if (__umul64hi(a, sq[k]) != 0 || __umul64hi(b, sum[k]) != 0 || load < t1 || (load >> 63)) err = 1;
+            loads[lane * K + k] = load;
+        }
+    if (__any(err) && lane == 0) dev_status[0] = (int32_t)ORCH_EDATA;
+}
+
+// the choosing wavefront when all lengths together are < 2^32 and their squares together are
+// sq_total < 2^62.  HALF: only lanes 0..31 call it (and are the active ones throughout).
+template <int K, bool HALF>
+__device__ __forceinline__ void tolerance_choose32(const uint64_t *__restrict__ csorted, int32_t n, int32_t D,
+                                                   uint64_t window, uint64_t a, uint64_t b, uint64_t sq_total,
+                                                   int32_t *ipos, uint64_t *loads, int32_t *dev_status,
+                                                   int *progress, int lane)
+{
+    static_assert(!HALF || K == 1, "32 lanes hold one instance each");
+    constexpr int W = HALF ? 32 : 64;   // lanes at work = steps per published chunk
+    const uint32_t win32 = window > 0xffffffffull ? 0xffffffffu : (uint32_t)window;
+    // leading bits of a sum of squares: (sq >> shift) < 2^31 for every sq <= sq_total
+    const int bits = 64 - __clzll((unsigned long long)(sq_total | 1));
+    const uint32_t shift = bits > 31 ? (uint32_t)(bits - 31) : 0u;   // <= 31
+    // slots past D: every bit of the length sum, the squares and their leading bits set, so they
+    // never hold the smallest sum and never equal the smallest leading bits inside the window
+    uint32_t sum[K], top[K];
+    uint64_t sq[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const bool real = lane * K + k < D;
+        sum[k] = real ? 0u : 0xffffffffu;
+        top[k] = real ? 0u : 0xffffffffu;
+        sq[k] = real ? 0ull : ~0ull;
+    }
+    uint32_t least = 0;   // smallest length sum, in every lane
+    const uint64_t all_lanes = __builtin_amdgcn_read_exec();
+    ChoiceLog log{ipos, progress, 0};
+    uint32_t c_cur = lane < n ? (uint32_t)csorted[lane] : 0;
+    for (int64_t t0 = 0; t0 < n; t0 += W) {
+        const uint32_t c_nxt = (t0 + W + lane < n) ? (uint32_t)csorted[t0 + W + lane] : 0;
+        const int m = (int)min((int64_t)W, (int64_t)n - t0);
+        for (int j = 0; j < m; ++j) {
+            const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)c_cur, j);  // the length
+            // leading bits of this lane's smallest squares inside the window (2^32 - 1: none inside)
+            uint32_t kx[K];
+            uint32_t key = 0xffffffffu;
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                kx[k] = (sum[k] - least < win32) ? top[k] : 0xffffffffu;
+                key = kx[k] < key ? kx[k] : key;
+            }
+            const uint32_t kmin = lanes_min_u32<HALF>(key);   // < 2^31: the holder of `least` is inside
+            uint64_t ball = __builtin_amdgcn_ballot_w64(key == kmin);
+            bool unique = __builtin_popcountll(ball) == 1;
+            if (K > 1 && unique) {   // one lane; one slot of it?
+                int hits = 0;
+#pragma unroll
+                for (int k = 0; k < K; ++k) hits += kx[k] == kmin ? 1 : 0;
+                unique = __builtin_amdgcn_ballot_w64(hits > 1) == 0;
+            }
+            int win = __builtin_ctzll(ball), kk = 0;
+            if (K > 1) {
+#pragma unroll
+                for (int k = K - 1; k >= 0; --k) kk = kx[k] == kmin ? k : kk;
+            }
+            if (__builtin_expect(!unique, 0)) {
+                // several candidates agree in the leading bits: the exact comparison among them,
+                // lowest instance on ties (high words, then low words among the lanes that hold the
+                // smallest high word)
+                uint64_t lq = ~0ull;
+#pragma unroll
+                for (int k = 0; k < K; ++k) lq = (kx[k] == kmin && sq[k] < lq) ? sq[k] : lq;
+                const uint32_t lh = (uint32_t)(lq >> 32), ll = (uint32_t)lq;
+                const uint32_t qh = lanes_min_u32<HALF>(lh);
+                const uint32_t ql = lanes_min_u32<HALF>(lh == qh ? ll : 0xffffffffu);
+                ball = __builtin_amdgcn_ballot_w64(lh == qh && ll == ql);
+                win = __builtin_ctzll(ball);
+                ball = 1ull << win;
+                if (K > 1) {
+#pragma unroll
+                    for (int k = K - 1; k >= 0; --k) kk = (kx[k] == kmin && sq[k] == lq) ? k : kk;
+                }
+            }
+            if (K > 1) kk = __builtin_amdgcn_readlane(kk, win);
+            // the winner's update; did it hold the smallest sum?  exec = the winner's lane for three
+            // instructions (restored before the statement ends); the slot is uniform
+            uint64_t was_least = 0;
+#pragma unroll
+            for (int k = 0; k < K; ++k)
+                if (K == 1 || kk == k) {
+                    uint64_t carry;
+                    asm volatile(
+                        "s_mov_b64 exec, %[m]\n\t"
+                        "v_cmp_eq_u32_e64 %[wl], %[sum], %[least]\n\t"
+                        "v_add_u32_e32 %[sum], %[c], %[sum]\n\t"
+                        "v_mad_u64_u32 %[sq], %[cy], %[c], %[c], %[sq]\n\t"
+                        "s_mov_b64 exec, %[all]"
+                        : [sum] "+v"(sum[k]), [sq] "+v"(sq[k]), [wl] "=&s"(was_least), [cy] "=&s"(carry)
+                        : [m] "s"(ball), [c] "s"(c), [least] "v"(least), [all] "s"(all_lanes));
+                    top[k] = __builtin_amdgcn_alignbit((uint32_t)(sq[k] >> 32), (uint32_t)sq[k], shift);
+                }
+            if (__builtin_expect(was_least != 0, 0)) {
                 uint32_t lm = sum[0];
 #pragma unroll
                 for (int k = 1; k < K; ++k) lm = sum[k] < lm ? sum[k] : lm;
-                const uint32_t least = wave_min_u32(lm);
-                uint64_t lq = ~0ull;  // this lane's smallest squares inside the window
-#pragma unroll
-                for (int k = 0; k < K; ++k) {
-                    const bool in = real[k] && sum[k] - least < win32;
-                    lq = (in && sq[k] < lq) ? sq[k] : lq;
-                }
-                const uint32_t lh = (uint32_t)(lq >> 32), ll = (uint32_t)lq;
-                const uint32_t qh = wave_min_u32(lh);  // < 2^31: some real instance holds `least`
-                const uint32_t ql = wave_min_u32(lh == qh ? ll : 0xffffffffu);
-                const uint64_t ball = __ballot(lh == qh && ll == ql);
-                const int win = __ffsll((unsigned long long)ball) - 1;
-                int kk = K - 1;
-#pragma unroll
-                for (int k = K - 2; k >= 0; --k)
-                    kk = (real[k] && sum[k] - least < win32 && sq[k] == lq) ? k : kk;
-                if (lane == win) {
-#pragma unroll
-                    for (int k = 0; k < K; ++k)
-                        if (k == kk) {
-                            sum[k] += c;
-                            sq[k] += (uint64_t)c * c;
-                            if (sq[k] >> 63) { err = 1; sq[k] = 0; }
-                        }
-                }
-                log_choice(log, lane, j, __builtin_amdgcn_readlane(lane * K + kk, win));
+                least = lanes_min_u32<HALF>(lm);
             }
-            publish_chunk(log, t0, n, lane, chunk);
-            c_cur = c_nxt;
+            log_choice(log, lane, j, win * K + kk);
         }
+        if (t0 + lane < n) ipos[t0 + lane] = log.rec;
+        publish_upto(progress, min((int64_t)n, t0 + W));
+        c_cur = c_nxt;
+    }
+    // Eq. 2, no-padding branch per instance (the squares cannot pass 2^62 here)
+    int err = 0;
 #pragma unroll
-        for (int k = 0; k < K; ++k)
-            if (real[k]) {
-                const uint64_t t1 = a * sq[k], t2 = b * (uint64_t)sum[k], load = t1 + t2;
-                if (__umul64hi(a, sq[k]) != 0 || __umul64hi(b, (uint64_t)sum[k]) != 0 || load < t1 || (load >> 63)) err = 1;
-                loads[lane * K + k] = load;
-            }
-        if (__any(err) && lane == 0) dev_status[0] = (int32_t)ORCH_EDATA;
+    for (int k = 0; k < K; ++k)
+        if (lane * K + k < D) {
+            const uint64_t t1 = a * sq[k], t2 = b * (uint64_t)sum[k], load = t1 + t2;
+            if (__umul64hi(a, sq[k]) != 0 || __umul64hi(b, (uint64_t)sum[k]) != 0 || load < t1 || (load >> 63)) err = 1;
+            loads[lane * K + k] = load;
+        }
+    if (__any(err) && lane == 0) dev_status[0] = (int32_t)ORCH_EDATA;
+}
+
+// HALF: K == 1 and D <= 32 (the instances sit in lanes 0..31)
+template <int K, bool HALF>
+__global__ __launch_bounds__(kGreedyThreads) void greedy_tolerance_kernel(ORCH_TOL_PARAMS)
+{
+    __shared__ uint32_t s_cnt[64 * K];
+    __shared__ unsigned long long s_tok[64 * K];
+    __shared__ unsigned long long s_sq[kGreedyThreads / 64];
+    __shared__ int s_progress, s_booked;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    for (int i = threadIdx.x; i < 64 * K; i += kGreedyThreads) { s_cnt[i] = 0; s_tok[i] = 0; }
+    if (threadIdx.x == 0) { s_progress = 0; s_booked = 0; }
+    // flags[1]: all lengths together < 2^32.  The keys are the lengths, longest first: with the
+    // longest < 2^30 the squares of all sequences together are < 2^62 and summed here.
+    const bool narrow = flags[1] != 0 && n > 0 && csorted[0] < (1ull << 30);
+    if (narrow) {
+        uint64_t part = 0;
+        for (int64_t i = threadIdx.x; i < n; i += kGreedyThreads) { const uint64_t c = csorted[i]; part += c * c; }
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) part += __shfl_xor(part, o);
+        if (lane == 0) s_sq[wave] = part;
+    }
+    __syncthreads();
+    if (wave >= 1) {
+        bookkeep_wave(ipos, sorted, lengths, n, D, lane, wave - 1, BookState{&s_progress, &s_booked, s_cnt, s_tok},
+                      inst, rank, start, dev_status);
+    } else if (narrow) {
+        uint64_t sq_total = 0;
+        for (int w = 0; w < kGreedyThreads / 64; ++w) sq_total += s_sq[w];
+        if (!HALF || lane < 32)
+            tolerance_choose32<K, HALF>(csorted, n, D, window, a, b, sq_total, ipos, loads, dev_status, &s_progress, lane);
+    } else {
+        tolerance_choose64<K>(csorted, n, D, window, a, b, ipos, loads, dev_status, &s_progress, lane);
     }
     __syncthreads();
     if (wave == 0) finish_layout(s_cnt, s_tok, D, seq_off, tok_off, cu_seqlens, dev_status);
 }
+#undef ORCH_TOL_PARAMS
 
 // ---------------------------------------------------------------------------
 // Algorithm 2 (Sec. 5.1, "Post-Balancing Algorithm with Paddings")
@@ -1243,24 +1349,18 @@ int launch_balance_tolerance(const int32_t *lengths, int32_t n, int32_t D, uint6
                        (uint64_t)1, 0, w.csorted, w.keyA, w.keyB, w.idxA, w.idxB, w.sorted, w.flags,
                        out.dev_status);
     const uint64_t window = v > 1 ? v : 1;
-    // both forms are enqueued; the flag written by the sort kernel decides on the device which
-    // of them does the work (the other returns at once)
-#define ORCH_TOL(K_)                                                                                        \
-    do {                                                                                                    \
-        hipLaunchKernelGGL(greedy_tolerance32_kernel<K_>, dim3(1), dim3(kGreedyThreads), 0, stream,         \
-                           w.csorted, w.sorted, lengths, n, D, window, phase.a, phase.b, w.ipos, out.inst, \
-                           w.rank, w.start, out.loads, out.seq_off, out.tok_off, out.cu_seqlens, w.flags,  \
-                           out.dev_status);                                                                 \
-        hipLaunchKernelGGL(greedy_tolerance_kernel<K_>, dim3(1), dim3(kGreedyThreads), 0, stream,           \
-                           w.csorted, w.sorted, lengths, n, D, window, phase.a, phase.b, w.ipos, out.inst, \
-                           w.rank, w.start, out.loads, out.seq_off, out.tok_off, out.cu_seqlens, w.flags,  \
-                           out.dev_status);                                                                 \
-    } while (0)
-    if (D <= 64) ORCH_TOL(1);
-    else if (D <= 128) ORCH_TOL(2);
-    else if (D <= 256) ORCH_TOL(4);
-    else if (D <= 512) ORCH_TOL(8);
-    else if (D <= 1024) ORCH_TOL(16);
+    // one launch; the flag written by the sort kernel decides on the device which form runs
+#define ORCH_TOL(K_, HALF_)                                                                                 \
+    hipLaunchKernelGGL((greedy_tolerance_kernel<K_, HALF_>), dim3(1), dim3(kGreedyThreads), 0, stream,      \
+                       w.csorted, w.sorted, lengths, n, D, window, phase.a, phase.b, w.ipos, out.inst,     \
+                       w.rank, w.start, out.loads, out.seq_off, out.tok_off, out.cu_seqlens, w.flags,      \
+                       out.dev_status)
+    if (D <= 32) ORCH_TOL(1, true);
+    else if (D <= 64) ORCH_TOL(1, false);
+    else if (D <= 128) ORCH_TOL(2, false);
+    else if (D <= 256) ORCH_TOL(4, false);
+    else if (D <= 512) ORCH_TOL(8, false);
+    else if (D <= 1024) ORCH_TOL(16, false);
     else ORCH_FAIL(ORCH_EUNSUPPORTED, "orch_balance_tolerance: D = %d > 1024", D);
 #undef ORCH_TOL
     if (n > 0)

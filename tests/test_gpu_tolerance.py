@@ -47,6 +47,14 @@ def test_edge_cases(gpu_device):
     for D in (63, 64, 65, 128, 129, 256, 257, 512, 513, 1024):  # every register-count variant, ragged
         check(wl.random_lengths(D, 2500, 1, 300), D, 150, 1, 1, dev)
     check(np.array([2**31 - 1, 2**30, 5], np.int32), 3, 1 << 20, 1, 1, dev)
+    # just inside the 32-bit form (longest < 2^30, all together < 2^32): squares near 2^61, the
+    # comparison by leading bits drops 30 of them, near-equal squares go to the exact comparison
+    near = np.array([2**29 + 3, 2**29 + 1, 2**29, 2**29, 2**29 - 1, 2**29 - 5, 2**29 - 9, 77, 5, 5, 1], np.int32)
+    for D, v in ((2, 1000), (3, 0), (3, 1 << 31), (5, 1 << 29), (40, 7), (100, 1 << 33)):
+        check(near, D, v, 0, 1, dev)
+    # many equal lengths: equal squares all the time (the exact comparison decides nearly every step)
+    for D in (4, 31, 32, 33, 64, 200):
+        check(np.repeat(np.array([900, 411, 411, 30, 7], np.int32), 120), D, 500, 1, 1, dev)
     # more than 2^32 tokens in total: the 64-bit form of the kernel
     big = np.concatenate([np.full(5, 2**30, np.int32), wl.random_lengths(9, 300, 1, 5000)])
     for D, v in ((5, 3000), (70, 1 << 29), (300, 0)):
