@@ -19,8 +19,8 @@
  *                         (Sec. 6, subsequence assembly).
  *   orch_comm_volume      Sec. 5.2.2: the communication-volume matrix V of a rearrangement.
  *   orch_varlen_attn_bwd  its backward (dq, dk, dv from dout, out and lse).
- *   orch_varlen_attn_fwd  the padding-free ("batched along the sequence
- *                         length") attention each instance then runs; its
+ *   orch_varlen_attn_fwd  the attention each instance then runs on its sequences,
+ *                         concatenated without padding (Sec. 7); its
  *                         quadratic term is beta*sum(l^2) in Eq. 2.
  *
  * Conventions
@@ -110,7 +110,7 @@ int orch_balance_static(const int32_t *lengths, int32_t n, int32_t D, orch_phase
 /* Largest n orch_balance_static accepts. */
 int32_t orch_balance_static_max_n(void);
 
-/* Sec. 5.1, Algorithm 2 ("Post-Balancing Algorithm with Paddings"): for phases that batch
+/* Sec. 5.1, Algorithm 2: the balancing for phases that batch
  * with paddings (the auditory encoder, Sec. 7), where a batch of cnt sequences costs
  * cnt * (its longest sequence) rows (Eq. 1, padding branch).  Sorts ascending by length
  * (ties: ascending index), finds the smallest bound b for which the greedy cut of that list
@@ -132,7 +132,7 @@ int32_t orch_balance_static_max_n(void);
 int orch_balance_padded(const int32_t *lengths, int32_t n, int32_t D, orch_phase phase,
                         orch_assignment out, uint64_t *bound, void *ws, size_t ws_bytes, void *stream);
 
-/* Appendix A, "Post-Balancing Algorithm 3rd": Algorithm 1 for models where the quadratic
+/* Appendix A, the third balancing algorithm: Algorithm 1 for models where the quadratic
  * term is not negligible (objective max_i L_i + lambda * sum_j l_ij^2).  Sequences are taken
  * longest first (ties: ascending index); each goes to the batch that the listing's comparator
  * CMP puts first.  CMP is not a strict weak order, so top() is fixed here by two passes:

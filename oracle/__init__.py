@@ -119,7 +119,7 @@ def sort_asc(lengths) -> np.ndarray:
 
 
 def least_batches(lengths, sorted_idx, bound: int):
-    """GetLeastBatches(bound) of Algorithm 2: (number of batches, batch of every sorted position)."""
+    """The batch-counting helper of Algorithm 2 at a bound: (number of batches, batch of every sorted position)."""
     L, srt = _i32(lengths), _i32(sorted_idx)
     batch_of = np.empty(len(L), np.int32)
     cnt = lib().orc_least_batches(_p(L), _p(srt), C.c_int32(len(L)), C.c_uint64(bound), _p(batch_of))

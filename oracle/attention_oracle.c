@@ -3,8 +3,8 @@
  * INFRASTRUCTURE: only tests, the smoke check and the bench's cpu_baseline leg
  * may call it; it shares no code with the HIP library and is never a fallback.
  *
- * The paper batches sequences "along the sequence length, with no padding"
- * and runs a flash-attention operator on them (Sec. 7, input preprocessing;
+ * The paper concatenates the sequences of a batch along the token axis without
+ * padding and runs a flash-attention operator on them (Sec. 7, input preprocessing;
  * Appendix A); the quantity that operator computes is the Transformer's
  * scaled-dot-product attention whose quadratic term is beta*sum(l^2) in Eq. 2.
  * This file is that definition written out, in fp64, on bf16-rounded inputs:

@@ -6,7 +6,7 @@
  *   - per-sequence cost from the no-padding branch of Eq. 2: a batch's cost
  *     alpha*sum(l) + beta*sum(l^2) is additive over sequences, so sequence s
  *     carries c_s = a*l_s^2 + b*l_s with a = beta, b = alpha (exact, u64);
- *   - Algorithm 1 ("Post-Balancing without paddings") with that cost as the
+ *   - Algorithm 1 (Sec. 5.1, batching without paddings) with that cost as the
  *     key: sort descending, then give every sequence in turn to the batch whose
  *     summed key is smallest (longest-processing-time-first greedy).  With
  *     a = 0, b = 1 this is Algorithm 1 literally;
@@ -341,7 +341,7 @@ int orc_pack_composed_pieces(const void *enc_rows, void *packed, const int32_t *
 }
 
 /* ---------------------------------------------------------------------------
- * Algorithm 2, "Post-Balancing Algorithm with Paddings" (Sec. 5.1).  A padded
+ * Algorithm 2 (Sec. 5.1), the balancing for phases that batch with paddings.  A padded
  * batch of k sequences costs k * (its longest sequence) rows (Eq. 1, padding
  * branch); the algorithm sorts ascending, and for an upper bound b on that
  * batch length cuts the sorted list greedily into the fewest batches, then
@@ -375,7 +375,7 @@ int orc_sort_asc(const int32_t *lengths, int32_t n, int32_t *sorted)
     return 0;
 }
 
-/* GetLeastBatches(b) of Algorithm 2: walk the ascending list; the current batch
+/* The batch-counting helper of Algorithm 2 (Sec. 5.1) for a bound b: walk the ascending list; the current batch
  * is closed (a new, empty one opened) when one more sequence would push its
  * padded length (count + 1) * length above b; the sequence is then put into the
  * last batch whatever its length.  batch_of[t] (may be NULL) receives the batch
@@ -384,7 +384,7 @@ int orc_sort_asc(const int32_t *lengths, int32_t n, int32_t *sorted)
 int64_t orc_least_batches(const int32_t *lengths, const int32_t *sorted, int32_t n, uint64_t bound,
                           int32_t *batch_of)
 {
-    int64_t batches = 1;  /* ret_batches = {{}} */
+    int64_t batches = 1;  /* the result starts as one empty batch */
     uint64_t in_last = 0;
     for (int32_t t = 0; t < n; ++t) {
         uint64_t len = (uint64_t)(uint32_t)lengths[sorted[t]];
@@ -405,9 +405,9 @@ int64_t orc_least_batches(const int32_t *lengths, const int32_t *sorted, int32_t
  *     takes the first (shortest) element, which need not be feasible, while with
  *     the longest one every batch can hold floor(n/d) + 1 >= ceil(n/d) sequences,
  *     so at most d batches are needed and the search has an answer;
- *   - loop body: mid = floor((left + right) / 2); if GetLeastBatches(mid) has at
+ *   - loop body: mid = floor((left + right) / 2); if the helper at bound mid needs at
  *     most d batches then right = mid, else left = mid + 1;
- *   - the batches returned are GetLeastBatches at the final bound (the last mid
+ *   - the batches returned are the helper's at the final bound (the last mid
  *     tried may have been an infeasible one);
  *   - the k-th batch is instance k; when fewer than d batches result the last
  *     instances stay empty;
@@ -472,7 +472,7 @@ done:
 }
 
 /* ---------------------------------------------------------------------------
- * "Post-Balancing Algorithm 3rd" (Appendix A): Algorithm 1 with the priority
+ * Appendix A, the third balancing algorithm: Algorithm 1 with the priority
  * queue ordered by CMP(a, b): when two batches' length sums differ by less than
  * the tolerance interval v, the one with the smaller sum of squared lengths comes
  * first, otherwise the one with the smaller length sum.  It serves the objective

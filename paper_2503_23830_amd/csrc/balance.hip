@@ -1,6 +1,6 @@
 // orch_balance: Eq. 2's per-sequence cost, Algorithm 1 (sort descending, then
 // longest-first greedy onto the least-loaded instance) and the packed layout.
-// (OrchMLLM Sec. 5.1; layout per Sec. 7 "batched along the sequence length".)
+// (Sec. 5.1; the layout is Sec. 7's: sequences concatenated along the token axis, unpadded.)
 //
 // orch_balance_padded: Algorithm 2 (the same sort, ascending, then the bound search
 // and the padded layout in one kernel; see padded_split_kernel).
@@ -1019,10 +1019,10 @@ __global__ __launch_bounds__(kGreedyThreads) void greedy_tolerance_kernel(ORCH_T
 #undef ORCH_TOL_PARAMS
 
 // ---------------------------------------------------------------------------
-// Algorithm 2 (Sec. 5.1, "Post-Balancing Algorithm with Paddings")
+// Algorithm 2 (Sec. 5.1, balancing for batches with paddings)
 // ---------------------------------------------------------------------------
 // The sequences arrive sorted ascending by length.  For a bound b on the padded
-// batch length (count * longest), GetLeastBatches(b) cuts the list greedily: a batch
+// batch length (count * longest), the algorithm's batch-counting helper cuts the list greedily: a batch
 // that starts at position p always takes p and then extends while
 // (q - p + 1) * len[q] <= b.  That product never decreases with q, so the end of a
 // batch is found by bisection instead of a walk, and one evaluation of the bound

@@ -34,7 +34,7 @@ def _cases():
 
 
 def batches_py(sorted_len, b):
-    """GetLeastBatches with Python lists, as the listing states it."""
+    """Algorithm 2's batch-counting helper with Python lists, as the listing states it."""
     ret = [[]]
     for l in sorted_len:
         if (len(ret[-1]) + 1) * l > b:
