@@ -309,15 +309,17 @@ __device__ __forceinline__ void attn_tile(
     };
 
     TileSrc src{k, v, row0, L, 0, Hkv, g_kv};
-    ps.begin(src, 0);
-    for (int it = 0; it < ntile_k; ++it) {
+    ps.begin_at(src, 0);
+    // tile `it` lives in stage it % 2; the loop is unrolled by the two stages so that the stage
+    // offset of every fragment read is an immediate
+    auto tile_step = [&](auto stage_tag, int it) {
+        constexpr int ST = decltype(stage_tag)::value;
         const int n0 = it * BN;
         ps.publish();
         if (it + 1 < ntile_k) {
             src.m0 = n0 + BN;
-            ps.begin(src, it + 1);
+            ps.begin_at(src, ST ^ 1);
         }
-
         // row blocks entirely above the diagonal have nothing to do in this tile;
         // blk[] ascends with mb, so the active ones are a suffix
         int first = 0;
@@ -326,8 +328,12 @@ __device__ __forceinline__ void attn_tile(
             for (int mb = 0; mb < MB; ++mb)
                 if (n0 > q0 + 32 * blk[mb] + 31) first = mb + 1;
         }
-        if (first == 0) compute_tile(std::integral_constant<int, 0>{}, n0, ps.x_base(it), ps.y_base(it));
-        else if (MB > 1 && first == 1) compute_tile(std::integral_constant<int, (MB > 1 ? 1 : 0)>{}, n0, ps.x_base(it), ps.y_base(it));
+        if (first == 0) compute_tile(std::integral_constant<int, 0>{}, n0, ps.x_at(ST), ps.y_at(ST));
+        else if (MB > 1 && first == 1) compute_tile(std::integral_constant<int, (MB > 1 ? 1 : 0)>{}, n0, ps.x_at(ST), ps.y_at(ST));
+    };
+    for (int it = 0; it < ntile_k; it += 2) {
+        tile_step(std::integral_constant<int, 0>{}, it);
+        if (it + 1 < ntile_k) tile_step(std::integral_constant<int, 1>{}, it + 1);
     }
 
     // ---- epilogue

@@ -552,7 +552,8 @@ __global__ void comm_volume_kernel(const int32_t *__restrict__ lengths, int32_t 
     const int32_t L = lengths[s], to = inst[s];
     const int32_t f = from ? from[s] : (int32_t)((s * D_src) / n);
     if (L < 0 || f < 0 || f >= D_src || to < 0 || to >= D_dst) {
-        dev_status[0] = (int32_t)ORCH_EDATA;
+        // several threads may find an error: an atomic store of the one value they all write
+        __hip_atomic_store(dev_status, (int32_t)ORCH_EDATA, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return;
     }
     if (L == 0) return;
