@@ -216,20 +216,23 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
         constexpr int every = kSlots / PS::NLOAD;
         if (i % every == 1 && has_next) PS::issue(pl, i / every);
     };
-    for (int it = 0; it < ntile_k; ++it) {
+    // tile `it` lives in stage it % 2; the loop is unrolled by the two stages so that the stage
+    // offset of every fragment read is an immediate
+    auto tile_step = [&](auto stage_tag, int it) {
+        constexpr int ST = decltype(stage_tag)::value;
         const int n0 = it * kT;
         ps.publish();
         has_next = it + 1 < ntile_k;
         if (has_next) src.m0 = n0 + kT;
-        const Plan pl = ps.plan(src, (it + 1) & 1);
+        const Plan pl = ps.plan(src, ST ^ 1);
         if (CAUSAL && n0 > q0 + 32 * wave + 31) {  // this wavefront's rows see none of the tile
             if (has_next) {
 #pragma unroll
                 for (int kq_ = 0; kq_ < PS::NLOAD; ++kq_) PS::issue(pl, kq_);
             }
-            continue;
+            return;
         }
-        const uint32_t kb = ps.x_base(it), vb = ps.y_base(it);
+        const uint32_t kb = ps.x_at(ST), vb = ps.y_at(ST);
 
         // per 32-key block: S^T = K Q^T and dP^T = V dout^T, then dS^T = P^T (dP^T - delta),
         // rounded to bf16 in the B-operand layout.  Fragment reads run PF steps ahead of the MFMAs
@@ -291,6 +294,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
             dma_slot(pl, 2 * NC + j);
             __builtin_amdgcn_sched_barrier(0);
         }
+    };
+    for (int it = 0; it < ntile_k; it += 2) {
+        tile_step(std::integral_constant<int, 0>{}, it);
+        if (it + 1 < ntile_k) tile_step(std::integral_constant<int, 1>{}, it + 1);
     }
 
     if (qm < L) {
@@ -381,10 +388,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(
     TileSrc src{q, dout, row0, L, m_begin, Hq, g_kv * group};
     float r_lse = 0.f, r_dlt = 0.f;
     // step st covers head g_kv * group + st / ntile_m, rows m_begin + 64 (st % ntile_m) ..
-    auto start_step = [&](int st) {
+    auto start_step = [&](int st, int stage) {
         src.hd = g_kv * group + st / ntile_m;
         src.m0 = m_begin + (st % ntile_m) * kT;
-        ps.begin(src, st);
+        ps.begin_at(src, stage);
         if (tid < kT) {
             int m = src.m0 + tid;
             m = m < L ? m : L - 1;
@@ -392,22 +399,25 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(
             if (DK) r_dlt = delta[(size_t)src.hd * total_tokens + row0 + m];
         }
     };
-    auto store_stats = [&](int st) {
-        if (tid < kT) { s_lse[st & 1][tid] = r_lse; s_dlt[st & 1][tid] = r_dlt; }
+    auto store_stats = [&](int stage) {
+        if (tid < kT) { s_lse[stage][tid] = r_lse; s_dlt[stage][tid] = r_dlt; }
     };
     if (steps > 0) {
-        start_step(0);
+        start_step(0, 0);
         store_stats(0);
     }
-    for (int st = 0; st < steps; ++st) {
+    // step st lives in stage st % 2; the loop is unrolled by the two stages so that the stage
+    // offset of every fragment read is an immediate
+    auto do_step = [&](auto stage_tag, int st) {
+        constexpr int ST = decltype(stage_tag)::value;
         const int m0 = m_begin + (st % ntile_m) * kT;
         ps.publish();
-        if (st + 1 < steps) start_step(st + 1);
+        if (st + 1 < steps) start_step(st + 1, ST ^ 1);
         // rows of the tile that lie before this wavefront's keys see none of them
         if (!(CAUSAL && m0 + kT - 1 < n0w)) {
-            const uint32_t qb = ps.x_base(st), ob = ps.y_base(st);
+            const uint32_t qb = ps.x_at(ST), ob = ps.y_at(ST);
             const uint32_t xb = DK ? qb : ob;
-            const float *lse_s = s_lse[st & 1], *dlt_s = s_dlt[st & 1];
+            const float *lse_s = s_lse[ST], *dlt_s = s_dlt[ST];
             // only tiles that touch the end of the sequence or the diagonal have masked elements
             const bool need_mask = m0 + kT > L || n0w + 32 > L || (CAUSAL && n0w + 31 > m0);
             // Fragment reads run PF steps ahead of the MFMAs that use them; the fences keep that order.
@@ -481,7 +491,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(
             }
         }
         // the next step's row statistics: its slot was last read in the previous step
-        if (st + 1 < steps) store_stats(st + 1);
+        if (st + 1 < steps) store_stats(ST ^ 1);
+    };
+    for (int st = 0; st < steps; st += 2) {
+        do_step(std::integral_constant<int, 0>{}, st);
+        if (st + 1 < steps) do_step(std::integral_constant<int, 1>{}, st + 1);
     }
 
     if (kn < L) {
