@@ -2,10 +2,12 @@
 // Sec. 5.2.1) on one device.  A sequence's rows are contiguous both in the
 // source (sequences concatenated in original order) and in the destination
 // (instance-major, push order), so the rearrangement is n contiguous segment
-// copies.  The destination is cut into fixed-size byte chunks; a persistent grid
-// walks the chunks, finds the segment(s) under each chunk by binary search in a
-// small segment table and streams 16 bytes per lane.  Pure HBM traffic:
-// 2 * row_bytes per row, no arithmetic.
+// copies.  The copied bytes are cut into 1 KB pieces, one per wavefront of a
+// one-shot grid: the wavefront finds its segment through a coarse table (granule ->
+// first segment under it) and a short walk, issues ONE 16-byte load and one store per
+// lane and ends.  Millions of short-lived wavefronts sweeping the buffers in address
+// order measured 20 % more HBM throughput here than a persistent grid with eight
+// accesses in flight per lane.  Pure HBM traffic: 2 * row_bytes per row, no arithmetic.
 //
 // orch_pack_composed: the rearrangement composition of Sec. 5.3.  The source rows lie
 // in an encoder phase's packed order and go straight to their place inside the
@@ -14,23 +16,29 @@
 // encoder assignment, destination start shifted by the modality's offset inside the
 // sequence).  Segments no longer tile the destination, so the copy kernel cuts the
 // COPIED bytes (a running prefix over segment lengths) into chunks instead.
+#include <algorithm>
+
 #include "common.h"
 
 namespace orch {
 namespace {
 
-struct PackHdr {
+struct alignas(32) PackHdr {
     int64_t nseg;        // segments in the table
     int64_t total_rows;  // rows the copy kernel moves
     int32_t ok;          // 0 -> the copy kernel must not touch memory
-    int32_t pad;
+    int32_t gshift;      // granule g of the coarse table covers copied bytes [g << gshift, (g + 1) << gshift)
 };
+
+// coarse table: at most this many granules (of at least 1 MiB) over the copied bytes
+constexpr int kGranules = 65536;
 
 struct PackWs {
     PackHdr *hdr;
     int64_t *src_cu;   // [n+1] exclusive prefix of lengths, original order
     int64_t *seg_dst;  // [n+1] destination row of segment p (relative), [nseg] = total
     int64_t *seg_src;  // [n]   source row of segment p
+    int32_t *gtab;     // [kGranules] segment that holds the first copied byte of a granule
 };
 
 size_t carve(PackWs &w, void *ws, int32_t n)
@@ -43,6 +51,7 @@ size_t carve(PackWs &w, void *ws, int32_t n)
     w.src_cu = (int64_t *)take(nn * 8);
     w.seg_dst = (int64_t *)take(nn * 8);
     w.seg_src = (int64_t *)take(nn * 8);
+    w.gtab = (int32_t *)take((size_t)kGranules * 4);
     return off;
 }
 
@@ -52,6 +61,7 @@ struct ComposeWs {
     int64_t *seg_pos;    // [n+1] exclusive prefix of segment lengths (rows), [nseg] = total
     int64_t *seg_dst;    // [n]   destination row of segment p (relative)
     int64_t *seg_src;    // [n]   source row of segment p
+    int32_t *gtab;       // [kGranules]
 };
 
 size_t carve(ComposeWs &w, void *ws, int32_t n)
@@ -65,6 +75,7 @@ size_t carve(ComposeWs &w, void *ws, int32_t n)
     w.seg_pos = (int64_t *)take(nn * 8);
     w.seg_dst = (int64_t *)take(nn * 8);
     w.seg_src = (int64_t *)take(nn * 8);
+    w.gtab = (int32_t *)take((size_t)kGranules * 4);
     return off;
 }
 
@@ -77,6 +88,7 @@ struct PiecesWs {
     int64_t *seg_pos;    // [P+1]   exclusive prefix of segment lengths (rows), [nseg] = total
     int64_t *seg_dst;    // [P]     destination row of segment (relative)
     int64_t *seg_src;    // [P]     source row of segment
+    int32_t *gtab;       // [kGranules]
 };
 
 size_t carve(PiecesWs &w, void *ws, int32_t n, int32_t P)
@@ -92,6 +104,7 @@ size_t carve(PiecesWs &w, void *ws, int32_t n, int32_t P)
     w.seg_pos = (int64_t *)take(pp * 8);
     w.seg_dst = (int64_t *)take(pp * 8);
     w.seg_src = (int64_t *)take(pp * 8);
+    w.gtab = (int32_t *)take((size_t)kGranules * 4);
     return off;
 }
 
@@ -112,6 +125,32 @@ __device__ __forceinline__ int64_t block_scan(int64_t *part, int tid, int64_t v)
     return part[tid];
 }
 
+// Last step of every prep kernel, all threads, after the header and the running sums are
+// written: the coarse table of the copy kernel.  Granules are 2^gshift copied bytes, at least
+// 1 MiB and few enough to fit the table; gtab[g] = the last segment that starts at or before
+// byte g << gshift (empty segments at that byte included: the copy kernel walks past them).
+__device__ void build_gtab(PackHdr *hdr, const int64_t *seg_pos, int64_t row_bytes, int32_t *gtab, int tid)
+{
+    __syncthreads();
+    const int64_t nseg = hdr->nseg;
+    const int64_t total = hdr->total_rows * row_bytes;
+    if (!hdr->ok || nseg <= 0 || total <= 0) return;
+    int gshift = 20;
+    while (((total - 1) >> gshift) >= kGranules) ++gshift;
+    if (tid == 0) hdr->gshift = gshift;
+    const int64_t ng = ((total - 1) >> gshift) + 1;
+    for (int64_t g = tid; g < ng; g += kPrepThreads) {
+        const int64_t x = g << gshift;
+        int64_t lo = 0, hi = nseg - 1;   // last p with seg_pos[p] * row_bytes <= x
+        while (lo < hi) {
+            const int64_t mid = (lo + hi + 1) >> 1;
+            if (seg_pos[mid] * row_bytes <= x) lo = mid;
+            else hi = mid - 1;
+        }
+        gtab[g] = (int32_t)lo;
+    }
+}
+
 // One workgroup: prefix-sum the lengths (source row of every sequence), then
 // build the segment table of the chosen instances and validate every segment
 // against the buffer sizes the caller stated.
@@ -120,7 +159,8 @@ __global__ __launch_bounds__(kPrepThreads) void pack_prep_kernel(
     const int32_t *__restrict__ inst, const int32_t *__restrict__ order,
     const int32_t *__restrict__ seq_off, const int64_t *__restrict__ tok_off,
     const int32_t *__restrict__ cu_seqlens, int32_t *dev_status, int32_t inst_begin,
-    int32_t inst_end, PackHdr *hdr, int64_t *src_cu, int64_t *seg_dst, int64_t *seg_src)
+    int32_t inst_end, PackHdr *hdr, int64_t *src_cu, int64_t *seg_dst, int64_t *seg_src,
+    int64_t row_bytes, int32_t *gtab)
 {
     __shared__ int64_t part[kPrepThreads];
     __shared__ int s_bad;
@@ -180,6 +220,7 @@ __global__ __launch_bounds__(kPrepThreads) void pack_prep_kernel(
         if (ok) seg_dst[p1 - p0] = rows;
         else dev_status[0] = (int32_t)ORCH_EDATA;
     }
+    build_gtab(hdr, seg_dst, row_bytes, gtab, tid);
 }
 
 // The source and destination sides of a composition, as the kernel needs them.
@@ -200,7 +241,7 @@ __global__ __launch_bounds__(kPrepThreads) void compose_prep_kernel(
     const int32_t *__restrict__ sub_len, const int32_t *__restrict__ sub_off, int32_t n,
     int64_t src_rows, int64_t packed_rows, int has_src, ComposeSide e, ComposeSide m,
     int32_t *dev_status, int32_t inst_begin, int32_t inst_end, PackHdr *hdr, int64_t *src_start,
-    int64_t *seg_pos, int64_t *seg_dst, int64_t *seg_src)
+    int64_t *seg_pos, int64_t *seg_dst, int64_t *seg_src, int64_t row_bytes, int32_t *gtab)
 {
     __shared__ int64_t part[kPrepThreads];
     __shared__ int s_bad;
@@ -284,6 +325,7 @@ __global__ __launch_bounds__(kPrepThreads) void compose_prep_kernel(
         if (ok) seg_pos[nseg] = part[kPrepThreads - 1];
         else dev_status[0] = (int32_t)ORCH_EDATA;
     }
+    build_gtab(hdr, seg_pos, row_bytes, gtab, tid);
 }
 
 // One workgroup, the composition with several pieces per example (Sec. 6, subsequence assembly).
@@ -298,7 +340,7 @@ __global__ __launch_bounds__(kPrepThreads) void compose_pieces_prep_kernel(
     const int32_t *__restrict__ piece_len, int32_t n, int32_t P, int64_t src_rows, int64_t packed_rows,
     int has_src, ComposeSide e, ComposeSide m, int32_t *dev_status, int32_t inst_begin, int32_t inst_end,
     PackHdr *hdr, int64_t *src_start, int64_t *piece_pre, int64_t *seg_base, int64_t *seg_pos,
-    int64_t *seg_dst, int64_t *seg_src)
+    int64_t *seg_dst, int64_t *seg_src, int64_t row_bytes, int32_t *gtab)
 {
     __shared__ int64_t part[kPrepThreads];
     __shared__ int s_bad;
@@ -439,98 +481,95 @@ __global__ __launch_bounds__(kPrepThreads) void compose_pieces_prep_kernel(
             else dev_status[0] = (int32_t)ORCH_EDATA;
         }
     }
+    build_gtab(hdr, seg_pos, row_bytes, gtab, tid);
 }
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kCopyThreads = 256;
-constexpr int kPer = 8;  // accesses in flight per lane
+constexpr int kCopyThreads = 64;   // one wavefront per workgroup
+// Workgroups per launch: grid size times workgroup size must stay below 2^32 threads (a larger
+// launch is cut short without an error); bigger copies take several launches.
+constexpr int64_t kCopyGrid = 1ll << 25;
 
-// last p in [lo, hi] with seg_pos[p] * row_bytes <= x
-__device__ __forceinline__ int64_t seg_of(const int64_t *__restrict__ seg_pos, int64_t lo, int64_t hi,
-                                          int64_t row_bytes, int64_t x)
-{
-    while (lo < hi) {
-        const int64_t mid = (lo + hi + 1) >> 1;
-        if (seg_pos[mid] * row_bytes <= x) lo = mid;
-        else hi = mid - 1;
-    }
-    return lo;
-}
-
-// Chunks are cut in the space of copied bytes: segment p covers
-// [seg_pos[p], seg_pos[p+1]) rows of it, read from row seg_src[p] and written to row
-// seg_dst[p].  For the plain pack the segments tile the destination and the caller
-// passes seg_pos = seg_dst.
+// Pieces are cut in the space of copied bytes: segment p covers [seg_pos[p], seg_pos[p+1])
+// rows of it, read from row seg_src[p] and written to row seg_dst[p].  For the plain pack the
+// segments tile the destination and the caller passes seg_pos = seg_dst.  A workgroup is one
+// wavefront and moves piece number piece0 + blockIdx.x, 64 accesses: granule table -> first
+// segment, a short walk to the segment that holds the piece's first byte, one load and one
+// store per lane.
 template <typename V>
 __global__ __launch_bounds__(kCopyThreads) void pack_copy_kernel(
     const char *__restrict__ src, char *__restrict__ dst, const PackHdr *__restrict__ hdr,
     const int64_t *__restrict__ seg_pos, const int64_t *__restrict__ seg_dst,
-    const int64_t *__restrict__ seg_src, int64_t row_bytes)
+    const int64_t *__restrict__ seg_src, const int32_t *__restrict__ gtab, int64_t row_bytes, int64_t piece0)
 {
-    if (!hdr->ok) return;
+    // a wavefront lives for one load and one store, so the chain of dependent scalar loads in
+    // front of them is kept short: header (one load), granule table, the four fields of the
+    // first segment together; anything else (a walk over short segments, a piece that straddles
+    // segments) is off the common path
+    PackHdr h = *hdr;
+    asm volatile("" : "+s"(h.nseg), "+s"(h.total_rows), "+s"(h.ok), "+s"(h.gshift));   // one load, up front
     constexpr int64_t VB = sizeof(V);
-    constexpr int64_t CB = (int64_t)kCopyThreads * kPer * VB;
-    const int64_t total = hdr->total_rows * row_bytes;
-    const int64_t nseg = hdr->nseg;
-    if (nseg <= 0 || total <= 0) return;
-    const int64_t nchunks = (total + CB - 1) / CB;
-    for (int64_t c = blockIdx.x; c < nchunks; c += gridDim.x) {
-        const int64_t cb = c * CB, ce = min(cb + CB, total);
-        const int64_t plo = seg_of(seg_pos, 0, nseg - 1, row_bytes, cb);
-        const int64_t phi = seg_of(seg_pos, plo, nseg - 1, row_bytes, ce - 1);
-        // usually one segment covers the whole chunk; otherwise walk the pieces
-        for (int64_t p = plo; p <= phi; ++p) {
-            const int64_t pos = seg_pos[p];
-            const int64_t a = max(cb, pos * row_bytes), b = min(ce, seg_pos[p + 1] * row_bytes);
-            if (a >= b) continue;
-            const char *sp = src + (seg_src[p] - pos) * row_bytes;
-            char *dp = dst + (seg_dst[p] - pos) * row_bytes;
-            for (int64_t x0 = a + (int64_t)threadIdx.x * VB; x0 < b; x0 += CB) {
-                V val[kPer];
-#pragma unroll
-                for (int u = 0; u < kPer; ++u) {
-                    const int64_t x = x0 + (int64_t)u * kCopyThreads * VB;
-                    if (x < b) val[u] = __builtin_nontemporal_load((const V *)(sp + x));
-                }
-#pragma unroll
-                for (int u = 0; u < kPer; ++u) {
-                    const int64_t x = x0 + (int64_t)u * kCopyThreads * VB;
-                    if (x < b) __builtin_nontemporal_store(val[u], (V *)(dp + x));
-                }
-            }
-        }
+    constexpr int64_t CB = (int64_t)kCopyThreads * VB;
+    const int64_t total = h.total_rows * row_bytes;
+    const int64_t cb = (piece0 + blockIdx.x) * CB;
+    if (!h.ok || h.nseg <= 0 || cb >= total) return;
+    const int64_t ce = min(cb + CB, total);
+    int64_t p = gtab[cb >> h.gshift];
+    int64_t pos = seg_pos[p], nxt = seg_pos[p + 1], srow = seg_src[p], drow = seg_dst[p];
+    // (the four loads are issued here, together: the empty statement keeps the compiler from
+    // moving them behind the branches below)
+    asm volatile("" : "+s"(pos), "+s"(nxt), "+s"(srow), "+s"(drow));
+    if (nxt * row_bytes <= cb) {   // uniform: walk to the segment that holds the piece's first byte
+        do { ++p; nxt = seg_pos[p + 1]; } while (p + 1 < h.nseg && nxt * row_bytes <= cb);
+        pos = seg_pos[p];
+        srow = seg_src[p];
+        drow = seg_dst[p];
     }
+    const int64_t x = cb + (int64_t)threadIdx.x * VB;
+    if (x >= ce) return;
+    if (nxt * row_bytes < ce) {    // the piece straddles segments: a lane walks on to its own
+        int64_t q = p;
+        while (seg_pos[q + 1] * row_bytes <= x) ++q;   // x < total = seg_pos[nseg] * row_bytes
+        const int64_t qpos = seg_pos[q];
+        const V val = __builtin_nontemporal_load((const V *)(src + (seg_src[q] - qpos) * row_bytes + x));
+        __builtin_nontemporal_store(val, (V *)(dst + (seg_dst[q] - qpos) * row_bytes + x));
+        return;
+    }
+    const V val = __builtin_nontemporal_load((const V *)(src + (srow - pos) * row_bytes + x));
+    __builtin_nontemporal_store(val, (V *)(dst + (drow - pos) * row_bytes + x));
 }
 
 // Copy kernel over at most max_bytes copied bytes, with the widest access that divides
 // the row size and both base addresses.
 void launch_copy(const void *src, void *dst, int64_t max_bytes, int64_t row_bytes, const PackHdr *hdr,
-                 const int64_t *seg_pos, const int64_t *seg_dst, const int64_t *seg_src,
+                 const int64_t *seg_pos, const int64_t *seg_dst, const int64_t *seg_src, const int32_t *gtab,
                  hipStream_t stream)
 {
     if (max_bytes <= 0) return;
     const uintptr_t mis = (uintptr_t)src | (uintptr_t)dst | (uintptr_t)row_bytes;
     int vb = 16;
     while (mis & (uintptr_t)(vb - 1)) vb >>= 1;
-    const int64_t cb = (int64_t)kCopyThreads * kPer * vb;
-    const int64_t nchunks = (max_bytes + cb - 1) / cb;
-    const int grid = (int)(nchunks < 256 * 8 ? nchunks : 256 * 8);
+    const int64_t cb = (int64_t)kCopyThreads * vb;
+    const int64_t npieces = (max_bytes + cb - 1) / cb;
     const char *s = (const char *)src;
     char *d = (char *)dst;
-    if (vb == 16)
-        hipLaunchKernelGGL(pack_copy_kernel<u32x4>, dim3(grid), dim3(kCopyThreads), 0, stream, s, d, hdr,
-                           seg_pos, seg_dst, seg_src, row_bytes);
-    else if (vb == 8)
-        hipLaunchKernelGGL(pack_copy_kernel<u32x2>, dim3(grid), dim3(kCopyThreads), 0, stream, s, d, hdr,
-                           seg_pos, seg_dst, seg_src, row_bytes);
-    else if (vb == 4)
-        hipLaunchKernelGGL(pack_copy_kernel<uint32_t>, dim3(grid), dim3(kCopyThreads), 0, stream, s, d, hdr,
-                           seg_pos, seg_dst, seg_src, row_bytes);
-    else
-        hipLaunchKernelGGL(pack_copy_kernel<uint16_t>, dim3(grid), dim3(kCopyThreads), 0, stream, s, d, hdr,
-                           seg_pos, seg_dst, seg_src, row_bytes);
+    for (int64_t p0 = 0; p0 < npieces; p0 += kCopyGrid) {
+        const dim3 grid((unsigned)std::min<int64_t>(kCopyGrid, npieces - p0));
+        if (vb == 16)
+            hipLaunchKernelGGL(pack_copy_kernel<u32x4>, grid, dim3(kCopyThreads), 0, stream, s, d, hdr, seg_pos,
+                               seg_dst, seg_src, gtab, row_bytes, p0);
+        else if (vb == 8)
+            hipLaunchKernelGGL(pack_copy_kernel<u32x2>, grid, dim3(kCopyThreads), 0, stream, s, d, hdr, seg_pos,
+                               seg_dst, seg_src, gtab, row_bytes, p0);
+        else if (vb == 4)
+            hipLaunchKernelGGL(pack_copy_kernel<uint32_t>, grid, dim3(kCopyThreads), 0, stream, s, d, hdr, seg_pos,
+                               seg_dst, seg_src, gtab, row_bytes, p0);
+        else
+            hipLaunchKernelGGL(pack_copy_kernel<uint16_t>, grid, dim3(kCopyThreads), 0, stream, s, d, hdr, seg_pos,
+                               seg_dst, seg_src, gtab, row_bytes, p0);
+    }
 }
 
 // Communication-volume matrix (Sec. 5.2.2, first loop of the node-wise rearrangement
@@ -581,10 +620,10 @@ int launch_pack(const void *tokens, void *packed, const int32_t *lengths, int32_
 
     hipLaunchKernelGGL(pack_prep_kernel, dim3(1), dim3(kPrepThreads), 0, stream, lengths, n, D, T,
                        packed_rows, a.inst, a.order, a.seq_off, a.tok_off, a.cu_seqlens, a.dev_status,
-                       inst_begin, inst_end, w.hdr, w.src_cu, w.seg_dst, w.seg_src);
+                       inst_begin, inst_end, w.hdr, w.src_cu, w.seg_dst, w.seg_src, row_bytes, w.gtab);
 
     launch_copy(tokens, packed, (packed_rows < T ? packed_rows : T) * row_bytes, row_bytes, w.hdr,
-                w.seg_dst, w.seg_dst, w.seg_src, stream);
+                w.seg_dst, w.seg_dst, w.seg_src, w.gtab, stream);
     ORCH_HIP_CHECK(hipGetLastError());
     return ORCH_OK;
 }
@@ -609,9 +648,9 @@ int launch_pack_composed(const void *enc_rows, void *packed, const int32_t *sub_
     if (src) e = ComposeSide{src->inst, src->order, src->seq_off, src->cu_seqlens, src->tok_off, src->dev_status, D_src};
     hipLaunchKernelGGL(compose_prep_kernel, dim3(1), dim3(kPrepThreads), 0, stream, sub_len, sub_off, n,
                        src_rows, packed_rows, src ? 1 : 0, e, m, dst.dev_status, inst_begin, inst_end, w.hdr,
-                       w.src_start, w.seg_pos, w.seg_dst, w.seg_src);
+                       w.src_start, w.seg_pos, w.seg_dst, w.seg_src, row_bytes, w.gtab);
     launch_copy(enc_rows, packed, (packed_rows < src_rows ? packed_rows : src_rows) * row_bytes, row_bytes,
-                w.hdr, w.seg_pos, w.seg_dst, w.seg_src, stream);
+                w.hdr, w.seg_pos, w.seg_dst, w.seg_src, w.gtab, stream);
     ORCH_HIP_CHECK(hipGetLastError());
     return ORCH_OK;
 }
@@ -636,9 +675,10 @@ int launch_pack_composed_pieces(const void *enc_rows, void *packed, const int32_
     if (src) e = ComposeSide{src->inst, src->order, src->seq_off, src->cu_seqlens, src->tok_off, src->dev_status, D_src};
     hipLaunchKernelGGL(compose_pieces_prep_kernel, dim3(1), dim3(kPrepThreads), 0, stream, piece_ptr, piece_off,
                        piece_len, n, P, src_rows, packed_rows, src ? 1 : 0, e, m, dst.dev_status, inst_begin,
-                       inst_end, w.hdr, w.src_start, w.piece_pre, w.seg_base, w.seg_pos, w.seg_dst, w.seg_src);
+                       inst_end, w.hdr, w.src_start, w.piece_pre, w.seg_base, w.seg_pos, w.seg_dst, w.seg_src,
+                       row_bytes, w.gtab);
     launch_copy(enc_rows, packed, (packed_rows < src_rows ? packed_rows : src_rows) * row_bytes, row_bytes,
-                w.hdr, w.seg_pos, w.seg_dst, w.seg_src, stream);
+                w.hdr, w.seg_pos, w.seg_dst, w.seg_src, w.gtab, stream);
     ORCH_HIP_CHECK(hipGetLastError());
     return ORCH_OK;
 }
