@@ -10,6 +10,7 @@ CSRC = os.path.join(PKG, "csrc")
 LIB_PATH = os.path.join(PKG, "liborch.so")
 PROF_PATH = os.path.join(PKG, "orch_prof")
 CEIL_PATH = os.path.join(PKG, "mfma_ceiling")
+COPY_PATH = os.path.join(PKG, "copy_shapes")
 SOURCES = ["api.hip", "balance.hip", "pack.hip", "attn.hip", "attn_bwd.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -54,6 +55,14 @@ def build_library(verbose: bool = False) -> str:
         print(" ".join(ceil), flush=True)
     _run(ceil)
     os.replace(CEIL_PATH + ".tmp", CEIL_PATH)
+    # copy-shape microbenchmark: context for the pack kernel's launch shape
+    cpy = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Wno-unused-command-line-argument",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-o", COPY_PATH + ".tmp",
+           os.path.join(CSRC, "copy_shapes.hip")]
+    if verbose:
+        print(" ".join(cpy), flush=True)
+    _run(cpy)
+    os.replace(COPY_PATH + ".tmp", COPY_PATH)
     return LIB_PATH
 
 
