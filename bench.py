@@ -554,7 +554,9 @@ def main():
     roof_pack = {"kernel": "pack_copy_kernel", "bound": "hbm", "achieved": pack_gbps, "peak": HBM_PEAK_GBPS,
                  "unit": "GB/s", "frac": pack_gbps / HBM_PEAK_GBPS, "traffic": traffic.get("pack"),
                  "traffic_source": traffic_src if traffic.get("pack") else None,
-                 "launch_ms": pack_ms, "bytes_per_launch": pack_bytes}
+                 "launch_ms": pack_ms, "bytes_per_launch": pack_bytes,
+                 "note": "one orch_pack call: pack_prep_kernel and the copy launches it takes (2^25 one-wavefront "
+                         "workgroups of 1 KB each per launch; %d launches here)" % max(1, -(-int(pack_bytes // 2) // (1 << 35)))}
     # top-level fields: the kernel `value` is about (attention); `kernels` holds both long kernels
     # of the step, `longest_kernel` names the one with the longer launch
     roofline = dict(roof_attn)

@@ -127,8 +127,9 @@ __device__ __forceinline__ int64_t block_scan(int64_t *part, int tid, int64_t v)
 
 // Last step of every prep kernel, all threads, after the header and the running sums are
 // written: the coarse table of the copy kernel.  Granules are 2^gshift copied bytes, at least
-// 1 MiB and few enough to fit the table; gtab[g] = the last segment that starts at or before
-// byte g << gshift (empty segments at that byte included: the copy kernel walks past them).
+// 1 MiB and few enough to fit the table; gtab[g] = the segment that holds byte g << gshift.  The
+// non-empty segments partition the copied bytes, so every segment writes the entries of the
+// granules that start inside it: nseg + granules steps in all, no searches.
 __device__ void build_gtab(PackHdr *hdr, const int64_t *seg_pos, int64_t row_bytes, int32_t *gtab, int tid)
 {
     __syncthreads();
@@ -138,16 +139,11 @@ __device__ void build_gtab(PackHdr *hdr, const int64_t *seg_pos, int64_t row_byt
     int gshift = 20;
     while (((total - 1) >> gshift) >= kGranules) ++gshift;
     if (tid == 0) hdr->gshift = gshift;
-    const int64_t ng = ((total - 1) >> gshift) + 1;
-    for (int64_t g = tid; g < ng; g += kPrepThreads) {
-        const int64_t x = g << gshift;
-        int64_t lo = 0, hi = nseg - 1;   // last p with seg_pos[p] * row_bytes <= x
-        while (lo < hi) {
-            const int64_t mid = (lo + hi + 1) >> 1;
-            if (seg_pos[mid] * row_bytes <= x) lo = mid;
-            else hi = mid - 1;
-        }
-        gtab[g] = (int32_t)lo;
+    const int64_t gmask = ((int64_t)1 << gshift) - 1;
+    for (int64_t p = tid; p < nseg; p += kPrepThreads) {
+        const int64_t b0 = seg_pos[p] * row_bytes, b1 = seg_pos[p + 1] * row_bytes;
+        // granules g with b0 <= g << gshift < b1
+        for (int64_t g = (b0 + gmask) >> gshift; (g << gshift) < b1; ++g) gtab[g] = (int32_t)p;
     }
 }
 
