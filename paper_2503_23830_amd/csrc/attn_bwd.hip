@@ -5,14 +5,14 @@
 //   delta_i = dout_i . out_i  (= sum_j p_ij dp_ij)      ds_ij = p_ij (dp_ij - delta_i)
 //   dq_i = scale * sum_j ds_ij k_j     dk_j = scale * sum_i ds_ij q_i     dv_j = sum_i p_ij dout_i
 //
-// Three or four launches, no atomics, so the result is deterministic:
-//   attn_bwd_delta_kernel  delta[h, i] in fp32, one pass over dout and out (HBM-bound).
+// Two or three launches after the tile table, no atomics, so the result is deterministic:
 //   attn_bwd_dq_kernel     query-stationary, shaped like the forward kernel: a workgroup of 4
 //                          wavefronts owns 128 query rows of one q-head, streams K/V tiles of
 //                          64 keys through LDS, recomputes the transposed scores
 //                          S^T = K Q^T and dP^T = V dout^T (a lane holds 16 keys of ONE query,
 //                          so lse and delta are per-lane scalars), and accumulates
-//                          dQ^T += K^T dS^T.
+//                          dQ^T += K^T dS^T.  It also computes delta[h, i] (fp32) for its rows
+//                          from the dout fragments it holds and writes it for the kernels below.
 //   dK, dV                 key-stationary: a workgroup owns 128 keys of one kv-head (32 per
 //                          wavefront, K or V fragments live in registers), loops over the q-heads
 //                          of the group and over 64-row tiles of Q and dout, computes S = Q K^T
@@ -99,35 +99,6 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b)
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __builtin_bit_cast(float, w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __builtin_bit_cast(float, w & 0xffff0000u); }
 
-// delta[h, i] = sum_x dout[i,h,x] * out[i,h,x]; HD/8 lanes share one (row, head).
-template <int HD>
-__global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const uint16_t *__restrict__ dout,
-                                                            const uint16_t *__restrict__ out,
-                                                            float *__restrict__ delta, int64_t total_tokens,
-                                                            int32_t Hq)
-{
-    constexpr int LPR = HD / 8;  // lanes per row
-    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int64_t rh = gid / LPR;  // row * Hq + head
-    const int part = (int)(gid % LPR);
-    float acc = 0.f;
-    const bool valid = rh < total_tokens * Hq;
-    if (valid) {
-        const u32x4 a = *(const u32x4 *)(dout + rh * HD + 8 * part);
-        const u32x4 b = *(const u32x4 *)(out + rh * HD + 8 * part);
-        acc = bf16_lo(a.x) * bf16_lo(b.x) + bf16_hi(a.x) * bf16_hi(b.x) + bf16_lo(a.y) * bf16_lo(b.y) +
-              bf16_hi(a.y) * bf16_hi(b.y) + bf16_lo(a.z) * bf16_lo(b.z) + bf16_hi(a.z) * bf16_hi(b.z) +
-              bf16_lo(a.w) * bf16_lo(b.w) + bf16_hi(a.w) * bf16_hi(b.w);
-    }
-#pragma unroll
-    for (int m = 1; m < LPR; m <<= 1) acc += __shfl_xor(acc, m);
-    if (valid && part == 0) {
-        const int64_t row = rh / Hq;
-        const int h = (int)(rh % Hq);
-        delta[(size_t)h * total_tokens + row] = acc;
-    }
-}
-
 // block -> (tile u, head).  With the kv-head count a multiple of 8 the kv-head is chosen by
 // blockIdx % 8, i.e. by XCD, so the workgroups that stream the same rows share an L2.
 __device__ __forceinline__ void block_to_tile(int bid, int heads, int Hkv, int group_of_heads, int &u, int &h)
@@ -149,8 +120,8 @@ __device__ __forceinline__ void block_to_tile(int bid, int heads, int Hkv, int g
 template <int HD, bool CAUSAL>
 __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
-    const uint16_t *__restrict__ dout, const float *__restrict__ lse, const float *__restrict__ delta,
-    uint16_t *__restrict__ dq, const int32_t *__restrict__ cu, const BwdHdr *__restrict__ hdr,
+    const uint16_t *__restrict__ dout, const float *__restrict__ lse, const uint16_t *__restrict__ out,
+    float *__restrict__ delta, uint16_t *__restrict__ dq, const int32_t *__restrict__ cu, const BwdHdr *__restrict__ hdr,
     const int32_t *__restrict__ tile_off, int32_t batch, int32_t total_tokens, int32_t Hq, int32_t Hkv,
     float scale, float scale_log2)
 {
@@ -192,7 +163,23 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
         }
     }
     const float lse2 = lse[(size_t)h * total_tokens + row0 + qm_c] * kLog2e;
-    const float dlt = delta[(size_t)h * total_tokens + row0 + qm_c];
+    // delta of this lane's query row = dout . out over the head dimension: the lane holds dout at
+    // columns 16 c + 8 g + [0..7], its partner (lane ^ 32) the other half.  Every (row, head) belongs
+    // to exactly one lane pair of this launch, which also writes it for the dK / dV kernels.
+    float dlt = 0.f;
+    {
+        const uint16_t *op = out + ((size_t)(row0 + qm_c) * Hq + h) * HD + 8 * g;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            const u32x4 a = __builtin_bit_cast(u32x4, dof[c]);
+            const u32x4 b = *(const u32x4 *)(op + 16 * c);
+            dlt += bf16_lo(a.x) * bf16_lo(b.x) + bf16_hi(a.x) * bf16_hi(b.x) + bf16_lo(a.y) * bf16_lo(b.y) +
+                   bf16_hi(a.y) * bf16_hi(b.y) + bf16_lo(a.z) * bf16_lo(b.z) + bf16_hi(a.z) * bf16_hi(b.z) +
+                   bf16_lo(a.w) * bf16_lo(b.w) + bf16_hi(a.w) * bf16_hi(b.w);
+        }
+        dlt += __shfl_xor(dlt, 32);
+        if (g == 0 && qm < L) delta[(size_t)h * total_tokens + row0 + qm] = dlt;
+    }
 
     f32x16 acc[NDB];
 #pragma unroll
@@ -820,8 +807,6 @@ int launch_attn_bwd(const void *q, const void *k, const void *v, const void *out
     if (scale <= 0.f) scale = 1.0f / sqrtf((float)d);
     const float sl2 = scale * kLog2e;
     if (batch > 0 && total_tokens > 0) {
-        const int64_t rows = (int64_t)total_tokens * Hq * (d / 8);
-        const unsigned dgrid = (unsigned)((rows + 255) / 256);
         const unsigned qgrid = (unsigned)(max_tiles * Hq), kgrid = (unsigned)(max_tiles * Hkv);
 #define ORCH_BWD_COMMON (const uint16_t *)q, (const uint16_t *)k, (const uint16_t *)v, (const uint16_t *)dout, lse, w.delta
 #define ORCH_BWD_TAIL cu_seqlens, w.hdr, w.tile_off, batch, total_tokens, Hq, Hkv, scale, sl2
@@ -830,10 +815,9 @@ int launch_attn_bwd(const void *q, const void *k, const void *v, const void *out
 // kernel's extra step per (key tile, head) costs more there than the second S product.
 #define ORCH_BWD_LAUNCH(HD_, C_)                                                                                  \
     do {                                                                                                          \
-        hipLaunchKernelGGL((attn_bwd_delta_kernel<HD_>), dim3(dgrid), dim3(256), 0, stream,                      \
-                           (const uint16_t *)dout, (const uint16_t *)out, w.delta, (int64_t)total_tokens, Hq);    \
         hipLaunchKernelGGL((attn_bwd_dq_kernel<HD_, C_>), dim3(qgrid), dim3(kThreads), 0, stream,                 \
-                           ORCH_BWD_COMMON, (uint16_t *)dq, ORCH_BWD_TAIL);                                       \
+                           (const uint16_t *)q, (const uint16_t *)k, (const uint16_t *)v, (const uint16_t *)dout, \
+                           lse, (const uint16_t *)out, w.delta, (uint16_t *)dq, ORCH_BWD_TAIL);                   \
         if (HD_ == 128) {                                                                                         \
             hipLaunchKernelGGL((attn_bwd_dkv_fused_kernel<128, C_>), dim3(kgrid), dim3(2 * kThreads), 0, stream,  \
                                ORCH_BWD_COMMON, (uint16_t *)dk, (uint16_t *)dv, ORCH_BWD_TAIL);                   \
