@@ -975,7 +975,9 @@ int launch_attn(const void *q, const void *k, const void *v, void *out, float *l
     int64_t max_tiles = (int64_t)total_tokens / BM + batch;
     if (max_seqlen > 0) max_tiles = std::min<int64_t>(max_tiles, (int64_t)batch * ((max_seqlen + BM - 1) / BM));
     const int64_t grid = max_tiles * Hq;
-    if (grid > 0x7fffffffLL) ORCH_FAIL(ORCH_EUNSUPPORTED, "orch_varlen_attn_fwd: %lld workgroups", (long long)grid);
+    // (a launch of 2^32 threads or more in all is cut short by the runtime without an error)
+    if (grid > 0x7fffffffLL || grid * (il ? kILThreads : kThreads) > 0xffffffffLL)
+        ORCH_FAIL(ORCH_EUNSUPPORTED, "orch_varlen_attn_fwd: %lld workgroups", (long long)grid);
     if (scale <= 0.f) scale = 1.0f / sqrtf((float)d);
     const float sl2 = scale * 1.4426950408889634f;
     if (grid > 0 && batch > 0) {

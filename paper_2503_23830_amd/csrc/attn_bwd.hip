@@ -803,7 +803,9 @@ int launch_attn_bwd(const void *q, const void *k, const void *v, const void *out
                        max_seqlen, w.hdr, w.tile_off, dev_status);
     int64_t max_tiles = (int64_t)total_tokens / kOwn + batch;
     if (max_seqlen > 0) max_tiles = std::min<int64_t>(max_tiles, (int64_t)batch * ((max_seqlen + kOwn - 1) / kOwn));
-    if (max_tiles * Hq > 0x7fffffffLL) ORCH_FAIL(ORCH_EUNSUPPORTED, "orch_varlen_attn_bwd: %lld workgroups", (long long)(max_tiles * Hq));
+    // (a launch of 2^32 threads or more in all is cut short by the runtime without an error)
+    if (max_tiles * Hq > 0x7fffffffLL || max_tiles * Hq * (2 * kThreads) > 0xffffffffLL)
+        ORCH_FAIL(ORCH_EUNSUPPORTED, "orch_varlen_attn_bwd: %lld workgroups", (long long)(max_tiles * Hq));
     if (scale <= 0.f) scale = 1.0f / sqrtf((float)d);
     const float sl2 = scale * kLog2e;
     if (batch > 0 && total_tokens > 0) {
