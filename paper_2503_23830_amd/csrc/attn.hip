@@ -4,21 +4,24 @@
 //
 // Common to both kernels below (head_dim 64: attn_fwd_kernel; head_dim 128:
 // attn_fwd_il_kernel, described at its definition): the transposed score
-// product, per-lane softmax statistics and the lazy reference maximum.
+// product, per-lane softmax statistics, and a softmax reference that is fixed in
+// the launch every call makes and moves lazily in the rare redo pass.
 //
 // attn_fwd_kernel: one workgroup (4 wavefronts) owns 128*MB consecutive query rows
 // of one sequence and one q-head; each wavefront owns MB blocks of 32 rows.  K/V tiles
 // of BN = 64 keys go from global memory into LDS by LDS-DMA (row-major, swizzled; two
-// stages, one barrier per tile) and are shared by the four wavefronts; the V^T operand
+// stages, one barrier per tile, the tile loop unrolled by the stages so that fragment
+// reads use immediate offsets) and are shared by the four wavefronts; the V^T operand
 // of the second product is read from the row-major V tile with transpose reads.  With
 // MB = 2 every K/V fragment read from LDS feeds two MFMAs, which halves LDS traffic per FLOP.  The scores are computed transposed,
 // S^T = K Q^T, with v_mfma_f32_32x32x16_bf16: in the accumulator layout every
 // lane then holds 16 keys of ONE query, so the online-softmax statistics are
 // per-lane scalars (one cross-lane exchange per tile), the probabilities are
 // already in the B-operand layout of the second product O^T += V^T P^T, and
-// rescaling O is a per-lane multiply.  The running maximum is only moved when a
-// row's maximum grows by more than 2^8 (exact: the stale reference cancels in
-// the final division), so O is rarely rescaled after the first tile.
+// rescaling O is a per-lane multiply.  In the moving-reference form the running
+// maximum is only moved when a row's maximum grows by more than 2^8 (exact: the
+// stale reference cancels in the final division), so O is rarely rescaled after the
+// first tile.
 #include <algorithm>
 #include <type_traits>
 
@@ -42,9 +45,9 @@ struct AttnHdr {
 // later blocks compute no maximum and O is never rescaled (the result is the same: the
 // reference cancels in the final division, and fp32 carries probabilities up to 2^64 times the
 // reference with the same relative precision).  A row whose sum of probabilities does not stay
-// below 2^64 marks its (query tile, head) in `redo`; the moving-reference form of the same
-// kernel, launched right after on the same grid, recomputes exactly the marked tiles and
-// returns at once on the others.
+// below 2^64 marks its (query tile, head) in `redo` and appends it to `redo_list`; the
+// moving-reference form of the same code, launched right after with a small grid, walks
+// that list (normally empty) and recomputes exactly the marked tiles.
 constexpr float kRedoSum = 1.8446744e19f;   // 2^64
 
 // tile_off[t] = number of BM-row query tiles in sequences before t.
@@ -392,9 +395,9 @@ __global__ __launch_bounds__(kThreads, (MB * HD > 128 ? 1 : (MB * HD > 64 ? 2 : 
 
 
 // ---------------------------------------------------------------------------
-// Interleaved variant (head_dim 128): 8 free-running wavefronts (two per SIMD)
-// own 32 query rows each.  No vector register ever stages K or V:
-//   * K and V tiles (64 keys x 256 B) go from global memory straight into LDS
+// Interleaved variant (head_dim 128): 8 wavefronts (two per SIMD) own 32 query
+// rows each.  No vector register ever stages K or V:
+//   * K and V blocks (32 keys x 256 B) go from global memory straight into LDS
 //     with 16-byte LDS-DMA loads.  A wave-wide load fills 1 KB of LDS in lane
 //     order, so bank conflicts are avoided by choosing WHICH 16-byte chunk of a
 //     row each lane fetches: row r keeps chunk c at slot c ^ swz(r).
@@ -405,15 +408,17 @@ __global__ __launch_bounds__(kThreads, (MB * HD > 128 ? 1 : (MB * HD > 64 ? 2 : 
 //     lane i receives element i%4 of the 8-byte words addressed by lanes
 //     i/4, 4 + i/4, 8 + i/4, 12 + i/4.  Two such reads are the A operand of
 //     O^T += V^T P^T for the keys a lane's P registers hold.
-// Four-stage rings for K and V (128 KB of LDS), K requested three tiles ahead and V
-// two; one workgroup barrier per 64-key tile.  The tile loop is unrolled by the ring
-// depth, so every fragment read is a fixed lane address plus an immediate offset.
-// The LDS-DMA unit is shared by the workgroup and a wavefront stalls at issue while
-// it is busy, so a wavefront's four loads per tile are spread over its two blocks.
+// Eight-stage rings of 32-key blocks for K and V (128 KB of LDS), block b in stage
+// b % 8; the workgroup meets at a barrier every four blocks, and what an interval of
+// four blocks reads was requested during the interval before it (see `block` below).
+// The block loop is unrolled by the ring depth, so every fragment read is a fixed
+// lane address plus an immediate offset.  The LDS-DMA unit is shared by the workgroup
+// and a wavefront stalls at issue while it is busy, so a wavefront's loads are spread
+// over the iterations that issue them, two per half.
 //
 // Each wavefront software-pipelines over 32-key blocks b.  Iteration b issues
-//     half 1:  O^T   += V(b-1)^T P(b-1) 8 MFMAs | row maxima of S(b), then exp of
-//                                                 its keys 0..15
+//     half 1:  O^T   += V(b-1)^T P(b-1) 8 MFMAs | (moving reference only: row maxima
+//                                                 of S(b)) exp of its keys 0..15
 //     half 2:  S(b+1) = K(b+1) Q^T      8 MFMAs | exp of S(b), keys 16..31
 // with the vector-ALU work cut into pieces that sit between consecutive MFMAs,
 // so the matrix core and the vector ALU of a SIMD are busy at the same time
@@ -423,9 +428,11 @@ __global__ __launch_bounds__(kThreads, (MB * HD > 128 ? 1 : (MB * HD > 64 ? 2 : 
 // chunk in half 2.  LDS fragments are single-buffered in registers too: fragment j
 // of K(b+1) is requested right after MFMA j of half 1 (its register was last read by
 // MFMA j of the previous half 2), the fragments of V(b) likewise during half 2.
-// Reference maximum: lazy (moves only on growth > 2^8).  The factor alpha_b that
-// carries O and l from the reference of block b-1 to that of block b is applied
-// in half 2 of iteration b: O has received P(b-1) V(b-1) and not yet P(b) V(b).
+// Reference maximum: fixed (the row's maximum over block 0, taken in the prologue) in
+// the launch every call makes; in the redo pass lazy (moves only on growth > 2^8), and
+// the factor alpha_b that carries O and l from the reference of block b-1 to that of
+// block b is applied at the end of iteration b: O has received P(b-1) V(b-1) and not
+// yet P(b) V(b).
 // ---------------------------------------------------------------------------
 constexpr int kILThreads = 512;
 
