@@ -5,11 +5,15 @@
 // orch_balance_padded: Algorithm 2 (the same sort, ascending, then the bound search
 // and the padded layout in one kernel; see padded_split_kernel).
 //
+// orch_balance_tolerance: Appendix A's third algorithm (the same sort by length, then
+// greedy_tolerance_kernel, the same layout kernel).
+//
 // orch_balance, three launches on the caller's stream:
 //   cost_sort_kernel   one 1024-thread workgroup: cost keys, then a stable LSD
 //                      radix sort (8-bit digits, only as many passes as the
 //                      largest key needs) of (~cost, index) pairs
-//   greedy_*_kernel    one workgroup of four wavefronts.  Wave 0 runs the serial
+//   greedy_kernel      one workgroup of four wavefronts (both forms of the loop in one
+//                      launch; a flag from the sort kernel picks one).  Wave 0 runs the serial
 //                      loop (in rounds of up to D items where the loads allow) and
 //                      does nothing but choose the receiving instance; it publishes
 //                      the choices per sorted position.  Waves 1-3 trail it, taking
