@@ -843,6 +843,10 @@ __device__ __forceinline__ void attn_il_tile(
             max_c();
         }
     }
+    // K block 0 is the one block that is read outside the interval scheme (just above), and the
+    // last requests of interval 0 reuse its stage: every wavefront has it in registers (its
+    // products are issued) before anybody goes on
+    __builtin_amdgcn_s_barrier();
 
     // One 32-key block whose ring stage BS = b % 8 is a compile-time constant.  The workgroup
     // meets at a barrier every FOUR blocks: interval I (blocks 4I .. 4I+3) reads K blocks 4I+1 ..
