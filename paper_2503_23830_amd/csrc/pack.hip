@@ -512,25 +512,43 @@ __global__ __launch_bounds__(kCopyThreads) void pack_copy_kernel(
     const int64_t cb = (piece0 + blockIdx.x) * CB;
     if (!h.ok || h.nseg <= 0 || cb >= total) return;
     const int64_t ce = min(cb + CB, total);
-    int64_t p = gtab[cb >> h.gshift];
+    const int64_t g = cb >> h.gshift;
+    int64_t p = gtab[g];
     int64_t pos = seg_pos[p], nxt = seg_pos[p + 1], srow = seg_src[p], drow = seg_dst[p];
     // (the four loads are issued here, together: the empty statement keeps the compiler from
     // moving them behind the branches below)
     asm volatile("" : "+s"(pos), "+s"(nxt), "+s"(srow), "+s"(drow));
-    if (nxt * row_bytes <= cb) {   // uniform: walk to the segment that holds the piece's first byte
-        do { ++p; nxt = seg_pos[p + 1]; } while (p + 1 < h.nseg && nxt * row_bytes <= cb);
+    // the segment of any byte of this piece lies in [p, last]: bisect there when a walk is needed,
+    // so that runs of short or empty segments cost a logarithm, not their count
+    int64_t last = h.nseg - 1;
+    if (nxt * row_bytes <= cb) {   // uniform: the segment that holds the piece's first byte
+        if (((g + 1) << h.gshift) < total) last = gtab[g + 1];
+        int64_t lo = p + 1, hi = last;   // last q with seg_pos[q] * row_bytes <= cb
+        while (lo < hi) {
+            const int64_t mid = (lo + hi + 1) >> 1;
+            if (seg_pos[mid] * row_bytes <= cb) lo = mid;
+            else hi = mid - 1;
+        }
+        p = lo;
         pos = seg_pos[p];
+        nxt = seg_pos[p + 1];
         srow = seg_src[p];
         drow = seg_dst[p];
     }
     const int64_t x = cb + (int64_t)threadIdx.x * VB;
     if (x >= ce) return;
-    if (nxt * row_bytes < ce) {    // the piece straddles segments: a lane walks on to its own
-        int64_t q = p;
-        while (seg_pos[q + 1] * row_bytes <= x) ++q;   // x < total = seg_pos[nseg] * row_bytes
-        const int64_t qpos = seg_pos[q];
-        const V val = __builtin_nontemporal_load((const V *)(src + (seg_src[q] - qpos) * row_bytes + x));
-        __builtin_nontemporal_store(val, (V *)(dst + (seg_dst[q] - qpos) * row_bytes + x));
+    if (nxt * row_bytes < ce) {    // the piece straddles segments: a lane finds its own
+        if (last == h.nseg - 1 && (((cb + CB - 1) >> h.gshift) + 1) << h.gshift < total)
+            last = gtab[((cb + CB - 1) >> h.gshift) + 1];
+        int64_t lo = p, hi = last;   // last q with seg_pos[q] * row_bytes <= x  (x < total)
+        while (lo < hi) {
+            const int64_t mid = (lo + hi + 1) >> 1;
+            if (seg_pos[mid] * row_bytes <= x) lo = mid;
+            else hi = mid - 1;
+        }
+        const int64_t qpos = seg_pos[lo];
+        const V val = __builtin_nontemporal_load((const V *)(src + (seg_src[lo] - qpos) * row_bytes + x));
+        __builtin_nontemporal_store(val, (V *)(dst + (seg_dst[lo] - qpos) * row_bytes + x));
         return;
     }
     const V val = __builtin_nontemporal_load((const V *)(src + (srow - pos) * row_bytes + x));

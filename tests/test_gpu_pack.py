@@ -54,6 +54,26 @@ def test_row_widths_and_alignment(gpu_device, H):
     assert np.array_equal(bits(packed), oracle.pack(wl.token_tag_np(np.arange(T), H), L, ref))
 
 
+@pytest.mark.parametrize("H,n,hi,zero", [(8, 60000, 3, 0.5), (1, 30000, 5, 0.9), (64, 40000, 40, 0.2)])
+def test_many_tiny_and_empty_sequences(gpu_device, H, n, hi, zero):
+    # thousands of segments under one lookup granule, long runs of empty ones, pieces that straddle
+    # dozens of segments: the copy kernel's searches instead of its common path
+    L = wl.random_lengths(900 + H, n, 0, hi, zero_frac=zero)
+    T = int(L.sum())
+    Ld, asg = run_balance(L, 64, 1, 3, gpu_device)
+    ref = oracle.balance(L, 64, 1, 3)
+    tokens = wl.token_tag_torch(0, T, H, gpu_device)
+    packed, guards = pack_with_guards(tokens, Ld, asg, T, H, gpu_device)
+    assert guards
+    assert np.array_equal(bits(packed), oracle.pack(wl.token_tag_np(np.arange(T), H), L, ref))
+    # one instance's share through inst_begin / inst_end
+    i0, i1 = 17, 19
+    rows = int(ref.tok_off[i1] - ref.tok_off[i0])
+    part, guards = pack_with_guards(tokens, Ld, asg, rows, H, gpu_device, i0, i1)
+    assert guards
+    assert np.array_equal(bits(part), bits(packed)[int(ref.tok_off[i0]): int(ref.tok_off[i1])])
+
+
 def test_instance_subrange(gpu_device):
     w = wl.WORKLOADS[3]
     L = wl.draw_lengths(w)
