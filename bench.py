@@ -236,6 +236,23 @@ def main():
     torch.cuda.synchronize()
     bwd_ms = wev[0].elapsed_time(wev[1]) / 3
 
+    # ---------------- the same forward launch on operands that barely switch ------------------
+    # q = k = v = 0.5 everywhere: the kernel runs the same instructions in the same number of clock
+    # cycles (fixed softmax reference, no data-dependent branch), so what changes is the clock the
+    # chip sustains under the operands' switching power.  Context for the roofline, never `value`.
+    qc, kc, vc = torch.full_like(q, 0.5), torch.full_like(k, 0.5), torch.full_like(v, 0.5)
+    oc = torch.empty_like(q)
+    orch.varlen_attn_fwd(qc, kc, vc, cu_view, w.causal, out=oc, ws=ws_attn)
+    cev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    cev[0].record()
+    for _ in range(5):
+        orch.varlen_attn_fwd(qc, kc, vc, cu_view, w.causal, out=oc, ws=ws_attn)
+    cev[1].record()
+    torch.cuda.synchronize()
+    const_ms = cev[0].elapsed_time(cev[1]) / 5
+    const_ok = bool(torch.all(oc[: min(T_i, 4096)].float() == 0.5).item())   # every output row is the mean of equal values
+    del qc, kc, vc, oc
+
     if args.calib_copy:
         ca = torch.zeros(1 << 29, dtype=torch.int16, device=dev)
         cb = torch.empty_like(ca)
@@ -549,6 +566,11 @@ def main():
                  "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic.get("attn"),
                  "traffic_source": traffic_src if traffic.get("attn") else None,
                  "launch_ms": attn_ms, "flop_per_launch": flops, "mfma_only_ceiling": ceiling,
+                 "same_launch_constant_operands": {
+                     "ms": const_ms, "tflops": flops / (const_ms * 1e-3) / 1e12,
+                     "frac": flops / (const_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "outputs_ok": const_ok,
+                     "note": "q = k = v = 0.5: same instruction stream and cycle count, higher sustained clock; "
+                             "the gap to `achieved` is the power limit under N(0,1) operands, not the kernel"},
                  "frac_of_measured_random_operand_ceiling":
                      (attn_tflops / ceiling["random_operands_tflops"]) if ceiling and ceiling.get("random_operands_tflops") else None}
     roof_pack = {"kernel": "pack_copy_kernel", "bound": "hbm", "achieved": pack_gbps, "peak": HBM_PEAK_GBPS,

@@ -7,6 +7,7 @@
 //
 //   orch_prof lengths.bin D a b H Hq Hkv d causal steps [pack_all]
 #include <hip/hip_runtime.h>
+#include <string.h>
 #include <stdint.h>
 #include <stdio.h>
 #include <stdlib.h>
@@ -42,10 +43,13 @@ __global__ void fill_words(uint16_t *p, size_t count, uint64_t seed)
         p[i] = (uint16_t)(mix(i ^ seed) >> 40);
 }
 
-// bf16 values with roughly unit variance (sum of four uniforms, centred)
-__global__ void fill_bf16(uint16_t *p, size_t count, uint64_t seed)
+// bf16 values with roughly unit variance (sum of four uniforms, centred); constant != 0: that
+// bf16 bit pattern everywhere (operands that barely switch, to see the same instruction stream
+// without the data's switching power)
+__global__ void fill_bf16(uint16_t *p, size_t count, uint64_t seed, uint16_t constant)
 {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x) {
+        if (constant) { p[i] = constant; continue; }
         uint64_t h = mix(i ^ seed);
         float s = 0.f;
         for (int j = 0; j < 4; ++j) s += (float)((h >> (16 * j)) & 0xffff) * (1.0f / 65536.0f);
@@ -65,7 +69,7 @@ __global__ void calib_copy_kernel(const uint4 *__restrict__ src, uint4 *__restri
 int main(int argc, char **argv)
 {
     if (argc < 11) {
-        fprintf(stderr, "usage: %s lengths.bin D a b H Hq Hkv d causal steps [pack_all=1] [split.bin]\n", argv[0]);
+        fprintf(stderr, "usage: %s lengths.bin D a b H Hq Hkv d causal steps [pack_all=1] [split.bin | -] [const]\n", argv[0]);
         return 2;
     }
     const char *path = argv[1];
@@ -74,7 +78,9 @@ int main(int argc, char **argv)
     const int H = atoi(argv[5]), Hq = atoi(argv[6]), Hkv = atoi(argv[7]), d = atoi(argv[8]);
     const int causal = atoi(argv[9]), steps = atoi(argv[10]);
     const int pack_all = argc > 11 ? atoi(argv[11]) : 1;
-    const char *split_path = argc > 12 ? argv[12] : nullptr;
+    const char *split_path = (argc > 12 && strcmp(argv[12], "-") != 0) ? argv[12] : nullptr;
+    // "const": q, k, v, dout all 0.5 instead of N(0,1) values
+    const uint16_t constant = (argc > 13 && strcmp(argv[13], "const") == 0) ? 0x3f00 : 0;
 
     FILE *f = fopen(path, "rb");
     if (!f) { perror(path); return 1; }
@@ -163,9 +169,9 @@ int main(int argc, char **argv)
     CK(hipMalloc(&o, std::max<size_t>(qn, 1) * 2));
     CK(hipMalloc(&k, std::max<size_t>(kn, 1) * 2));
     CK(hipMalloc(&v, std::max<size_t>(kn, 1) * 2));
-    hipLaunchKernelGGL(fill_bf16, dim3(4096), dim3(256), 0, st, q, qn, 11ull);
-    hipLaunchKernelGGL(fill_bf16, dim3(4096), dim3(256), 0, st, k, kn, 22ull);
-    hipLaunchKernelGGL(fill_bf16, dim3(4096), dim3(256), 0, st, v, kn, 33ull);
+    hipLaunchKernelGGL(fill_bf16, dim3(4096), dim3(256), 0, st, q, qn, 11ull, constant);
+    hipLaunchKernelGGL(fill_bf16, dim3(4096), dim3(256), 0, st, k, kn, 22ull, constant);
+    hipLaunchKernelGGL(fill_bf16, dim3(4096), dim3(256), 0, st, v, kn, 33ull, constant);
     size_t wsa = orch_varlen_attn_workspace(batch, Ti, Hq);
     void *ws_a;
     CK(hipMalloc(&ws_a, wsa));
@@ -208,7 +214,7 @@ int main(int argc, char **argv)
         CK(hipMalloc(&dq, std::max<size_t>(qn, 1) * 2));
         CK(hipMalloc(&dk, std::max<size_t>(kn, 1) * 2));
         CK(hipMalloc(&dv, std::max<size_t>(kn, 1) * 2));
-        hipLaunchKernelGGL(fill_bf16, dim3(4096), dim3(256), 0, st, dout, qn, 44ull);
+        hipLaunchKernelGGL(fill_bf16, dim3(4096), dim3(256), 0, st, dout, qn, 44ull, constant);
         size_t wsw = orch_varlen_attn_bwd_workspace(batch, Ti, Hq);
         void *ws_w;
         CK(hipMalloc(&ws_w, wsw));
