@@ -728,6 +728,40 @@ __device__ __forceinline__ void attn_il_tile(
             }
         }
     };
+    // Fixed reference: the same pipeline laid out EVENLY, one element entering per MFMA slot.  Slot
+    // g = 0..15 of iteration b (half 1: g = j, half 2: g = 8 + j) holds stage A of element g - 2 of
+    // block b, stage B of element g - 3 and stage C/D of element g - 4; the last elements of a
+    // block run over into the next iteration: stage A of elements 14, 15 of block b-1 sits in its
+    // slots 0, 1, their stage B in slots 1, 2 (element 13: slot 0), stage C/D of elements 12..15 in
+    // slots 0..3.  Every slot then carries one fma, one exp2, one add and half a pack (24-28
+    // vector-ALU cycles against the 32 of its MFMA) instead of 40-52 cycles in the first slots and
+    // 8-28 in the last ones.  P's chunk 0 (elements 0..7) is complete by slot 12, its chunk 1 by
+    // slot 3 of the next iteration: before the MFMAs that read them (slots 0..3 and 4..7 of half 1).
+    // The row sum goes straight into l_run.
+    auto even_items = [&](const f32x16 &Sx, int ea, int eb, int ec) {
+        if (ea >= 0 && ea < 16) {   // A
+            xs[ea] = Sx[ea] * scale_log2 - mbias;
+            asm volatile("" : "+v"(xs[ea]));
+        }
+        if (eb >= 0 && eb < 16) {   // B
+            ps[eb] = __builtin_amdgcn_exp2f(xs[eb]);
+            asm volatile("" : "+v"(ps[eb]));
+        }
+        if (ec >= 0 && ec < 16) {   // C, and D for a completed pair
+            l_run += ps[ec];
+            if (ec & 1) {
+                uint32_t pk = pack_bf16(ps[ec - 1], ps[ec]);
+                asm volatile("" : "+v"(pk), "+v"(l_run));
+                u32x4 w = __builtin_bit_cast(u32x4, P[ec >> 3]);
+                w[(ec & 7) >> 1] = pk;
+                P[ec >> 3] = __builtin_bit_cast(bf16x8, w);
+            }
+        }
+    };
+    auto even_tick = [&](const f32x16 &Sc, const f32x16 &Sp, int g) {
+        even_items(Sc, g - 2, g - 3, g - 4);       // block b
+        even_items(Sp, g + 14, g + 13, g + 12);    // block b-1 (slots 0..3 only)
+    };
     auto mfma = [](const bf16x8 &a, const bf16x8 &b, const f32x16 &c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
     };
@@ -767,7 +801,8 @@ __device__ __forceinline__ void attn_il_tile(
             if (WITH_MAX && j == 2) max_b(Sc);
             if (WITH_MAX && j == 3) max_c();
             // chunk 0 of P is rewritten from tick 2 on: MFMAs 0..3 have read it by then
-            if (j >= T0) exp_tick(Sc, j - T0);
+            if (FIXED) even_tick(Sc, Sn, j);   // Sn still holds S(b-1) during half 1
+            else if (j >= T0) exp_tick(Sc, j - T0);
             if (LOADS && j == 2 && ds.on) dma_run(ds.j[0]);
             if (LOADS && j == 6 && ds.on) dma_run(ds.j[1]);
             ORCH_SB();
@@ -787,7 +822,8 @@ __device__ __forceinline__ void attn_il_tile(
             // V(b), the fragment that MFMA j of the next half 1 reads
             read_v1(j % NDB, j / NDB, V_OFF);
             ORCH_SB();
-            exp_tick(Sc, 8 - T0 + j);
+            if (FIXED) even_tick(Sc, Sc, 8 + j);   // (no element of block b-1 is left by now)
+            else exp_tick(Sc, 8 - T0 + j);
             if (LOADS && j == 2 && ds.on) dma_run(ds.j[2]);
             if (LOADS && j == 6 && ds.on) dma_run(ds.j[3]);
             ORCH_SB();
@@ -796,10 +832,7 @@ __device__ __forceinline__ void attn_il_tile(
             exp_tick(Sc, 12);
             exp_tick(Sc, 13);
         }
-        if (FIXED) {
-            l_run += psum;
-            return;
-        }
+        if (FIXED) return;   // (the row sum went into l_run as it was formed)
         // ---- carry O and l to the reference of block b (rarely != 1), add this block's sum
         if (moved) {
 #pragma unroll
@@ -821,6 +854,15 @@ __device__ __forceinline__ void attn_il_tile(
     __builtin_amdgcn_s_barrier();
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk) P[kk] = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
+    if (FIXED) {
+        // "block -1", whose last pipeline stages sit in the first slots of iteration 0: all zeros
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            S[1][e] = -INFINITY;
+            xs[e] = -INFINITY;
+            ps[e] = 0.f;
+        }
+    }
     if (nblk_w > 0) {
         read_k(0);
         read_v(0);
@@ -879,7 +921,17 @@ __device__ __forceinline__ void attn_il_tile(
         if (b0 + 7 < nblk_wg) block(std::integral_constant<int, 7>{}, b0 + 7);
     }
     // ---- drain: O^T += V(B-1)^T P(B-1) for the wavefront's last block; both are in registers
+    // (fixed reference: after the pipeline stages of its last elements, which no further
+    // iteration carries)
     if (nblk_w > 0) {
+        if (FIXED) {
+            auto flush = [&](const f32x16 &Sl) {
+#pragma unroll
+                for (int g = 16; g < 20; ++g) even_items(Sl, g - 2, g - 3, g - 4);
+            };
+            if ((nblk_w - 1) & 1) flush(S[1]);
+            else flush(S[0]);
+        }
 #pragma unroll
         for (int j = 0; j < 2 * NDB; ++j) {
             const int db = j % NDB, kk = j / NDB;
